@@ -1,0 +1,140 @@
+/*
+ * ogc_mlp.h — C ABI of the MI355X (gfx950) fused-MLP library.
+ *
+ * The library runs a chain of MatMul + bias + activation layers ("MLP subgraph", arxiv 2301.01333
+ * Section VII) as fused GPU kernels: for layer l = 0..L-1, Y_l[M,N_l] = post_ops(X_l[M,K_l] W_l[K_l,N_l])
+ * with X_{l+1} = Y_l.  fp32, bf16 and int8 (u8 activations x s8 per-output-channel weights, int32
+ * accumulation, dequantize / requantize as fused post-ops) are supported.
+ *
+ * Conventions common to every entry point
+ *   - All shapes, dtypes, activations and quantization parameters are static: fixed when the plan is
+ *     made (the paper specialises for static shapes and folds quantization constants, Sections I, V).
+ *   - Tensors at the boundary are plain row-major ("input and output matrices are in plain layouts",
+ *     Section VII).  Weights are [K,N] row-major (B[K,N] of Section III).  Blocked layouts exist only
+ *     inside the packed blob and the workspace.
+ *   - "dev" pointers are device (HBM) addresses on the current HIP device; "host" pointers are ordinary
+ *     process memory.  The library never allocates, frees or retains device memory: x, y, raw weights,
+ *     packed and workspace are owned by the caller.  The plan is host memory owned by the library until
+ *     ogc_mlp_destroy.
+ *   - ogc_mlp_prepack_weights and ogc_mlp_run only enqueue work on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and return without synchronising.
+ *   - Errors are return codes; nothing throws or aborts across this boundary.  Every argument check
+ *     happens before the first launch, so a call that returns an argument error has touched nothing.
+ *   - A plan may be used from several host threads; concurrent ogc_mlp_run calls on different streams
+ *     need distinct workspace buffers.
+ */
+#ifndef OGC_MLP_H
+#define OGC_MLP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OGC_OK = 0,
+    OGC_ERR_INVALID_ARG = -1,   /* NULL where a pointer is required, bad enum value, bad quant parameter */
+    OGC_ERR_UNSUPPORTED = -2,   /* legal description the kernels do not cover (see ogc_mlp_plan) */
+    OGC_ERR_SHAPE = -3,         /* non-positive or inconsistent dimensions */
+    OGC_ERR_ALIGNMENT = -4,     /* packed / workspace pointer not 256-byte aligned, x / y not element aligned */
+    OGC_ERR_WORKSPACE = -5,     /* workspace is NULL although ogc_mlp_workspace_bytes() > 0 */
+    OGC_ERR_NOT_PREPACKED = -6, /* ogc_mlp_run before any ogc_mlp_prepack_weights on this plan */
+    OGC_ERR_DEVICE = -7         /* the HIP runtime reported an error at launch */
+} ogc_status;
+
+typedef enum { OGC_F32 = 0, OGC_BF16 = 1, OGC_I8 = 2 } ogc_dtype; /* OGC_I8: u8 activations x s8 weights */
+typedef enum { OGC_ACT_NONE = 0, OGC_ACT_RELU = 1, OGC_ACT_GELU_TANH = 2, OGC_ACT_SIGMOID = 3 } ogc_act;
+typedef enum { OGC_OUT_SAME = 0, OGC_OUT_F32 = 1 } ogc_out_kind;
+typedef enum { OGC_MODE_AUTO = 0, OGC_MODE_PER_LAYER = 1, OGC_MODE_FUSED = 2 } ogc_mode;
+
+/* One layer: [M,k] x [k,n] -> [M,n].
+ * Post-ops, in this order (fine-grain fusion of the matmul's successors, Section V):
+ *   float dtypes: y = acc + bias[n]; y = act(y); last layer with residual: y += x0[m,n]; round to dtype.
+ *   OGC_I8 (low-precision conversion + compensated weight, Section V; scheme of Section VII):
+ *       acc2 = sum_k x_q*w_q - in_zp*sum_k w_q   (int32, exact)
+ *       y    = fma((float)acc2, in_scale*w_scale[n], bias[n])      (no bias: plain product)
+ *       y    = act(y)
+ *       out == OGC_OUT_F32: store y as fp32 (last layer only);
+ *       else q = clamp(rne(y * (1.0f/out_scale)) + out_zp, 0, 255) stored as u8.
+ * For OGC_I8 the caller sets in_scale/in_zp of layer l+1 equal to out_scale/out_zp of layer l. */
+typedef struct {
+    int32_t k, n;          /* > 0; k of layer l+1 must equal n of layer l; OGC_I8: k <= 65536 */
+    int32_t has_bias;      /* 0 or 1; bias is fp32[n] for every dtype */
+    int32_t act;           /* ogc_act */
+    float in_scale;        /* OGC_I8: a_s > 0, finite.  Ignored otherwise */
+    int32_t in_zp;         /* OGC_I8: a_z in [0,255] */
+    float out_scale;       /* OGC_I8 with OGC_OUT_SAME: c_s > 0, finite */
+    int32_t out_zp;        /* OGC_I8 with OGC_OUT_SAME: c_z in [0,255] */
+    int32_t out;           /* ogc_out_kind; OGC_OUT_F32 only for OGC_I8 and only on the last layer */
+} ogc_layer_desc;
+
+typedef struct {
+    int32_t dtype;                 /* ogc_dtype */
+    int32_t m;                     /* batch rows, > 0 */
+    int32_t n_layers;              /* 1..16 */
+    const ogc_layer_desc* layers;  /* host, n_layers entries; copied by ogc_mlp_plan */
+    int32_t ld_x, ld_y;            /* row strides of x and y in elements; ld_x >= k0, ld_y >= n_last */
+    int32_t residual;              /* 1: last layer adds x (float dtypes only; requires n_last == k0) */
+    int32_t mode;                  /* ogc_mode */
+} ogc_mlp_desc;
+
+typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
+
+/* Makes a plan from a static description: validates it, chooses between the fused-chain kernel (one
+ * workgroup keeps its batch tile's activations in LDS across all layers: coarse-grain fusion, Section V)
+ * and per-layer kernels with workspace buffer reuse (Section VI), picks tile shapes (the role of the
+ * template-parameter heuristic, Section III) and lays out the packed blob and the workspace.
+ * Host only: no device call is made.  *out_plan is written only on OGC_OK.
+ * OGC_ERR_UNSUPPORTED: OGC_MODE_FUSED requested but a layer is too wide for the LDS activation tile. */
+ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc /*host*/, ogc_mlp_plan_t* out_plan /*host*/);
+
+/* Size of the packed-weights blob (blocked weights + per-channel parameters of every layer). */
+ogc_status ogc_mlp_packed_bytes(ogc_mlp_plan_t plan, size_t* bytes /*host*/);
+
+/* Size of the workspace ogc_mlp_run needs (0 for the fused-chain kernel).  Per-layer mode: the
+ * intermediate activations share slots assigned by life span; a chain needs two. */
+ogc_status ogc_mlp_workspace_bytes(ogc_mlp_plan_t plan, size_t* bytes /*host*/);
+
+/* Which kernel family the plan chose: *mode is OGC_MODE_PER_LAYER or OGC_MODE_FUSED. */
+ogc_status ogc_mlp_chosen_mode(ogc_mlp_plan_t plan, int32_t* mode /*host*/);
+
+/* Buffer-reuse result for layer `layer`'s output (Section VI, memory buffer optimisation): *slot is the
+ * workspace slot index (-1 = the caller's y, or LDS in fused mode), *offset its byte offset in workspace. */
+ogc_status ogc_mlp_buffer_assignment(ogc_mlp_plan_t plan, int32_t layer, int32_t* slot /*host*/, size_t* offset /*host*/);
+
+/* Constant-weight preprocessing (Section V): reorders every layer's plain [k,n] weights into the blocked
+ * MFMA operand layout (zero padded) and precomputes everything that depends only on constants: for
+ * OGC_I8 the per-channel combined scale in_scale*w_scale[n] and the zero-point compensation from the
+ * column sums of w_q; bias is copied (zero padded).  Call once per weight set; raw weights may be
+ * released once the stream has passed this call.
+ *   w       host array of n_layers dev pointers: fp32 / bf16 / s8 weights, plain [k,n] row-major, contiguous
+ *   bias    host array of n_layers dev pointers to fp32[n] (entry may be NULL where has_bias == 0);
+ *           the array itself may be NULL if no layer has a bias
+ *   w_scale OGC_I8: host array of n_layers dev pointers to fp32[n] (> 0); otherwise NULL
+ *   packed  dev, ogc_mlp_packed_bytes() bytes, 256-byte aligned; fully overwritten */
+ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, const float* const* bias,
+                                   const float* const* w_scale, void* packed, void* stream);
+
+/* Runs the chain: x[m, k0] (row stride ld_x) -> y[m, n_last] (row stride ld_y), both dev, plain row-major,
+ * element type of the plan's dtype (u8 for OGC_I8; fp32 y if the last layer has OGC_OUT_F32).
+ * x and y must not overlap.  packed is the blob written by ogc_mlp_prepack_weights for this plan;
+ * workspace is dev, 256-byte aligned, ogc_mlp_workspace_bytes() bytes (may be NULL when that is 0) and
+ * holds no state between calls. */
+ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream);
+
+/* Releases the plan (NULL is ignored). */
+void ogc_mlp_destroy(ogc_mlp_plan_t plan);
+
+/* Static, NUL-terminated description of a status code. */
+const char* ogc_status_string(ogc_status s);
+
+/* Name of the kernel that ogc_mlp_run launches for layer `layer` (fused mode: the same name for every
+ * layer), for matching profiler output.  Returns NULL on a bad argument. */
+const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OGC_MLP_H */

@@ -1,0 +1,215 @@
+"""Thin ctypes binding of libogc_mlp.so (include/ogc_mlp.h): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  PyTorch appears here only as the owner
+of device memory and streams.  There is no CPU fallback: if the shared library is missing, loading
+it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+OGC_F32, OGC_BF16, OGC_I8 = 0, 1, 2
+OGC_ACT_NONE, OGC_ACT_RELU, OGC_ACT_GELU_TANH, OGC_ACT_SIGMOID = 0, 1, 2, 3
+OGC_OUT_SAME, OGC_OUT_F32 = 0, 1
+OGC_MODE_AUTO, OGC_MODE_PER_LAYER, OGC_MODE_FUSED = 0, 1, 2
+OGC_OK = 0
+DTYPES = {"f32": OGC_F32, "bf16": OGC_BF16, "i8": OGC_I8}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libogc_mlp.so")
+
+EXPORTS = [
+    "ogc_mlp_plan", "ogc_mlp_packed_bytes", "ogc_mlp_workspace_bytes", "ogc_mlp_chosen_mode",
+    "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
+    "ogc_status_string", "ogc_mlp_kernel_name",
+]
+
+
+class ogc_layer_desc(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_int32), ("n", ctypes.c_int32), ("has_bias", ctypes.c_int32), ("act", ctypes.c_int32),
+                ("in_scale", ctypes.c_float), ("in_zp", ctypes.c_int32), ("out_scale", ctypes.c_float),
+                ("out_zp", ctypes.c_int32), ("out", ctypes.c_int32)]
+
+
+class ogc_mlp_desc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("m", ctypes.c_int32), ("n_layers", ctypes.c_int32),
+                ("layers", ctypes.POINTER(ogc_layer_desc)), ("ld_x", ctypes.c_int32), ("ld_y", ctypes.c_int32),
+                ("residual", ctypes.c_int32), ("mode", ctypes.c_int32)]
+
+
+class OgcError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (what, status_string(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """Loads the shared library (fails loudly if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s not found: build it with `python -m paper_2301_01333_amd.build` (there is no fallback path)" % LIB_PATH)
+        l = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        l.ogc_mlp_plan.argtypes = [ctypes.POINTER(ogc_mlp_desc), ctypes.POINTER(vp)]
+        l.ogc_mlp_plan.restype = i32
+        l.ogc_mlp_packed_bytes.argtypes = [vp, ctypes.POINTER(sz)]
+        l.ogc_mlp_packed_bytes.restype = i32
+        l.ogc_mlp_workspace_bytes.argtypes = [vp, ctypes.POINTER(sz)]
+        l.ogc_mlp_workspace_bytes.restype = i32
+        l.ogc_mlp_chosen_mode.argtypes = [vp, ctypes.POINTER(i32)]
+        l.ogc_mlp_chosen_mode.restype = i32
+        l.ogc_mlp_buffer_assignment.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(sz)]
+        l.ogc_mlp_buffer_assignment.restype = i32
+        l.ogc_mlp_prepack_weights.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp]
+        l.ogc_mlp_prepack_weights.restype = i32
+        l.ogc_mlp_run.argtypes = [vp, vp, vp, vp, vp, vp]
+        l.ogc_mlp_run.restype = i32
+        l.ogc_mlp_destroy.argtypes = [vp]
+        l.ogc_mlp_destroy.restype = None
+        l.ogc_status_string.argtypes = [i32]
+        l.ogc_status_string.restype = ctypes.c_char_p
+        l.ogc_mlp_kernel_name.argtypes = [vp, i32]
+        l.ogc_mlp_kernel_name.restype = ctypes.c_char_p
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().ogc_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != OGC_OK:
+        raise OgcError(status, what)
+
+
+# ---- one function per entry point, same names ---------------------------------------------------
+def ogc_mlp_plan(dtype: int, m: int, layers: Sequence[dict], ld_x: int, ld_y: int, residual: int = 0, mode: int = 0) -> int:
+    """layers: dicts with k, n, has_bias, act, in_scale, in_zp, out_scale, out_zp, out.  Returns the plan handle."""
+    arr = (ogc_layer_desc * max(len(layers), 1))()
+    for i, ly in enumerate(layers):
+        arr[i] = ogc_layer_desc(int(ly["k"]), int(ly["n"]), int(ly.get("has_bias", 0)), int(ly.get("act", 0)),
+                                float(ly.get("in_scale", 0.0)), int(ly.get("in_zp", 0)), float(ly.get("out_scale", 0.0)),
+                                int(ly.get("out_zp", 0)), int(ly.get("out", 0)))
+    desc = ogc_mlp_desc(int(dtype), int(m), len(layers), arr, int(ld_x), int(ld_y), int(residual), int(mode))
+    handle = ctypes.c_void_p()
+    _check(lib().ogc_mlp_plan(ctypes.byref(desc), ctypes.byref(handle)), "ogc_mlp_plan")
+    return handle.value
+
+
+def ogc_mlp_packed_bytes(plan: int) -> int:
+    v = ctypes.c_size_t()
+    _check(lib().ogc_mlp_packed_bytes(plan, ctypes.byref(v)), "ogc_mlp_packed_bytes")
+    return v.value
+
+
+def ogc_mlp_workspace_bytes(plan: int) -> int:
+    v = ctypes.c_size_t()
+    _check(lib().ogc_mlp_workspace_bytes(plan, ctypes.byref(v)), "ogc_mlp_workspace_bytes")
+    return v.value
+
+
+def ogc_mlp_chosen_mode(plan: int) -> int:
+    v = ctypes.c_int32()
+    _check(lib().ogc_mlp_chosen_mode(plan, ctypes.byref(v)), "ogc_mlp_chosen_mode")
+    return v.value
+
+
+def ogc_mlp_buffer_assignment(plan: int, layer: int):
+    s, o = ctypes.c_int32(), ctypes.c_size_t()
+    _check(lib().ogc_mlp_buffer_assignment(plan, int(layer), ctypes.byref(s), ctypes.byref(o)), "ogc_mlp_buffer_assignment")
+    return s.value, o.value
+
+
+def _ptr_array(ptrs: Optional[Sequence[Optional[int]]], n: int):
+    if ptrs is None:
+        return None
+    arr = (ctypes.c_void_p * max(n, 1))()
+    for i in range(n):
+        arr[i] = ptrs[i] if ptrs[i] else None
+    return arr
+
+
+def ogc_mlp_prepack_weights(plan: int, w_ptrs, bias_ptrs, w_scale_ptrs, packed_ptr: int, stream: int = 0) -> None:
+    n = len(w_ptrs)
+    _check(lib().ogc_mlp_prepack_weights(plan, _ptr_array(w_ptrs, n), _ptr_array(bias_ptrs, n), _ptr_array(w_scale_ptrs, n),
+                                         packed_ptr, stream), "ogc_mlp_prepack_weights")
+
+
+def ogc_mlp_run(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, workspace_ptr: int, stream: int = 0) -> None:
+    _check(lib().ogc_mlp_run(plan, x_ptr, y_ptr, packed_ptr, workspace_ptr or None, stream), "ogc_mlp_run")
+
+
+def ogc_mlp_destroy(plan: int) -> None:
+    lib().ogc_mlp_destroy(plan)
+
+
+def ogc_mlp_kernel_name(plan: int, layer: int) -> str:
+    r = lib().ogc_mlp_kernel_name(plan, int(layer))
+    return r.decode() if r else ""
+
+
+# ---- convenience wrapper: owns the torch tensors the library needs ---------------------------------
+class FusedMLP:
+    """plan + packed blob + workspace for one static MLP chain on the current CUDA/HIP device."""
+
+    def __init__(self, dtype: str, m: int, layers: Sequence, ld_x: Optional[int] = None, ld_y: Optional[int] = None,
+                 residual: bool = False, mode: int = OGC_MODE_AUTO):
+        import torch
+
+        self.torch = torch
+        self.dtype = dtype
+        self.m = m
+        self.layer_dicts = []
+        for ly in layers:
+            d = ly if isinstance(ly, dict) else dict(
+                k=ly.k, n=ly.n, has_bias=int(ly.has_bias), act=ly.act, in_scale=ly.in_scale, in_zp=ly.in_zp,
+                out_scale=ly.out_scale, out_zp=ly.out_zp, out=OGC_OUT_F32 if ly.out_f32 else OGC_OUT_SAME)
+            self.layer_dicts.append(d)
+        self.k0 = self.layer_dicts[0]["k"]
+        self.n_last = self.layer_dicts[-1]["n"]
+        self.ld_x = ld_x or self.k0
+        self.ld_y = ld_y or self.n_last
+        self.out_f32 = self.layer_dicts[-1].get("out", 0) == OGC_OUT_F32
+        self.plan = ogc_mlp_plan(DTYPES[dtype], m, self.layer_dicts, self.ld_x, self.ld_y, int(residual), mode)
+        self.mode = ogc_mlp_chosen_mode(self.plan)
+        self.packed_bytes = ogc_mlp_packed_bytes(self.plan)
+        self.workspace_bytes = ogc_mlp_workspace_bytes(self.plan)
+        self.packed = None
+        self.workspace = None
+
+    def close(self):
+        if getattr(self, "plan", None):
+            ogc_mlp_destroy(self.plan)
+            self.plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _stream(self) -> int:
+        return int(self.torch.cuda.current_stream().cuda_stream)
+
+    def prepack(self, w: List, bias: Optional[List] = None, w_scale: Optional[List] = None) -> None:
+        """w / bias / w_scale: lists of device tensors (bias and w_scale entries may be None)."""
+        torch = self.torch
+        dev = w[0].device
+        self.packed = torch.empty(max(self.packed_bytes, 256), dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(max(self.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+        wp = [t.data_ptr() for t in w]
+        bp = None if bias is None else [None if t is None else t.data_ptr() for t in bias]
+        sp = None if w_scale is None else [None if t is None else t.data_ptr() for t in w_scale]
+        ogc_mlp_prepack_weights(self.plan, wp, bp, sp, self.packed.data_ptr(), self._stream())
+
+    def run(self, x, y) -> None:
+        ogc_mlp_run(self.plan, x.data_ptr(), y.data_ptr(), self.packed.data_ptr(),
+                    self.workspace.data_ptr() if self.workspace_bytes else 0, self._stream())

@@ -1,0 +1,376 @@
+// Host side of the fused-MLP library: plan construction (validation, kernel-family and tile choice,
+// packed-blob and workspace layout, buffer reuse) and the C ABI declared in include/ogc_mlp.h.
+// No device memory is allocated here and no device call is made outside prepack / run.
+#include <atomic>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ogc_internal.h"
+
+namespace {
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct LayerPlan {
+    ogc_layer_desc d;
+    int kp;           // padded K (elements) of this layer's input
+    int kc;           // 16-byte chunks per input row
+    int npw;          // padded rows of the packed weights
+    int nb_out;       // 32-channel blocks written to a KB16 output (0 for the last layer)
+    int kc_out;       // chunks per row of the KB16 output
+    int tile;         // per-layer mode: tile configuration
+    size_t w_off, scale_off, bias_off, ncomp_off;  // offsets in the packed blob
+    int out_slot;     // workspace slot of the output (-1: caller's y / LDS)
+    size_t out_off;   // byte offset of that slot in the workspace
+    float inv_cs;
+};
+
+}  // namespace
+
+struct ogc_mlp_plan_s {
+    ogc_mlp_desc desc;
+    std::vector<LayerPlan> layers;
+    int esz;
+    int mode;  // OGC_MODE_PER_LAYER or OGC_MODE_FUSED
+    int mp;    // padded batch rows of the workspace buffers
+    size_t packed_bytes, workspace_bytes;
+    int lds_buf_bytes;  // fused mode
+    std::vector<size_t> slot_off, slot_size;
+    std::atomic<int> prepacked;
+};
+
+namespace {
+
+// Memory-buffer reuse across the chain (Section VI): life-span analysis over the topologically ordered
+// fused ops; an intermediate buffer is reclaimable once its single consumer has run; among the free
+// buffers the most recently used one is taken (its lines are the likeliest to still be in cache).
+void assign_buffers(ogc_mlp_plan_s* p) {
+    const int L = (int)p->layers.size();
+    struct Slot { size_t size; int last_use; int busy_until; };
+    std::vector<Slot> slots;
+    for (int l = 0; l < L; ++l) p->layers[l].out_slot = -1;
+    for (int l = 0; l + 1 < L; ++l) {
+        const size_t need = (size_t)p->mp * p->layers[l + 1].kc * 16;
+        // tensor l is produced by step l and consumed by step l+1: its buffer is busy through step l+1.
+        int best = -1;
+        for (int s = 0; s < (int)slots.size(); ++s)
+            if (slots[s].busy_until < l && (best < 0 || slots[s].last_use > slots[best].last_use)) best = s;
+        if (best < 0) {
+            slots.push_back({0, -1, -1});
+            best = (int)slots.size() - 1;
+        }
+        if (slots[best].size < need) slots[best].size = need;
+        slots[best].busy_until = l + 1;
+        slots[best].last_use = l + 1;
+        p->layers[l].out_slot = best;
+    }
+    size_t off = 0;
+    p->slot_off.clear();
+    p->slot_size.clear();
+    for (auto& s : slots) {
+        p->slot_off.push_back(off);
+        p->slot_size.push_back(s.size);
+        off += round_up(s.size, 256);
+    }
+    p->workspace_bytes = off;
+    for (int l = 0; l + 1 < L; ++l) p->layers[l].out_off = p->slot_off[p->layers[l].out_slot];
+}
+
+int env_int(const char* name, int dflt) {
+    const char* v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : dflt;
+}
+
+// Tile choice for a per-layer launch (the role of the template-parameter heuristic of Section III:
+// balance the number of workgroups against the 256 CUs, prefer the largest tile for operand reuse).
+int choose_tile(int m, int n) {
+    const int forced = env_int("OGC_TILE", -1);
+    if (forced >= 0 && forced < OGC_NUM_TILES) return forced;
+    for (int t = 0; t < OGC_NUM_TILES; ++t) {
+        const OgcTileInfo ti = ogc_tile_info(t);
+        const long tiles = (long)((m + ti.bm - 1) / ti.bm) * ((n + ti.bn - 1) / ti.bn);
+        if (tiles >= 256 || t == OGC_NUM_TILES - 1) return t;
+    }
+    return OGC_TILE_SMALL;
+}
+
+ogc_status validate(const ogc_mlp_desc* d) {
+    if (!d || !d->layers) return OGC_ERR_INVALID_ARG;
+    if (d->dtype != OGC_F32 && d->dtype != OGC_BF16 && d->dtype != OGC_I8) return OGC_ERR_INVALID_ARG;
+    if (d->mode != OGC_MODE_AUTO && d->mode != OGC_MODE_PER_LAYER && d->mode != OGC_MODE_FUSED) return OGC_ERR_INVALID_ARG;
+    if (d->n_layers < 1 || d->n_layers > OGC_MAX_LAYERS) return OGC_ERR_SHAPE;
+    if (d->m < 1) return OGC_ERR_SHAPE;
+    if (d->residual != 0 && d->residual != 1) return OGC_ERR_INVALID_ARG;
+    for (int l = 0; l < d->n_layers; ++l) {
+        const ogc_layer_desc& y = d->layers[l];
+        if (y.k < 1 || y.n < 1) return OGC_ERR_SHAPE;
+        if (l > 0 && y.k != d->layers[l - 1].n) return OGC_ERR_SHAPE;
+        if (y.has_bias != 0 && y.has_bias != 1) return OGC_ERR_INVALID_ARG;
+        if (y.act < OGC_ACT_NONE || y.act > OGC_ACT_SIGMOID) return OGC_ERR_INVALID_ARG;
+        if (y.out != OGC_OUT_SAME && y.out != OGC_OUT_F32) return OGC_ERR_INVALID_ARG;
+        if (y.out == OGC_OUT_F32 && (d->dtype != OGC_I8 || l != d->n_layers - 1)) return OGC_ERR_INVALID_ARG;
+        if (d->dtype == OGC_I8) {
+            if (y.k > 65536) return OGC_ERR_SHAPE;
+            if (!(y.in_scale > 0.0f) || !std::isfinite(y.in_scale)) return OGC_ERR_INVALID_ARG;
+            if (y.in_zp < 0 || y.in_zp > 255) return OGC_ERR_INVALID_ARG;
+            if (y.out == OGC_OUT_SAME) {
+                if (!(y.out_scale > 0.0f) || !std::isfinite(y.out_scale)) return OGC_ERR_INVALID_ARG;
+                if (y.out_zp < 0 || y.out_zp > 255) return OGC_ERR_INVALID_ARG;
+            }
+        }
+    }
+    const int k0 = d->layers[0].k, nl = d->layers[d->n_layers - 1].n;
+    if (d->ld_x < k0 || d->ld_y < nl) return OGC_ERR_SHAPE;
+    if (d->residual) {
+        if (d->dtype == OGC_I8) return OGC_ERR_INVALID_ARG;
+        if (nl != k0) return OGC_ERR_SHAPE;
+    }
+    return OGC_OK;
+}
+
+void fill_args(const ogc_mlp_plan_s* p, int l, const uint8_t* packed, OgcLayerArgs* a) {
+    const LayerPlan& lp = p->layers[l];
+    std::memset(a, 0, sizeof(*a));
+    a->w = packed + lp.w_off;
+    a->scale = (const float*)(packed + lp.scale_off);
+    a->bias = (const float*)(packed + lp.bias_off);
+    a->ncomp = (const int32_t*)(packed + lp.ncomp_off);
+    a->M = p->desc.m;
+    a->K = lp.d.k;
+    a->N = lp.d.n;
+    a->KC = lp.kc;
+    a->KC_out = lp.kc_out;
+    a->NB_out = lp.nb_out;
+    a->act = lp.d.act;
+    a->has_comp = (p->desc.dtype == OGC_I8 && lp.d.in_zp != 128) ? 1 : 0;
+    a->out_f32 = (lp.d.out == OGC_OUT_F32) ? 1 : 0;
+    a->inv_cs = lp.inv_cs;
+    a->zp_out = (float)lp.d.out_zp;
+}
+
+}  // namespace
+
+extern "C" {
+
+ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
+    if (!out_plan) return OGC_ERR_INVALID_ARG;
+    ogc_status st = validate(desc);
+    if (st != OGC_OK) return st;
+    ogc_mlp_plan_s* p = new (std::nothrow) ogc_mlp_plan_s();
+    if (!p) return OGC_ERR_INVALID_ARG;
+    p->desc = *desc;
+    p->desc.layers = nullptr;
+    p->prepacked.store(0);
+    const int L = desc->n_layers;
+    const int esz = desc->dtype == OGC_F32 ? 4 : (desc->dtype == OGC_BF16 ? 2 : 1);
+    p->esz = esz;
+    const int kgran = desc->dtype == OGC_I8 ? 64 : 32;  // padded K granularity in elements (>= 64 bytes)
+    p->layers.resize(L);
+    int max_kc = 0;
+    for (int l = 0; l < L; ++l) {
+        LayerPlan& lp = p->layers[l];
+        lp.d = desc->layers[l];
+        lp.kp = (int)round_up((size_t)lp.d.k, kgran);
+        lp.kc = lp.kp * esz / 16;
+        if (lp.kc > max_kc) max_kc = lp.kc;
+        lp.inv_cs = (desc->dtype == OGC_I8 && lp.d.out == OGC_OUT_SAME) ? 1.0f / lp.d.out_scale : 0.0f;
+    }
+    for (int l = 0; l < L; ++l) {
+        LayerPlan& lp = p->layers[l];
+        if (l + 1 < L) {
+            lp.nb_out = p->layers[l + 1].kp / 32;
+            lp.kc_out = p->layers[l + 1].kc;
+        } else {
+            lp.nb_out = 0;
+            lp.kc_out = 0;
+        }
+    }
+    // Kernel family.  The fused-chain kernel needs two LDS activation buffers of 32 rows x widest padded row.
+    const size_t lds_need = (size_t)2 * max_kc * 512;
+    const bool fused_fits = lds_need <= ogc_fused_lds_limit();
+    size_t wbytes = 0;
+    for (int l = 0; l < L; ++l) wbytes += (size_t)p->layers[l].kp * esz * p->layers[l].d.n;
+    int mode = desc->mode;
+    if (mode == OGC_MODE_FUSED && !fused_fits) {
+        delete p;
+        return OGC_ERR_UNSUPPORTED;
+    }
+    if (mode == OGC_MODE_AUTO) {
+        // Every 32-row workgroup of the fused kernel streams all weights once: worth it while the batch is
+        // small (few workgroups, launch-latency bound) or the weights are small enough to sit in L2.
+        mode = (fused_fits && (desc->m <= 512 || wbytes <= (size_t)512 * 1024)) ? OGC_MODE_FUSED : OGC_MODE_PER_LAYER;
+    }
+    p->mode = mode;
+    p->lds_buf_bytes = max_kc * 512;
+    p->mp = (int)round_up((size_t)desc->m, 256);
+    // Packed blob layout.
+    size_t off = 0;
+    for (int l = 0; l < L; ++l) {
+        LayerPlan& lp = p->layers[l];
+        const int rows = lp.nb_out * 32 > lp.d.n ? lp.nb_out * 32 : lp.d.n;
+        if (mode == OGC_MODE_PER_LAYER) {
+            lp.tile = choose_tile(desc->m, rows);
+            lp.npw = (int)round_up((size_t)rows, ogc_tile_info(lp.tile).bn);
+        } else {
+            lp.tile = -1;
+            lp.npw = (int)round_up((size_t)rows, 32);
+        }
+        lp.w_off = off;
+        off += round_up((size_t)lp.npw * lp.kc * 16, 256);
+        lp.scale_off = off;
+        off += round_up((size_t)lp.npw * 4, 256);
+        lp.bias_off = off;
+        off += round_up((size_t)lp.npw * 4, 256);
+        lp.ncomp_off = off;
+        off += round_up((size_t)lp.npw * 4, 256);
+    }
+    p->packed_bytes = off;
+    if (mode == OGC_MODE_PER_LAYER) {
+        assign_buffers(p);
+    } else {
+        for (int l = 0; l < L; ++l) {
+            p->layers[l].out_slot = -1;
+            p->layers[l].out_off = 0;
+        }
+        p->workspace_bytes = 0;
+    }
+    *out_plan = p;
+    return OGC_OK;
+}
+
+ogc_status ogc_mlp_packed_bytes(ogc_mlp_plan_t plan, size_t* bytes) {
+    if (!plan || !bytes) return OGC_ERR_INVALID_ARG;
+    *bytes = plan->packed_bytes;
+    return OGC_OK;
+}
+
+ogc_status ogc_mlp_workspace_bytes(ogc_mlp_plan_t plan, size_t* bytes) {
+    if (!plan || !bytes) return OGC_ERR_INVALID_ARG;
+    *bytes = plan->workspace_bytes;
+    return OGC_OK;
+}
+
+ogc_status ogc_mlp_chosen_mode(ogc_mlp_plan_t plan, int32_t* mode) {
+    if (!plan || !mode) return OGC_ERR_INVALID_ARG;
+    *mode = plan->mode;
+    return OGC_OK;
+}
+
+ogc_status ogc_mlp_buffer_assignment(ogc_mlp_plan_t plan, int32_t layer, int32_t* slot, size_t* offset) {
+    if (!plan || !slot || !offset) return OGC_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= (int)plan->layers.size()) return OGC_ERR_INVALID_ARG;
+    *slot = plan->layers[layer].out_slot;
+    *offset = plan->layers[layer].out_off;
+    return OGC_OK;
+}
+
+ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, const float* const* bias,
+                                   const float* const* w_scale, void* packed, void* stream) {
+    if (!plan || !w || !packed) return OGC_ERR_INVALID_ARG;
+    if (((uintptr_t)packed & 255) != 0) return OGC_ERR_ALIGNMENT;
+    const int L = (int)plan->layers.size();
+    const bool i8 = plan->desc.dtype == OGC_I8;
+    if (i8 && !w_scale) return OGC_ERR_INVALID_ARG;
+    for (int l = 0; l < L; ++l) {
+        if (!w[l]) return OGC_ERR_INVALID_ARG;
+        if (plan->layers[l].d.has_bias && (!bias || !bias[l])) return OGC_ERR_INVALID_ARG;
+        if (i8 && !w_scale[l]) return OGC_ERR_INVALID_ARG;
+    }
+    uint8_t* blob = (uint8_t*)packed;
+    for (int l = 0; l < L; ++l) {
+        const LayerPlan& lp = plan->layers[l];
+        int rc = ogc_launch_prepack_weights(w[l], blob + lp.w_off, lp.d.k, lp.d.n, lp.kc, lp.npw, plan->esz, stream);
+        if (rc != 0) return OGC_ERR_DEVICE;
+        rc = ogc_launch_prepack_params(plan->desc.dtype, w[l], i8 ? w_scale[l] : nullptr, lp.d.has_bias ? bias[l] : nullptr,
+                                       lp.d.in_scale, lp.d.in_zp, lp.d.k, lp.d.n, lp.npw, (float*)(blob + lp.scale_off),
+                                       (float*)(blob + lp.bias_off), (int32_t*)(blob + lp.ncomp_off), stream);
+        if (rc != 0) return OGC_ERR_DEVICE;
+    }
+    plan->prepacked.store(1);
+    return OGC_OK;
+}
+
+ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream) {
+    if (!plan || !x || !y || !packed) return OGC_ERR_INVALID_ARG;
+    if (!plan->prepacked.load()) return OGC_ERR_NOT_PREPACKED;
+    if (((uintptr_t)packed & 255) != 0) return OGC_ERR_ALIGNMENT;
+    const int esz = plan->esz;
+    const int L = (int)plan->layers.size();
+    const LayerPlan& last = plan->layers[L - 1];
+    const int eo = (last.d.out == OGC_OUT_F32) ? 4 : esz;
+    if (((uintptr_t)x % esz) != 0 || ((uintptr_t)y % eo) != 0) return OGC_ERR_ALIGNMENT;
+    if (plan->workspace_bytes > 0) {
+        if (!workspace) return OGC_ERR_WORKSPACE;
+        if (((uintptr_t)workspace & 255) != 0) return OGC_ERR_ALIGNMENT;
+    }
+    const uint8_t* blob = (const uint8_t*)packed;
+    const long long ldx_b = (long long)plan->desc.ld_x * esz, ldy_b = (long long)plan->desc.ld_y * eo;
+    const int x_vec = ((uintptr_t)x % 16 == 0) && (ldx_b % 16 == 0) && (((long long)plan->layers[0].d.k * esz) % 16 == 0);
+    const int y_vec = ((uintptr_t)y % 16 == 0) && (ldy_b % 16 == 0);
+
+    auto finish_args = [&](int l, OgcLayerArgs* a) {
+        fill_args(plan, l, blob, a);
+        if (l == 0) {
+            a->x = (const uint8_t*)x;
+            a->ldx_bytes = ldx_b;
+            a->x_vec_ok = x_vec;
+        }
+        if (l == L - 1) {
+            a->y = (uint8_t*)y;
+            a->ldy_bytes = ldy_b;
+            a->y_vec_ok = y_vec;
+            if (plan->desc.residual) {
+                a->res = (const uint8_t*)x;
+                a->ldres_bytes = ldx_b;
+            }
+        }
+    };
+
+    if (plan->mode == OGC_MODE_FUSED) {
+        OgcChainArgs c;
+        std::memset(&c, 0, sizeof(c));
+        c.n_layers = L;
+        c.lds_buf_bytes = plan->lds_buf_bytes;
+        for (int l = 0; l < L; ++l) finish_args(l, &c.layer[l]);
+        const int rc = ogc_launch_fused(plan->desc.dtype, &c, (plan->desc.m + 31) / 32, stream);
+        return rc == 0 ? OGC_OK : OGC_ERR_DEVICE;
+    }
+    uint8_t* ws = (uint8_t*)workspace;
+    for (int l = 0; l < L; ++l) {
+        OgcLayerArgs a;
+        finish_args(l, &a);
+        if (l > 0) a.x = ws + plan->layers[l - 1].out_off;
+        if (l < L - 1) a.y = ws + plan->layers[l].out_off;
+        const int rc = ogc_launch_layer(plan->desc.dtype, plan->layers[l].tile, l == 0, l == L - 1, &a, stream);
+        if (rc != 0) return OGC_ERR_DEVICE;
+    }
+    return OGC_OK;
+}
+
+void ogc_mlp_destroy(ogc_mlp_plan_t plan) { delete plan; }
+
+const char* ogc_status_string(ogc_status s) {
+    switch (s) {
+    case OGC_OK: return "ok";
+    case OGC_ERR_INVALID_ARG: return "invalid argument";
+    case OGC_ERR_UNSUPPORTED: return "unsupported configuration";
+    case OGC_ERR_SHAPE: return "bad or inconsistent shape";
+    case OGC_ERR_ALIGNMENT: return "misaligned pointer";
+    case OGC_ERR_WORKSPACE: return "workspace missing";
+    case OGC_ERR_NOT_PREPACKED: return "weights not prepacked";
+    case OGC_ERR_DEVICE: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer) {
+    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return nullptr;
+    if (plan->mode == OGC_MODE_FUSED) return ogc_fused_kernel_name(plan->desc.dtype);
+    const int L = (int)plan->layers.size();
+    return ogc_layer_kernel_name(plan->desc.dtype, plan->layers[layer].tile, layer == 0, layer == L - 1);
+}
+
+}  // extern "C"

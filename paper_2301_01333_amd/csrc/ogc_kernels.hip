@@ -1,0 +1,605 @@
+// gfx950 (MI355X, CDNA4) kernels of the fused-MLP library: weight prepack, per-layer GEMM + register
+// epilogue, and the fused multi-layer chain kernel.  Wave64, 32x32 MFMA tiles, LDS staging.
+//
+// Orientation.  Every kernel computes the TRANSPOSED product tile D[n][m] = sum_k W[n][k] X[m][k]: the
+// packed weights are the first MFMA operand (rows = output channel n) and the activations the second
+// (columns = batch row m).  In the 32x32 MFMA result layout a lane then owns one batch row (m = lane%32)
+// and 16 output channels in four runs of four (n = 8*g + 4*(lane/32) + e for register 4*g+e), so the
+// per-channel post-ops read their parameters as float4 and the outputs of one row are packed along n,
+// which is contiguous both in the plain row-major result and in the next layer's operand layout.
+#include <hip/hip_runtime.h>
+
+#include "ogc_internal.h"
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+#define OGC_DEV static __device__ __forceinline__
+
+template <int DT> struct AccT { typedef v16f type; };
+template <> struct AccT<OGC_I8> { typedef v16i type; };
+
+template <int DT> struct Elt { enum { size = DT == OGC_F32 ? 4 : (DT == OGC_BF16 ? 2 : 1) }; };
+
+// One 32(n) x 32(m) x 32-byte-of-K MFMA step (GEMM main loop; the role of the batch-reduce GEMM
+// microkernel of Section III).  w and x are the lane's 16 bytes of the two operands.
+template <int DT> OGC_DEV void mma32(typename AccT<DT>::type& c, const v4i& w, const v4i& x) {
+    if constexpr (DT == OGC_I8) {
+        c = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, c, 0, 0, 0);
+    } else if constexpr (DT == OGC_BF16) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, w), __builtin_bit_cast(v8bf, x), c, 0, 0, 0);
+    } else {
+        const v4f wf = __builtin_bit_cast(v4f, w), xf = __builtin_bit_cast(v4f, x);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(wf.x, xf.x, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(wf.y, xf.y, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(wf.z, xf.z, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(wf.w, xf.w, c, 0, 0, 0);
+    }
+}
+
+OGC_DEV uint32_t f32_to_bf16_rne(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+OGC_DEV float bf16_to_f32(uint32_t h) { return __builtin_bit_cast(float, h << 16); }
+
+// Exchange between the two half-waves: afterwards a = {a.lo, b.lo}, b = {a.hi, b.hi} (lo = lanes 0..31).
+OGC_DEV void swap32(uint32_t& a, uint32_t& b) {
+    auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+    a = r[0];
+    b = r[1];
+}
+
+// ------------------------------------------------------------------------------------------------
+// Epilogue (post-op anchor #1 of the fused-op template, Section IV: the post-ops run on the accumulator
+// tile while it is still in registers).  Turns one 32x32 accumulator block into 16 fp32 values per lane.
+//   float dtypes: y = act(acc + bias[n])
+//   I8: y = act(fma((float)(acc + ncomp[n]), scale[n], bias[n])); unless out_f32:
+//       out = min(max(rne(y * inv_cs) + zp_out, 0), 255)      (an integer-valued float)
+// ------------------------------------------------------------------------------------------------
+OGC_DEV float act_apply(float y, int act) {
+    if (act == OGC_ACT_RELU) return (y > 0.0f) ? y : 0.0f;
+    if (act == OGC_ACT_GELU_TANH) {
+        // 0.5*y*(1+tanh(u)) == y / (1 + exp(-2u)),  u = sqrt(2/pi)*(y + 0.044715*y^3)
+        float u = 0.7978845608028654f * (y + 0.044715f * y * y * y);
+        return __fdividef(y, 1.0f + __expf(-2.0f * u));
+    }
+    if (act == OGC_ACT_SIGMOID) return 1.0f / (1.0f + expf(-y));
+    return y;
+}
+
+template <int DT>
+OGC_DEV void epilogue_values(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, int n0, int h, float (&out)[16]) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int n = n0 + 8 * g + 4 * h;
+        const v4f b4 = *(const v4f*)(a.bias + n);
+        if constexpr (DT == OGC_I8) {
+            const v4f s4 = *(const v4f*)(a.scale + n);
+            v4i c4 = {0, 0, 0, 0};
+            if (a.has_comp) c4 = *(const v4i*)(a.ncomp + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float f = (float)(acc[4 * g + e] + c4[e]);
+                out[4 * g + e] = __builtin_fmaf(f, s4[e], b4[e]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[4 * g + e] = acc[4 * g + e] + b4[e];
+        }
+    }
+    const int act = a.act;
+    if (act != OGC_ACT_NONE) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) out[i] = act_apply(out[i], act);
+    }
+    if constexpr (DT == OGC_I8) {
+        if (!a.out_f32) {
+            const float inv = a.inv_cs, zp = a.zp_out;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float r = __builtin_rintf(out[i] * inv);
+                r = r + zp;
+                out[i] = __builtin_fminf(__builtin_fmaxf(r, 0.0f), 255.0f);
+            }
+        }
+    }
+}
+
+// Converts the 16 values of a lane to the stored type, exchanges quads between the half-waves so that
+// each lane holds 16 CONSECUTIVE channels (n0 + 16*(lane/32) ...), and returns them as NDW 16-byte chunks.
+//   EO = bytes per stored element (1: u8/s8, 2: bf16, 4: fp32); NDW == EO.
+//   bias_s8: store u8 values with 128 subtracted (internal activation form).
+template <int EO>
+OGC_DEV void pack_block(const float (&out)[16], bool bias_s8, v4i (&chunk)[EO]) {
+    uint32_t dw[4][EO];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        if constexpr (EO == 1) {
+            uint32_t p = (uint32_t)out[4 * g] | ((uint32_t)out[4 * g + 1] << 8) | ((uint32_t)out[4 * g + 2] << 16) |
+                         ((uint32_t)out[4 * g + 3] << 24);
+            dw[g][0] = bias_s8 ? (p ^ 0x80808080u) : p;
+        } else if constexpr (EO == 2) {
+            dw[g][0] = f32_to_bf16_rne(out[4 * g]) | (f32_to_bf16_rne(out[4 * g + 1]) << 16);
+            dw[g][1] = f32_to_bf16_rne(out[4 * g + 2]) | (f32_to_bf16_rne(out[4 * g + 3]) << 16);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dw[g][e] = __builtin_bit_cast(uint32_t, out[4 * g + e]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < EO; ++j) {
+        swap32(dw[0][j], dw[2][j]);
+        swap32(dw[1][j], dw[3][j]);
+    }
+    // lane order after the exchange: quads [0],[2],[1],[3]
+    uint32_t seq[4 * EO];
+    const int order[4] = {0, 2, 1, 3};
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int j = 0; j < EO; ++j) seq[q * EO + j] = dw[order[q]][j];
+#pragma unroll
+    for (int c = 0; c < EO; ++c) chunk[c] = (v4i){(int)seq[4 * c], (int)seq[4 * c + 1], (int)seq[4 * c + 2], (int)seq[4 * c + 3]};
+}
+
+// Adds the residual x0[m, n0+16h .. +15] (plain row-major, same dtype) to the lane's 16 values.  The
+// exchange has not happened yet, so the values are still in register order: out[4g+e] <-> n0+8g+4h+e.
+template <int DT>
+OGC_DEV void add_residual(float (&out)[16], const OgcLayerArgs& a, int m, int n0, int h) {
+    if (m >= a.M) return;
+    const uint8_t* row = a.res + (long long)m * a.ldres_bytes;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int n = n0 + 8 * g + 4 * h;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (n + e < a.N) {
+                if constexpr (DT == OGC_F32) out[4 * g + e] = out[4 * g + e] + *(const float*)(row + (size_t)(n + e) * 4);
+                if constexpr (DT == OGC_BF16) out[4 * g + e] = out[4 * g + e] + bf16_to_f32(*(const uint16_t*)(row + (size_t)(n + e) * 2));
+            }
+        }
+    }
+}
+
+// Final store of a block to the caller's plain row-major y (post-op reorder to the plain layout at the
+// graph boundary, Sections IV-V).  The lane holds channels nl .. nl+15 of row m as EO chunks.
+template <int EO>
+OGC_DEV void store_plain(const v4i (&chunk)[EO], const OgcLayerArgs& a, int m, int nl) {
+    if (m >= a.M || nl >= a.N) return;
+    uint8_t* p = a.y + (long long)m * a.ldy_bytes + (size_t)nl * EO;
+    if (a.y_vec_ok && nl + 16 <= a.N) {
+#pragma unroll
+        for (int c = 0; c < EO; ++c) *(v4i*)(p + 16 * c) = chunk[c];
+    } else {
+        const int cnt = (a.N - nl < 16) ? (a.N - nl) : 16;
+#pragma unroll
+        for (int c = 0; c < EO; ++c) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const uint32_t v = (uint32_t)chunk[c][d];
+                if constexpr (EO == 1) {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        if (c * 16 + d * 4 + b < cnt) p[c * 16 + d * 4 + b] = (uint8_t)(v >> (8 * b));
+                } else if constexpr (EO == 2) {
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        if (c * 8 + d * 2 + b < cnt) ((uint16_t*)p)[c * 8 + d * 2 + b] = (uint16_t)(v >> (16 * b));
+                } else {
+                    if (c * 4 + d < cnt) ((uint32_t*)p)[c * 4 + d] = v;
+                }
+            }
+        }
+    }
+}
+
+// Complete epilogue of one 32x32 block.  OUT_PLAIN = 0: write the block into a KB16 activation buffer at
+// `yblk` (base of the 32-row block row: global workspace or LDS), directly in the next layer's operand
+// layout (layout propagation, Section V).  OUT_PLAIN = 1: write to the caller's y.
+template <int DT, int OUT_PLAIN, typename YP>
+OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, int n0, int m0, int lane, YP yblk) {
+    const int h = lane >> 5, mm = lane & 31;
+    float out[16];
+    epilogue_values<DT>(acc, a, n0, h, out);
+    constexpr int E = Elt<DT>::size;
+    if constexpr (OUT_PLAIN) {
+        if constexpr (DT != OGC_I8) {
+            if (a.res) add_residual<DT>(out, a, m0 + mm, n0, h);
+        }
+        if (DT == OGC_I8 && a.out_f32) {
+            v4i ch[4];
+            pack_block<4>(out, false, ch);
+            store_plain<4>(ch, a, m0 + mm, n0 + 16 * h);
+        } else {
+            v4i ch[E];
+            pack_block<E>(out, false, ch);
+            store_plain<E>(ch, a, m0 + mm, n0 + 16 * h);
+        }
+    } else {
+        v4i ch[E];
+        pack_block<E>(out, DT == OGC_I8, ch);
+        const int c0 = ((n0 >> 5) * 2 + h) * E;
+#pragma unroll
+        for (int c = 0; c < E; ++c) *(v4i*)(yblk + ((size_t)(c0 + c) * 32 + mm) * 16) = ch[c];
+    }
+}
+
+// Loads one 16-byte chunk (row m, bytes kb..kb+15 of the row) of the caller's plain x, zero-filling
+// everything outside [0,M) x [0,K*elt) (pre-op reorder from the plain layout, Section IV, anchor #4).
+// u8 inputs are converted to the internal s8 form on the way.
+template <int DT> OGC_DEV v4i load_plain_chunk(const OgcLayerArgs& a, int m, int kb) {
+    const int kbytes = a.K * Elt<DT>::size;
+    v4i v = {0, 0, 0, 0};
+    if (m < a.M && kb < kbytes) {
+        const uint8_t* p = a.x + (long long)m * a.ldx_bytes + kb;
+        if (a.x_vec_ok) {
+            v = *(const v4i*)p;
+        } else {
+            uint32_t d[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (kb + j < kbytes) d[j >> 2] |= (uint32_t)p[j] << (8 * (j & 3));
+            v = (v4i){(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
+        }
+        if constexpr (DT == OGC_I8) {
+            // bytes past K hold 0x80 after the flip only if they were flipped: flip valid bytes only
+            uint32_t msk[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int rem = kbytes - (kb + 4 * q);
+                msk[q] = rem >= 4 ? 0x80808080u : (rem <= 0 ? 0u : (0x80808080u >> (8 * (4 - rem))));
+            }
+            v = (v4i){(int)((uint32_t)v[0] ^ msk[0]), (int)((uint32_t)v[1] ^ msk[1]), (int)((uint32_t)v[2] ^ msk[2]),
+                      (int)((uint32_t)v[3] ^ msk[3])};
+        }
+    }
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Per-layer kernel: one workgroup computes a BN x BM tile of D = W X^T over the whole K, LDS double
+// buffered, then runs the epilogue in registers.  Grid: one workgroup per tile, XCD-aware order.
+// ------------------------------------------------------------------------------------------------
+template <int TILE> struct TileCfg;
+template <> struct TileCfg<OGC_TILE_BIG> { enum { WN = 2, WM = 2, TN = 4, TM = 4 }; };
+template <> struct TileCfg<OGC_TILE_MID> { enum { WN = 2, WM = 2, TN = 2, TM = 2 }; };
+template <> struct TileCfg<OGC_TILE_SMALL> { enum { WN = 2, WM = 1, TN = 1, TM = 1 }; };
+
+template <int DT, int TILE, int X_PLAIN, int OUT_PLAIN>
+__global__ void __launch_bounds__(TileCfg<TILE>::WN* TileCfg<TILE>::WM * 64)
+ogc_layer_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_per_xcd) {
+    typedef TileCfg<TILE> C;
+    constexpr int NT = C::WN * C::WM * 64;
+    constexpr int BN = C::WN * C::TN * 32, BM = C::WM * C::TM * 32;
+    constexpr int W_BYTES = BN * 64, X_BYTES = BM * 64, STAGE = W_BYTES + X_BYTES;
+    constexpr int PW = W_BYTES / 16 / NT, PX = X_BYTES / 16 / NT;
+    static_assert(PW >= 1 && PX >= 1 && PW * NT * 16 == W_BYTES && PX * NT * 16 == X_BYTES, "tile/thread mismatch");
+    extern __shared__ __align__(16) uint8_t smem[];
+
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so that the
+    // workgroups sharing an activation tile share one L2.
+    const int wg = blockIdx.x;
+    const int t = (wg & 7) * tiles_per_xcd + (wg >> 3);
+    if (t >= tiles_total) return;
+    const int n_base = (t % tiles_n) * BN, m_base = (t / tiles_n) * BM;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave % C::WN, wm = wave / C::WN;
+    const int KT = a.KC >> 2;  // 64-byte k-steps
+
+    v4i wreg[PW], xreg[PX];
+    auto load_global = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < PW; ++i) {
+            const int p = tid + i * NT;
+            const uint8_t* g = a.w + ((size_t)((n_base >> 5) + (p >> 7)) * a.KC + (size_t)kt * 4) * 512 + (p & 127) * 16;
+            wreg[i] = *(const v4i*)g;
+        }
+#pragma unroll
+        for (int i = 0; i < PX; ++i) {
+            const int p = tid + i * NT;
+            if constexpr (X_PLAIN) {
+                const int mr = p % BM, kc = p / BM;
+                xreg[i] = load_plain_chunk<DT>(a, m_base + mr, kt * 64 + kc * 16);
+            } else {
+                const uint8_t* g = a.x + ((size_t)((m_base >> 5) + (p >> 7)) * a.KC + (size_t)kt * 4) * 512 + (p & 127) * 16;
+                xreg[i] = *(const v4i*)g;
+            }
+        }
+    };
+    auto store_lds = [&](int buf) {
+        uint8_t* ws = smem + buf * STAGE;
+        uint8_t* xs = ws + W_BYTES;
+#pragma unroll
+        for (int i = 0; i < PW; ++i) *(v4i*)(ws + (tid + i * NT) * 16) = wreg[i];
+#pragma unroll
+        for (int i = 0; i < PX; ++i) {
+            const int p = tid + i * NT;
+            if constexpr (X_PLAIN) {
+                const int mr = p % BM, kc = p / BM;
+                *(v4i*)(xs + (((mr >> 5) * 4 + kc) * 32 + (mr & 31)) * 16) = xreg[i];
+            } else {
+                *(v4i*)(xs + p * 16) = xreg[i];
+            }
+        }
+    };
+
+    typename AccT<DT>::type acc[C::TN][C::TM];
+#pragma unroll
+    for (int i = 0; i < C::TN; ++i)
+#pragma unroll
+        for (int j = 0; j < C::TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        const bool more = kt + 1 < KT;
+        if (more) load_global(kt + 1);
+        const uint8_t* ws = smem + (kt & 1) * STAGE + (wn * C::TN) * 2048 + lane * 16;
+        const uint8_t* xs = smem + (kt & 1) * STAGE + W_BYTES + (wm * C::TM) * 2048 + lane * 16;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            v4i wf[C::TN], xf[C::TM];
+#pragma unroll
+            for (int i = 0; i < C::TN; ++i) wf[i] = *(const v4i*)(ws + i * 2048 + s * 1024);
+#pragma unroll
+            for (int j = 0; j < C::TM; ++j) xf[j] = *(const v4i*)(xs + j * 2048 + s * 1024);
+#pragma unroll
+            for (int i = 0; i < C::TN; ++i)
+#pragma unroll
+                for (int j = 0; j < C::TM; ++j) mma32<DT>(acc[i][j], wf[i], xf[j]);
+        }
+        if (more) store_lds((kt + 1) & 1);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < C::TN; ++i) {
+        const int n0 = n_base + (wn * C::TN + i) * 32;
+#pragma unroll
+        for (int j = 0; j < C::TM; ++j) {
+            const int m0 = m_base + (wm * C::TM + j) * 32;
+            if constexpr (OUT_PLAIN) {
+                if (n0 < a.N && m0 < a.M) epilogue_block<DT, 1>(acc[i][j], a, n0, m0, lane, (uint8_t*)nullptr);
+            } else {
+                if ((n0 >> 5) < a.NB_out)
+                    epilogue_block<DT, 0>(acc[i][j], a, n0, m0, lane, a.y + (size_t)(m0 >> 5) * a.KC_out * 512);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fused multi-layer chain kernel (coarse-grain fusion, Section V: the batch loops of consecutive layers
+// are merged, so a batch tile's activations stay in the fastest memory for the next matmul).  One
+// workgroup owns 32 batch rows for the whole chain.  The tile's activations ping-pong between two LDS
+// buffers in KB16 layout; weights are used once per workgroup and stream from global memory straight
+// into the MFMA operand registers (the packed layout is already in lane order, 1 KiB per wave load).
+// ------------------------------------------------------------------------------------------------
+#define OGC_FUSED_WAVES 8
+#define OGC_FUSED_THREADS (OGC_FUSED_WAVES * 64)
+
+template <int DT, int OUT_PLAIN>
+OGC_DEV void fused_layer(const OgcLayerArgs& a, const uint8_t* xin, uint8_t* xout, int m0, int wave, int lane) {
+    const int nblocks = OUT_PLAIN ? ((a.N + 31) >> 5) : a.NB_out;
+    const int KP2 = a.KC >> 1;  // 32-byte k-steps
+    for (int nb = wave; nb < nblocks; nb += OGC_FUSED_WAVES) {
+        typename AccT<DT>::type acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0;
+        const uint8_t* wp = a.w + (size_t)nb * a.KC * 512 + lane * 16;
+        const uint8_t* xp = xin + lane * 16;
+        int kp = 0;
+        for (; kp + 4 <= KP2; kp += 4) {
+            v4i wf[4], xf[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) wf[u] = *(const v4i*)(wp + (size_t)(kp + u) * 1024);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) xf[u] = *(const v4i*)(xp + (size_t)(kp + u) * 1024);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) mma32<DT>(acc, wf[u], xf[u]);
+        }
+        for (; kp < KP2; ++kp) {
+            const v4i wf = *(const v4i*)(wp + (size_t)kp * 1024);
+            const v4i xf = *(const v4i*)(xp + (size_t)kp * 1024);
+            mma32<DT>(acc, wf, xf);
+        }
+        epilogue_block<DT, OUT_PLAIN>(acc, a, nb * 32, m0, lane, xout);
+    }
+}
+
+template <int DT>
+__global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_fused_chain_kernel(const OgcChainArgs c) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.x * 32;
+    uint8_t* buf0 = smem;
+    uint8_t* buf1 = smem + c.lds_buf_bytes;
+
+    // Stage the plain input tile into LDS in operand layout (pre-op reorder fused at the chain entry).
+    {
+        const OgcLayerArgs& a = c.layer[0];
+        const int pieces = a.KC * 32;
+        for (int p = tid; p < pieces; p += OGC_FUSED_THREADS) {
+            const int mr = p & 31, kc = p >> 5;
+            *(v4i*)(buf0 + (size_t)p * 16) = load_plain_chunk<DT>(a, m0 + mr, kc * 16);
+        }
+    }
+    __syncthreads();
+    for (int l = 0; l < c.n_layers; ++l) {
+        const uint8_t* xin = (l & 1) ? buf1 : buf0;
+        uint8_t* xout = (l & 1) ? buf0 : buf1;
+        if (l + 1 < c.n_layers) {
+            fused_layer<DT, 0>(c.layer[l], xin, xout, m0, wave, lane);
+            __syncthreads();
+        } else {
+            fused_layer<DT, 1>(c.layer[l], xin, nullptr, m0, wave, lane);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Constant-weight preprocessing (Section V): plain [K,N] -> KB16 blocked, zero padded; per-channel
+// parameters.  One thread per 16-byte chunk / per channel.
+// ------------------------------------------------------------------------------------------------
+__global__ void ogc_prepack_weights_kernel(const uint8_t* __restrict__ w, uint8_t* __restrict__ out, int K, int N, int KC,
+                                           int NPw, int esz) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)(NPw >> 5) * KC * 32;
+    if (idx >= total) return;
+    const int r = (int)(idx & 31);
+    const long long q = idx >> 5;
+    const int c = (int)(q % KC);
+    const int nb = (int)(q / KC);
+    const int n = nb * 32 + r;
+    const int epc = 16 / esz;  // elements per chunk
+    uint32_t d[4] = {0, 0, 0, 0};
+    if (n < N) {
+        for (int j = 0; j < epc; ++j) {
+            const int k = c * epc + j;
+            if (k < K) {
+                const uint8_t* src = w + ((size_t)k * N + n) * esz;
+                for (int b = 0; b < esz; ++b) {
+                    const int byte = j * esz + b;
+                    d[byte >> 2] |= (uint32_t)src[b] << (8 * (byte & 3));
+                }
+            }
+        }
+    }
+    *(v4i*)(out + (size_t)idx * 16) = (v4i){(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
+}
+
+__global__ void ogc_prepack_params_kernel(int dtype, const int8_t* __restrict__ wq, const float* __restrict__ w_scale,
+                                          const float* __restrict__ bias, float in_scale, int in_zp, int K, int N, int NPw,
+                                          float* __restrict__ scale_out, float* __restrict__ bias_out,
+                                          int32_t* __restrict__ ncomp_out) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= NPw) return;
+    const bool valid = n < N;
+    bias_out[n] = (valid && bias) ? bias[n] : 0.0f;
+    if (dtype == OGC_I8) {
+        int32_t wsum = 0;
+        if (valid)
+            for (int k = 0; k < K; ++k) wsum += (int32_t)wq[(size_t)k * N + n];
+        ncomp_out[n] = -(in_zp - 128) * wsum;
+        scale_out[n] = valid ? in_scale * w_scale[n] : 0.0f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Launchers
+// ------------------------------------------------------------------------------------------------
+template <int TILE> static OgcTileInfo tile_info_t() {
+    typedef TileCfg<TILE> C;
+    OgcTileInfo i;
+    i.bn = C::WN * C::TN * 32;
+    i.bm = C::WM * C::TM * 32;
+    i.threads = C::WN * C::WM * 64;
+    i.lds_bytes = (size_t)2 * (i.bn + i.bm) * 64;
+    return i;
+}
+
+extern "C" OgcTileInfo ogc_tile_info(int tile) {
+    switch (tile) {
+    case OGC_TILE_BIG: return tile_info_t<OGC_TILE_BIG>();
+    case OGC_TILE_MID: return tile_info_t<OGC_TILE_MID>();
+    default: return tile_info_t<OGC_TILE_SMALL>();
+    }
+}
+
+template <int DT, int TILE, int XP, int OP>
+static int launch_layer_t(const OgcLayerArgs* a, hipStream_t stream) {
+    const OgcTileInfo ti = tile_info_t<TILE>();
+    auto kern = ogc_layer_kernel<DT, TILE, XP, OP>;
+    static bool attr_set = false;  // raising the LDS limit is idempotent; a race only repeats it
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ti.lds_bytes);
+        if (e != hipSuccess) return (int)e;
+        attr_set = true;
+    }
+    const int nrows = OP ? a->N : a->NB_out * 32;
+    const int tiles_n = (nrows + ti.bn - 1) / ti.bn;
+    const int tiles_m = (a->M + ti.bm - 1) / ti.bm;
+    const int total = tiles_n * tiles_m;
+    const int per_xcd = (total + 7) / 8;
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(ti.threads), ti.lds_bytes, stream, *a, tiles_n, total, per_xcd);
+    return (int)hipGetLastError();
+}
+
+template <int DT, int TILE>
+static int launch_layer_io(int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
+    if (xp) return op ? launch_layer_t<DT, TILE, 1, 1>(a, s) : launch_layer_t<DT, TILE, 1, 0>(a, s);
+    return op ? launch_layer_t<DT, TILE, 0, 1>(a, s) : launch_layer_t<DT, TILE, 0, 0>(a, s);
+}
+
+template <int DT>
+static int launch_layer_tile(int tile, int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
+    switch (tile) {
+    case OGC_TILE_BIG: return launch_layer_io<DT, OGC_TILE_BIG>(xp, op, a, s);
+    case OGC_TILE_MID: return launch_layer_io<DT, OGC_TILE_MID>(xp, op, a, s);
+    default: return launch_layer_io<DT, OGC_TILE_SMALL>(xp, op, a, s);
+    }
+}
+
+extern "C" int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain, const OgcLayerArgs* a, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    switch (dtype) {
+    case OGC_F32: return launch_layer_tile<OGC_F32>(tile, x_plain, out_plain, a, s);
+    case OGC_BF16: return launch_layer_tile<OGC_BF16>(tile, x_plain, out_plain, a, s);
+    default: return launch_layer_tile<OGC_I8>(tile, x_plain, out_plain, a, s);
+    }
+}
+
+extern "C" size_t ogc_fused_lds_limit(void) { return 160 * 1024; }
+extern "C" int ogc_fused_threads(void) { return OGC_FUSED_THREADS; }
+
+template <int DT> static int launch_fused_t(const OgcChainArgs* c, int m_blocks, hipStream_t stream) {
+    auto kern = ogc_fused_chain_kernel<DT>;
+    const size_t lds = (size_t)2 * c->lds_buf_bytes;
+    static size_t attr_max = 0;
+    if (lds > attr_max) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return (int)e;
+        attr_max = lds;
+    }
+    hipLaunchKernelGGL(kern, dim3(m_blocks), dim3(OGC_FUSED_THREADS), lds, stream, *c);
+    return (int)hipGetLastError();
+}
+
+extern "C" int ogc_launch_fused(int dtype, const OgcChainArgs* c, int m_blocks, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    switch (dtype) {
+    case OGC_F32: return launch_fused_t<OGC_F32>(c, m_blocks, s);
+    case OGC_BF16: return launch_fused_t<OGC_BF16>(c, m_blocks, s);
+    default: return launch_fused_t<OGC_I8>(c, m_blocks, s);
+    }
+}
+
+extern "C" int ogc_launch_prepack_weights(const void* w, void* out, int K, int N, int KC, int NPw, int esz, void* stream) {
+    const long long total = (long long)(NPw >> 5) * KC * 32;
+    const int threads = 256;
+    const long long blocks = (total + threads - 1) / threads;
+    hipLaunchKernelGGL(ogc_prepack_weights_kernel, dim3((unsigned)blocks), dim3(threads), 0, (hipStream_t)stream,
+                       (const uint8_t*)w, (uint8_t*)out, K, N, KC, NPw, esz);
+    return (int)hipGetLastError();
+}
+
+extern "C" int ogc_launch_prepack_params(int dtype, const void* w, const float* w_scale, const float* bias, float in_scale,
+                                         int in_zp, int K, int N, int NPw, float* scale_out, float* bias_out,
+                                         int32_t* ncomp_out, void* stream) {
+    const int threads = 64;
+    hipLaunchKernelGGL(ogc_prepack_params_kernel, dim3((NPw + threads - 1) / threads), dim3(threads), 0, (hipStream_t)stream,
+                       dtype, (const int8_t*)w, w_scale, bias, in_scale, in_zp, K, N, NPw, scale_out, bias_out, ncomp_out);
+    return (int)hipGetLastError();
+}
+
+extern "C" const char* ogc_layer_kernel_name(int, int, int, int) { return "ogc_layer_kernel"; }
+extern "C" const char* ogc_fused_kernel_name(int) { return "ogc_fused_chain_kernel"; }

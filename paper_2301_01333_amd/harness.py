@@ -1,0 +1,54 @@
+"""Glue between a synthetic workload (numpy arrays) and the GPU library: uploads the arrays as device
+tensors, builds the plan, prepacks, runs, downloads.  Marshalling only; no arithmetic of the method."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+
+from . import binding
+
+
+def _to_device(torch, arr: np.ndarray):
+    a = np.ascontiguousarray(arr)
+    return torch.from_numpy(a.view(np.uint8).reshape(-1).copy()).cuda()
+
+
+class DeviceMLP:
+    """A workload resident on the GPU: plan, packed weights, input and output buffers."""
+
+    def __init__(self, wl, mode: int = binding.OGC_MODE_AUTO, ld_y: Optional[int] = None, x_byte_offset: int = 0):
+        import torch
+
+        self.torch = torch
+        self.wl = wl
+        xb = wl.x.base if wl.x.base is not None else wl.x
+        if xb.ndim != 2 or xb.shape[0] != wl.x.shape[0]:
+            xb = np.ascontiguousarray(wl.x)
+        self.ld_x = xb.shape[1]
+        last = wl.layers[-1]
+        self.out_np_dtype = np.float32 if (wl.dtype == "i8" and last.out_f32) else {"f32": np.float32, "bf16": np.uint16, "i8": np.uint8}[wl.dtype]
+        self.ld_y = ld_y or last.n
+        self.mlp = binding.FusedMLP(wl.dtype, wl.m, wl.layers, self.ld_x, self.ld_y, wl.residual, mode)
+        self.w = [_to_device(torch, w) for w in wl.w]
+        self.bias = [None if b is None else _to_device(torch, b) for b in wl.bias]
+        self.w_scale = None if wl.dtype != "i8" else [_to_device(torch, s) for s in wl.w_scale]
+        self.mlp.prepack(self.w, self.bias, self.w_scale)
+        xbytes = np.ascontiguousarray(xb).view(np.uint8).reshape(-1)
+        if x_byte_offset:
+            xbytes = np.concatenate([np.zeros(x_byte_offset, np.uint8), xbytes])
+        self.x_store = torch.from_numpy(xbytes.copy()).cuda()
+        self.x = self.x_store[x_byte_offset:]
+        ybytes = wl.m * self.ld_y * np.dtype(self.out_np_dtype).itemsize
+        self.y = torch.full((ybytes,), 0xCD, dtype=torch.uint8, device="cuda")
+
+    def run(self) -> None:
+        self.mlp.run(self.x, self.y)
+
+    def result(self) -> np.ndarray:
+        self.torch.cuda.synchronize()
+        full = self.y.cpu().numpy().view(self.out_np_dtype).reshape(self.wl.m, self.ld_y)
+        return full
+
+    def close(self):
+        self.mlp.close()

@@ -1,0 +1,202 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  int8 results must be bit-exact; bf16 within 1e-2 and fp32 within 1e-5, relative, with the
+absolute floor tied to the output magnitude: |gpu-ref| <= tol*|ref| + tol*max|ref|."""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2301_01333_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+RELU, NONE, GELU, SIGM = synth.ACT_RELU, synth.ACT_NONE, synth.ACT_GELU_TANH, synth.ACT_SIGMOID
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+MODES = {"fused": binding.OGC_MODE_FUSED, "per_layer": binding.OGC_MODE_PER_LAYER, "auto": binding.OGC_MODE_AUTO}
+
+
+def as_f32(wl, a):
+    return synth.bf16_bits_to_f32(a) if a.dtype == np.uint16 else a.astype(np.float32)
+
+
+def assert_close(got, ref, tol, what=""):
+    got, ref = got.astype(np.float64), ref.astype(np.float64)
+    assert np.isfinite(got).all(), what
+    bound = tol * np.abs(ref) + tol * np.abs(ref).max()
+    err = np.abs(got - ref)
+    if not (err <= bound).all():
+        i = int((err - bound).argmax())
+        raise AssertionError("%s: %d of %d outside tolerance; worst at %s: got %g ref %g bound %g" % (
+            what, int((err > bound).sum()), err.size, np.unravel_index(i, err.shape), got.flat[i], ref.flat[i], bound.flat[i]))
+
+
+def run_gpu(wl, mode, tile=None, **kw):
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    old = os.environ.get("OGC_TILE")
+    if tile is not None:
+        os.environ["OGC_TILE"] = str(tile)
+    try:
+        d = DeviceMLP(wl, MODES[mode], **kw)
+    finally:
+        if tile is not None:
+            if old is None:
+                os.environ.pop("OGC_TILE")
+            else:
+                os.environ["OGC_TILE"] = old
+    d.run()
+    y = d.result().copy()
+    chosen = d.mlp.mode
+    d.close()
+    return y, chosen
+
+
+def check(wl, mode, oracle_mod, tile=None, rows=None, **kw):
+    print("case:", wl.name, wl.dtype, "M=%d" % wl.m, wl.dims, "mode=%s tile=%s" % (mode, tile), kw, flush=True)
+    got, _ = run_gpu(wl, mode, tile, **kw)
+    n = wl.layers[-1].n
+    pad = got[:, n:]
+    got = got[:, :n]
+    if pad.size:
+        assert (pad.view(np.uint8) == 0xCD).all(), "bytes beyond n_last in a strided y were touched"
+    slices = rows or [slice(0, wl.m)]
+    for sl in slices:
+        ref = oracle_mod.mlp(wl, rows=sl)
+        g = got[sl]
+        if ref.dtype == np.uint8:
+            if not np.array_equal(g, ref):
+                bad = np.argwhere(g != ref)
+                raise AssertionError("int8 mismatch: %d of %d differ; first at %s: got %d ref %d" % (
+                    len(bad), ref.size, bad[0].tolist(), g[tuple(bad[0])], ref[tuple(bad[0])]))
+        elif wl.dtype == "i8":
+            assert_close(g, ref, 1e-5, "int8 chain, fp32 output")
+        else:
+            assert_close(as_f32(wl, g), as_f32(wl, ref), TOL[wl.dtype], "vs fp32-accumulate oracle")
+            ref64 = oracle_mod.mlp(wl, rows=sl, accum_double=True)
+            assert_close(as_f32(wl, g), as_f32(wl, ref64), TOL[wl.dtype], "vs fp64 oracle")
+    return got
+
+
+# ---------------------------------------------------------------- the five configurations, full size
+@pytest.mark.parametrize("mode", ["auto", "per_layer"])
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_small_configs_full(oracle_mod, cfg, mode):
+    check(synth.make_config(cfg), mode, oracle_mod)
+
+
+@pytest.mark.parametrize("nl", [1, 2, 3, 4])
+@pytest.mark.parametrize("mode", ["fused", "per_layer"])
+def test_cfg3_u8_intermediates_bit_exact(oracle_mod, nl, mode):
+    """The first nl layers of config 3 as a chain of their own: the requantized u8 tensor is the output."""
+    full = synth.make_config(3)
+    wl = synth.Workload("cfg3[:%d]" % nl, "i8", full.m, full.layers[:nl], False, full.x, full.w[:nl], full.bias[:nl],
+                        full.w_scale[:nl], full.seed)
+    got = check(wl, mode, oracle_mod)
+    assert len(np.unique(got)) > 50   # not degenerate
+
+
+def test_cfg4_full_size_sampled_rows(oracle_mod):
+    wl = synth.make_config(4)
+    check(wl, "auto", oracle_mod, rows=[slice(0, 40), slice(2031, 2065), slice(4070, 4096)])
+
+
+def test_cfg5_full_size_sampled_rows(oracle_mod):
+    wl = synth.make_config(5)
+    got = check(wl, "auto", oracle_mod, rows=[slice(0, 48), slice(16370, 16400), slice(32730, 32768)])
+    assert got.min() == 128 and got.max() == 255 and len(np.unique(got)) > 100
+
+
+# ---------------------------------------------------------------- reduced sizes: several tiles + ragged tails
+@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f32"])
+def test_per_layer_ragged(oracle_mod, dtype, tile):
+    m = {0: 300, 1: 150, 2: 77}[tile]
+    dims = [100, 333, 72, 33] if dtype == "i8" else [50, 290, 40, 19]
+    wl = synth.make_mlp(dtype, m, dims, [RELU, RELU, NONE if dtype != "i8" else RELU], seed=500 + tile, name="ragged")
+    check(wl, "per_layer", oracle_mod, tile=tile)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f32"])
+def test_fused_ragged(oracle_mod, dtype):
+    wl = synth.make_mlp(dtype, 77, [37, 130, 300, 9], [RELU, GELU if dtype != "i8" else RELU, RELU], seed=600, name="ragged")
+    check(wl, "fused", oracle_mod)
+
+
+@pytest.mark.parametrize("mode", ["fused", "per_layer"])
+def test_reduced_cfg4_and_cfg5(oracle_mod, mode):
+    check(synth.make_config(4, m=160), "per_layer", oracle_mod, tile=1)   # hidden 4096 does not fit the fused kernel
+    check(synth.make_config(5, m=96), mode, oracle_mod)
+
+
+# ---------------------------------------------------------------- edge cases
+@pytest.mark.parametrize("mode", ["fused", "per_layer"])
+def test_edges_int8(oracle_mod, mode):
+    # single row, single output channel, K = 1
+    check(synth.make_mlp("i8", 1, [1, 1], [RELU], seed=1), mode, oracle_mod)
+    # zero points away from 128 (compensation path), weights including -128, unpadded K
+    check(synth.make_mlp("i8", 33, [479, 65, 31], [RELU, RELU], seed=2, a_z=3, c_z=200, wq_lo=-128), mode, oracle_mod)
+    check(synth.make_mlp("i8", 40, [64, 64], [NONE], seed=3, a_z=0, c_z=0, wq_lo=-128), mode, oracle_mod)
+    check(synth.make_mlp("i8", 40, [64, 64], [RELU], seed=4, a_z=255, c_z=255), mode, oracle_mod)
+    # fp32 result straight from the first layer; sigmoid and no activation
+    check(synth.make_mlp("i8", 19, [70, 5], [SIGM], seed=5, last_f32=True), mode, oracle_mod)
+    check(synth.make_mlp("i8", 19, [70, 5], [NONE], seed=6, last_f32=True, has_bias=False), mode, oracle_mod)
+    # strided x and y, x not 16-byte aligned
+    check(synth.make_mlp("i8", 50, [100, 48], [RELU], seed=7, ld_x=112), mode, oracle_mod, ld_y=64)
+    check(synth.make_mlp("i8", 50, [96, 48], [RELU], seed=8), mode, oracle_mod, x_byte_offset=3)
+    # saturation on both ends: tiny output scale
+    wl = synth.make_mlp("i8", 20, [128, 40], [NONE], seed=9)
+    wl.layers[0].out_scale = wl.layers[0].out_scale / 50.0
+    got = check(wl, mode, oracle_mod)
+    assert (got == 0).any() and (got == 255).any()
+
+
+@pytest.mark.parametrize("mode", ["fused", "per_layer"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_edges_float(oracle_mod, dtype, mode):
+    check(synth.make_mlp(dtype, 1, [1, 1], [NONE], seed=11), mode, oracle_mod)
+    check(synth.make_mlp(dtype, 3, [13, 1], [SIGM], seed=12), mode, oracle_mod)
+    check(synth.make_mlp(dtype, 70, [40, 64, 40], [GELU, NONE], seed=13, residual=True), mode, oracle_mod)
+    check(synth.make_mlp(dtype, 50, [24, 36], [RELU], seed=14, ld_x=40, has_bias=False), mode, oracle_mod, ld_y=52)
+    esz = 4 if dtype == "f32" else 2
+    check(synth.make_mlp(dtype, 50, [32, 32], [RELU], seed=15), mode, oracle_mod, x_byte_offset=esz)
+
+
+def test_zero_and_identity_weights(oracle_mod):
+    wl = synth.make_mlp("i8", 64, [64, 64], [RELU], seed=21)
+    wl.w[0][:] = 0
+    got = check(wl, "per_layer", oracle_mod)
+    assert (got == got[0]).all()          # every row equals requant(ReLU(bias)), whatever x is
+    wl = synth.make_mlp("i8", 64, [64, 64], [RELU], seed=22, has_bias=False)
+    wl.w[0][:] = np.eye(64, dtype=np.int8)
+    wl.w_scale[0][:] = 1.0
+    wl.layers[0].in_scale = wl.layers[0].out_scale = 0.25
+    got = check(wl, "fused", oracle_mod)
+    assert np.array_equal(got, np.maximum(wl.x, 128))
+
+
+def test_run_is_repeatable_and_workspace_is_stateless(oracle_mod):
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    wl = synth.make_config(5, m=512)
+    d = DeviceMLP(wl, binding.OGC_MODE_PER_LAYER)
+    d.run()
+    a = d.result().copy()
+    d.mlp.workspace.fill_(0x5A)
+    d.y.fill_(0)
+    for _ in range(3):
+        d.run()
+    b = d.result().copy()
+    d.close()
+    assert np.array_equal(a, b)
+    assert np.array_equal(a, oracle_mod.mlp(wl))
+
+
+def test_run_before_prepack_is_refused():
+    import torch
+
+    m = binding.FusedMLP("f32", 4, [dict(k=4, n=4)], mode=binding.OGC_MODE_AUTO)
+    x = torch.zeros(16, device="cuda")
+    with pytest.raises(binding.OgcError) as e:
+        binding.ogc_mlp_run(m.plan, x.data_ptr(), x.data_ptr(), x.data_ptr(), 0, 0)
+    assert e.value.status == -6
+    m.close()
