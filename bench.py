@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-MLP hot path on one MI355X.
+
+`python bench.py --gpus 1 --steps K --warmup W` prints ONE JSON line.  A step is one pass of the whole
+hot path (input staging, every layer's MFMA main loop + register epilogue, inter-layer hand-off, final
+store: one ogc_mlp_run call) over one batch of seeded synthetic input that is already resident in HBM.
+The headline workload is configuration 5 (int8, M=32768, 4 x 1024->1024, ReLU + requantize), the largest
+single-GPU configuration; the other four are reported under "per_config".  The roofline object is for the
+dominant kernel of the headline workload, timed live with HIP events around every launch; cpu_baseline is
+the CPU oracle timed on a bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"i8": (5.0e15, "TOP/s"), "bf16": (2.5e15, "TFLOP/s"), "f32": (157.3e12, "TFLOP/s")}
+HBM_PEAK = 8.0e12
+METRIC = "fused-MLP TFLOPS/TOPS + fraction of MFMA or HBM roofline, per config"
+
+
+def _median(v):
+    s = sorted(v)
+    return s[len(s) // 2]
+
+
+def time_steps(dev, steps, warmup):
+    """Wall-clock time of exactly `steps` runs, synchronised on both sides."""
+    import torch
+
+    for _ in range(warmup):
+        dev.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        dev.run()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def profile_launches(dev, reps=30):
+    """Per-launch durations (seconds), median over reps, from HIP events recorded around every launch."""
+    dev.run_profiled()
+    rows = [dev.run_profiled() for _ in range(reps)]
+    n = len(rows[0])
+    return [_median([r[i] for r in rows]) * 1e-3 for i in range(n)]
+
+
+def config_report(idx, steps, warmup, with_floor=None):
+    from paper_2301_01333_amd import binding, synth
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    wl = synth.make_config(idx)
+    dev = DeviceMLP(wl)
+    sec = time_steps(dev, steps, warmup)
+    launches = profile_launches(dev)
+    nl = binding.ogc_mlp_num_launches(dev.mlp.plan)
+    peak, unit = PEAK[wl.dtype]
+    ops, abytes = wl.ops, wl.algorithmic_bytes
+    ridge = peak / HBM_PEAK
+    bound = "mfma" if ops / abytes > ridge else "hbm"
+    rep = {
+        "config": idx, "workload": wl.name, "dtype": wl.dtype, "mode": "fused" if dev.mlp.mode == binding.OGC_MODE_FUSED else "per_layer",
+        "launches": nl, "ms_per_step": sec * 1e3, "gpu_ms_sum_of_launches": sum(launches) * 1e3,
+        "tops_or_tflops": ops / sec / 1e12, "algorithmic_GBps": abytes / sec / 1e9, "bound": bound,
+        "frac_of_bound": (ops / sec / peak) if bound == "mfma" else (abytes / sec / HBM_PEAK),
+        "ops": ops, "algorithmic_bytes": abytes,
+    }
+    if with_floor is not None:
+        rep["launch_floor_ms"] = with_floor * 1e3
+        rep["frac_of_latency_aware_bound"] = (with_floor + abytes / HBM_PEAK) / sec
+    return wl, dev, rep, launches
+
+
+def launch_floor(steps, warmup):
+    """Per-call time of the smallest possible chain (1x1x1): the floor one library call costs on this machine."""
+    from paper_2301_01333_amd import synth
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    wl = synth.make_mlp("f32", 1, [1, 1], [0], seed=1)
+    dev = DeviceMLP(wl)
+    sec = time_steps(dev, steps, warmup)
+    dev.close()
+    return sec
+
+
+def cpu_baseline(idx, budget_s=15.0):
+    """The CPU oracle, as it stands, on a bounded row sample of the headline workload."""
+    import oracle
+    from paper_2301_01333_amd import synth
+
+    full = synth.make_config(idx)
+    probe_rows = 32
+    wl = synth.make_config(idx, m=probe_rows)
+    t0 = time.perf_counter()
+    oracle.mlp(wl)
+    t_probe = max(time.perf_counter() - t0, 1e-4)
+    rows = int(max(probe_rows, min(full.m, probe_rows * budget_s / t_probe)))
+    rows = max(32, rows // 32 * 32)
+    wl = synth.make_config(idx, m=rows)
+    t0 = time.perf_counter()
+    oracle.mlp(wl)
+    dt = time.perf_counter() - t0
+    return {"value": wl.ops / dt / 1e12, "unit": "TOP/s" if wl.dtype == "i8" else "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": "first %d of %d rows of config %d, all layers, %.1f s of CPU time" % (rows, full.m, idx, dt)}
+
+
+def read_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if present."""
+    path = os.path.join(ROOT, "profiles", "cfg5_layer_kernel_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", type=int, default=5, help="headline configuration (1..5)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--only-headline", action="store_true", help="skip the per_config table")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        return 2
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    from paper_2301_01333_amd import binding
+
+    binding.lib()  # fail loudly if the HIP library is missing
+    floor = launch_floor(args.steps, args.warmup)
+    wl, dev, head, launches = config_report(args.config, args.steps, args.warmup)
+    peak, unit = PEAK[wl.dtype]
+    # dominant kernel = the launch with the longest duration; its algorithmic work is that layer's
+    # 2*M*K*N (mfma bound) or the chain's algorithmic bytes (hbm bound, fused single launch)
+    if head["mode"] == "per_layer":
+        i = max(range(len(launches)), key=lambda j: launches[j])
+        ly = wl.layers[i]
+        work = 2.0 * wl.m * ly.k * ly.n
+        dom = {"kernel": binding.ogc_mlp_kernel_name(dev.mlp.plan, i), "launch": i,
+               "launch_us": [round(t * 1e6, 2) for t in launches]}
+    else:
+        i = 0
+        work = float(wl.ops)
+        dom = {"kernel": binding.ogc_mlp_kernel_name(dev.mlp.plan, 0), "launch": 0, "launch_us": [round(launches[0] * 1e6, 2)]}
+    if head["bound"] == "mfma":
+        roof = {"bound": "mfma", "achieved": work / launches[i] / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s" if wl.dtype != "i8" else "TOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": wl.algorithmic_bytes / launches[i] / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = read_traffic() if args.config == 5 else None
+    roof.update(dom)
+    dev.close()
+
+    per = []
+    if not args.only_headline:
+        for idx in (1, 2, 3, 4, 5):
+            if idx == args.config:
+                r = dict(head)
+            else:
+                _, d, r, _ = config_report(idx, args.steps, args.warmup, with_floor=floor if idx <= 3 else None)
+                d.close()
+            if idx <= 3 and "launch_floor_ms" not in r:
+                r["launch_floor_ms"] = floor * 1e3
+            per.append(r)
+
+    out = {
+        "metric": METRIC, "value": head["tops_or_tflops"], "unit": "TOPS" if wl.dtype == "i8" else "TFLOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"i8": "u8", "bf16": "bf16", "f32": "f32"}[wl.dtype], "data": "synthetic",
+        "config": {"workload": wl.name, "mode": head["mode"], "launches_per_step": head["launches"],
+                   "ops_per_step": wl.ops, "algorithmic_bytes_per_step": wl.algorithmic_bytes},
+        "frac_of_peak_whole_step": head["frac_of_bound"],
+        "roofline": roof,
+        "cpu_baseline": None if args.no_cpu else cpu_baseline(args.config),
+        "launch_floor_us": floor * 1e6,
+        "per_config": per,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

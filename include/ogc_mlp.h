@@ -124,6 +124,16 @@ ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, co
  * holds no state between calls. */
 ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream);
 
+/* Number of kernel launches one ogc_mlp_run makes: 1 for the fused-chain kernel, n_layers otherwise. */
+ogc_status ogc_mlp_num_launches(ogc_mlp_plan_t plan, int32_t* n /*host*/);
+
+/* ogc_mlp_run with a HIP event recorded on `stream` around every launch; waits for the last one and writes
+ * each launch's duration in milliseconds to launch_ms[0 .. ogc_mlp_num_launches()-1] (host).  This is the
+ * per-operation measurement of Section VII (layers timed separately while still run back to back as a
+ * chain).  Unlike ogc_mlp_run it synchronises with the stream and creates/destroys HIP events. */
+ogc_status ogc_mlp_run_profiled(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace,
+                                void* stream, float* launch_ms /*host*/);
+
 /* Releases the plan (NULL is ignored). */
 void ogc_mlp_destroy(ogc_mlp_plan_t plan);
 

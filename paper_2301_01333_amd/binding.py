@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(_HERE, "libogc_mlp.so")
 EXPORTS = [
     "ogc_mlp_plan", "ogc_mlp_packed_bytes", "ogc_mlp_workspace_bytes", "ogc_mlp_chosen_mode",
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
-    "ogc_status_string", "ogc_mlp_kernel_name",
+    "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled",
 ]
 
 
@@ -71,6 +71,10 @@ def lib():
         l.ogc_mlp_prepack_weights.restype = i32
         l.ogc_mlp_run.argtypes = [vp, vp, vp, vp, vp, vp]
         l.ogc_mlp_run.restype = i32
+        l.ogc_mlp_num_launches.argtypes = [vp, ctypes.POINTER(i32)]
+        l.ogc_mlp_num_launches.restype = i32
+        l.ogc_mlp_run_profiled.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
+        l.ogc_mlp_run_profiled.restype = i32
         l.ogc_mlp_destroy.argtypes = [vp]
         l.ogc_mlp_destroy.restype = None
         l.ogc_status_string.argtypes = [i32]
@@ -147,6 +151,20 @@ def ogc_mlp_run(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, workspace_pt
     _check(lib().ogc_mlp_run(plan, x_ptr, y_ptr, packed_ptr, workspace_ptr or None, stream), "ogc_mlp_run")
 
 
+def ogc_mlp_num_launches(plan: int) -> int:
+    v = ctypes.c_int32()
+    _check(lib().ogc_mlp_num_launches(plan, ctypes.byref(v)), "ogc_mlp_num_launches")
+    return v.value
+
+
+def ogc_mlp_run_profiled(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, workspace_ptr: int, stream: int = 0):
+    """Returns the list of per-launch durations in milliseconds."""
+    n = ogc_mlp_num_launches(plan)
+    ms = (ctypes.c_float * n)()
+    _check(lib().ogc_mlp_run_profiled(plan, x_ptr, y_ptr, packed_ptr, workspace_ptr or None, stream, ms), "ogc_mlp_run_profiled")
+    return [float(v) for v in ms]
+
+
 def ogc_mlp_destroy(plan: int) -> None:
     lib().ogc_mlp_destroy(plan)
 
@@ -213,3 +231,7 @@ class FusedMLP:
     def run(self, x, y) -> None:
         ogc_mlp_run(self.plan, x.data_ptr(), y.data_ptr(), self.packed.data_ptr(),
                     self.workspace.data_ptr() if self.workspace_bytes else 0, self._stream())
+
+    def run_profiled(self, x, y):
+        return ogc_mlp_run_profiled(self.plan, x.data_ptr(), y.data_ptr(), self.packed.data_ptr(),
+                                    self.workspace.data_ptr() if self.workspace_bytes else 0, self._stream())

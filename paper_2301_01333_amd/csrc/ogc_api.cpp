@@ -8,6 +8,8 @@
 #include <new>
 #include <vector>
 
+#include <hip/hip_runtime_api.h>
+
 #include "ogc_internal.h"
 
 namespace {
@@ -293,7 +295,10 @@ ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, co
     return OGC_OK;
 }
 
-ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream) {
+// Shared body of ogc_mlp_run / ogc_mlp_run_profiled.  With ev != NULL, event ev[i] is recorded on the stream
+// before launch i and ev[n] after the last one.
+static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream,
+                           hipEvent_t* ev) {
     if (!plan || !x || !y || !packed) return OGC_ERR_INVALID_ARG;
     if (!plan->prepacked.load()) return OGC_ERR_NOT_PREPACKED;
     if (((uintptr_t)packed & 255) != 0) return OGC_ERR_ALIGNMENT;
@@ -335,8 +340,11 @@ ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* 
         c.n_layers = L;
         c.lds_buf_bytes = plan->lds_buf_bytes;
         for (int l = 0; l < L; ++l) finish_args(l, &c.layer[l]);
+        if (ev && hipEventRecord(ev[0], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
         const int rc = ogc_launch_fused(plan->desc.dtype, &c, (plan->desc.m + 31) / 32, stream);
-        return rc == 0 ? OGC_OK : OGC_ERR_DEVICE;
+        if (rc != 0) return OGC_ERR_DEVICE;
+        if (ev && hipEventRecord(ev[1], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
+        return OGC_OK;
     }
     uint8_t* ws = (uint8_t*)workspace;
     for (int l = 0; l < L; ++l) {
@@ -344,10 +352,43 @@ ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* 
         finish_args(l, &a);
         if (l > 0) a.x = ws + plan->layers[l - 1].out_off;
         if (l < L - 1) a.y = ws + plan->layers[l].out_off;
+        if (ev && hipEventRecord(ev[l], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
         const int rc = ogc_launch_layer(plan->desc.dtype, plan->layers[l].tile, l == 0, l == L - 1, &a, stream);
         if (rc != 0) return OGC_ERR_DEVICE;
     }
+    if (ev && hipEventRecord(ev[L], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
     return OGC_OK;
+}
+
+ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream) {
+    return run_impl(plan, x, y, packed, workspace, stream, nullptr);
+}
+
+ogc_status ogc_mlp_num_launches(ogc_mlp_plan_t plan, int32_t* n) {
+    if (!plan || !n) return OGC_ERR_INVALID_ARG;
+    *n = plan->mode == OGC_MODE_FUSED ? 1 : (int32_t)plan->layers.size();
+    return OGC_OK;
+}
+
+ogc_status ogc_mlp_run_profiled(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace,
+                                void* stream, float* launch_ms) {
+    if (!plan || !launch_ms) return OGC_ERR_INVALID_ARG;
+    const int n = plan->mode == OGC_MODE_FUSED ? 1 : (int)plan->layers.size();
+    hipEvent_t ev[OGC_MAX_LAYERS + 1];
+    int made = 0;
+    ogc_status st = OGC_OK;
+    for (; made <= n; ++made)
+        if (hipEventCreate(&ev[made]) != hipSuccess) {
+            st = OGC_ERR_DEVICE;
+            break;
+        }
+    if (st == OGC_OK) st = run_impl(plan, x, y, packed, workspace, stream, ev);
+    if (st == OGC_OK && hipEventSynchronize(ev[n]) != hipSuccess) st = OGC_ERR_DEVICE;
+    if (st == OGC_OK)
+        for (int i = 0; i < n; ++i)
+            if (hipEventElapsedTime(&launch_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = OGC_ERR_DEVICE;
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    return st;
 }
 
 void ogc_mlp_destroy(ogc_mlp_plan_t plan) { delete plan; }

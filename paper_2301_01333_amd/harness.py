@@ -45,6 +45,9 @@ class DeviceMLP:
     def run(self) -> None:
         self.mlp.run(self.x, self.y)
 
+    def run_profiled(self):
+        return self.mlp.run_profiled(self.x, self.y)
+
     def result(self) -> np.ndarray:
         self.torch.cuda.synchronize()
         full = self.y.cpu().numpy().view(self.out_np_dtype).reshape(self.wl.m, self.ld_y)

@@ -1,0 +1,138 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the header declares,
+validates descriptions, lays out the packed blob and assigns workspace buffers by life span."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2301_01333_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _built():
+    return os.path.exists(b.LIB_PATH)
+
+
+pytestmark = pytest.mark.skipif(not _built(), reason="libogc_mlp.so not built (python -m paper_2301_01333_amd.build)")
+
+
+def layer(k, n, **kw):
+    d = dict(k=k, n=n, has_bias=1, act=b.OGC_ACT_RELU, in_scale=0.05, in_zp=128, out_scale=0.1, out_zp=128, out=0)
+    d.update(kw)
+    return d
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "ogc_mlp.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ogc_[a-z_0-9]+)\s*\(", hdr))
+    assert {"ogc_mlp_plan", "ogc_mlp_prepack_weights", "ogc_mlp_run"} <= declared
+    lib = ctypes.CDLL(b.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(b.EXPORTS)
+
+
+def test_status_strings():
+    for s in range(0, -8, -1):
+        assert b.status_string(s) and b.status_string(s) != "unknown status"
+    assert b.status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(dtype=7), -1),
+    (dict(m=0), -3),
+    (dict(layers=[]), -3),
+    (dict(layers=[layer(8, 8), layer(9, 4)]), -3),                 # k of layer 1 != n of layer 0
+    (dict(layers=[layer(0, 8)]), -3),
+    (dict(layers=[layer(8, 8, act=9)]), -1),
+    (dict(layers=[layer(70000, 8)]), -3),                          # int8 K limit
+    (dict(layers=[layer(8, 8, in_scale=0.0)]), -1),
+    (dict(layers=[layer(8, 8, in_scale=float("inf"))]), -1),
+    (dict(layers=[layer(8, 8, in_zp=256)]), -1),
+    (dict(layers=[layer(8, 8, out_scale=-1.0)]), -1),
+    (dict(layers=[layer(8, 8, out=1), layer(8, 8)]), -1),          # fp32 output only on the last layer
+    (dict(dtype=b.OGC_F32, layers=[layer(8, 8, out=1)]), -1),      # and only for int8
+    (dict(ld_x=7), -3),
+    (dict(ld_y=7), -3),
+    (dict(residual=1), -1),                                        # no residual for int8
+    (dict(dtype=b.OGC_BF16, residual=1, layers=[layer(8, 16)], ld_y=16), -3),
+    (dict(mode=5), -1),
+    (dict(mode=b.OGC_MODE_FUSED, dtype=b.OGC_BF16, layers=[layer(1024, 4096), layer(4096, 1024)], ld_x=1024, ld_y=1024), -2),
+])
+def test_plan_rejects_bad_descriptions(kw, status):
+    args = dict(dtype=b.OGC_I8, m=16, layers=[layer(8, 8)], ld_x=8, ld_y=8, residual=0, mode=0)
+    args.update(kw)
+    with pytest.raises(b.OgcError) as e:
+        b.ogc_mlp_plan(args["dtype"], args["m"], args["layers"], args["ld_x"], args["ld_y"], args["residual"], args["mode"])
+    assert e.value.status == status
+
+
+def test_null_arguments_are_refused():
+    lib = b.lib()
+    assert lib.ogc_mlp_plan(None, None) == -1
+    assert lib.ogc_mlp_packed_bytes(None, None) == -1
+    assert lib.ogc_mlp_run(None, None, None, None, None, None) == -1
+    assert lib.ogc_mlp_prepack_weights(None, None, None, None, None, None) == -1
+    lib.ogc_mlp_destroy(None)
+    assert lib.ogc_mlp_kernel_name(None, 0) is None
+
+
+def test_run_and_prepack_argument_checks_need_no_device():
+    p = b.ogc_mlp_plan(b.OGC_I8, 64, [layer(64, 64), layer(64, 64)], 64, 64, 0, b.OGC_MODE_PER_LAYER)
+    lib = b.lib()
+    fake = 0x7F0000000000  # never dereferenced: every check below fails before any launch
+    assert lib.ogc_mlp_run(p, fake, fake, fake, fake, None) == -6              # not prepacked
+    arr = (ctypes.c_void_p * 2)(fake, fake)
+    assert lib.ogc_mlp_prepack_weights(p, arr, None, arr, fake, None) == -1      # bias missing though has_bias
+    assert lib.ogc_mlp_prepack_weights(p, arr, arr, None, fake, None) == -1      # int8 needs w_scale
+    assert lib.ogc_mlp_prepack_weights(p, arr, arr, arr, fake + 8, None) == -4   # packed misaligned
+    b.ogc_mlp_destroy(p)
+
+
+def test_mode_choice_and_sizes():
+    # config 3 shape: small batch -> fused chain kernel, no workspace
+    dims = [479, 1024, 1024, 512, 256, 1]
+    ls = [layer(dims[i], dims[i + 1]) for i in range(5)]
+    ls[-1].update(out=1, act=b.OGC_ACT_SIGMOID)
+    p = b.ogc_mlp_plan(b.OGC_I8, 256, ls, 479, 1, 0, 0)
+    assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_FUSED
+    assert b.ogc_mlp_workspace_bytes(p) == 0 and b.ogc_mlp_num_launches(p) == 1
+    # packed weights: K padded to 64 (479 -> 512), rows padded to 32/64; per-channel params on top
+    assert b.ogc_mlp_packed_bytes(p) >= 512 * 1024 + 1024 * 1024 + 1024 * 512 + 512 * 256 + 256 * 32
+    assert b.ogc_mlp_packed_bytes(p) < 1.1 * (512 * 1024 + 1024 * 1024 + 1024 * 512 + 512 * 256 + 256 * 64) + 5 * 3 * 4096
+    b.ogc_mlp_destroy(p)
+    # config 5 shape: large batch, wide layers -> per-layer kernels
+    p = b.ogc_mlp_plan(b.OGC_I8, 32768, [layer(1024, 1024, has_bias=0)] * 4, 1024, 1024, 0, 0)
+    assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_PER_LAYER and b.ogc_mlp_num_launches(p) == 4
+    assert b.ogc_mlp_kernel_name(p, 0)
+    b.ogc_mlp_destroy(p)
+
+
+def test_buffer_reuse_is_ping_pong_for_a_chain():
+    """Life-span reuse: layer l's output may take the buffer of layer l-2's output (dead once layer l-1 has
+    run), never that of layer l-1's (live as the input).  Peak = two slots of the largest intermediate."""
+    m = 1000
+    dims = [64, 256, 512, 128, 1024, 64]
+    p = b.ogc_mlp_plan(b.OGC_I8, m, [layer(dims[i], dims[i + 1]) for i in range(5)], 64, 64, 0, b.OGC_MODE_PER_LAYER)
+    slots = [b.ogc_mlp_buffer_assignment(p, l) for l in range(5)]
+    assert [s for s, _ in slots] == [0, 1, 0, 1, -1]
+    for l in range(1, 4):
+        assert slots[l][0] != slots[l - 1][0]
+    mp = (m + 255) // 256 * 256
+    sizes = [mp * dims[l + 1] for l in range(4)]
+    want = max(sizes[0], sizes[2]) + max(sizes[1], sizes[3])
+    assert b.ogc_mlp_workspace_bytes(p) == want
+    assert slots[0][1] == 0 and slots[1][1] == max(sizes[0], sizes[2])
+    with pytest.raises(b.OgcError):
+        b.ogc_mlp_buffer_assignment(p, 5)
+    b.ogc_mlp_destroy(p)
+    # two layers: one slot; one layer: none
+    p = b.ogc_mlp_plan(b.OGC_BF16, 64, [layer(32, 64), layer(64, 32)], 32, 32, 0, b.OGC_MODE_PER_LAYER)
+    assert b.ogc_mlp_workspace_bytes(p) == 256 * 64 * 2
+    b.ogc_mlp_destroy(p)
+    p = b.ogc_mlp_plan(b.OGC_F32, 64, [layer(32, 64)], 32, 64, 0, b.OGC_MODE_PER_LAYER)
+    assert b.ogc_mlp_workspace_bytes(p) == 0
+    b.ogc_mlp_destroy(p)
