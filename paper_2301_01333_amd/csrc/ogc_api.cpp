@@ -88,14 +88,17 @@ int env_int(const char* name, int dflt) {
 
 // Tile choice for a per-layer launch (the role of the template-parameter heuristic of Section III:
 // balance the number of workgroups against the 256 CUs, prefer the largest tile for operand reuse).
-int choose_tile(int m, int n) {
+// dma_ok: the pipelined global->LDS kernel can read this layer's input (always true for KB16 workspace
+// inputs; for the caller's plain x it needs 16-byte aligned rows and no K padding).
+int choose_tile(int m, int n, bool dma_ok) {
     const int forced = env_int("OGC_TILE", -1);
-    if (forced >= 0 && forced < OGC_NUM_TILES) return forced;
-    for (int t = 0; t < OGC_NUM_TILES; ++t) {
+    if (forced >= 0 && forced < OGC_NUM_TILES) return (forced == OGC_TILE_DMA && !dma_ok) ? OGC_TILE_MID : forced;
+    auto tiles = [&](int t) {
         const OgcTileInfo ti = ogc_tile_info(t);
-        const long tiles = (long)((m + ti.bm - 1) / ti.bm) * ((n + ti.bn - 1) / ti.bn);
-        if (tiles >= 256 || t == OGC_NUM_TILES - 1) return t;
-    }
+        return (long)((m + ti.bm - 1) / ti.bm) * ((n + ti.bn - 1) / ti.bn);
+    };
+    if (dma_ok && tiles(OGC_TILE_DMA) >= 96) return OGC_TILE_DMA;
+    if (tiles(OGC_TILE_MID) >= 128) return OGC_TILE_MID;
     return OGC_TILE_SMALL;
 }
 
@@ -214,7 +217,8 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         LayerPlan& lp = p->layers[l];
         const int rows = lp.nb_out * 32 > lp.d.n ? lp.nb_out * 32 : lp.d.n;
         if (mode == OGC_MODE_PER_LAYER) {
-            lp.tile = choose_tile(desc->m, rows);
+            const bool dma_ok = l > 0 || (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k);
+            lp.tile = choose_tile(desc->m, rows, dma_ok);
             lp.npw = (int)round_up((size_t)rows, ogc_tile_info(lp.tile).bn);
         } else {
             lp.tile = -1;

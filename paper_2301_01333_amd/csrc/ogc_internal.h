@@ -54,7 +54,7 @@ struct OgcChainArgs {
     OgcLayerArgs layer[OGC_MAX_LAYERS];
 };
 
-enum { OGC_TILE_BIG = 0, OGC_TILE_MID = 1, OGC_TILE_SMALL = 2, OGC_NUM_TILES = 3 };
+enum { OGC_TILE_BIG = 0, OGC_TILE_MID = 1, OGC_TILE_SMALL = 2, OGC_TILE_DMA = 3, OGC_NUM_TILES = 4 };
 
 struct OgcTileInfo {
     int bn, bm, threads;

@@ -9,6 +9,8 @@
 // which is contiguous both in the plain row-major result and in the next layer's operand layout.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "ogc_internal.h"
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -378,6 +380,181 @@ ogc_layer_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_p
 }
 
 // ------------------------------------------------------------------------------------------------
+// Per-layer kernel, pipelined variant for large layers.  Same tile mathematics as above, but the operand
+// tiles go from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no
+// ds_write) through a ring of NST stages, so that NST-1 k-steps of loads are in flight per workgroup, and
+// the register budget (<= 256 VGPRs) lets two workgroups share a CU: one workgroup's epilogue and barrier
+// waits overlap the other's MFMA main loop.  Both packed weights and KB16 activations are already in
+// lane order, so every wave-level load moves one contiguous KiB on both sides.
+//   workgroup tile: BN = 2*TN*32 channels x BM = 2*TM*32 batch rows, 4 waves as 2 x 2, 64-byte k-steps
+//   stage layout  : [BN/32 weight chunks of 2 KiB][BM/32 activation chunks of 2 KiB]
+// X_PLAIN reads the caller's row-major x (16-byte aligned rows, K*elt a multiple of 64; rows past M are
+// clamped to the last row and never stored); u8 inputs are flipped to s8 after the LDS read.
+// LDS reads are issued from inline assembly so that the only waits on the load counter are the explicit
+// ones below (the loads land in order: waiting until at most LOADS*(NST-2) remain guarantees the oldest
+// stage is complete).
+// ------------------------------------------------------------------------------------------------
+OGC_DEV uint32_t lds_addr_of(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+template <int OFF> OGC_DEV v4i lds_read_b128(uint32_t addr) {
+    v4i r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+// Waits for every outstanding LDS read of this wave; the fragments pass through the statement so that no
+// consumer can be scheduled above it.
+template <int NW, int NX> OGC_DEV void lds_wait_all(v4i (&w)[NW], v4i (&x)[NX]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < NW; ++i) asm volatile("" : "+v"(w[i]));
+#pragma unroll
+    for (int j = 0; j < NX; ++j) asm volatile("" : "+v"(x[j]));
+}
+
+template <int N> OGC_DEV void wait_loads_then_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int TN, int TM, int NST> struct DmaCfg {
+    enum {
+        BN = 2 * TN * 32, BM = 2 * TM * 32, NT = 256,
+        W_OPS = BN / 16, X_OPS = BM / 16, OPS = W_OPS + X_OPS, OPS_PER_WAVE = OPS / 4,
+        STAGE = (BN + BM) * 64, LDS = STAGE * NST
+    };
+    static_assert(OPS % 4 == 0, "stage must split evenly over 4 waves");
+};
+
+template <int DT, int TN, int TM, int NST, int X_PLAIN, int OUT_PLAIN>
+__global__ void __launch_bounds__(256, 2)
+ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_per_xcd) {
+    typedef DmaCfg<TN, TM, NST> C;
+    extern __shared__ __align__(1024) uint8_t smem[];
+    const int wg = blockIdx.x;
+    const int t = (wg & 7) * tiles_per_xcd + (wg >> 3);
+    if (t >= tiles_total) return;
+    const int n_base = (t % tiles_n) * C::BN, m_base = (t / tiles_n) * C::BM;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave & 1, wm = wave >> 1;
+    const int KT = a.KC >> 2;
+
+    // Per-wave load descriptors: op o of a stage is 1 KiB = two 512-byte slabs of one 32-row chunk.
+    const uint8_t* gsrc[C::OPS_PER_WAVE];
+    long long gstep[C::OPS_PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < C::OPS_PER_WAVE; ++i) {
+        const int o = wave * C::OPS_PER_WAVE + i;
+        if (o < C::W_OPS) {
+            gsrc[i] = a.w + ((size_t)((n_base >> 5) + (o >> 1)) * a.KC + (o & 1) * 2) * 512 + lane * 16;
+            gstep[i] = 2048;
+        } else {
+            const int ox = o - C::W_OPS;
+            if constexpr (X_PLAIN) {
+                int row = m_base + (ox >> 1) * 32 + (lane & 31);
+                row = row < a.M ? row : a.M - 1;
+                gsrc[i] = a.x + (long long)row * a.ldx_bytes + ((ox & 1) * 2 + (lane >> 5)) * 16;
+                gstep[i] = 64;
+            } else {
+                gsrc[i] = a.x + ((size_t)((m_base >> 5) + (ox >> 1)) * a.KC + (ox & 1) * 2) * 512 + lane * 16;
+                gstep[i] = 2048;
+            }
+        }
+    }
+    auto issue = [&](int kt, int stage) {
+        uint8_t* dst = smem + stage * C::STAGE + wave * C::OPS_PER_WAVE * 1024;
+#pragma unroll
+        for (int i = 0; i < C::OPS_PER_WAVE; ++i)
+            __builtin_amdgcn_global_load_lds((const void*)(gsrc[i] + (long long)kt * gstep[i]),
+                                             (__attribute__((address_space(3))) void*)(dst + i * 1024), 16, 0, 0);
+    };
+
+    typename AccT<DT>::type acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const uint32_t lds0 = lds_addr_of(smem);
+    const uint32_t w_rd = lds0 + (wn * TN) * 2048 + lane * 16;
+    const uint32_t x_rd = lds0 + C::BN * 64 + (wm * TM) * 2048 + lane * 16;
+
+    auto compute = [&](int stage) {
+        const uint32_t wa = w_rd + stage * C::STAGE, xa = x_rd + stage * C::STAGE;
+        v4i wf0[TN], xf0[TM], wf1[TN], xf1[TM];
+        auto rd = [&](v4i(&wf)[TN], v4i(&xf)[TM], auto sub) {
+            constexpr int S = decltype(sub)::value;
+            wf[0] = lds_read_b128<S * 1024>(wa);
+            if constexpr (TN > 1) wf[1] = lds_read_b128<2048 + S * 1024>(wa);
+            if constexpr (TN > 2) wf[2] = lds_read_b128<4096 + S * 1024>(wa);
+            if constexpr (TN > 3) wf[3] = lds_read_b128<6144 + S * 1024>(wa);
+            xf[0] = lds_read_b128<S * 1024>(xa);
+            if constexpr (TM > 1) xf[1] = lds_read_b128<2048 + S * 1024>(xa);
+            if constexpr (TM > 2) xf[2] = lds_read_b128<4096 + S * 1024>(xa);
+            if constexpr (TM > 3) xf[3] = lds_read_b128<6144 + S * 1024>(xa);
+        };
+        auto flip = [&](v4i(&xf)[TM]) {
+            if constexpr (X_PLAIN && DT == OGC_I8) {
+#pragma unroll
+                for (int j = 0; j < TM; ++j) xf[j] = xf[j] ^ (v4i){(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
+            }
+        };
+        rd(wf0, xf0, std::integral_constant<int, 0>());
+        lds_wait_all(wf0, xf0);
+        rd(wf1, xf1, std::integral_constant<int, 1>());
+        flip(xf0);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j) mma32<DT>(acc[i][j], wf0[i], xf0[j]);
+        lds_wait_all(wf1, xf1);
+        flip(xf1);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j) mma32<DT>(acc[i][j], wf1[i], xf1[j]);
+    };
+
+    // prologue: NST-1 stages in flight
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < KT) issue(s, s);
+    int stage = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        // loads outstanding here (oldest first): stages kt .. min(kt+NST-2, KT-1)
+        const int newer = (KT - 1 - kt) < (NST - 2) ? (KT - 1 - kt) : (NST - 2);
+        if (newer >= 2) wait_loads_then_barrier<2 * C::OPS_PER_WAVE>();
+        else if (newer == 1) wait_loads_then_barrier<C::OPS_PER_WAVE>();
+        else wait_loads_then_barrier<0>();
+        // every wave has finished reading stage kt-1 (previous iteration): its buffer is free again
+        const int nk = kt + NST - 1;
+        int nstage = stage + NST - 1;
+        nstage = nstage >= NST ? nstage - NST : nstage;
+        if (nk < KT) issue(nk, nstage);
+        compute(stage);
+        stage = stage + 1 == NST ? 0 : stage + 1;
+    }
+
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+        const int n0 = n_base + (wn * TN + i) * 32;
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int m0 = m_base + (wm * TM + j) * 32;
+            if constexpr (OUT_PLAIN) {
+                if (n0 < a.N && m0 < a.M) epilogue_block<DT, 1>(acc[i][j], a, n0, m0, lane, (uint8_t*)nullptr);
+            } else {
+                if ((n0 >> 5) < a.NB_out)
+                    epilogue_block<DT, 0>(acc[i][j], a, n0, m0, lane, a.y + (size_t)(m0 >> 5) * a.KC_out * 512);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Fused multi-layer chain kernel (coarse-grain fusion, Section V: the batch loops of consecutive layers
 // are merged, so a batch tile's activations stay in the fastest memory for the next matmul).  One
 // workgroup owns 32 batch rows for the whole chain.  The tile's activations ping-pong between two LDS
@@ -507,7 +684,21 @@ template <int TILE> static OgcTileInfo tile_info_t() {
     return i;
 }
 
+// The pipelined kernel's shape: 128 channels x 256 batch rows, 3 stages of 24 KiB (two workgroups per CU).
+#define OGC_DMA_TN 2
+#define OGC_DMA_TM 4
+#define OGC_DMA_NST 3
+
 extern "C" OgcTileInfo ogc_tile_info(int tile) {
+    if (tile == OGC_TILE_DMA) {
+        typedef DmaCfg<OGC_DMA_TN, OGC_DMA_TM, OGC_DMA_NST> C;
+        OgcTileInfo i;
+        i.bn = C::BN;
+        i.bm = C::BM;
+        i.threads = C::NT;
+        i.lds_bytes = C::LDS;
+        return i;
+    }
     switch (tile) {
     case OGC_TILE_BIG: return tile_info_t<OGC_TILE_BIG>();
     case OGC_TILE_MID: return tile_info_t<OGC_TILE_MID>();
@@ -549,8 +740,44 @@ static int launch_layer_tile(int tile, int xp, int op, const OgcLayerArgs* a, hi
     }
 }
 
+template <int DT, int XP, int OP>
+static int launch_dma_t(const OgcLayerArgs* a, hipStream_t stream) {
+    typedef DmaCfg<OGC_DMA_TN, OGC_DMA_TM, OGC_DMA_NST> C;
+    auto kern = ogc_layer_dma_kernel<DT, OGC_DMA_TN, OGC_DMA_TM, OGC_DMA_NST, XP, OP>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+        if (e != hipSuccess) return (int)e;
+        attr_set = true;
+    }
+    const int nrows = OP ? a->N : a->NB_out * 32;
+    const int tiles_n = (nrows + C::BN - 1) / C::BN;
+    const int tiles_m = (a->M + C::BM - 1) / C::BM;
+    const int total = tiles_n * tiles_m;
+    const int per_xcd = (total + 7) / 8;
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(C::NT), C::LDS, stream, *a, tiles_n, total, per_xcd);
+    return (int)hipGetLastError();
+}
+
+template <int DT>
+static int launch_dma_io(int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
+    if (xp) return op ? launch_dma_t<DT, 1, 1>(a, s) : launch_dma_t<DT, 1, 0>(a, s);
+    return op ? launch_dma_t<DT, 0, 1>(a, s) : launch_dma_t<DT, 0, 0>(a, s);
+}
+
 extern "C" int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain, const OgcLayerArgs* a, void* stream) {
     hipStream_t s = (hipStream_t)stream;
+    if (tile == OGC_TILE_DMA) {
+        if (x_plain && !a->x_vec_ok) {
+            tile = OGC_TILE_MID;  // caller's x is not 16-byte aligned: same channel padding, register-staged loads
+        } else {
+            switch (dtype) {
+            case OGC_F32: return launch_dma_io<OGC_F32>(x_plain, out_plain, a, s);
+            case OGC_BF16: return launch_dma_io<OGC_BF16>(x_plain, out_plain, a, s);
+            default: return launch_dma_io<OGC_I8>(x_plain, out_plain, a, s);
+            }
+        }
+    }
     switch (dtype) {
     case OGC_F32: return launch_layer_tile<OGC_F32>(tile, x_plain, out_plain, a, s);
     case OGC_BF16: return launch_layer_tile<OGC_BF16>(tile, x_plain, out_plain, a, s);
@@ -601,5 +828,7 @@ extern "C" int ogc_launch_prepack_params(int dtype, const void* w, const float* 
     return (int)hipGetLastError();
 }
 
-extern "C" const char* ogc_layer_kernel_name(int, int, int, int) { return "ogc_layer_kernel"; }
+extern "C" const char* ogc_layer_kernel_name(int, int tile, int, int) {
+    return tile == OGC_TILE_DMA ? "ogc_layer_dma_kernel" : "ogc_layer_kernel";
+}
 extern "C" const char* ogc_fused_kernel_name(int) { return "ogc_fused_chain_kernel"; }
