@@ -36,6 +36,49 @@ def build_library(verbose: bool = True) -> str:
     return LIB
 
 
+def check_stream_kernel_registers(verbose: bool = True) -> None:
+    """The stream kernel keeps its operands and accumulators in v80..v255 behind the compiler's back
+    (amdgpu_num_vgpr caps the compiler below v80).  This compiles the kernels to assembly and fails if any
+    compiler-generated instruction of those kernels names a register at or above v80, or if they contain calls."""
+    import re
+    import tempfile
+
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    with tempfile.TemporaryDirectory() as td:
+        out = os.path.join(td, "k.s")
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off", "-Xclang", "-target-feature",
+               "-Xclang", "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-S", "--cuda-device-only",
+               "-o", out, os.path.join(CSRC, "ogc_kernels.hip")]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc -S failed\n" + r.stdout)
+        text = open(out).read()
+    reg = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
+    checked = 0
+    for m in re.finditer(r"^(_Z20ogc_layer_dma_kernel\w*):[^\n]*\n(.*?)\n\ts_endpgm", text, re.S | re.M):
+        name, body = m.group(1), m.group(2)
+        in_asm, worst = False, -1
+        for line in body.splitlines():
+            if "#ASMSTART" in line:
+                in_asm = True
+            elif "#ASMEND" in line:
+                in_asm = False
+            elif not in_asm:
+                code = line.split(";")[0]
+                if "s_swappc" in code or "s_setpc" in code:
+                    raise RuntimeError("%s contains a call: %s" % (name, line.strip()))
+                for a, b, c in reg.findall(code):
+                    worst = max(worst, int(a or c))
+        if worst >= 80:
+            raise RuntimeError("%s: compiler code uses v%d, which the hand-scheduled loop owns" % (name, worst))
+        checked += 1
+    if checked == 0:
+        raise RuntimeError("no stream kernels found in the assembly")
+    if verbose:
+        print("stream kernels checked: %d (compiler stays below v80, no calls)" % checked, flush=True)
+
+
 if __name__ == "__main__":
     print(build_library())
+    check_stream_kernel_registers()
     sys.exit(0)

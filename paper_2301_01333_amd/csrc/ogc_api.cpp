@@ -92,11 +92,13 @@ int env_int(const char* name, int dflt) {
 // inputs; for the caller's plain x it needs 16-byte aligned rows and no K padding).
 int choose_tile(int m, int n, bool dma_ok) {
     const int forced = env_int("OGC_TILE", -1);
-    if (forced >= 0 && forced < OGC_NUM_TILES) return (forced == OGC_TILE_DMA && !dma_ok) ? OGC_TILE_MID : forced;
+    if (forced >= 0 && forced < OGC_NUM_TILES)
+        return ((forced == OGC_TILE_DMA || forced == OGC_TILE_DMA8) && !dma_ok) ? OGC_TILE_MID : forced;
     auto tiles = [&](int t) {
         const OgcTileInfo ti = ogc_tile_info(t);
         return (long)((m + ti.bm - 1) / ti.bm) * ((n + ti.bn - 1) / ti.bn);
     };
+    if (dma_ok && tiles(OGC_TILE_DMA8) >= 224) return OGC_TILE_DMA8;
     if (dma_ok && tiles(OGC_TILE_DMA) >= 96) return OGC_TILE_DMA;
     if (tiles(OGC_TILE_MID) >= 128) return OGC_TILE_MID;
     return OGC_TILE_SMALL;
@@ -154,6 +156,16 @@ void fill_args(const ogc_mlp_plan_s* p, int l, const uint8_t* packed, OgcLayerAr
     a->out_f32 = (lp.d.out == OGC_OUT_F32) ? 1 : 0;
     a->inv_cs = lp.inv_cs;
     a->zp_out = (float)lp.d.out_zp;
+    a->has_bias = lp.d.has_bias;
+    a->q_hi = 255.0f - (float)lp.d.out_zp;
+    const bool internal = l + 1 < (int)p->layers.size();  // result stays in the s8-with-128-subtracted form
+    if (internal && lp.d.out_zp == 128) {
+        a->q_add = 0;
+        a->q_xor = 0;
+    } else {
+        a->q_add = (uint32_t)lp.d.out_zp * 0x01010101u;
+        a->q_xor = internal ? 0x80808080u : 0u;
+    }
 }
 
 }  // namespace
@@ -217,7 +229,9 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         LayerPlan& lp = p->layers[l];
         const int rows = lp.nb_out * 32 > lp.d.n ? lp.nb_out * 32 : lp.d.n;
         if (mode == OGC_MODE_PER_LAYER) {
-            const bool dma_ok = l > 0 || (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k);
+            // the stream kernel keeps its accumulators in fixed registers: no out-of-line calls (sigmoid) in it
+            const bool dma_ok = desc->dtype != OGC_F32 && lp.d.act != OGC_ACT_SIGMOID &&
+                                (l > 0 || (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
             lp.tile = choose_tile(desc->m, rows, dma_ok);
             lp.npw = (int)round_up((size_t)rows, ogc_tile_info(lp.tile).bn);
         } else {

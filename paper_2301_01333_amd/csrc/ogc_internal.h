@@ -46,6 +46,9 @@ struct OgcLayerArgs {
     int32_t res_vec_ok;
     float inv_cs;          // I8: 1.0f/out_scale
     float zp_out;          // I8: (float)out_zp
+    int32_t has_bias;
+    float q_hi;            // I8: 255 - out_zp
+    uint32_t q_add, q_xor; // I8: packed-byte zero-point add and u8 -> internal s8 flip for four results at once
 };
 
 struct OgcChainArgs {
@@ -54,7 +57,7 @@ struct OgcChainArgs {
     OgcLayerArgs layer[OGC_MAX_LAYERS];
 };
 
-enum { OGC_TILE_BIG = 0, OGC_TILE_MID = 1, OGC_TILE_SMALL = 2, OGC_TILE_DMA = 3, OGC_NUM_TILES = 4 };
+enum { OGC_TILE_BIG = 0, OGC_TILE_MID = 1, OGC_TILE_SMALL = 2, OGC_TILE_DMA = 3, OGC_TILE_DMA8 = 4, OGC_NUM_TILES = 5 };
 
 struct OgcTileInfo {
     int bn, bm, threads;

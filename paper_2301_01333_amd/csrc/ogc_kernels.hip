@@ -42,10 +42,11 @@ template <int DT> OGC_DEV void mma32(typename AccT<DT>::type& c, const v4i& w, c
     }
 }
 
-OGC_DEV uint32_t f32_to_bf16_rne(float f) {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+// Two fp32 -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32); lo goes to bits 15:0.
+OGC_DEV uint32_t f32x2_to_bf16x2(float lo, float hi) {
+    const v2bf p = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, p);
 }
 OGC_DEV float bf16_to_f32(uint32_t h) { return __builtin_bit_cast(float, h << 16); }
 
@@ -63,18 +64,31 @@ OGC_DEV void swap32(uint32_t& a, uint32_t& b) {
 //   I8: y = act(fma((float)(acc + ncomp[n]), scale[n], bias[n])); unless out_f32:
 //       out = min(max(rne(y * inv_cs) + zp_out, 0), 255)      (an integer-valued float)
 // ------------------------------------------------------------------------------------------------
-OGC_DEV float act_apply(float y, int act) {
-    if (act == OGC_ACT_RELU) return (y > 0.0f) ? y : 0.0f;
-    if (act == OGC_ACT_GELU_TANH) {
-        // 0.5*y*(1+tanh(u)) == y / (1 + exp(-2u)),  u = sqrt(2/pi)*(y + 0.044715*y^3)
-        float u = 0.7978845608028654f * (y + 0.044715f * y * y * y);
-        return __fdividef(y, 1.0f + __expf(-2.0f * u));
+// Accurate logistic function (correctly rounded division, libm-grade exp); kept out of line: it is the
+// rare last-layer activation and its code would otherwise be replicated for every accumulator block.
+static __device__ __attribute__((noinline)) float sigmoid_accurate(float y) { return 1.0f / (1.0f + expf(-y)); }
+
+// Applies the activation to the 16 values of a lane.  `act` is uniform over the launch.
+// CALLS = false leaves out the sigmoid (an out-of-line call), for kernels that keep state in fixed registers.
+template <bool CALLS> OGC_DEV void act_apply16(float (&out)[16], int act) {
+    if (act == OGC_ACT_RELU) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) out[i] = __builtin_fmaxf(out[i], 0.0f);
+    } else if (act == OGC_ACT_GELU_TANH) {
+        // 0.5*y*(1+tanh(u)) == y / (1 + exp(-2u)), u = sqrt(2/pi)*(y + 0.044715*y^3);
+        // exp(-2u) = exp2(y*(k1 + k2*y^2)) with k1 = -2*sqrt(2/pi)*log2(e), k2 = k1*0.044715
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float y = out[i];
+            const float arg = y * __builtin_fmaf(-0.10294324f, y * y, -2.3022082f);
+            out[i] = y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(arg));
+        }
+    } else if (CALLS && act == OGC_ACT_SIGMOID) {
+        for (int i = 0; i < 16; ++i) out[i] = sigmoid_accurate(out[i]);
     }
-    if (act == OGC_ACT_SIGMOID) return 1.0f / (1.0f + expf(-y));
-    return y;
 }
 
-template <int DT>
+template <int DT, bool CALLS>
 OGC_DEV void epilogue_values(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, int n0, int h, float (&out)[16]) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -94,11 +108,7 @@ OGC_DEV void epilogue_values(const typename AccT<DT>::type& acc, const OgcLayerA
             for (int e = 0; e < 4; ++e) out[4 * g + e] = acc[4 * g + e] + b4[e];
         }
     }
-    const int act = a.act;
-    if (act != OGC_ACT_NONE) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) out[i] = act_apply(out[i], act);
-    }
+    act_apply16<CALLS>(out, a.act);
     if constexpr (DT == OGC_I8) {
         if (!a.out_f32) {
             const float inv = a.inv_cs, zp = a.zp_out;
@@ -126,8 +136,8 @@ OGC_DEV void pack_block(const float (&out)[16], bool bias_s8, v4i (&chunk)[EO]) 
                          ((uint32_t)out[4 * g + 3] << 24);
             dw[g][0] = bias_s8 ? (p ^ 0x80808080u) : p;
         } else if constexpr (EO == 2) {
-            dw[g][0] = f32_to_bf16_rne(out[4 * g]) | (f32_to_bf16_rne(out[4 * g + 1]) << 16);
-            dw[g][1] = f32_to_bf16_rne(out[4 * g + 2]) | (f32_to_bf16_rne(out[4 * g + 3]) << 16);
+            dw[g][0] = f32x2_to_bf16x2(out[4 * g], out[4 * g + 1]);
+            dw[g][1] = f32x2_to_bf16x2(out[4 * g + 2], out[4 * g + 3]);
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) dw[g][e] = __builtin_bit_cast(uint32_t, out[4 * g + e]);
@@ -203,11 +213,58 @@ OGC_DEV void store_plain(const v4i (&chunk)[EO], const OgcLayerArgs& a, int m, i
 // Complete epilogue of one 32x32 block.  OUT_PLAIN = 0: write the block into a KB16 activation buffer at
 // `yblk` (base of the 32-row block row: global workspace or LDS), directly in the next layer's operand
 // layout (layout propagation, Section V).  OUT_PLAIN = 1: write to the caller's y.
-template <int DT, int OUT_PLAIN, typename YP>
+// Int8 layer with ReLU and a requantized u8 result: the common case, five VALU operations per element.
+// Equivalent, value for value, to the reference sequence relu -> *inv -> rne -> +zp -> clamp[0,255]:
+//   t = y*inv; t = med3(t, 0, 255-zp)  (a negative y lands on 0 exactly as relu(y)=0 does; 255-zp is an
+//   integer, so clamping before the rounding cannot change which integer is reached);
+//   v_cvt_pk_u8_f32 rounds to nearest even and packs the byte; zp is added to four packed bytes at once
+//   (no byte can carry: each is <= 255-zp).  q_add / q_xor are precomputed on the host: zp*0x01010101 and,
+//   for the internal s8 form, 0x80808080 (both 0 when zp = 128 and the result stays internal).
+template <int OUT_PLAIN, typename YP>
+OGC_DEV void epilogue_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, int n0, int m0, int lane, YP yblk) {
+    const int h = lane >> 5, mm = lane & 31;
+    const float inv = a.inv_cs, hi = a.q_hi;
+    uint32_t dw[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int n = n0 + 8 * g + 4 * h;
+        const v4f s4 = *(const v4f*)(a.scale + n);
+        v4f b4 = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (a.has_bias) b4 = *(const v4f*)(a.bias + n);
+        v4i c4 = {0, 0, 0, 0};
+        if (a.has_comp) c4 = *(const v4i*)(a.ncomp + n);
+        uint32_t p = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float f = (float)(acc[4 * g + e] + c4[e]);
+            const float y = __builtin_fmaf(f, s4[e], b4[e]);
+            const float t = __builtin_amdgcn_fmed3f(y * inv, 0.0f, hi);
+            p = __builtin_amdgcn_cvt_pk_u8_f32(t, e, p);
+        }
+        dw[g] = (p + a.q_add) ^ a.q_xor;
+    }
+    swap32(dw[0], dw[2]);
+    swap32(dw[1], dw[3]);
+    const v4i ch = {(int)dw[0], (int)dw[2], (int)dw[1], (int)dw[3]};  // 16 consecutive channels from n0+16h
+    if constexpr (OUT_PLAIN) {
+        const v4i arr[1] = {ch};
+        store_plain<1>(arr, a, m0 + mm, n0 + 16 * h);
+    } else {
+        *(v4i*)(yblk + ((size_t)((n0 >> 5) * 2 + h) * 32 + mm) * 16) = ch;
+    }
+}
+
+template <int DT, int OUT_PLAIN, bool CALLS = true, typename YP>
 OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, int n0, int m0, int lane, YP yblk) {
+    if constexpr (DT == OGC_I8) {
+        if (a.act == OGC_ACT_RELU && !a.out_f32) {
+            epilogue_block_i8_relu<OUT_PLAIN>(acc, a, n0, m0, lane, yblk);
+            return;
+        }
+    }
     const int h = lane >> 5, mm = lane & 31;
     float out[16];
-    epilogue_values<DT>(acc, a, n0, h, out);
+    epilogue_values<DT, CALLS>(acc, a, n0, h, out);
     constexpr int E = Elt<DT>::size;
     if constexpr (OUT_PLAIN) {
         if constexpr (DT != OGC_I8) {
@@ -379,180 +436,7 @@ ogc_layer_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_p
     }
 }
 
-// ------------------------------------------------------------------------------------------------
-// Per-layer kernel, pipelined variant for large layers.  Same tile mathematics as above, but the operand
-// tiles go from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no
-// ds_write) through a ring of NST stages, so that NST-1 k-steps of loads are in flight per workgroup, and
-// the register budget (<= 256 VGPRs) lets two workgroups share a CU: one workgroup's epilogue and barrier
-// waits overlap the other's MFMA main loop.  Both packed weights and KB16 activations are already in
-// lane order, so every wave-level load moves one contiguous KiB on both sides.
-//   workgroup tile: BN = 2*TN*32 channels x BM = 2*TM*32 batch rows, 4 waves as 2 x 2, 64-byte k-steps
-//   stage layout  : [BN/32 weight chunks of 2 KiB][BM/32 activation chunks of 2 KiB]
-// X_PLAIN reads the caller's row-major x (16-byte aligned rows, K*elt a multiple of 64; rows past M are
-// clamped to the last row and never stored); u8 inputs are flipped to s8 after the LDS read.
-// LDS reads are issued from inline assembly so that the only waits on the load counter are the explicit
-// ones below (the loads land in order: waiting until at most LOADS*(NST-2) remain guarantees the oldest
-// stage is complete).
-// ------------------------------------------------------------------------------------------------
-OGC_DEV uint32_t lds_addr_of(const void* p) {
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
-}
-
-template <int OFF> OGC_DEV v4i lds_read_b128(uint32_t addr) {
-    v4i r;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-    return r;
-}
-
-// Waits for every outstanding LDS read of this wave; the fragments pass through the statement so that no
-// consumer can be scheduled above it.
-template <int NW, int NX> OGC_DEV void lds_wait_all(v4i (&w)[NW], v4i (&x)[NX]) {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-    for (int i = 0; i < NW; ++i) asm volatile("" : "+v"(w[i]));
-#pragma unroll
-    for (int j = 0; j < NX; ++j) asm volatile("" : "+v"(x[j]));
-}
-
-template <int N> OGC_DEV void wait_loads_then_barrier() {
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
-}
-
-template <int TN, int TM, int NST> struct DmaCfg {
-    enum {
-        BN = 2 * TN * 32, BM = 2 * TM * 32, NT = 256,
-        W_OPS = BN / 16, X_OPS = BM / 16, OPS = W_OPS + X_OPS, OPS_PER_WAVE = OPS / 4,
-        STAGE = (BN + BM) * 64, LDS = STAGE * NST
-    };
-    static_assert(OPS % 4 == 0, "stage must split evenly over 4 waves");
-};
-
-template <int DT, int TN, int TM, int NST, int X_PLAIN, int OUT_PLAIN>
-__global__ void __launch_bounds__(256, 2)
-ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_per_xcd) {
-    typedef DmaCfg<TN, TM, NST> C;
-    extern __shared__ __align__(1024) uint8_t smem[];
-    const int wg = blockIdx.x;
-    const int t = (wg & 7) * tiles_per_xcd + (wg >> 3);
-    if (t >= tiles_total) return;
-    const int n_base = (t % tiles_n) * C::BN, m_base = (t / tiles_n) * C::BM;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wn = wave & 1, wm = wave >> 1;
-    const int KT = a.KC >> 2;
-
-    // Per-wave load descriptors: op o of a stage is 1 KiB = two 512-byte slabs of one 32-row chunk.
-    const uint8_t* gsrc[C::OPS_PER_WAVE];
-    long long gstep[C::OPS_PER_WAVE];
-#pragma unroll
-    for (int i = 0; i < C::OPS_PER_WAVE; ++i) {
-        const int o = wave * C::OPS_PER_WAVE + i;
-        if (o < C::W_OPS) {
-            gsrc[i] = a.w + ((size_t)((n_base >> 5) + (o >> 1)) * a.KC + (o & 1) * 2) * 512 + lane * 16;
-            gstep[i] = 2048;
-        } else {
-            const int ox = o - C::W_OPS;
-            if constexpr (X_PLAIN) {
-                int row = m_base + (ox >> 1) * 32 + (lane & 31);
-                row = row < a.M ? row : a.M - 1;
-                gsrc[i] = a.x + (long long)row * a.ldx_bytes + ((ox & 1) * 2 + (lane >> 5)) * 16;
-                gstep[i] = 64;
-            } else {
-                gsrc[i] = a.x + ((size_t)((m_base >> 5) + (ox >> 1)) * a.KC + (ox & 1) * 2) * 512 + lane * 16;
-                gstep[i] = 2048;
-            }
-        }
-    }
-    auto issue = [&](int kt, int stage) {
-        uint8_t* dst = smem + stage * C::STAGE + wave * C::OPS_PER_WAVE * 1024;
-#pragma unroll
-        for (int i = 0; i < C::OPS_PER_WAVE; ++i)
-            __builtin_amdgcn_global_load_lds((const void*)(gsrc[i] + (long long)kt * gstep[i]),
-                                             (__attribute__((address_space(3))) void*)(dst + i * 1024), 16, 0, 0);
-    };
-
-    typename AccT<DT>::type acc[TN][TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-
-    const uint32_t lds0 = lds_addr_of(smem);
-    const uint32_t w_rd = lds0 + (wn * TN) * 2048 + lane * 16;
-    const uint32_t x_rd = lds0 + C::BN * 64 + (wm * TM) * 2048 + lane * 16;
-
-    auto compute = [&](int stage) {
-        const uint32_t wa = w_rd + stage * C::STAGE, xa = x_rd + stage * C::STAGE;
-        v4i wf0[TN], xf0[TM], wf1[TN], xf1[TM];
-        auto rd = [&](v4i(&wf)[TN], v4i(&xf)[TM], auto sub) {
-            constexpr int S = decltype(sub)::value;
-            wf[0] = lds_read_b128<S * 1024>(wa);
-            if constexpr (TN > 1) wf[1] = lds_read_b128<2048 + S * 1024>(wa);
-            if constexpr (TN > 2) wf[2] = lds_read_b128<4096 + S * 1024>(wa);
-            if constexpr (TN > 3) wf[3] = lds_read_b128<6144 + S * 1024>(wa);
-            xf[0] = lds_read_b128<S * 1024>(xa);
-            if constexpr (TM > 1) xf[1] = lds_read_b128<2048 + S * 1024>(xa);
-            if constexpr (TM > 2) xf[2] = lds_read_b128<4096 + S * 1024>(xa);
-            if constexpr (TM > 3) xf[3] = lds_read_b128<6144 + S * 1024>(xa);
-        };
-        auto flip = [&](v4i(&xf)[TM]) {
-            if constexpr (X_PLAIN && DT == OGC_I8) {
-#pragma unroll
-                for (int j = 0; j < TM; ++j) xf[j] = xf[j] ^ (v4i){(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
-            }
-        };
-        rd(wf0, xf0, std::integral_constant<int, 0>());
-        lds_wait_all(wf0, xf0);
-        rd(wf1, xf1, std::integral_constant<int, 1>());
-        flip(xf0);
-#pragma unroll
-        for (int i = 0; i < TN; ++i)
-#pragma unroll
-            for (int j = 0; j < TM; ++j) mma32<DT>(acc[i][j], wf0[i], xf0[j]);
-        lds_wait_all(wf1, xf1);
-        flip(xf1);
-#pragma unroll
-        for (int i = 0; i < TN; ++i)
-#pragma unroll
-            for (int j = 0; j < TM; ++j) mma32<DT>(acc[i][j], wf1[i], xf1[j]);
-    };
-
-    // prologue: NST-1 stages in flight
-#pragma unroll
-    for (int s = 0; s < NST - 1; ++s)
-        if (s < KT) issue(s, s);
-    int stage = 0;
-    for (int kt = 0; kt < KT; ++kt) {
-        // loads outstanding here (oldest first): stages kt .. min(kt+NST-2, KT-1)
-        const int newer = (KT - 1 - kt) < (NST - 2) ? (KT - 1 - kt) : (NST - 2);
-        if (newer >= 2) wait_loads_then_barrier<2 * C::OPS_PER_WAVE>();
-        else if (newer == 1) wait_loads_then_barrier<C::OPS_PER_WAVE>();
-        else wait_loads_then_barrier<0>();
-        // every wave has finished reading stage kt-1 (previous iteration): its buffer is free again
-        const int nk = kt + NST - 1;
-        int nstage = stage + NST - 1;
-        nstage = nstage >= NST ? nstage - NST : nstage;
-        if (nk < KT) issue(nk, nstage);
-        compute(stage);
-        stage = stage + 1 == NST ? 0 : stage + 1;
-    }
-
-#pragma unroll
-    for (int i = 0; i < TN; ++i) {
-        const int n0 = n_base + (wn * TN + i) * 32;
-#pragma unroll
-        for (int j = 0; j < TM; ++j) {
-            const int m0 = m_base + (wm * TM + j) * 32;
-            if constexpr (OUT_PLAIN) {
-                if (n0 < a.N && m0 < a.M) epilogue_block<DT, 1>(acc[i][j], a, n0, m0, lane, (uint8_t*)nullptr);
-            } else {
-                if ((n0 >> 5) < a.NB_out)
-                    epilogue_block<DT, 0>(acc[i][j], a, n0, m0, lane, a.y + (size_t)(m0 >> 5) * a.KC_out * 512);
-            }
-        }
-    }
-}
+#include "ogc_layer_stream.h"
 
 // ------------------------------------------------------------------------------------------------
 // Fused multi-layer chain kernel (coarse-grain fusion, Section V: the batch loops of consecutive layers
@@ -684,19 +568,16 @@ template <int TILE> static OgcTileInfo tile_info_t() {
     return i;
 }
 
-// The pipelined kernel's shape: 128 channels x 256 batch rows, 3 stages of 24 KiB (two workgroups per CU).
-#define OGC_DMA_TN 2
-#define OGC_DMA_TM 4
-#define OGC_DMA_NST 3
-
 extern "C" OgcTileInfo ogc_tile_info(int tile) {
-    if (tile == OGC_TILE_DMA) {
-        typedef DmaCfg<OGC_DMA_TN, OGC_DMA_TM, OGC_DMA_NST> C;
+    if (tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8) {
         OgcTileInfo i;
-        i.bn = C::BN;
-        i.bm = C::BM;
-        i.threads = C::NT;
-        i.lds_bytes = C::LDS;
+        if (tile == OGC_TILE_DMA) {
+            typedef StreamCfg<0> C;
+            i.bn = C::BN, i.bm = C::BM, i.threads = C::NT, i.lds_bytes = C::LDS;
+        } else {
+            typedef StreamCfg<1> C;
+            i.bn = C::BN, i.bm = C::BM, i.threads = C::NT, i.lds_bytes = C::LDS;
+        }
         return i;
     }
     switch (tile) {
@@ -740,10 +621,10 @@ static int launch_layer_tile(int tile, int xp, int op, const OgcLayerArgs* a, hi
     }
 }
 
-template <int DT, int XP, int OP>
+template <int DT, int SHAPE, int XP, int OP>
 static int launch_dma_t(const OgcLayerArgs* a, hipStream_t stream) {
-    typedef DmaCfg<OGC_DMA_TN, OGC_DMA_TM, OGC_DMA_NST> C;
-    auto kern = ogc_layer_dma_kernel<DT, OGC_DMA_TN, OGC_DMA_TM, OGC_DMA_NST, XP, OP>;
+    typedef StreamCfg<SHAPE> C;
+    auto kern = ogc_layer_dma_kernel<DT, SHAPE, XP, OP>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
@@ -755,27 +636,29 @@ static int launch_dma_t(const OgcLayerArgs* a, hipStream_t stream) {
     const int tiles_m = (a->M + C::BM - 1) / C::BM;
     const int total = tiles_n * tiles_m;
     const int per_xcd = (total + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(C::NT), C::LDS, stream, *a, tiles_n, total, per_xcd);
+    const int max_slots = SHAPE ? 32 : 64;  // 32 CUs per XCD, one or two resident workgroups per CU
+    const int slots = per_xcd < max_slots ? per_xcd : max_slots;
+    hipLaunchKernelGGL(kern, dim3(slots * 8), dim3(C::NT), C::LDS, stream, *a, tiles_n, total, per_xcd, slots);
     return (int)hipGetLastError();
 }
 
-template <int DT>
+template <int DT, int SHAPE>
 static int launch_dma_io(int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
-    if (xp) return op ? launch_dma_t<DT, 1, 1>(a, s) : launch_dma_t<DT, 1, 0>(a, s);
-    return op ? launch_dma_t<DT, 0, 1>(a, s) : launch_dma_t<DT, 0, 0>(a, s);
+    if (xp) return op ? launch_dma_t<DT, SHAPE, 1, 1>(a, s) : launch_dma_t<DT, SHAPE, 1, 0>(a, s);
+    return op ? launch_dma_t<DT, SHAPE, 0, 1>(a, s) : launch_dma_t<DT, SHAPE, 0, 0>(a, s);
 }
 
 extern "C" int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain, const OgcLayerArgs* a, void* stream) {
     hipStream_t s = (hipStream_t)stream;
-    if (tile == OGC_TILE_DMA) {
+    if (tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8) {
         if (x_plain && !a->x_vec_ok) {
             tile = OGC_TILE_MID;  // caller's x is not 16-byte aligned: same channel padding, register-staged loads
         } else {
-            switch (dtype) {
-            case OGC_F32: return launch_dma_io<OGC_F32>(x_plain, out_plain, a, s);
-            case OGC_BF16: return launch_dma_io<OGC_BF16>(x_plain, out_plain, a, s);
-            default: return launch_dma_io<OGC_I8>(x_plain, out_plain, a, s);
-            }
+            if (dtype == OGC_BF16 && tile == OGC_TILE_DMA) return launch_dma_io<OGC_BF16, 0>(x_plain, out_plain, a, s);
+            if (dtype == OGC_BF16) return launch_dma_io<OGC_BF16, 1>(x_plain, out_plain, a, s);
+            if (dtype == OGC_I8 && tile == OGC_TILE_DMA) return launch_dma_io<OGC_I8, 0>(x_plain, out_plain, a, s);
+            if (dtype == OGC_I8) return launch_dma_io<OGC_I8, 1>(x_plain, out_plain, a, s);
+            return (int)hipErrorInvalidValue;  // the plan never selects this kernel for fp32
         }
     }
     switch (dtype) {
@@ -829,6 +712,6 @@ extern "C" int ogc_launch_prepack_params(int dtype, const void* w, const float* 
 }
 
 extern "C" const char* ogc_layer_kernel_name(int, int tile, int, int) {
-    return tile == OGC_TILE_DMA ? "ogc_layer_dma_kernel" : "ogc_layer_kernel";
+    return (tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8) ? "ogc_layer_dma_kernel" : "ogc_layer_kernel";
 }
 extern "C" const char* ogc_fused_kernel_name(int) { return "ogc_fused_chain_kernel"; }

@@ -1,0 +1,345 @@
+// Per-layer kernel for large bf16 / int8 layers: persistent, pipelined "stream" variant.  Included by
+// ogc_kernels.hip after the epilogue has been defined.
+//
+// Same tile mathematics as ogc_layer_kernel, but
+//   * the operand tiles go from global memory straight into LDS (global_load_lds_dwordx4: no staging
+//     registers, no ds_write) through a ring of three stages, so two k-steps of loads are in flight per
+//     workgroup.  Packed weights and KB16 activations are already in lane order: every wave-level load
+//     moves one contiguous KiB on both sides;
+//   * a workgroup is persistent: it walks a list of tiles and treats (tile, k-step) as one long stream, so
+//     the loads of the next tile's first k-steps are already in flight while the current tile's epilogue
+//     runs, and no pipeline ramp is paid per tile;
+//   * two workgroups share a CU (256 VGPRs each): one workgroup's epilogue and barrier waits overlap the
+//     other's MFMA main loop;
+//   * the main loop is hand scheduled in inline assembly on a fixed register map, software pipelined by half
+//     a k-step: one block = 6 LDS operand reads for the NEXT half-step, 8 MFMAs on the current operands with
+//     up to 6 direct loads of a later ring stage issued between them, one wait.  (A load instruction occupies
+//     the wave until the texture-address unit accepts it, and that unit serves the whole CU at about one KiB
+//     per 19 clocks: issued back to back the loads would stall the wave for as long as its MFMAs take.  And
+//     the compiler's own wait insertion cannot tell ring slots apart: it would wait for every outstanding
+//     direct load before any LDS read.)
+//
+//   workgroup tile: 128 channels x 256 batch rows, 4 waves as 2 x 2, wave tile 64 x 128 (2 x 4 MFMA blocks),
+//                   64-byte k-steps; stage layout [4 weight chunks of 2 KiB][8 activation chunks of 2 KiB]
+//   register map  : v0..v79   compiler (addresses, epilogue) -- amdgpu_num_vgpr keeps it below v80 (on this
+//                             unified register file the attribute counts in pairs, hence 40); the kernel
+//                             contains no calls (they would bring the callee's register conventions in)
+//                   v80..v103 operand set F0: W0 W1 X0 X1 X2 X3 (4 registers each)
+//                   v104..v127 operand set F1
+//                   v128..v255 accumulators, block b = 2*... i*4+j at v[128+16b .. 143+16b]
+// X_PLAIN reads the caller's row-major x (16-byte aligned rows, no K padding; rows past M are clamped to
+// the last row and never stored); u8 inputs are flipped to s8 after the LDS read.
+// Loads land in order: waiting until at most 6*(newer stages) remain guarantees the oldest stage is
+// complete.  After an epilogue (whose own loads and stores share that counter) the next wait is for zero.
+#ifndef OGC_LAYER_STREAM_H
+#define OGC_LAYER_STREAM_H
+
+OGC_DEV uint32_t lds_addr_of(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+template <int N> OGC_DEV void wait_loads_then_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// Two shapes share the code below:
+//   shape 0: 4 waves (2 x 2), workgroup tile 128 channels x 256 rows, 3-stage ring of 24 KiB, two workgroups
+//            per CU (one's epilogue overlaps the other's main loop); 48 bytes loaded per CU clock at MFMA peak
+//   shape 1: 8 waves (4 x 2), workgroup tile 256 x 256, 4-stage ring of 32 KiB, one workgroup per CU; 32 bytes
+//            per CU clock at MFMA peak -- the global->LDS path delivers about 53, so this is the shape for
+//            layers with enough tiles to fill the chip
+// In both, a wave owns 64 channels x 128 rows (2 x 4 MFMA blocks) and 256 VGPRs.
+template <int SHAPE> struct StreamCfg {
+    enum {
+        TN = 2, TM = 4, WAVES_N = SHAPE ? 4 : 2, WAVES_M = 2, WAVES = WAVES_N * WAVES_M, NT = WAVES * 64,
+        NST = SHAPE ? 4 : 3, BN = WAVES_N * TN * 32, BM = WAVES_M * TM * 32,
+        W_OPS = BN / 16, X_OPS = BM / 16, OPS = W_OPS + X_OPS, OPW = OPS / WAVES,
+        STAGE = (BN + BM) * 64, LDS = STAGE * NST, COMPILER_VGPRS = 80, NUM_VGPR_ATTR = COMPILER_VGPRS / 2
+    };
+    static_assert(OPW == (SHAPE ? 4 : 6) && OPS % WAVES == 0, "loads per wave and stage");
+};
+
+// ---- assembly building blocks ----------------------------------------------------------------------------
+// operand registers of set F (base 80 or 104): W0 = v[F:F+3], W1 = v[F+4:F+7], Xj = v[F+8+4j : F+11+4j]
+#define OGC_W(F, i) "v[" #F "+4*" #i ":" #F "+3+4*" #i "]"
+#define OGC_X(F, j) "v[" #F "+8+4*" #j ":" #F "+11+4*" #j "]"
+#define OGC_ACC(b) "v[128+16*" #b ":143+16*" #b "]"
+// reads the operand set F from LDS at %[wa] / %[xa]
+#define OGC_READ(F)                                               \
+    "ds_read_b128 " OGC_W(F, 0) ", %[wa]\n\t"                       \
+    "ds_read_b128 " OGC_W(F, 1) ", %[wa] offset:2048\n\t"           \
+    "ds_read_b128 " OGC_X(F, 0) ", %[xa]\n\t"                       \
+    "ds_read_b128 " OGC_X(F, 1) ", %[xa] offset:2048\n\t"           \
+    "ds_read_b128 " OGC_X(F, 2) ", %[xa] offset:4096\n\t"           \
+    "ds_read_b128 " OGC_X(F, 3) ", %[xa] offset:6144\n\t"
+#define OGC_NOREAD(F)
+// u8 -> s8 on the sixteen activation registers of set F (v[F+8 .. F+23]); %[flip] = 0x80808080
+#define OGC_FLIP4(F, j)                                          \
+    "v_xor_b32 v[" #F "+8+4*" #j "], %[flip], v[" #F "+8+4*" #j "]\n\t"   \
+    "v_xor_b32 v[" #F "+9+4*" #j "], %[flip], v[" #F "+9+4*" #j "]\n\t"   \
+    "v_xor_b32 v[" #F "+10+4*" #j "], %[flip], v[" #F "+10+4*" #j "]\n\t" \
+    "v_xor_b32 v[" #F "+11+4*" #j "], %[flip], v[" #F "+11+4*" #j "]\n\t"
+#define OGC_FLIP(F) OGC_FLIP4(F, 0) OGC_FLIP4(F, 1) OGC_FLIP4(F, 2) OGC_FLIP4(F, 3)
+#define OGC_NOFLIP(F)
+#define OGC_MFMA(OP, F, b, i, j) OP " " OGC_ACC(b) ", " OGC_W(F, i) ", " OGC_X(F, j) ", " OGC_ACC(b) "\n\t"
+#define OGC_MFMA_Z(OP, F, b, i, j) OP " " OGC_ACC(b) ", " OGC_W(F, i) ", " OGC_X(F, j) ", 0\n\t"
+#define OGC_DMA(i, off) "s_add_u32 m0, %[m0b], " #off "\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[g" #i "], off\n\t"
+#define OGC_NODMA(i, off)
+// eight MFMAs on operand set F with the six loads interleaved
+#define OGC_MFMAS(OP, M, D, F)                                                                          \
+    "s_nop 1\n\t" M(OP, F, 0, 0, 0) D(0, 0) M(OP, F, 1, 0, 1) D(1, 1024) M(OP, F, 2, 0, 2) D(2, 2048)    \
+        M(OP, F, 3, 0, 3) D(3, 3072) M(OP, F, 4, 1, 0) D(4, 4096) M(OP, F, 5, 1, 1) D(5, 5120)           \
+            M(OP, F, 6, 1, 2) M(OP, F, 7, 1, 3)
+#define OGC_MFMAS4(OP, M, D, F)                                                                         \
+    "s_nop 1\n\t" M(OP, F, 0, 0, 0) D(0, 0) M(OP, F, 1, 0, 1) M(OP, F, 2, 0, 2) D(1, 1024) M(OP, F, 3, 0, 3) \
+        M(OP, F, 4, 1, 0) D(2, 2048) M(OP, F, 5, 1, 1) M(OP, F, 6, 1, 2) D(3, 3072) M(OP, F, 7, 1, 3)
+#define OGC_G_OPERANDS \
+    [g0] "v"(g[0]), [g1] "v"(g[1]), [g2] "v"(g[2]), [g3] "v"(g[3]), [g4] "v"(g[4]), [g5] "v"(g[5]), [m0b] "s"(m0b)
+
+// One half-step: MFMAs on operand set CUR (80 or 104) while the other set is read for the next half-step.
+//   READ: fetch the other set; DMA: issue this wave's six loads; ZERO: the accumulators start from zero;
+//   FLIP: the freshly read activations are u8 and must become s8.
+template <int DT, int OPW, int CUR, bool READ, bool DMA, bool ZERO, bool FLIP>
+OGC_DEV void half_step(uint32_t wa, uint32_t xa, const uint64_t (&g)[6], uint32_t m0b) {
+    static_assert(CUR == 80 || CUR == 104, "operand set");
+    static_assert(!(ZERO && DMA), "unused variant");
+    const uint32_t flip = 0x80808080u;
+#define OGC_HS(OP, CURF, NXTF)                                                                                   \
+    if constexpr (READ && DMA && FLIP && OPW == 6)                                                               \
+        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA, OGC_DMA, CURF) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(NXTF) \
+                     ::[wa] "v"(wa), [xa] "v"(xa), [flip] "s"(flip), OGC_G_OPERANDS : "memory");                 \
+    else if constexpr (READ && DMA && !FLIP && OPW == 6)                                                         \
+        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA, OGC_DMA, CURF) "s_waitcnt lgkmcnt(0)"                 \
+                     ::[wa] "v"(wa), [xa] "v"(xa), OGC_G_OPERANDS : "memory");                                   \
+    else if constexpr (READ && DMA && FLIP && OPW == 4)                                                          \
+        asm volatile(OGC_READ(NXTF) OGC_MFMAS4(OP, OGC_MFMA, OGC_DMA, CURF) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(NXTF) \
+                     ::[wa] "v"(wa), [xa] "v"(xa), [flip] "s"(flip), OGC_G_OPERANDS : "memory");                 \
+    else if constexpr (READ && DMA && !FLIP && OPW == 4)                                                         \
+        asm volatile(OGC_READ(NXTF) OGC_MFMAS4(OP, OGC_MFMA, OGC_DMA, CURF) "s_waitcnt lgkmcnt(0)"                \
+                     ::[wa] "v"(wa), [xa] "v"(xa), OGC_G_OPERANDS : "memory");                                   \
+    else if constexpr (READ && !DMA && ZERO && FLIP)                                                             \
+        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA_Z, OGC_NODMA, CURF) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(NXTF) \
+                     ::[wa] "v"(wa), [xa] "v"(xa), [flip] "s"(flip) : "memory");                                 \
+    else if constexpr (READ && !DMA && ZERO && !FLIP)                                                            \
+        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA_Z, OGC_NODMA, CURF) "s_waitcnt lgkmcnt(0)"             \
+                     ::[wa] "v"(wa), [xa] "v"(xa) : "memory");                                                   \
+    else if constexpr (READ && !DMA && !ZERO && FLIP)                                                            \
+        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA, OGC_NODMA, CURF) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(NXTF) \
+                     ::[wa] "v"(wa), [xa] "v"(xa), [flip] "s"(flip) : "memory");                                 \
+    else if constexpr (READ && !DMA && !ZERO && !FLIP)                                                           \
+        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA, OGC_NODMA, CURF) "s_waitcnt lgkmcnt(0)"               \
+                     ::[wa] "v"(wa), [xa] "v"(xa) : "memory");                                                   \
+    else if constexpr (!READ && !DMA && !ZERO)                                                                   \
+        asm volatile(OGC_MFMAS(OP, OGC_MFMA, OGC_NODMA, CURF) "s_nop 0" ::: "memory");                            \
+    else                                                                                                         \
+        static_assert(READ, "unused variant");
+#define OGC_HS_SETS(OP)                 \
+    if constexpr (CUR == 80) {          \
+        OGC_HS(OP, 80, 104)             \
+    } else {                            \
+        OGC_HS(OP, 104, 80)             \
+    }
+    if constexpr (DT == OGC_I8) {
+        OGC_HS_SETS("v_mfma_i32_32x32x32_i8")
+    } else {
+        static_assert(DT == OGC_BF16, "the stream kernel covers int8 and bf16");
+        OGC_HS_SETS("v_mfma_f32_32x32x16_bf16")
+    }
+#undef OGC_HS_SETS
+#undef OGC_HS
+}
+
+// Copies accumulator block B (v[128+16B ..]) into compiler-visible registers.  The block's last MFMA may
+// still be in flight: the caller has waited for it (see the s_nop before the epilogue).
+template <int DT, int B> OGC_DEV typename AccT<DT>::type take_acc_block() {
+    int r[16];
+    asm volatile(
+        "v_mov_b32 %0, v[%c16+0]\n\tv_mov_b32 %1, v[%c16+1]\n\tv_mov_b32 %2, v[%c16+2]\n\tv_mov_b32 %3, v[%c16+3]\n\t"
+        "v_mov_b32 %4, v[%c16+4]\n\tv_mov_b32 %5, v[%c16+5]\n\tv_mov_b32 %6, v[%c16+6]\n\tv_mov_b32 %7, v[%c16+7]\n\t"
+        "v_mov_b32 %8, v[%c16+8]\n\tv_mov_b32 %9, v[%c16+9]\n\tv_mov_b32 %10, v[%c16+10]\n\tv_mov_b32 %11, v[%c16+11]\n\t"
+        "v_mov_b32 %12, v[%c16+12]\n\tv_mov_b32 %13, v[%c16+13]\n\tv_mov_b32 %14, v[%c16+14]\n\tv_mov_b32 %15, v[%c16+15]"
+        : "=v"(r[0]), "=v"(r[1]), "=v"(r[2]), "=v"(r[3]), "=v"(r[4]), "=v"(r[5]), "=v"(r[6]), "=v"(r[7]), "=v"(r[8]),
+          "=v"(r[9]), "=v"(r[10]), "=v"(r[11]), "=v"(r[12]), "=v"(r[13]), "=v"(r[14]), "=v"(r[15])
+        : "n"(128 + 16 * B));
+    typename AccT<DT>::type acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if constexpr (DT == OGC_I8) acc[i] = r[i];
+        else acc[i] = __builtin_bit_cast(float, r[i]);
+    }
+    return acc;
+}
+
+// Grid: 8 * slots workgroups (slots <= tiles_per_xcd).  Workgroup wg belongs to XCD wg%8 and is slot wg/8 of
+// it; XCD x owns the contiguous tile range [x*tiles_per_xcd, (x+1)*tiles_per_xcd) and its slots walk that
+// range with stride `slots`, so the workgroups of one XCD always work on neighbouring tiles (the n-tiles of
+// one batch tile share its activations through that XCD's L2).
+template <int DT, int SHAPE, int X_PLAIN, int OUT_PLAIN>
+__global__ void __launch_bounds__(StreamCfg<SHAPE>::NT, 2) __attribute__((amdgpu_num_vgpr(40)))
+ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_per_xcd, int slots) {
+    typedef StreamCfg<SHAPE> C;
+    static_assert(C::NUM_VGPR_ATTR == 40, "keep the attribute above in step with the register map");
+    constexpr int OPW = C::OPW, NST = C::NST;
+    constexpr int TN = C::TN, TM = C::TM;
+    constexpr bool FLIP = X_PLAIN && DT == OGC_I8;
+    extern __shared__ __align__(1024) uint8_t smem[];
+    // v80..v255 are used by the assembly below only; naming the last one makes the kernel own all 256.
+    asm volatile("; operand sets and accumulators live in v80..v255" ::: "v255");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave % C::WAVES_N, wm = wave / C::WAVES_N;
+    const int KT = a.KC >> 2;
+    const int xcd = blockIdx.x & 7;
+    int t_end = (xcd + 1) * tiles_per_xcd;
+    t_end = t_end < tiles_total ? t_end : tiles_total;
+    int cur_tile = xcd * tiles_per_xcd + (blockIdx.x >> 3);
+    if (cur_tile >= t_end) return;
+    const int my_tiles = (t_end - cur_tile + slots - 1) / slots;
+    const int total_steps = my_tiles * KT;
+
+    // ---- prefetch cursor: per-wave load descriptors of the tile being fetched --------------------------
+    // op o of a stage is 1 KiB = two 512-byte slabs of one 32-row chunk; wave w issues ops w*OPW .. +OPW-1.
+    // The k-steps of a tile are walked in rotated order, starting at rot = n_tile*KT/tiles_n: the workgroups
+    // that share a batch tile (its n-tiles, resident together on one XCD) then touch different k-slices of the
+    // activations at any moment, so each slice is missed in L2 by one of them and hit by the others later,
+    // instead of all of them waiting on the same miss.  Accumulation order within a tile is free (integer
+    // sums are exact; float sums stay within the stated tolerance).
+    const uint8_t* gsrc[6];
+    int pf_tile = cur_tile, pf_kt = 0, pf_rot = 0;
+    auto setup_src = [&](int t) {
+        const int n_base = (t % tiles_n) * C::BN, m_base = (t / tiles_n) * C::BM;
+        pf_rot = (int)(((long long)(t % tiles_n) * KT) / tiles_n);
+#pragma unroll
+        for (int i = 0; i < OPW; ++i) {
+            const int o = wave * OPW + i;
+            if (o < C::W_OPS) {
+                gsrc[i] = a.w + ((size_t)((n_base >> 5) + (o >> 1)) * a.KC + (o & 1) * 2) * 512 + lane * 16;
+            } else {
+                const int ox = o - C::W_OPS;
+                if constexpr (X_PLAIN) {
+                    int row = m_base + (ox >> 1) * 32 + (lane & 31);
+                    row = row < a.M ? row : a.M - 1;
+                    gsrc[i] = a.x + (long long)row * a.ldx_bytes + ((ox & 1) * 2 + (lane >> 5)) * 16;
+                } else {
+                    gsrc[i] = a.x + ((size_t)((m_base >> 5) + (ox >> 1)) * a.KC + (ox & 1) * 2) * 512 + lane * 16;
+                }
+            }
+        }
+    };
+    // Global addresses of the prefetch cursor's k-step, then the cursor advance.
+    auto pf_addresses = [&](uint64_t(&g)[6]) {
+        int kphys = pf_kt + pf_rot;
+        kphys = kphys >= KT ? kphys - KT : kphys;
+#pragma unroll
+        for (int i = 0; i < OPW; ++i) {
+            const int o = wave * OPW + i;
+            const long long step = (X_PLAIN && o >= C::W_OPS) ? 64 : 2048;
+            g[i] = (uint64_t)(uintptr_t)(gsrc[i] + (long long)kphys * step);
+        }
+#pragma unroll
+        for (int i = OPW; i < 6; ++i) g[i] = 0;
+        if (++pf_kt == KT) {
+            pf_kt = 0;
+            pf_tile += slots;
+            if (pf_tile < t_end) setup_src(pf_tile);
+        }
+    };
+    const uint32_t lds0 = lds_addr_of(smem);
+    const uint32_t m0_wave = lds0 + wave * OPW * 1024;  // + stage*STAGE: where this wave's loads land
+    auto prologue_loads = [&](int stage) {
+        if (pf_tile >= t_end) return;
+        uint64_t g[6];
+        pf_addresses(g);
+        const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + stage * C::STAGE);
+        if constexpr (OPW == 6)
+            asm volatile(OGC_DMA(0, 0) OGC_DMA(1, 1024) OGC_DMA(2, 2048) OGC_DMA(3, 3072) OGC_DMA(4, 4096) OGC_DMA(5, 5120)
+                         "s_nop 0" ::OGC_G_OPERANDS
+                         : "memory");
+        else
+            asm volatile(OGC_DMA(0, 0) OGC_DMA(1, 1024) OGC_DMA(2, 2048) OGC_DMA(3, 3072) "s_nop 0" ::OGC_G_OPERANDS : "memory");
+    };
+    const uint32_t w_rd = lds0 + (wn * TN) * 2048 + lane * 16;
+    const uint32_t x_rd = lds0 + C::BN * 64 + (wm * TM) * 2048 + lane * 16;
+    auto wait_barrier = [&](int newer_stages) {  // newer_stages: load stages allowed to remain in flight
+        if (newer_stages >= 3) wait_loads_then_barrier<3 * OPW>();
+        else if (newer_stages == 2) wait_loads_then_barrier<2 * OPW>();
+        else if (newer_stages == 1) wait_loads_then_barrier<OPW>();
+        else wait_loads_then_barrier<0>();
+    };
+
+    // Schedule (software pipelined by half a k-step; the ring slot of step q is q % NST):
+    //   prologue: loads of steps 0..NST-1 in flight; wait for step 0; barrier; read F0(step 0)
+    //   step q, first half : read F1(q) | MFMA on F0
+    //           wait for the loads of step q+1 (steps q+2..q+NST-1 may stay in flight); barrier B_q
+    //           -- every wave has now finished ALL its LDS reads of steps <= q, so slot q % NST is free --
+    //           second half: read F0(q+1) | MFMA on F1 | loads of step q+NST into slot q % NST
+    //           last step of a tile: epilogue from registers (the next tile's loads keep flying)
+    const uint64_t g_none[6] = {0, 0, 0, 0, 0, 0};
+    setup_src(pf_tile);
+#pragma unroll
+    for (int st = 0; st < NST; ++st) prologue_loads(st);
+    wait_barrier(total_steps - 1 < NST - 1 ? total_steps - 1 : NST - 1);
+    if constexpr (FLIP) {
+        const uint32_t flip = 0x80808080u;
+        asm volatile(OGC_READ(80) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(80)::[wa] "v"(w_rd), [xa] "v"(x_rd), [flip] "s"(flip)
+                     : "memory");
+    } else {
+        asm volatile(OGC_READ(80) "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
+    }
+    int stage = 0, kt = 0;
+    bool drained = false;  // an epilogue ran since the last wait: its loads and stores are pending too
+    for (int q = 0; q < total_steps; ++q) {
+        const bool more = q + 1 < total_steps;
+        const int nstage = stage == NST - 1 ? 0 : stage + 1;
+        {  // first half: MFMA on F0, fetch F1 (the second 32 bytes of this step)
+            const uint32_t wa = w_rd + stage * C::STAGE + 1024, xa = x_rd + stage * C::STAGE + 1024;
+            if (kt == 0) half_step<DT, OPW, 80, true, false, true, FLIP>(wa, xa, g_none, 0);
+            else half_step<DT, OPW, 80, true, false, false, FLIP>(wa, xa, g_none, 0);
+        }
+        if (more) {  // second half: MFMA on F1, fetch F0 of the next step, issue the loads of step q+3
+            // loads outstanding, oldest first: step q+1, then q+2 .. q+NST-1 as far as they exist
+            const int newer = total_steps - 2 - q < NST - 2 ? total_steps - 2 - q : NST - 2;
+            wait_barrier(drained ? 0 : newer);
+            drained = false;
+            const uint32_t wa = w_rd + nstage * C::STAGE, xa = x_rd + nstage * C::STAGE;
+            if (pf_tile < t_end) {
+                uint64_t g[6];
+                pf_addresses(g);
+                const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + stage * C::STAGE);
+                half_step<DT, OPW, 104, true, true, false, FLIP>(wa, xa, g, m0b);
+            } else {
+                half_step<DT, OPW, 104, true, false, false, FLIP>(wa, xa, g_none, 0);
+            }
+        } else {
+            half_step<DT, OPW, 104, false, false, false, false>(0, 0, g_none, 0);
+        }
+        stage = nstage;
+        if (++kt == KT) {
+            kt = 0;
+            // the accumulators are read by ordinary vector instructions next: let the last MFMA drain first
+            asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+            const int n_base = (cur_tile % tiles_n) * C::BN + wn * TN * 32, m_base = (cur_tile / tiles_n) * C::BM + wm * TM * 32;
+            auto block = [&](auto tag) {
+                constexpr int B = decltype(tag)::value;
+                const int n0 = n_base + (B / 4) * 32, m0 = m_base + (B % 4) * 32;
+                if constexpr (OUT_PLAIN) {
+                    if (n0 < a.N && m0 < a.M) epilogue_block<DT, 1, false>(take_acc_block<DT, B>(), a, n0, m0, lane, (uint8_t*)nullptr);
+                } else {
+                    if ((n0 >> 5) < a.NB_out)
+                        epilogue_block<DT, 0, false>(take_acc_block<DT, B>(), a, n0, m0, lane, a.y + (size_t)(m0 >> 5) * a.KC_out * 512);
+                }
+            };
+            block(std::integral_constant<int, 0>());
+            block(std::integral_constant<int, 1>());
+            block(std::integral_constant<int, 2>());
+            block(std::integral_constant<int, 3>());
+            block(std::integral_constant<int, 4>());
+            block(std::integral_constant<int, 5>());
+            block(std::integral_constant<int, 6>());
+            block(std::integral_constant<int, 7>());
+            cur_tile += slots;
+            drained = true;
+        }
+    }
+}
+
+#endif

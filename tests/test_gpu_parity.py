@@ -107,10 +107,10 @@ def test_cfg5_full_size_sampled_rows(oracle_mod):
 
 
 # ---------------------------------------------------------------- reduced sizes: several tiles + ragged tails
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("dtype", ["i8", "bf16", "f32"])
 def test_per_layer_ragged(oracle_mod, dtype, tile):
-    m = {0: 300, 1: 150, 2: 77, 3: 600}[tile]
+    m = {0: 300, 1: 150, 2: 77, 3: 600, 4: 700}[tile]
     dims = [100, 333, 72, 33] if dtype == "i8" else [50, 290, 40, 19]
     wl = synth.make_mlp(dtype, m, dims, [RELU, RELU, NONE if dtype != "i8" else RELU], seed=500 + tile, name="ragged")
     check(wl, "per_layer", oracle_mod, tile=tile)
@@ -128,19 +128,24 @@ def test_reduced_cfg4_and_cfg5(oracle_mod, mode):
     check(synth.make_config(5, m=96), mode, oracle_mod)
 
 
+@pytest.mark.parametrize("tile", [3, 4])
 @pytest.mark.parametrize("dtype", ["i8", "bf16", "f32"])
-def test_pipelined_kernel_plain_input(oracle_mod, dtype):
-    """Tile 3 = the global->LDS pipelined kernel, reading the caller's plain x directly (aligned rows, K a
-    multiple of 64 bytes), with a ragged batch, short and long K, and a misaligned x that must fall back."""
+def test_pipelined_kernel_plain_input(oracle_mod, dtype, tile):
+    """Tiles 3 and 4 = the two shapes of the persistent global->LDS stream kernel (fp32 falls back to the
+    register-staged kernel), reading the caller's plain x directly (aligned rows, no K padding), with a ragged
+    batch, short and long K, several tiles per workgroup, and a misaligned x that must fall back."""
     k = {"i8": 192, "bf16": 96, "f32": 64}[dtype]
     wl = synth.make_mlp(dtype, 700, [k, 160, 64, 40], [RELU, RELU, RELU], seed=700, name="dma")
-    check(wl, "per_layer", oracle_mod, tile=3)
-    check(synth.make_mlp(dtype, 300, [64, 200], [RELU], seed=701, name="dma-1layer"), "per_layer", oracle_mod, tile=3)
-    check(synth.make_mlp(dtype, 257, [1024, 96], [NONE], seed=702, name="dma-longk", has_bias=False), "per_layer", oracle_mod, tile=3)
+    check(wl, "per_layer", oracle_mod, tile=tile)
+    check(synth.make_mlp(dtype, 300, [64, 200], [RELU], seed=701, name="dma-1layer"), "per_layer", oracle_mod, tile=tile)
+    check(synth.make_mlp(dtype, 257, [1024, 96], [NONE], seed=702, name="dma-longk", has_bias=False), "per_layer", oracle_mod, tile=tile)
+    # more tiles than resident workgroups: every workgroup walks several tiles (stream across tile boundaries)
+    check(synth.make_mlp(dtype, 9000, [k, 520, 300], [RELU, GELU if dtype != "i8" else RELU], seed=705, name="dma-many-tiles"),
+          "per_layer", oracle_mod, tile=tile, rows=[slice(0, 70), slice(4400, 4480), slice(8930, 9000)])
     esz = {"i8": 1, "bf16": 2, "f32": 4}[dtype]
-    check(synth.make_mlp(dtype, 300, [64, 200], [RELU], seed=703, name="dma-misaligned"), "per_layer", oracle_mod, tile=3,
+    check(synth.make_mlp(dtype, 300, [64, 200], [RELU], seed=703, name="dma-misaligned"), "per_layer", oracle_mod, tile=tile,
           x_byte_offset=esz)
-    check(synth.make_mlp(dtype, 300, [64, 70], [RELU], seed=704, name="dma-strided", ld_x=80), "per_layer", oracle_mod, tile=3,
+    check(synth.make_mlp(dtype, 300, [64, 70], [RELU], seed=704, name="dma-strided", ld_x=80), "per_layer", oracle_mod, tile=tile,
           ld_y=72)
 
 
