@@ -99,7 +99,7 @@ int choose_tile(int m, int n, bool dma_ok) {
         return (long)((m + ti.bm - 1) / ti.bm) * ((n + ti.bn - 1) / ti.bn);
     };
     if (dma_ok && tiles(OGC_TILE_DMA8) >= 224) return OGC_TILE_DMA8;
-    if (dma_ok && tiles(OGC_TILE_DMA) >= 96) return OGC_TILE_DMA;
+    if (dma_ok && tiles(OGC_TILE_DMA) >= 384) return OGC_TILE_DMA;
     if (tiles(OGC_TILE_MID) >= 128) return OGC_TILE_MID;
     return OGC_TILE_SMALL;
 }
@@ -231,6 +231,7 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         if (mode == OGC_MODE_PER_LAYER) {
             // the stream kernel keeps its accumulators in fixed registers: no out-of-line calls (sigmoid) in it
             const bool dma_ok = desc->dtype != OGC_F32 && lp.d.act != OGC_ACT_SIGMOID &&
+                                !(desc->dtype == OGC_I8 && lp.d.in_zp != 128) &&
                                 (l > 0 || (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
             lp.tile = choose_tile(desc->m, rows, dma_ok);
             lp.npw = (int)round_up((size_t)rows, ogc_tile_info(lp.tile).bn);

@@ -88,24 +88,45 @@ template <bool CALLS> OGC_DEV void act_apply16(float (&out)[16], int act) {
     }
 }
 
-template <int DT, bool CALLS>
-OGC_DEV void epilogue_values(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, int n0, int h, float (&out)[16]) {
+// Per-channel post-op parameters of one 32-channel block as a lane needs them: entry g covers the channels
+// n0 + 8g + 4*(lane/32) .. +3 (the lane's registers 4g .. 4g+3).  s: combined scale (I8), b: bias, c: negated
+// zero-point compensation (I8).
+struct BlockParams {
+    v4f s[4];
+    v4f b[4];
+    v4i c[4];
+};
+
+// From the packed blob in global memory (arrays indexed by absolute channel).
+template <int DT>
+OGC_DEV void load_block_params(BlockParams& p, const OgcLayerArgs& a, int n0, int h) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const int n = n0 + 8 * g + 4 * h;
-        const v4f b4 = *(const v4f*)(a.bias + n);
+        p.s[g] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+        p.b[g] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+        p.c[g] = (v4i){0, 0, 0, 0};
+        if (a.has_bias) p.b[g] = *(const v4f*)(a.bias + n);
         if constexpr (DT == OGC_I8) {
-            const v4f s4 = *(const v4f*)(a.scale + n);
-            v4i c4 = {0, 0, 0, 0};
-            if (a.has_comp) c4 = *(const v4i*)(a.ncomp + n);
+            p.s[g] = *(const v4f*)(a.scale + n);
+            if (a.has_comp) p.c[g] = *(const v4i*)(a.ncomp + n);
+        }
+    }
+}
+
+template <int DT, bool CALLS>
+OGC_DEV void epilogue_values(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, const BlockParams& p, float (&out)[16]) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        if constexpr (DT == OGC_I8) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float f = (float)(acc[4 * g + e] + c4[e]);
-                out[4 * g + e] = __builtin_fmaf(f, s4[e], b4[e]);
+                const float f = (float)(acc[4 * g + e] + p.c[g][e]);
+                out[4 * g + e] = __builtin_fmaf(f, p.s[g][e], p.b[g][e]);
             }
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) out[4 * g + e] = acc[4 * g + e] + b4[e];
+            for (int e = 0; e < 4; ++e) out[4 * g + e] = acc[4 * g + e] + p.b[g][e];
         }
     }
     act_apply16<CALLS>(out, a.act);
@@ -221,27 +242,22 @@ OGC_DEV void store_plain(const v4i (&chunk)[EO], const OgcLayerArgs& a, int m, i
 //   (no byte can carry: each is <= 255-zp).  q_add / q_xor are precomputed on the host: zp*0x01010101 and,
 //   for the internal s8 form, 0x80808080 (both 0 when zp = 128 and the result stays internal).
 template <int OUT_PLAIN, typename YP>
-OGC_DEV void epilogue_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, int n0, int m0, int lane, YP yblk) {
+OGC_DEV void epilogue_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, const BlockParams& p, int n0, int m0, int lane,
+                                    YP yblk) {
     const int h = lane >> 5, mm = lane & 31;
     const float inv = a.inv_cs, hi = a.q_hi;
     uint32_t dw[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        const int n = n0 + 8 * g + 4 * h;
-        const v4f s4 = *(const v4f*)(a.scale + n);
-        v4f b4 = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (a.has_bias) b4 = *(const v4f*)(a.bias + n);
-        v4i c4 = {0, 0, 0, 0};
-        if (a.has_comp) c4 = *(const v4i*)(a.ncomp + n);
-        uint32_t p = 0;
+        uint32_t q = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float f = (float)(acc[4 * g + e] + c4[e]);
-            const float y = __builtin_fmaf(f, s4[e], b4[e]);
+            const float f = (float)(acc[4 * g + e] + p.c[g][e]);
+            const float y = __builtin_fmaf(f, p.s[g][e], p.b[g][e]);
             const float t = __builtin_amdgcn_fmed3f(y * inv, 0.0f, hi);
-            p = __builtin_amdgcn_cvt_pk_u8_f32(t, e, p);
+            q = __builtin_amdgcn_cvt_pk_u8_f32(t, e, q);
         }
-        dw[g] = (p + a.q_add) ^ a.q_xor;
+        dw[g] = (q + a.q_add) ^ a.q_xor;
     }
     swap32(dw[0], dw[2]);
     swap32(dw[1], dw[3]);
@@ -254,17 +270,20 @@ OGC_DEV void epilogue_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, int 
     }
 }
 
-template <int DT, int OUT_PLAIN, bool CALLS = true, typename YP>
-OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, int n0, int m0, int lane, YP yblk) {
-    if constexpr (DT == OGC_I8) {
-        if (a.act == OGC_ACT_RELU && !a.out_f32) {
-            epilogue_block_i8_relu<OUT_PLAIN>(acc, a, n0, m0, lane, yblk);
+// PATH: -1 = pick the int8 ReLU-requantize fast path at run time, 1 = the caller knows it applies (only that
+// code is generated), 0 = the caller knows it does not.
+template <int DT, int OUT_PLAIN, bool CALLS = true, int PATH = -1, typename YP>
+OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, const BlockParams& p, int n0, int m0,
+                            int lane, YP yblk) {
+    if constexpr (DT == OGC_I8 && PATH != 0) {
+        if (PATH == 1 || (a.act == OGC_ACT_RELU && !a.out_f32)) {
+            epilogue_block_i8_relu<OUT_PLAIN>(acc, a, p, n0, m0, lane, yblk);
             return;
         }
     }
     const int h = lane >> 5, mm = lane & 31;
     float out[16];
-    epilogue_values<DT, CALLS>(acc, a, n0, h, out);
+    epilogue_values<DT, CALLS>(acc, a, p, out);
     constexpr int E = Elt<DT>::size;
     if constexpr (OUT_PLAIN) {
         if constexpr (DT != OGC_I8) {
@@ -286,6 +305,14 @@ OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerAr
 #pragma unroll
         for (int c = 0; c < E; ++c) *(v4i*)(yblk + ((size_t)(c0 + c) * 32 + mm) * 16) = ch[c];
     }
+}
+
+// Same, reading the block's parameters from the packed blob.
+template <int DT, int OUT_PLAIN, bool CALLS = true, typename YP>
+OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, int n0, int m0, int lane, YP yblk) {
+    BlockParams p;
+    load_block_params<DT>(p, a, n0, lane >> 5);
+    epilogue_block<DT, OUT_PLAIN, CALLS>(acc, a, p, n0, m0, lane, yblk);
 }
 
 // Loads one 16-byte chunk (row m, bytes kb..kb+15 of the row) of the caller's plain x, zero-filling
@@ -621,10 +648,10 @@ static int launch_layer_tile(int tile, int xp, int op, const OgcLayerArgs* a, hi
     }
 }
 
-template <int DT, int SHAPE, int XP, int OP>
+template <int DT, int SHAPE, int XP, int OP, int EPI>
 static int launch_dma_t(const OgcLayerArgs* a, hipStream_t stream) {
     typedef StreamCfg<SHAPE> C;
-    auto kern = ogc_layer_dma_kernel<DT, SHAPE, XP, OP>;
+    auto kern = ogc_layer_dma_kernel<DT, SHAPE, XP, OP, EPI>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
@@ -642,10 +669,21 @@ static int launch_dma_t(const OgcLayerArgs* a, hipStream_t stream) {
     return (int)hipGetLastError();
 }
 
-template <int DT, int SHAPE>
+template <int DT, int SHAPE, int EPI>
 static int launch_dma_io(int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
-    if (xp) return op ? launch_dma_t<DT, SHAPE, 1, 1>(a, s) : launch_dma_t<DT, SHAPE, 1, 0>(a, s);
-    return op ? launch_dma_t<DT, SHAPE, 0, 1>(a, s) : launch_dma_t<DT, SHAPE, 0, 0>(a, s);
+    if (xp) return op ? launch_dma_t<DT, SHAPE, 1, 1, EPI>(a, s) : launch_dma_t<DT, SHAPE, 1, 0, EPI>(a, s);
+    return op ? launch_dma_t<DT, SHAPE, 0, 1, EPI>(a, s) : launch_dma_t<DT, SHAPE, 0, 0, EPI>(a, s);
+}
+
+// EPI = 1: int8 layer with ReLU and a requantized result (the five-op epilogue only)
+template <int SHAPE>
+static int launch_dma_dtype(int dtype, int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
+    if (dtype == OGC_BF16) return launch_dma_io<OGC_BF16, SHAPE, 0>(xp, op, a, s);
+    if (dtype == OGC_I8) {
+        if (a->act == OGC_ACT_RELU && !a->out_f32) return launch_dma_io<OGC_I8, SHAPE, 1>(xp, op, a, s);
+        return launch_dma_io<OGC_I8, SHAPE, 0>(xp, op, a, s);
+    }
+    return (int)hipErrorInvalidValue;  // the plan never selects this kernel for fp32
 }
 
 extern "C" int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain, const OgcLayerArgs* a, void* stream) {
@@ -654,11 +692,8 @@ extern "C" int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain,
         if (x_plain && !a->x_vec_ok) {
             tile = OGC_TILE_MID;  // caller's x is not 16-byte aligned: same channel padding, register-staged loads
         } else {
-            if (dtype == OGC_BF16 && tile == OGC_TILE_DMA) return launch_dma_io<OGC_BF16, 0>(x_plain, out_plain, a, s);
-            if (dtype == OGC_BF16) return launch_dma_io<OGC_BF16, 1>(x_plain, out_plain, a, s);
-            if (dtype == OGC_I8 && tile == OGC_TILE_DMA) return launch_dma_io<OGC_I8, 0>(x_plain, out_plain, a, s);
-            if (dtype == OGC_I8) return launch_dma_io<OGC_I8, 1>(x_plain, out_plain, a, s);
-            return (int)hipErrorInvalidValue;  // the plan never selects this kernel for fp32
+            if (tile == OGC_TILE_DMA) return launch_dma_dtype<0>(dtype, x_plain, out_plain, a, s);
+            return launch_dma_dtype<1>(dtype, x_plain, out_plain, a, s);
         }
     }
     switch (dtype) {

@@ -39,7 +39,7 @@ OGC_DEV uint32_t lds_addr_of(const void* p) {
 }
 
 template <int N> OGC_DEV void wait_loads_then_barrier() {
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
 // Two shapes share the code below:
@@ -54,7 +54,8 @@ template <int SHAPE> struct StreamCfg {
         TN = 2, TM = 4, WAVES_N = SHAPE ? 4 : 2, WAVES_M = 2, WAVES = WAVES_N * WAVES_M, NT = WAVES * 64,
         NST = SHAPE ? 4 : 3, BN = WAVES_N * TN * 32, BM = WAVES_M * TM * 32,
         W_OPS = BN / 16, X_OPS = BM / 16, OPS = W_OPS + X_OPS, OPW = OPS / WAVES,
-        STAGE = (BN + BM) * 64, LDS = STAGE * NST, COMPILER_VGPRS = 80, NUM_VGPR_ATTR = COMPILER_VGPRS / 2
+        STAGE = (BN + BM) * 64, RING = STAGE * NST, PARAMS = 2 * BN * 4, LDS = RING + 2 * PARAMS,
+        COMPILER_VGPRS = 80, NUM_VGPR_ATTR = COMPILER_VGPRS / 2
     };
     static_assert(OPW == (SHAPE ? 4 : 6) && OPS % WAVES == 0, "loads per wave and stage");
 };
@@ -174,7 +175,8 @@ template <int DT, int B> OGC_DEV typename AccT<DT>::type take_acc_block() {
 // it; XCD x owns the contiguous tile range [x*tiles_per_xcd, (x+1)*tiles_per_xcd) and its slots walk that
 // range with stride `slots`, so the workgroups of one XCD always work on neighbouring tiles (the n-tiles of
 // one batch tile share its activations through that XCD's L2).
-template <int DT, int SHAPE, int X_PLAIN, int OUT_PLAIN>
+// EPI: 1 = int8 ReLU + requantize epilogue only, 0 = every other combination
+template <int DT, int SHAPE, int X_PLAIN, int OUT_PLAIN, int EPI>
 __global__ void __launch_bounds__(StreamCfg<SHAPE>::NT, 2) __attribute__((amdgpu_num_vgpr(40)))
 ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_per_xcd, int slots) {
     typedef StreamCfg<SHAPE> C;
@@ -273,6 +275,22 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     //           -- every wave has now finished ALL its LDS reads of steps <= q, so slot q % NST is free --
     //           second half: read F0(q+1) | MFMA on F1 | loads of step q+NST into slot q % NST
     //           last step of a tile: epilogue from registers (the next tile's loads keep flying)
+    // Per-channel parameters of a tile's 128/256 channels are staged in LDS (two buffers, alternating per tile)
+    // as soon as the previous tile's epilogue is done: the epilogue then reads them with LDS loads, which do
+    // not queue behind the direct loads in flight the way global loads would.  Layout: scale | bias.  (The plan
+    // selects this kernel only for int8 layers whose input zero point is 128: no compensation term.)
+    typedef __attribute__((address_space(3))) uint8_t lds_u8;
+    lds_u8* const params_lds = (lds_u8*)smem + C::RING;
+    auto stage_params = [&](int t, int buf) {
+        if (tid < C::BN) {
+            const int n = (t % tiles_n) * C::BN + tid;
+            lds_u8* pb = params_lds + buf * C::PARAMS;
+            ((__attribute__((address_space(3))) float*)pb)[tid] = (DT == OGC_I8) ? a.scale[n] : 0.0f;
+            ((__attribute__((address_space(3))) float*)pb)[C::BN + tid] = a.has_bias ? a.bias[n] : 0.0f;
+        }
+    };
+    int pbuf = 0;
+    stage_params(cur_tile, 0);
     const uint64_t g_none[6] = {0, 0, 0, 0, 0, 0};
     setup_src(pf_tile);
 #pragma unroll
@@ -318,24 +336,47 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             // the accumulators are read by ordinary vector instructions next: let the last MFMA drain first
             asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
             const int n_base = (cur_tile % tiles_n) * C::BN + wn * TN * 32, m_base = (cur_tile / tiles_n) * C::BM + wm * TM * 32;
+            BlockParams prm;
+            auto read_params = [&](int i) {  // the lane's parameters for weight block i of this wave
+                const lds_u8* pb = params_lds + pbuf * C::PARAMS;
+                const int nl = (wn * TN + i) * 32 + 4 * (lane >> 5);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    prm.s[g] = *(const __attribute__((address_space(3))) v4f*)(pb + (nl + 8 * g) * 4);
+                    prm.b[g] = *(const __attribute__((address_space(3))) v4f*)(pb + (C::BN + nl + 8 * g) * 4);
+                    prm.c[g] = (v4i){0, 0, 0, 0};
+                }
+            };
             auto block = [&](auto tag) {
                 constexpr int B = decltype(tag)::value;
                 const int n0 = n_base + (B / 4) * 32, m0 = m_base + (B % 4) * 32;
                 if constexpr (OUT_PLAIN) {
-                    if (n0 < a.N && m0 < a.M) epilogue_block<DT, 1, false>(take_acc_block<DT, B>(), a, n0, m0, lane, (uint8_t*)nullptr);
+                    if (n0 < a.N && m0 < a.M)
+                        epilogue_block<DT, 1, false, EPI>(take_acc_block<DT, B>(), a, prm, n0, m0, lane, (uint8_t*)nullptr);
                 } else {
                     if ((n0 >> 5) < a.NB_out)
-                        epilogue_block<DT, 0, false>(take_acc_block<DT, B>(), a, n0, m0, lane, a.y + (size_t)(m0 >> 5) * a.KC_out * 512);
+                        epilogue_block<DT, 0, false, EPI>(take_acc_block<DT, B>(), a, prm, n0, m0, lane,
+                                                     a.y + (size_t)(m0 >> 5) * a.KC_out * 512);
                 }
             };
+            read_params(0);
             block(std::integral_constant<int, 0>());
             block(std::integral_constant<int, 1>());
             block(std::integral_constant<int, 2>());
             block(std::integral_constant<int, 3>());
+            read_params(1);
             block(std::integral_constant<int, 4>());
             block(std::integral_constant<int, 5>());
             block(std::integral_constant<int, 6>());
             block(std::integral_constant<int, 7>());
+            // the next tile's parameters go to the other buffer (waves still in this epilogue keep reading this
+            // one); the barrier of the next tile's first step orders the writes before its epilogue's reads, and
+            // a one-step tile has no such barrier, hence the explicit one
+            if (cur_tile + slots < t_end) {
+                stage_params(cur_tile + slots, pbuf ^ 1);
+                if (KT == 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            }
+            pbuf ^= 1;
             cur_tile += slots;
             drained = true;
         }
