@@ -32,17 +32,22 @@ def _median(v):
 
 
 def time_steps(dev, steps, warmup):
-    """Wall-clock time of exactly `steps` runs, synchronised on both sides."""
+    """Time of exactly `steps` runs: wall clock synchronised on both sides, and a HIP event pair recorded on
+    the launch stream around the same region.  Returns (wall seconds per step, event seconds per step)."""
     import torch
 
     for _ in range(warmup):
         dev.run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    e0.record()
     for _ in range(steps):
         dev.run()
+    e1.record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    wall = (time.perf_counter() - t0) / steps
+    return wall, e0.elapsed_time(e1) * 1e-3 / steps
 
 
 def profile_launches(dev, reps=30):
@@ -59,7 +64,7 @@ def config_report(idx, steps, warmup, with_floor=None):
 
     wl = synth.make_config(idx)
     dev = DeviceMLP(wl)
-    sec = time_steps(dev, steps, warmup)
+    sec, ev_sec = time_steps(dev, steps, warmup)
     launches = profile_launches(dev)
     nl = binding.ogc_mlp_num_launches(dev.mlp.plan)
     peak, unit = PEAK[wl.dtype]
@@ -68,7 +73,8 @@ def config_report(idx, steps, warmup, with_floor=None):
     bound = "mfma" if ops / abytes > ridge else "hbm"
     rep = {
         "config": idx, "workload": wl.name, "dtype": wl.dtype, "mode": "fused" if dev.mlp.mode == binding.OGC_MODE_FUSED else "per_layer",
-        "launches": nl, "ms_per_step": sec * 1e3, "gpu_ms_sum_of_launches": sum(launches) * 1e3,
+        "launches": nl, "ms_per_step": sec * 1e3, "ms_per_step_hip_events": ev_sec * 1e3,
+        "ms_sum_of_per_launch_event_pairs": sum(launches) * 1e3,
         "tops_or_tflops": ops / sec / 1e12, "algorithmic_GBps": abytes / sec / 1e9, "bound": bound,
         "frac_of_bound": (ops / sec / peak) if bound == "mfma" else (abytes / sec / HBM_PEAK),
         "ops": ops, "algorithmic_bytes": abytes,
@@ -86,30 +92,37 @@ def launch_floor(steps, warmup):
 
     wl = synth.make_mlp("f32", 1, [1, 1], [0], seed=1)
     dev = DeviceMLP(wl)
-    sec = time_steps(dev, steps, warmup)
+    sec, _ = time_steps(dev, steps, warmup)
     dev.close()
     return sec
 
 
-def cpu_baseline(idx, budget_s=15.0):
-    """The CPU oracle, as it stands, on a bounded row sample of the headline workload."""
+def cpu_baseline(idx, budget_s=20.0):
+    """The CPU oracle, as it stands, timed for about budget_s seconds on a bounded sample of the headline
+    workload: a leading slice of its rows if one pass over all rows would take longer, else whole passes."""
     import oracle
     from paper_2301_01333_amd import synth
 
     full = synth.make_config(idx)
-    probe_rows = 32
+    probe_rows = min(full.m, 256)
     wl = synth.make_config(idx, m=probe_rows)
     t0 = time.perf_counter()
     oracle.mlp(wl)
     t_probe = max(time.perf_counter() - t0, 1e-4)
-    rows = int(max(probe_rows, min(full.m, probe_rows * budget_s / t_probe)))
+    rows = int(min(full.m, probe_rows * budget_s / t_probe))
     rows = max(32, rows // 32 * 32)
     wl = synth.make_config(idx, m=rows)
-    t0 = time.perf_counter()
-    oracle.mlp(wl)
-    dt = time.perf_counter() - t0
-    return {"value": wl.ops / dt / 1e12, "unit": "TOP/s" if wl.dtype == "i8" else "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": "first %d of %d rows of config %d, all layers, %.1f s of CPU time" % (rows, full.m, idx, dt)}
+    passes, ops, t0 = 0, 0.0, time.perf_counter()
+    while True:
+        oracle.mlp(wl)
+        passes += 1
+        ops += wl.ops
+        dt = time.perf_counter() - t0
+        if dt >= 0.6 * budget_s or passes >= 64:
+            break
+    return {"value": ops / dt / 1e12, "unit": "TOP/s" if wl.dtype == "i8" else "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": "%d pass(es) over the first %d of %d rows of config %d, all layers, %.1f s of CPU time"
+            % (passes, rows, full.m, idx, dt)}
 
 
 def read_traffic():
@@ -132,6 +145,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="headline configuration (1..5)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--only-headline", action="store_true", help="skip the per_config table")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (reference reading for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE runs of this same command)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported" % args.gpus,
@@ -148,26 +164,46 @@ def main():
     floor = launch_floor(args.steps, args.warmup)
     wl, dev, head, launches = config_report(args.config, args.steps, args.warmup)
     peak, unit = PEAK[wl.dtype]
-    # dominant kernel = the launch with the longest duration; its algorithmic work is that layer's
-    # 2*M*K*N (mfma bound) or the chain's algorithmic bytes (hbm bound, fused single launch)
+    # dominant kernel = the kernel (name with template arguments) with the largest share of the step; its
+    # duration is the mean over its launches in one step, its work the mean of those layers' 2*M*K*N
+    # (mfma bound) or the chain's algorithmic bytes (hbm bound, fused single launch)
     if head["mode"] == "per_layer":
-        i = max(range(len(launches)), key=lambda j: launches[j])
-        ly = wl.layers[i]
-        work = 2.0 * wl.m * ly.k * ly.n
-        dom = {"kernel": binding.ogc_mlp_kernel_name(dev.mlp.plan, i), "launch": i,
-               "launch_us": [round(t * 1e6, 2) for t in launches]}
+        names = [binding.ogc_mlp_kernel_name(dev.mlp.plan, j) for j in range(len(launches))]
+        share = {}
+        for j, nm in enumerate(names):
+            share[nm] = share.get(nm, 0.0) + launches[j]
+        kname = max(share, key=share.get)
+        idxs = [j for j, nm in enumerate(names) if nm == kname]
+        dur = share[kname] / len(idxs)
+        work = sum(2.0 * wl.m * wl.layers[j].k * wl.layers[j].n for j in idxs) / len(idxs)
+        dom = {"kernel": kname, "launches_of_kernel": idxs, "launch_us": [round(t * 1e6, 2) for t in launches],
+               "launch_kernels": names}
     else:
-        i = 0
+        dur = launches[0]
         work = float(wl.ops)
-        dom = {"kernel": binding.ogc_mlp_kernel_name(dev.mlp.plan, 0), "launch": 0, "launch_us": [round(launches[0] * 1e6, 2)]}
+        dom = {"kernel": binding.ogc_mlp_kernel_name(dev.mlp.plan, 0), "launches_of_kernel": [0],
+               "launch_us": [round(launches[0] * 1e6, 2)]}
+    # An event pair around a single launch also times the gap to the next command (2-3 us here), while the
+    # launches of a step run back to back.  The per-launch pairs therefore give each launch's share, and the
+    # event pair around the whole timed region gives the total: duration = share * region time per step.
+    dom["avg_launch_us_single_pair"] = round(dur * 1e6, 3)
+    dur *= head["ms_per_step_hip_events"] * 1e-3 / sum(launches)
+    dom["avg_launch_us"] = round(dur * 1e6, 3)
     if head["bound"] == "mfma":
-        roof = {"bound": "mfma", "achieved": work / launches[i] / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s" if wl.dtype != "i8" else "TOP/s"}
+        roof = {"bound": "mfma", "achieved": work / dur / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s" if wl.dtype != "i8" else "TOP/s"}
     else:
-        roof = {"bound": "hbm", "achieved": wl.algorithmic_bytes / launches[i] / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
+        roof = {"bound": "hbm", "achieved": wl.algorithmic_bytes / dur / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = read_traffic() if args.config == 5 else None
     roof.update(dom)
     dev.close()
+    if args.copy_calibration:
+        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     per = []
     if not args.only_headline:

@@ -430,7 +430,9 @@ const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer) {
     if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return nullptr;
     if (plan->mode == OGC_MODE_FUSED) return ogc_fused_kernel_name(plan->desc.dtype);
     const int L = (int)plan->layers.size();
-    return ogc_layer_kernel_name(plan->desc.dtype, plan->layers[layer].tile, layer == 0, layer == L - 1);
+    const ogc_layer_desc& d = plan->layers[layer].d;
+    return ogc_layer_kernel_name(plan->desc.dtype, plan->layers[layer].tile, layer == 0, layer == L - 1, d.act,
+                                 d.out == OGC_OUT_F32);
 }
 
 }  // extern "C"

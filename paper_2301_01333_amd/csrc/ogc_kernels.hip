@@ -9,6 +9,8 @@
 // which is contiguous both in the plain row-major result and in the next layer's operand layout.
 #include <hip/hip_runtime.h>
 
+#include <stdio.h>
+#include <string.h>
 #include <type_traits>
 
 #include "ogc_internal.h"
@@ -746,7 +748,23 @@ extern "C" int ogc_launch_prepack_params(int dtype, const void* w, const float* 
     return (int)hipGetLastError();
 }
 
-extern "C" const char* ogc_layer_kernel_name(int, int tile, int, int) {
-    return (tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8) ? "ogc_layer_dma_kernel" : "ogc_layer_kernel";
+// Kernel names with their template arguments, spelled the way a kernel trace prints them.
+extern "C" const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, int out_plain, int act, int out_f32) {
+    static char names[3][OGC_NUM_TILES][2][2][2][48];
+    if (dtype < 0 || dtype > 2 || tile < 0 || tile >= OGC_NUM_TILES) return "?";
+    const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8;
+    const int epi = stream && dtype == OGC_I8 && act == OGC_ACT_RELU && !out_f32;
+    char* n = names[dtype][tile][x_plain != 0][out_plain != 0][epi];
+    if (!n[0]) {
+        char tmp[48];
+        if (stream)
+            snprintf(tmp, sizeof tmp, "ogc_layer_dma_kernel<%d, %d, %d, %d, %d>", dtype, tile == OGC_TILE_DMA8, x_plain != 0, out_plain != 0, epi);
+        else
+            snprintf(tmp, sizeof tmp, "ogc_layer_kernel<%d, %d, %d, %d>", dtype, tile, x_plain != 0, out_plain != 0);
+        memcpy(n, tmp, sizeof tmp);  // every writer stores the same bytes
+    }
+    return n;
 }
-extern "C" const char* ogc_fused_kernel_name(int) { return "ogc_fused_chain_kernel"; }
+extern "C" const char* ogc_fused_kernel_name(int dtype) {
+    return dtype == OGC_F32 ? "ogc_fused_chain_kernel<0>" : dtype == OGC_BF16 ? "ogc_fused_chain_kernel<1>" : "ogc_fused_chain_kernel<2>";
+}
