@@ -12,12 +12,14 @@
 //   * two workgroups share a CU (256 VGPRs each): one workgroup's epilogue and barrier waits overlap the
 //     other's MFMA main loop;
 //   * the main loop is hand scheduled in inline assembly on a fixed register map, software pipelined by half
-//     a k-step: one block = 6 LDS operand reads for the NEXT half-step, 8 MFMAs on the current operands with
-//     up to 6 direct loads of a later ring stage issued between them, one wait.  (A load instruction occupies
-//     the wave until the texture-address unit accepts it, and that unit serves the whole CU at about one KiB
-//     per 19 clocks: issued back to back the loads would stall the wave for as long as its MFMAs take.  And
-//     the compiler's own wait insertion cannot tell ring slots apart: it would wait for every outstanding
-//     direct load before any LDS read.)
+//     a k-step, one block per k-step: LDS operand reads for the next half-step go out ahead of the 8 MFMAs
+//     on the current operands, the workgroup barrier sits between two MFMAs so the matrix pipe keeps working
+//     while the waves synchronise, and the direct loads of a later ring stage (with their address updates)
+//     are issued between the remaining MFMAs.  (A load instruction occupies the wave until the
+//     texture-address unit accepts it, and that unit serves the whole CU at about one KiB per 19 clocks:
+//     issued back to back the loads would stall the wave for as long as its MFMAs take.  And the compiler's
+//     own wait insertion cannot tell ring slots apart: it would wait for every outstanding direct load
+//     before any LDS read.)  Nothing but scalar bookkeeping runs between two blocks.
 //
 //   workgroup tile: 128 channels x 256 batch rows, 4 waves as 2 x 2, wave tile 64 x 128 (2 x 4 MFMA blocks),
 //                   64-byte k-steps; stage layout [4 weight chunks of 2 KiB][8 activation chunks of 2 KiB]
@@ -36,10 +38,6 @@
 
 OGC_DEV uint32_t lds_addr_of(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
-}
-
-template <int N> OGC_DEV void wait_loads_then_barrier() {
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
 // Two shapes share the code below:
@@ -65,89 +63,217 @@ template <int SHAPE> struct StreamCfg {
 #define OGC_W(F, i) "v[" #F "+4*" #i ":" #F "+3+4*" #i "]"
 #define OGC_X(F, j) "v[" #F "+8+4*" #j ":" #F "+11+4*" #j "]"
 #define OGC_ACC(b) "v[128+16*" #b ":143+16*" #b "]"
-// reads the operand set F from LDS at %[wa] / %[xa]
-#define OGC_READ(F)                                               \
-    "ds_read_b128 " OGC_W(F, 0) ", %[wa]\n\t"                       \
-    "ds_read_b128 " OGC_W(F, 1) ", %[wa] offset:2048\n\t"           \
-    "ds_read_b128 " OGC_X(F, 0) ", %[xa]\n\t"                       \
-    "ds_read_b128 " OGC_X(F, 1) ", %[xa] offset:2048\n\t"           \
-    "ds_read_b128 " OGC_X(F, 2) ", %[xa] offset:4096\n\t"           \
-    "ds_read_b128 " OGC_X(F, 3) ", %[xa] offset:6144\n\t"
-#define OGC_NOREAD(F)
-// u8 -> s8 on the sixteen activation registers of set F (v[F+8 .. F+23]); %[flip] = 0x80808080
+// reads the operand set F from LDS at the addresses in the registers WA / XA
+#define OGC_READ(F, WA, XA)                                         \
+    "ds_read_b128 " OGC_W(F, 0) ", " WA "\n\t"                       \
+    "ds_read_b128 " OGC_W(F, 1) ", " WA " offset:2048\n\t"           \
+    "ds_read_b128 " OGC_X(F, 0) ", " XA "\n\t"                       \
+    "ds_read_b128 " OGC_X(F, 1) ", " XA " offset:2048\n\t"           \
+    "ds_read_b128 " OGC_X(F, 2) ", " XA " offset:4096\n\t"           \
+    "ds_read_b128 " OGC_X(F, 3) ", " XA " offset:6144\n\t"
+// u8 -> s8 on the four registers of activation operand j of set F; %[flip] = 0x80808080
 #define OGC_FLIP4(F, j)                                          \
     "v_xor_b32 v[" #F "+8+4*" #j "], %[flip], v[" #F "+8+4*" #j "]\n\t"   \
     "v_xor_b32 v[" #F "+9+4*" #j "], %[flip], v[" #F "+9+4*" #j "]\n\t"   \
     "v_xor_b32 v[" #F "+10+4*" #j "], %[flip], v[" #F "+10+4*" #j "]\n\t" \
-    "v_xor_b32 v[" #F "+11+4*" #j "], %[flip], v[" #F "+11+4*" #j "]\n\t"
+    "v_xor_b32 v[" #F "+11+4*" #j "], %[flip], v[" #F "+11+4*" #j "]\n\t" \
+    "s_nop 1\n\t"
+#define OGC_NOFLIP4(F, j)
 #define OGC_FLIP(F) OGC_FLIP4(F, 0) OGC_FLIP4(F, 1) OGC_FLIP4(F, 2) OGC_FLIP4(F, 3)
-#define OGC_NOFLIP(F)
 #define OGC_MFMA(OP, F, b, i, j) OP " " OGC_ACC(b) ", " OGC_W(F, i) ", " OGC_X(F, j) ", " OGC_ACC(b) "\n\t"
 #define OGC_MFMA_Z(OP, F, b, i, j) OP " " OGC_ACC(b) ", " OGC_W(F, i) ", " OGC_X(F, j) ", 0\n\t"
-#define OGC_DMA(i, off) "s_add_u32 m0, %[m0b], " #off "\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[g" #i "], off\n\t"
-#define OGC_NODMA(i, off)
-// eight MFMAs on operand set F with the six loads interleaved
-#define OGC_MFMAS(OP, M, D, F)                                                                          \
-    "s_nop 1\n\t" M(OP, F, 0, 0, 0) D(0, 0) M(OP, F, 1, 0, 1) D(1, 1024) M(OP, F, 2, 0, 2) D(2, 2048)    \
-        M(OP, F, 3, 0, 3) D(3, 3072) M(OP, F, 4, 1, 0) D(4, 4096) M(OP, F, 5, 1, 1) D(5, 5120)           \
-            M(OP, F, 6, 1, 2) M(OP, F, 7, 1, 3)
-#define OGC_MFMAS4(OP, M, D, F)                                                                         \
-    "s_nop 1\n\t" M(OP, F, 0, 0, 0) D(0, 0) M(OP, F, 1, 0, 1) M(OP, F, 2, 0, 2) D(1, 1024) M(OP, F, 3, 0, 3) \
-        M(OP, F, 4, 1, 0) D(2, 2048) M(OP, F, 5, 1, 1) M(OP, F, 6, 1, 2) D(3, 3072) M(OP, F, 7, 1, 3)
-#define OGC_G_OPERANDS \
-    [g0] "v"(g[0]), [g1] "v"(g[1]), [g2] "v"(g[2]), [g3] "v"(g[3]), [g4] "v"(g[4]), [g5] "v"(g[5]), [m0b] "s"(m0b)
+// one direct load of 1 KiB into LDS at m0 = %[m0b] + off, then the cursor of that load moves on by INC
+#define OGC_DMA(i, off, INC)                                                                   \
+    "s_add_u32 m0, %[m0b], " #off "\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[g" #i "], off\n\t"  \
+    "v_lshl_add_u64 %[g" #i "], %[g" #i "], 0, %[" INC "]\n\t"
+#define OGC_NODMA(i, off, INC)
 
-// One half-step: MFMAs on operand set CUR (80 or 104) while the other set is read for the next half-step.
-//   READ: fetch the other set; DMA: issue this wave's six loads; ZERO: the accumulators start from zero;
-//   FLIP: the freshly read activations are u8 and must become s8.
-template <int DT, int OPW, int CUR, bool READ, bool DMA, bool ZERO, bool FLIP>
-OGC_DEV void half_step(uint32_t wa, uint32_t xa, const uint64_t (&g)[6], uint32_t m0b) {
-    static_assert(CUR == 80 || CUR == 104, "operand set");
-    static_assert(!(ZERO && DMA), "unused variant");
+// One k-step of the main loop as a single block.  On entry operand set F0 (v80..) holds the first 32 bytes of
+// this step's operands; SOC / SON are the LDS byte offsets of this step's second half and of the next
+// step's first half.
+//   reads F1 | 8 MFMAs on F0 | wait F1 | 2 MFMAs on F1 | wait for the next stage's loads, barrier |
+//   reads F0 of the next step | 6 MFMAs on F1 with this wave's direct loads between them | wait F0
+// The two MFMAs ahead of the barrier keep the matrix pipe fed while the workgroup synchronises.
+//   MZ: MFMA macro of the first half (accumulate or start from zero); FL: flip macro (X_PLAIN u8 input);
+//   SYNC: text of the wait + barrier; RD: reads of the next step or nothing; D: load macro; LW/LX: which
+//   loads of a wave fetch weights (ops 0,1) and activations (the rest); OFS: LDS stride between a wave's loads
+#define OGC_STEP_HEAD                                   \
+    "v_add_u32 %[t0], %[soc], %[wrd]\n\t"               \
+    "v_add_u32 %[t1], %[soc], %[xrd]\n\t"               \
+    "v_add_u32 %[t2], %[son], %[wrd]\n\t"               \
+    "v_add_u32 %[t3], %[son], %[xrd]\n\t"
+#define OGC_STEP_FIRST(OP, MZ, FL)                                                                        \
+    OGC_READ(104, "%[t0]", "%[t1]")                                                                       \
+    FL(80, 0) MZ(OP, 80, 0, 0, 0) FL(80, 1) MZ(OP, 80, 1, 0, 1) FL(80, 2) MZ(OP, 80, 2, 0, 2) FL(80, 3)   \
+        MZ(OP, 80, 3, 0, 3) MZ(OP, 80, 4, 1, 0) MZ(OP, 80, 5, 1, 1) MZ(OP, 80, 6, 1, 2) MZ(OP, 80, 7, 1, 3) \
+            "s_waitcnt lgkmcnt(0)\n\t" FL(104, 0) OGC_MFMA(OP, 104, 0, 0, 0) FL(104, 1) OGC_MFMA(OP, 104, 1, 0, 1)
+#define OGC_STEP_SYNC(VMN) "s_waitcnt vmcnt(" #VMN ")\n\ts_barrier\n\t" OGC_READ(80, "%[t2]", "%[t3]")
+#define OGC_STEP_NOSYNC
+#define OGC_STEP_REST6(OP, FL, D, O1, O2, O3, O4, O5)                                                     \
+    FL(104, 2) OGC_MFMA(OP, 104, 2, 0, 2) D(0, 0, "incw") FL(104, 3) OGC_MFMA(OP, 104, 3, 0, 3)           \
+        D(1, O1, "incw") OGC_MFMA(OP, 104, 4, 1, 0) D(2, O2, "incx") OGC_MFMA(OP, 104, 5, 1, 1)           \
+            D(3, O3, "incx") OGC_MFMA(OP, 104, 6, 1, 2) D(4, O4, "incx") OGC_MFMA(OP, 104, 7, 1, 3)       \
+                D(5, O5, "incx") "s_waitcnt lgkmcnt(0)"
+#define OGC_STEP_REST4(OP, FL, D, O1, O2, O3)                                                             \
+    FL(104, 2) OGC_MFMA(OP, 104, 2, 0, 2) D(0, 0, "incw") FL(104, 3) OGC_MFMA(OP, 104, 3, 0, 3)           \
+        D(1, O1, "incw") OGC_MFMA(OP, 104, 4, 1, 0) D(2, O2, "incx") OGC_MFMA(OP, 104, 5, 1, 1)           \
+            D(3, O3, "incx") OGC_MFMA(OP, 104, 6, 1, 2) OGC_MFMA(OP, 104, 7, 1, 3) "s_waitcnt lgkmcnt(0)"
+
+// Step modes: 0 = loads of the stage NST steps ahead are issued and VM newer loads may stay in flight at the
+// barrier; 1 = the same but everything outstanding is awaited (after an epilogue, whose stores share the
+// counter); 2 = no loads left to issue, everything awaited; 3 = last step of the stream: no barrier, no reads
+template <int DT, int OPW, int VM, int MODE, bool ZERO, bool FLIP>
+OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t soc, uint32_t son, uint64_t (&g)[6], uint64_t incw, uint64_t incx,
+                    uint32_t m0b) {
+    static_assert((OPW == 6 && VM == 6) || (OPW == 4 && (VM == 8 || VM == 4)), "loads allowed in flight at the barrier");
     const uint32_t flip = 0x80808080u;
-#define OGC_HS(OP, CURF, NXTF)                                                                                   \
-    if constexpr (READ && DMA && FLIP && OPW == 6)                                                               \
-        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA, OGC_DMA, CURF) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(NXTF) \
-                     ::[wa] "v"(wa), [xa] "v"(xa), [flip] "s"(flip), OGC_G_OPERANDS : "memory");                 \
-    else if constexpr (READ && DMA && !FLIP && OPW == 6)                                                         \
-        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA, OGC_DMA, CURF) "s_waitcnt lgkmcnt(0)"                 \
-                     ::[wa] "v"(wa), [xa] "v"(xa), OGC_G_OPERANDS : "memory");                                   \
-    else if constexpr (READ && DMA && FLIP && OPW == 4)                                                          \
-        asm volatile(OGC_READ(NXTF) OGC_MFMAS4(OP, OGC_MFMA, OGC_DMA, CURF) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(NXTF) \
-                     ::[wa] "v"(wa), [xa] "v"(xa), [flip] "s"(flip), OGC_G_OPERANDS : "memory");                 \
-    else if constexpr (READ && DMA && !FLIP && OPW == 4)                                                         \
-        asm volatile(OGC_READ(NXTF) OGC_MFMAS4(OP, OGC_MFMA, OGC_DMA, CURF) "s_waitcnt lgkmcnt(0)"                \
-                     ::[wa] "v"(wa), [xa] "v"(xa), OGC_G_OPERANDS : "memory");                                   \
-    else if constexpr (READ && !DMA && ZERO && FLIP)                                                             \
-        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA_Z, OGC_NODMA, CURF) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(NXTF) \
-                     ::[wa] "v"(wa), [xa] "v"(xa), [flip] "s"(flip) : "memory");                                 \
-    else if constexpr (READ && !DMA && ZERO && !FLIP)                                                            \
-        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA_Z, OGC_NODMA, CURF) "s_waitcnt lgkmcnt(0)"             \
-                     ::[wa] "v"(wa), [xa] "v"(xa) : "memory");                                                   \
-    else if constexpr (READ && !DMA && !ZERO && FLIP)                                                            \
-        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA, OGC_NODMA, CURF) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(NXTF) \
-                     ::[wa] "v"(wa), [xa] "v"(xa), [flip] "s"(flip) : "memory");                                 \
-    else if constexpr (READ && !DMA && !ZERO && !FLIP)                                                           \
-        asm volatile(OGC_READ(NXTF) OGC_MFMAS(OP, OGC_MFMA, OGC_NODMA, CURF) "s_waitcnt lgkmcnt(0)"               \
-                     ::[wa] "v"(wa), [xa] "v"(xa) : "memory");                                                   \
-    else if constexpr (!READ && !DMA && !ZERO)                                                                   \
-        asm volatile(OGC_MFMAS(OP, OGC_MFMA, OGC_NODMA, CURF) "s_nop 0" ::: "memory");                            \
-    else                                                                                                         \
-        static_assert(READ, "unused variant");
-#define OGC_HS_SETS(OP)                 \
-    if constexpr (CUR == 80) {          \
-        OGC_HS(OP, 80, 104)             \
-    } else {                            \
-        OGC_HS(OP, 104, 80)             \
+    uint32_t t0, t1, t2, t3;
+#define OGC_STEP_OUT [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3)
+#define OGC_STEP_IN [wrd] "v"(w_rd), [xrd] "v"(x_rd), [soc] "s"(soc), [son] "s"(son), [flip] "s"(flip)
+#define OGC_STEP_G6 [g0] "+v"(g[0]), [g1] "+v"(g[1]), [g2] "+v"(g[2]), [g3] "+v"(g[3]), [g4] "+v"(g[4]), [g5] "+v"(g[5])
+#define OGC_STEP_G4 [g0] "+v"(g[0]), [g1] "+v"(g[1]), [g2] "+v"(g[2]), [g3] "+v"(g[3])
+#define OGC_STEP_DMA_IN [incw] "s"(incw), [incx] "s"(incx), [m0b] "s"(m0b)
+#define OGC_STEP(OP, MZ, FL)                                                                                        \
+    if constexpr (MODE == 0 && OPW == 6)                                                                            \
+        asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(6)                                      \
+                         OGC_STEP_REST6(OP, FL, OGC_DMA, 4096, 8192, 12288, 16384, 20480)                           \
+                     : OGC_STEP_OUT, OGC_STEP_G6 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
+    else if constexpr (MODE == 1 && OPW == 6)                                                                       \
+        asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(0)                                      \
+                         OGC_STEP_REST6(OP, FL, OGC_DMA, 4096, 8192, 12288, 16384, 20480)                           \
+                     : OGC_STEP_OUT, OGC_STEP_G6 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
+    else if constexpr (MODE == 0 && OPW == 4 && VM == 8)                                                            \
+        asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(8)                                      \
+                         OGC_STEP_REST4(OP, FL, OGC_DMA, 8192, 16384, 24576)                                        \
+                     : OGC_STEP_OUT, OGC_STEP_G4 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
+    else if constexpr (MODE == 0 && OPW == 4 && VM == 4)                                                            \
+        asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(4)                                      \
+                         OGC_STEP_REST4(OP, FL, OGC_DMA, 8192, 16384, 24576)                                        \
+                     : OGC_STEP_OUT, OGC_STEP_G4 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
+    else if constexpr (MODE == 1 && OPW == 4)                                                                       \
+        asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(0)                                      \
+                         OGC_STEP_REST4(OP, FL, OGC_DMA, 8192, 16384, 24576)                                        \
+                     : OGC_STEP_OUT, OGC_STEP_G4 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
+    else if constexpr (MODE == 2)                                                                                   \
+        asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(0)                                      \
+                         OGC_STEP_REST4(OP, FL, OGC_NODMA, 0, 0, 0)                                                 \
+                     : OGC_STEP_OUT : OGC_STEP_IN : "memory");                                                      \
+    else                                                                                                            \
+        asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_NOSYNC                                       \
+                         OGC_STEP_REST4(OP, FL, OGC_NODMA, 0, 0, 0)                                                 \
+                     : OGC_STEP_OUT : OGC_STEP_IN : "memory");
+#define OGC_STEP_ZF(OP)                                        \
+    if constexpr (ZERO && FLIP) {                              \
+        OGC_STEP(OP, OGC_MFMA_Z, OGC_FLIP4)                    \
+    } else if constexpr (ZERO && !FLIP) {                      \
+        OGC_STEP(OP, OGC_MFMA_Z, OGC_NOFLIP4)                  \
+    } else if constexpr (!ZERO && FLIP) {                      \
+        OGC_STEP(OP, OGC_MFMA, OGC_FLIP4)                      \
+    } else {                                                   \
+        OGC_STEP(OP, OGC_MFMA, OGC_NOFLIP4)                    \
     }
     if constexpr (DT == OGC_I8) {
-        OGC_HS_SETS("v_mfma_i32_32x32x32_i8")
+        OGC_STEP_ZF("v_mfma_i32_32x32x32_i8")
     } else {
         static_assert(DT == OGC_BF16, "the stream kernel covers int8 and bf16");
-        OGC_HS_SETS("v_mfma_f32_32x32x16_bf16")
+        OGC_STEP_ZF("v_mfma_f32_32x32x16_bf16")
     }
-#undef OGC_HS_SETS
-#undef OGC_HS
+#undef OGC_STEP_ZF
+#undef OGC_STEP
+}
+
+// A run of n ordinary k-steps (accumulating, loads to issue in every one, no tile change of the prefetch
+// cursor) as one block with its loop control inside, so that between two MFMAs of a wave there are never more
+// than a handful of other instructions: with two waves per SIMD running in lockstep (they meet at the barrier
+// every step) any stretch without MFMAs is a stretch where the matrix pipe idles.
+//   tw / tx : LDS read addresses of the current stage (first half; the second half is 1 KiB further)
+//   sst     : byte offset of the current stage in the ring; sprev: of the previous one
+//   kph     : physical k-step the prefetch cursor points at (the walk over k is rotated and wraps at KT)
+// LATE waves issue their loads among the first-half MFMAs (for the stage freed by the previous step's
+// barrier), the others after the barrier: the two waves of a SIMD then never wait for the texture-address
+// unit at the same time, and only half the workgroup's loads queue up there at once.
+#define OGC_READ_HI(F, WA, XA)                                      \
+    "ds_read_b128 " OGC_W(F, 0) ", " WA " offset:1024\n\t"           \
+    "ds_read_b128 " OGC_W(F, 1) ", " WA " offset:3072\n\t"           \
+    "ds_read_b128 " OGC_X(F, 0) ", " XA " offset:1024\n\t"           \
+    "ds_read_b128 " OGC_X(F, 1) ", " XA " offset:3072\n\t"           \
+    "ds_read_b128 " OGC_X(F, 2) ", " XA " offset:5120\n\t"           \
+    "ds_read_b128 " OGC_X(F, 3) ", " XA " offset:7168\n\t"
+#define OGC_RUN(OP, FL, DA, DB, SLOT, VMN, O1, O2, O3, O4, O5, D45)                                             \
+    ".Lks%=:\n\t"                                                                                                \
+    "s_add_u32 %[son], %[sst], %[stg]\n\t"                                                                       \
+    "s_cmp_lg_u32 %[son], %[ring]\n\t"                                                                           \
+    "s_cselect_b32 %[son], %[son], 0\n\t"                                                                        \
+    OGC_READ_HI(104, "%[tw]", "%[tx]")                                                                           \
+    "s_waitcnt lgkmcnt(6)\n\t"                                                                                   \
+    FL(80, 0) OGC_MFMA(OP, 80, 0, 0, 0)                                                                          \
+    "v_add_u32 %[tw], %[son], %[wrd]\n\t"                                                                        \
+    "v_add_u32 %[tx], %[son], %[xrd]\n\t"                                                                        \
+    FL(80, 1) OGC_MFMA(OP, 80, 1, 0, 1)                                                                          \
+    "s_add_u32 %[kph], %[kph], 1\n\t"                                                                            \
+    "s_cmp_eq_u32 %[kph], %[ktt]\n\t"                                                                            \
+    "s_cselect_b64 %[incw], %[incww], %[incwn]\n\t"                                                              \
+    "s_cselect_b64 %[incx], %[incxw], %[incxn]\n\t"                                                              \
+    "s_cselect_b32 %[kph], 0, %[kph]\n\t"                                                                        \
+    "s_add_u32 %[m0b], %[m0w], %[" SLOT "]\n\t"                                                                  \
+    FL(80, 2) OGC_MFMA(OP, 80, 2, 0, 2) DA(0, 0, "incw") FL(80, 3) OGC_MFMA(OP, 80, 3, 0, 3) DA(1, O1, "incw")   \
+    OGC_MFMA(OP, 80, 4, 1, 0) DA(2, O2, "incx") OGC_MFMA(OP, 80, 5, 1, 1) DA(3, O3, "incx")                      \
+    OGC_MFMA(OP, 80, 6, 1, 2) OGC_MFMA(OP, 80, 7, 1, 3)                                                          \
+    "s_waitcnt lgkmcnt(0)\n\t"                                                                                   \
+    FL(104, 0) OGC_MFMA(OP, 104, 0, 0, 0) FL(104, 1) OGC_MFMA(OP, 104, 1, 0, 1)                                  \
+    "s_waitcnt vmcnt(" #VMN ")\n\ts_barrier\n\t"                                                                 \
+    OGC_READ(80, "%[tw]", "%[tx]")                                                                               \
+    FL(104, 2) OGC_MFMA(OP, 104, 2, 0, 2) DB(0, 0, "incw") FL(104, 3) OGC_MFMA(OP, 104, 3, 0, 3)                 \
+    DB(1, O1, "incw") OGC_MFMA(OP, 104, 4, 1, 0) DB(2, O2, "incx") OGC_MFMA(OP, 104, 5, 1, 1) DB(3, O3, "incx")  \
+    OGC_MFMA(OP, 104, 6, 1, 2) D45(4, O4, "incx") OGC_MFMA(OP, 104, 7, 1, 3) D45(5, O5, "incx")                  \
+    "s_mov_b32 %[sprev], %[sst]\n\t"                                                                             \
+    "s_mov_b32 %[sst], %[son]\n\t"                                                                               \
+    "s_sub_u32 %[n], %[n], 1\n\t"                                                                                \
+    "s_cmp_lg_u32 %[n], 0\n\t"                                                                                   \
+    "s_cbranch_scc1 .Lks%=\n\t"                                                                                  \
+    "s_waitcnt lgkmcnt(0)"
+
+template <int DT, int SHAPE, bool LATE, bool FLIP>
+OGC_DEV void k_steps_run(uint32_t w_rd, uint32_t x_rd, uint64_t (&g)[6], uint32_t& sst, uint32_t& sprev, uint32_t& kph, uint32_t n,
+                         uint32_t kt_total, uint32_t m0w, uint64_t incwn, uint64_t incww, uint64_t incxn, uint64_t incxw) {
+    typedef StreamCfg<SHAPE> C;
+    static_assert(!(LATE && SHAPE == 0), "only the eight-wave shape splits its waves into two groups");
+    const uint32_t flip = 0x80808080u;
+    sst = __builtin_amdgcn_readfirstlane(sst);
+    sprev = __builtin_amdgcn_readfirstlane(sprev);
+    kph = __builtin_amdgcn_readfirstlane(kph);
+    n = __builtin_amdgcn_readfirstlane(n);
+    kt_total = __builtin_amdgcn_readfirstlane(kt_total);
+    m0w = __builtin_amdgcn_readfirstlane(m0w);
+    uint32_t tw = sst + w_rd, tx = sst + x_rd, son, m0b;
+    uint64_t incw, incx;
+#define OGC_RUN_OUT [son] "=&s"(son), [m0b] "=&s"(m0b), [incw] "=&s"(incw), [incx] "=&s"(incx), [tw] "+v"(tw), [tx] "+v"(tx), \
+                    [sst] "+s"(sst), [sprev] "+s"(sprev), [kph] "+s"(kph), [n] "+s"(n)
+#define OGC_RUN_IN [wrd] "v"(w_rd), [xrd] "v"(x_rd), [ktt] "s"(kt_total), [m0w] "s"(m0w), [incwn] "s"(incwn), [incww] "s"(incww), \
+                   [incxn] "s"(incxn), [incxw] "s"(incxw), [flip] "s"(flip), [stg] "n"(C::STAGE), [ring] "n"(C::RING)
+#define OGC_RUN_SHAPES(OP, FL)                                                                                              \
+    if constexpr (SHAPE == 0)                                                                                               \
+        asm volatile(OGC_RUN(OP, FL, OGC_NODMA, OGC_DMA, "sst", 6, 4096, 8192, 12288, 16384, 20480, OGC_DMA)                \
+                     : OGC_RUN_OUT, OGC_STEP_G6 : OGC_RUN_IN : "memory", "scc");                                            \
+    else if constexpr (!LATE)                                                                                               \
+        asm volatile(OGC_RUN(OP, FL, OGC_NODMA, OGC_DMA, "sst", 8, 8192, 16384, 24576, 0, 0, OGC_NODMA)                     \
+                     : OGC_RUN_OUT, OGC_STEP_G4 : OGC_RUN_IN : "memory", "scc");                                            \
+    else                                                                                                                    \
+        asm volatile(OGC_RUN(OP, FL, OGC_DMA, OGC_NODMA, "sprev", 8, 8192, 16384, 24576, 0, 0, OGC_NODMA)                   \
+                     : OGC_RUN_OUT, OGC_STEP_G4 : OGC_RUN_IN : "memory", "scc");
+#define OGC_RUN_FL(OP)                          \
+    if constexpr (FLIP) {                       \
+        OGC_RUN_SHAPES(OP, OGC_FLIP4)           \
+    } else {                                    \
+        OGC_RUN_SHAPES(OP, OGC_NOFLIP4)         \
+    }
+    if constexpr (DT == OGC_I8) {
+        OGC_RUN_FL("v_mfma_i32_32x32x32_i8")
+    } else {
+        OGC_RUN_FL("v_mfma_f32_32x32x16_bf16")
+    }
+#undef OGC_RUN_FL
+#undef OGC_RUN_SHAPES
 }
 
 // Copies accumulator block B (v[128+16B ..]) into compiler-visible registers.  The block's last MFMA may
@@ -181,170 +307,216 @@ __global__ void __launch_bounds__(StreamCfg<SHAPE>::NT, 2) __attribute__((amdgpu
 ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_per_xcd, int slots) {
     typedef StreamCfg<SHAPE> C;
     static_assert(C::NUM_VGPR_ATTR == 40, "keep the attribute above in step with the register map");
-    constexpr int OPW = C::OPW, NST = C::NST;
+    constexpr int OPW = C::OPW, NST = C::NST, VM = (NST - 2) * OPW;
     constexpr int TN = C::TN, TM = C::TM;
     constexpr bool FLIP = X_PLAIN && DT == OGC_I8;
     extern __shared__ __align__(1024) uint8_t smem[];
     // v80..v255 are used by the assembly below only; naming the last one makes the kernel own all 256.
     asm volatile("; operand sets and accumulators live in v80..v255" ::: "v255");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave % C::WAVES_N, wm = wave / C::WAVES_N;
     const int KT = a.KC >> 2;
     const int xcd = blockIdx.x & 7;
     int t_end = (xcd + 1) * tiles_per_xcd;
     t_end = t_end < tiles_total ? t_end : tiles_total;
-    int cur_tile = xcd * tiles_per_xcd + (blockIdx.x >> 3);
-    if (cur_tile >= t_end) return;
-    const int my_tiles = (t_end - cur_tile + slots - 1) / slots;
+    const int first_tile = xcd * tiles_per_xcd + (blockIdx.x >> 3);
+    if (first_tile >= t_end) return;
+    // (integer divisions run on the vector ALU: readfirstlane tells the compiler the results are wave-uniform)
+    const int my_tiles = __builtin_amdgcn_readfirstlane((t_end - first_tile + slots - 1) / slots);
     const int total_steps = my_tiles * KT;
+    // tile coordinates advance by `slots` tiles at a time: (n, m) += (dn, dm) with a carry, no division
+    const int dm = __builtin_amdgcn_readfirstlane(slots / tiles_n), dn = slots - dm * tiles_n;
+    auto next_tile = [&](int& n, int& m) {
+        n += dn;
+        m += dm;
+        if (n >= tiles_n) {
+            n -= tiles_n;
+            ++m;
+        }
+    };
 
-    // ---- prefetch cursor: per-wave load descriptors of the tile being fetched --------------------------
-    // op o of a stage is 1 KiB = two 512-byte slabs of one 32-row chunk; wave w issues ops w*OPW .. +OPW-1.
+    // ---- prefetch cursor ------------------------------------------------------------------------------
+    // A stage is OPS loads of 1 KiB (two 512-byte slabs of one 32-row chunk); load i of wave w is op
+    // o = i*WAVES + w, so loads 0 and 1 of every wave fetch weights and the others activations.  g[i] is the
+    // global address of this wave's load i for the k-step the cursor points at; the step block advances it.
     // The k-steps of a tile are walked in rotated order, starting at rot = n_tile*KT/tiles_n: the workgroups
     // that share a batch tile (its n-tiles, resident together on one XCD) then touch different k-slices of the
     // activations at any moment, so each slice is missed in L2 by one of them and hit by the others later,
     // instead of all of them waiting on the same miss.  Accumulation order within a tile is free (integer
     // sums are exact; float sums stay within the stated tolerance).
-    const uint8_t* gsrc[6];
-    int pf_tile = cur_tile, pf_kt = 0, pf_rot = 0;
-    auto setup_src = [&](int t) {
-        const int n_base = (t % tiles_n) * C::BN, m_base = (t / tiles_n) * C::BM;
-        pf_rot = (int)(((long long)(t % tiles_n) * KT) / tiles_n);
+    static_assert(C::W_OPS == 2 * C::WAVES, "loads 0,1 of a wave are weights, the rest activations");
+    uint64_t g[6] = {0, 0, 0, 0, 0, 0};
+    const long long x_step = X_PLAIN ? 64 : 2048;
+    int pf_m = __builtin_amdgcn_readfirstlane(first_tile / tiles_n), pf_n = first_tile - pf_m * tiles_n;
+    int pf_left = my_tiles, pf_kt = 0, pf_kphys = 0;
+    auto setup_src = [&]() {  // addresses of the cursor tile's first (rotated) k-step
+        pf_kphys = __builtin_amdgcn_readfirstlane((int)((uint32_t)(pf_n * KT) / (uint32_t)tiles_n));
+        pf_kt = 0;
+        const int n_base = pf_n * C::BN, m_base = pf_m * C::BM;
 #pragma unroll
         for (int i = 0; i < OPW; ++i) {
-            const int o = wave * OPW + i;
-            if (o < C::W_OPS) {
-                gsrc[i] = a.w + ((size_t)((n_base >> 5) + (o >> 1)) * a.KC + (o & 1) * 2) * 512 + lane * 16;
+            const int o = i * C::WAVES + wave;
+            const uint8_t* src;
+            if (i < 2) {
+                src = a.w + ((size_t)((n_base >> 5) + (o >> 1)) * a.KC + (o & 1) * 2) * 512 + lane * 16 + (long long)pf_kphys * 2048;
             } else {
                 const int ox = o - C::W_OPS;
                 if constexpr (X_PLAIN) {
                     int row = m_base + (ox >> 1) * 32 + (lane & 31);
                     row = row < a.M ? row : a.M - 1;
-                    gsrc[i] = a.x + (long long)row * a.ldx_bytes + ((ox & 1) * 2 + (lane >> 5)) * 16;
+                    src = a.x + (long long)row * a.ldx_bytes + ((ox & 1) * 2 + (lane >> 5)) * 16;
                 } else {
-                    gsrc[i] = a.x + ((size_t)((m_base >> 5) + (ox >> 1)) * a.KC + (ox & 1) * 2) * 512 + lane * 16;
+                    src = a.x + ((size_t)((m_base >> 5) + (ox >> 1)) * a.KC + (ox & 1) * 2) * 512 + lane * 16;
                 }
+                src += (long long)pf_kphys * x_step;
             }
+            g[i] = (uint64_t)(uintptr_t)src;
         }
     };
-    // Global addresses of the prefetch cursor's k-step, then the cursor advance.
-    auto pf_addresses = [&](uint64_t(&g)[6]) {
-        int kphys = pf_kt + pf_rot;
-        kphys = kphys >= KT ? kphys - KT : kphys;
-#pragma unroll
-        for (int i = 0; i < OPW; ++i) {
-            const int o = wave * OPW + i;
-            const long long step = (X_PLAIN && o >= C::W_OPS) ? 64 : 2048;
-            g[i] = (uint64_t)(uintptr_t)(gsrc[i] + (long long)kphys * step);
-        }
-#pragma unroll
-        for (int i = OPW; i < 6; ++i) g[i] = 0;
-        if (++pf_kt == KT) {
-            pf_kt = 0;
-            pf_tile += slots;
-            if (pf_tile < t_end) setup_src(pf_tile);
+    // The address increments that take the cursor from its current k-step to the next one of the same tile
+    // (the rotated walk wraps from the last physical k-step back to the first).
+    uint64_t incw = 2048, incx = (uint64_t)x_step;
+    const uint64_t incw_wrap = (uint64_t)(-(long long)(KT - 1) * 2048), incx_wrap = (uint64_t)(-(long long)(KT - 1) * x_step);
+    auto set_increments = [&]() {  // for the transition out of the cursor's current k-step
+        const bool wrap = pf_kphys + 1 == KT;
+        incw = wrap ? incw_wrap : (uint64_t)2048;
+        incx = wrap ? incx_wrap : (uint64_t)x_step;
+        pf_kphys = wrap ? 0 : pf_kphys + 1;
+    };
+    // after the loads of `n` more k-steps have been issued: a finished tile moves the cursor to the next one
+    auto cursor_advanced = [&](int n) {
+        pf_kt += n;
+        if (pf_kt == KT) {
+            --pf_left;
+            next_tile(pf_n, pf_m);
+            if (pf_left > 0) setup_src();
+            else pf_kt = 0;
         }
     };
     const uint32_t lds0 = lds_addr_of(smem);
-    const uint32_t m0_wave = lds0 + wave * OPW * 1024;  // + stage*STAGE: where this wave's loads land
-    auto prologue_loads = [&](int stage) {
-        if (pf_tile >= t_end) return;
-        uint64_t g[6];
-        pf_addresses(g);
-        const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + stage * C::STAGE);
-        if constexpr (OPW == 6)
-            asm volatile(OGC_DMA(0, 0) OGC_DMA(1, 1024) OGC_DMA(2, 2048) OGC_DMA(3, 3072) OGC_DMA(4, 4096) OGC_DMA(5, 5120)
-                         "s_nop 0" ::OGC_G_OPERANDS
-                         : "memory");
-        else
-            asm volatile(OGC_DMA(0, 0) OGC_DMA(1, 1024) OGC_DMA(2, 2048) OGC_DMA(3, 3072) "s_nop 0" ::OGC_G_OPERANDS : "memory");
-    };
+    const uint32_t m0_wave = lds0 + wave * 1024;  // + stage*STAGE + i*WAVES*1024: where this wave's load i lands
     const uint32_t w_rd = lds0 + (wn * TN) * 2048 + lane * 16;
     const uint32_t x_rd = lds0 + C::BN * 64 + (wm * TM) * 2048 + lane * 16;
-    auto wait_barrier = [&](int newer_stages) {  // newer_stages: load stages allowed to remain in flight
-        if (newer_stages >= 3) wait_loads_then_barrier<3 * OPW>();
-        else if (newer_stages == 2) wait_loads_then_barrier<2 * OPW>();
-        else if (newer_stages == 1) wait_loads_then_barrier<OPW>();
-        else wait_loads_then_barrier<0>();
-    };
 
-    // Schedule (software pipelined by half a k-step; the ring slot of step q is q % NST):
-    //   prologue: loads of steps 0..NST-1 in flight; wait for step 0; barrier; read F0(step 0)
-    //   step q, first half : read F1(q) | MFMA on F0
-    //           wait for the loads of step q+1 (steps q+2..q+NST-1 may stay in flight); barrier B_q
-    //           -- every wave has now finished ALL its LDS reads of steps <= q, so slot q % NST is free --
-    //           second half: read F0(q+1) | MFMA on F1 | loads of step q+NST into slot q % NST
-    //           last step of a tile: epilogue from registers (the next tile's loads keep flying)
+    // Schedule (the ring slot of step q is q % NST):
+    //   prologue: loads of the first steps in flight; wait for step 0; barrier; read F0(step 0)
+    //   step q  : its barrier B_q comes after every wave has finished ALL its LDS reads of steps <= q and has
+    //             seen its own loads of step q+1 land, so after B_q stage q+1 is complete and slot q % NST is
+    //             free.  An "early" wave issues the loads of step q+NST right after B_q; a "late" wave (the
+    //             second wave of each SIMD in the eight-wave shape) issues them during the first half of step
+    //             q+1, so it runs one stage behind: its prologue issues NST-1 stages
+    //   last step of a tile: epilogue from registers (the next tile's loads keep flying)
     // Per-channel parameters of a tile's 128/256 channels are staged in LDS (two buffers, alternating per tile)
     // as soon as the previous tile's epilogue is done: the epilogue then reads them with LDS loads, which do
     // not queue behind the direct loads in flight the way global loads would.  Layout: scale | bias.  (The plan
     // selects this kernel only for int8 layers whose input zero point is 128: no compensation term.)
     typedef __attribute__((address_space(3))) uint8_t lds_u8;
     lds_u8* const params_lds = (lds_u8*)smem + C::RING;
-    auto stage_params = [&](int t, int buf) {
+    auto stage_params = [&](int n_tile, int buf) {
         if (tid < C::BN) {
-            const int n = (t % tiles_n) * C::BN + tid;
+            const int n = n_tile * C::BN + tid;
             lds_u8* pb = params_lds + buf * C::PARAMS;
             ((__attribute__((address_space(3))) float*)pb)[tid] = (DT == OGC_I8) ? a.scale[n] : 0.0f;
             ((__attribute__((address_space(3))) float*)pb)[C::BN + tid] = a.has_bias ? a.bias[n] : 0.0f;
         }
     };
+    const bool late = SHAPE == 1 && wave >= 4;
+    int cur_n = pf_n, cur_m = pf_m, tiles_left = my_tiles;
     int pbuf = 0;
-    stage_params(cur_tile, 0);
-    const uint64_t g_none[6] = {0, 0, 0, 0, 0, 0};
-    setup_src(pf_tile);
+    stage_params(cur_n, 0);
+    setup_src();
+    int fetched = 0;  // k-steps whose loads this wave has issued
+    {
+        const int want = late ? NST - 1 : NST;
 #pragma unroll
-    for (int st = 0; st < NST; ++st) prologue_loads(st);
-    wait_barrier(total_steps - 1 < NST - 1 ? total_steps - 1 : NST - 1);
-    if constexpr (FLIP) {
-        const uint32_t flip = 0x80808080u;
-        asm volatile(OGC_READ(80) "s_waitcnt lgkmcnt(0)\n\t" OGC_FLIP(80)::[wa] "v"(w_rd), [xa] "v"(x_rd), [flip] "s"(flip)
-                     : "memory");
-    } else {
-        asm volatile(OGC_READ(80) "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
-    }
-    int stage = 0, kt = 0;
-    bool drained = false;  // an epilogue ran since the last wait: its loads and stores are pending too
-    for (int q = 0; q < total_steps; ++q) {
-        const bool more = q + 1 < total_steps;
-        const int nstage = stage == NST - 1 ? 0 : stage + 1;
-        {  // first half: MFMA on F0, fetch F1 (the second 32 bytes of this step)
-            const uint32_t wa = w_rd + stage * C::STAGE + 1024, xa = x_rd + stage * C::STAGE + 1024;
-            if (kt == 0) half_step<DT, OPW, 80, true, false, true, FLIP>(wa, xa, g_none, 0);
-            else half_step<DT, OPW, 80, true, false, false, FLIP>(wa, xa, g_none, 0);
-        }
-        if (more) {  // second half: MFMA on F1, fetch F0 of the next step, issue the loads of step q+3
-            // loads outstanding, oldest first: step q+1, then q+2 .. q+NST-1 as far as they exist
-            const int newer = total_steps - 2 - q < NST - 2 ? total_steps - 2 - q : NST - 2;
-            wait_barrier(drained ? 0 : newer);
-            drained = false;
-            const uint32_t wa = w_rd + nstage * C::STAGE, xa = x_rd + nstage * C::STAGE;
-            if (pf_tile < t_end) {
-                uint64_t g[6];
-                pf_addresses(g);
-                const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + stage * C::STAGE);
-                half_step<DT, OPW, 104, true, true, false, FLIP>(wa, xa, g, m0b);
-            } else {
-                half_step<DT, OPW, 104, true, false, false, FLIP>(wa, xa, g_none, 0);
+        for (int st = 0; st < NST; ++st) {
+            if (st < want && fetched < total_steps) {
+                set_increments();
+                const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + st * C::STAGE);
+                if constexpr (OPW == 6)
+                    asm volatile(OGC_DMA(0, 0, "incw") OGC_DMA(1, 4096, "incw") OGC_DMA(2, 8192, "incx") OGC_DMA(3, 12288, "incx")
+                                     OGC_DMA(4, 16384, "incx") OGC_DMA(5, 20480, "incx") "s_nop 0"
+                                 : OGC_STEP_G6 : OGC_STEP_DMA_IN : "memory", "scc");
+                else
+                    asm volatile(OGC_DMA(0, 0, "incw") OGC_DMA(1, 8192, "incw") OGC_DMA(2, 16384, "incx") OGC_DMA(3, 24576, "incx")
+                                     "s_nop 0"
+                                 : OGC_STEP_G4 : OGC_STEP_DMA_IN : "memory", "scc");
+                ++fetched;
+                cursor_advanced(1);
             }
-        } else {
-            half_step<DT, OPW, 104, false, false, false, false>(0, 0, g_none, 0);
         }
-        stage = nstage;
-        if (++kt == KT) {
+        // step 0 has landed when at most fetched-1 newer stages remain in flight
+        if (fetched >= 4) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(3 * OPW) : "memory");
+        else if (fetched == 3) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * OPW) : "memory");
+        else if (fetched == 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(OPW) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+    asm volatile(OGC_READ(80, "%[wa]", "%[xa]") "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
+    uint32_t sst = 0, sprev = (NST - 1) * C::STAGE;  // ring offsets of the current and the previous step's stage
+    int kt = 0, q = 0;
+    bool drained = false;  // an epilogue ran since the last wait: its loads and stores are pending too
+    while (q < total_steps) {
+        const bool can_fetch = fetched < total_steps;
+        if (kt > 0 && !drained && can_fetch) {
+            // a run of ordinary steps: up to the end of this tile, of the cursor's tile, or of the stream
+            int n = KT - kt;
+            n = n < KT - pf_kt ? n : KT - pf_kt;
+            n = n < total_steps - fetched ? n : total_steps - fetched;
+            uint32_t kph = (uint32_t)pf_kphys;
+            if (late) k_steps_run<DT, SHAPE, SHAPE == 1, FLIP>(w_rd, x_rd, g, sst, sprev, kph, n, KT, m0_wave, 2048, incw_wrap, (uint64_t)x_step, incx_wrap);
+            else k_steps_run<DT, SHAPE, false, FLIP>(w_rd, x_rd, g, sst, sprev, kph, n, KT, m0_wave, 2048, incw_wrap, (uint64_t)x_step, incx_wrap);
+            pf_kphys = (int)kph;
+            kt += n;
+            q += n;
+            fetched += n;
+            cursor_advanced(n);
+        } else {
+            const uint32_t snext = sst + C::STAGE == C::RING ? 0 : sst + C::STAGE;
+            const uint32_t soc = sst + 1024, son = snext;
+            const bool zero = kt == 0;
+            if (can_fetch) {
+                set_increments();
+                const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + (late ? sprev : sst));
+                // a late wave has one stage fewer in flight at this point (its loads follow the barrier here)
+                if (drained) {
+                    if (zero) k_step<DT, OPW, VM, 1, true, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
+                    else k_step<DT, OPW, VM, 1, false, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
+                } else if (late) {
+                    if (zero) k_step<DT, OPW, SHAPE == 1 ? 4 : VM, 0, true, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
+                    else k_step<DT, OPW, SHAPE == 1 ? 4 : VM, 0, false, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
+                } else {
+                    if (zero) k_step<DT, OPW, VM, 0, true, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
+                    else k_step<DT, OPW, VM, 0, false, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
+                }
+                ++fetched;
+                cursor_advanced(1);
+            } else if (q + 1 < total_steps) {
+                if (zero) k_step<DT, OPW, VM, 2, true, FLIP>(w_rd, x_rd, soc, son, g, 0, 0, 0);
+                else k_step<DT, OPW, VM, 2, false, FLIP>(w_rd, x_rd, soc, son, g, 0, 0, 0);
+            } else {
+                if (zero) k_step<DT, OPW, VM, 3, true, FLIP>(w_rd, x_rd, soc, son, g, 0, 0, 0);
+                else k_step<DT, OPW, VM, 3, false, FLIP>(w_rd, x_rd, soc, son, g, 0, 0, 0);
+            }
+            sprev = sst;
+            sst = snext;
+            drained = false;
+            ++kt;
+            ++q;
+        }
+        if (kt == KT) {
             kt = 0;
             // the accumulators are read by ordinary vector instructions next: let the last MFMA drain first
             asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
-            const int n_base = (cur_tile % tiles_n) * C::BN + wn * TN * 32, m_base = (cur_tile / tiles_n) * C::BM + wm * TM * 32;
+            const int n_base = cur_n * C::BN + wn * TN * 32, m_base = cur_m * C::BM + wm * TM * 32;
             BlockParams prm;
             auto read_params = [&](int i) {  // the lane's parameters for weight block i of this wave
                 const lds_u8* pb = params_lds + pbuf * C::PARAMS;
                 const int nl = (wn * TN + i) * 32 + 4 * (lane >> 5);
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    prm.s[g] = *(const __attribute__((address_space(3))) v4f*)(pb + (nl + 8 * g) * 4);
-                    prm.b[g] = *(const __attribute__((address_space(3))) v4f*)(pb + (C::BN + nl + 8 * g) * 4);
-                    prm.c[g] = (v4i){0, 0, 0, 0};
+                for (int gq = 0; gq < 4; ++gq) {
+                    prm.s[gq] = *(const __attribute__((address_space(3))) v4f*)(pb + (nl + 8 * gq) * 4);
+                    prm.b[gq] = *(const __attribute__((address_space(3))) v4f*)(pb + (C::BN + nl + 8 * gq) * 4);
+                    prm.c[gq] = (v4i){0, 0, 0, 0};
                 }
             };
             auto block = [&](auto tag) {
@@ -372,12 +544,12 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             // the next tile's parameters go to the other buffer (waves still in this epilogue keep reading this
             // one); the barrier of the next tile's first step orders the writes before its epilogue's reads, and
             // a one-step tile has no such barrier, hence the explicit one
-            if (cur_tile + slots < t_end) {
-                stage_params(cur_tile + slots, pbuf ^ 1);
+            next_tile(cur_n, cur_m);
+            if (--tiles_left > 0) {
+                stage_params(cur_n, pbuf ^ 1);
                 if (KT == 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             }
             pbuf ^= 1;
-            cur_tile += slots;
             drained = true;
         }
     }
