@@ -24,6 +24,7 @@ struct LayerPlan {
     int nb_out;       // 32-channel blocks written to a KB16 output (0 for the last layer)
     int kc_out;       // chunks per row of the KB16 output
     int tile;         // per-layer mode: tile configuration
+    int ksplit_log2;  // stream tiles only: the reduction axis is cut into 1 << ksplit_log2 ranges (0: not split)
     size_t w_off, scale_off, bias_off, ncomp_off;  // offsets in the packed blob
     int out_slot;     // workspace slot of the output (-1: caller's y / LDS)
     size_t out_off;   // byte offset of that slot in the workspace
@@ -40,6 +41,7 @@ struct ogc_mlp_plan_s {
     int mp;    // padded batch rows of the workspace buffers
     size_t packed_bytes, workspace_bytes;
     int lds_buf_bytes;  // fused mode
+    size_t partial_off, partial_bytes;  // split-K partial accumulators, after the activation slots
     std::vector<size_t> slot_off, slot_size;
     std::atomic<int> prepacked;
 };
@@ -234,9 +236,31 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
                                 !(desc->dtype == OGC_I8 && lp.d.in_zp != 128) &&
                                 (l > 0 || (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
             lp.tile = choose_tile(desc->m, rows, dma_ok);
+            lp.ksplit_log2 = 0;
+            // Too few 256x256 tiles for the chip but a long reduction axis: cut K into ranges (the paper's
+            // k-slicing, Section III) so that tiles x ranges fill the CUs; a second pass adds the ranges.
+            {
+                const OgcTileInfo t8 = ogc_tile_info(OGC_TILE_DMA8);
+                const long tiles8 = (long)((desc->m + t8.bm - 1) / t8.bm) * ((rows + t8.bn - 1) / t8.bn);
+                const int kt = lp.kc / 4;
+                const int forced_tile = env_int("OGC_TILE", -1), forced_split = env_int("OGC_KSPLIT", -1);
+                if (forced_split >= 0) {
+                    if (forced_split > 0 && (lp.tile == OGC_TILE_DMA8 || lp.tile == OGC_TILE_DMA) && forced_split <= 3 &&
+                        kt % (1 << forced_split) == 0)
+                        lp.ksplit_log2 = forced_split;
+                } else if (dma_ok && forced_tile < 0 && lp.tile != OGC_TILE_DMA8 && lp.tile != OGC_TILE_DMA) {
+                    for (int ls = 1; ls <= 3; ++ls)
+                        if (kt % (1 << ls) == 0 && (kt >> ls) >= 8 && (tiles8 << ls) >= 192) {
+                            lp.tile = OGC_TILE_DMA8;
+                            lp.ksplit_log2 = ls;
+                            break;
+                        }
+                }
+            }
             lp.npw = (int)round_up((size_t)rows, ogc_tile_info(lp.tile).bn);
         } else {
             lp.tile = -1;
+            lp.ksplit_log2 = 0;
             lp.npw = (int)round_up((size_t)rows, 32);
         }
         lp.w_off = off;
@@ -249,8 +273,20 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         off += round_up((size_t)lp.npw * 4, 256);
     }
     p->packed_bytes = off;
+    p->partial_off = p->partial_bytes = 0;
     if (mode == OGC_MODE_PER_LAYER) {
         assign_buffers(p);
+        for (int l = 0; l < L; ++l) {
+            const LayerPlan& lp = p->layers[l];
+            if (lp.ksplit_log2 > 0) {
+                const size_t need = ((size_t)p->mp * lp.npw * 4) << lp.ksplit_log2;
+                if (need > p->partial_bytes) p->partial_bytes = need;
+            }
+        }
+        if (p->partial_bytes > 0) {
+            p->partial_off = round_up(p->workspace_bytes, 256);
+            p->workspace_bytes = p->partial_off + p->partial_bytes;
+        }
     } else {
         for (int l = 0; l < L; ++l) {
             p->layers[l].out_slot = -1;
@@ -349,6 +385,7 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
             if (plan->desc.residual) {
                 a->res = (const uint8_t*)x;
                 a->ldres_bytes = ldx_b;
+                a->res_vec_ok = ((uintptr_t)x % 16 == 0) && (ldx_b % 16 == 0);
             }
         }
     };
@@ -371,6 +408,12 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
         finish_args(l, &a);
         if (l > 0) a.x = ws + plan->layers[l - 1].out_off;
         if (l < L - 1) a.y = ws + plan->layers[l].out_off;
+        if (plan->layers[l].ksplit_log2 > 0) {
+            a.ksplit_log2 = plan->layers[l].ksplit_log2;
+            a.partial = ws + plan->partial_off;
+            a.pmb = plan->mp / 32;
+            a.pnb = plan->layers[l].npw / 32;
+        }
         if (ev && hipEventRecord(ev[l], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
         const int rc = ogc_launch_layer(plan->desc.dtype, plan->layers[l].tile, l == 0, l == L - 1, &a, stream);
         if (rc != 0) return OGC_ERR_DEVICE;
@@ -432,7 +475,7 @@ const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer) {
     const int L = (int)plan->layers.size();
     const ogc_layer_desc& d = plan->layers[layer].d;
     return ogc_layer_kernel_name(plan->desc.dtype, plan->layers[layer].tile, layer == 0, layer == L - 1, d.act,
-                                 d.out == OGC_OUT_F32);
+                                 d.out == OGC_OUT_F32, plan->layers[layer].ksplit_log2 > 0);
 }
 
 }  // extern "C"

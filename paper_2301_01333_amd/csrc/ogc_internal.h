@@ -49,6 +49,13 @@ struct OgcLayerArgs {
     int32_t has_bias;
     float q_hi;            // I8: 255 - out_zp
     uint32_t q_add, q_xor; // I8: packed-byte zero-point add and u8 -> internal s8 flip for four results at once
+    // Split-K (stream kernel only): the reduction axis is cut into 1 << ksplit_log2 equal ranges, each computed by
+    // its own workgroup, which writes its raw accumulators to `partial`; a second kernel adds the ranges in a
+    // fixed order and applies the epilogue.  Partial layout: [range][M block of 32][N block of 32][4][64 lanes]
+    // x 16 bytes, i.e. each wave stores its accumulator registers as they are.
+    int32_t ksplit_log2;
+    uint8_t* partial;
+    int32_t pmb, pnb;      // 32-row / 32-channel blocks per range in `partial`
 };
 
 struct OgcChainArgs {
@@ -74,7 +81,7 @@ int ogc_launch_fused(int dtype, const OgcChainArgs* c, int m_blocks, void* strea
 int ogc_launch_prepack_weights(const void* w, void* out, int K, int N, int KC, int NPw, int esz, void* stream);
 int ogc_launch_prepack_params(int dtype, const void* w, const float* w_scale, const float* bias, float in_scale, int in_zp,
                               int K, int N, int NPw, float* scale_out, float* bias_out, int32_t* ncomp_out, void* stream);
-const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, int out_plain, int act, int out_f32);
+const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, int out_plain, int act, int out_f32, int split);
 const char* ogc_fused_kernel_name(int dtype);
 size_t ogc_fused_lds_limit(void);
 int ogc_fused_threads(void);

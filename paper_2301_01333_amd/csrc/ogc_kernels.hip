@@ -191,6 +191,20 @@ OGC_DEV void add_residual(float (&out)[16], const OgcLayerArgs& a, int m, int n0
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const int n = n0 + 8 * g + 4 * h;
+        if (a.res_vec_ok && n + 4 <= a.N) {  // four consecutive channels in one load (n is a multiple of 4)
+            if constexpr (DT == OGC_F32) {
+                const v4f r = *(const v4f*)(row + (size_t)n * 4);
+                out[4 * g] += r.x, out[4 * g + 1] += r.y, out[4 * g + 2] += r.z, out[4 * g + 3] += r.w;
+            }
+            if constexpr (DT == OGC_BF16) {
+                const uint2 r = *(const uint2*)(row + (size_t)n * 2);
+                out[4 * g] += __builtin_bit_cast(float, r.x << 16);
+                out[4 * g + 1] += __builtin_bit_cast(float, r.x & 0xffff0000u);
+                out[4 * g + 2] += __builtin_bit_cast(float, r.y << 16);
+                out[4 * g + 3] += __builtin_bit_cast(float, r.y & 0xffff0000u);
+            }
+            continue;
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (n + e < a.N) {
@@ -616,6 +630,43 @@ extern "C" OgcTileInfo ogc_tile_info(int tile) {
     }
 }
 
+// Second pass of a split-K layer: adds the partial accumulators of the k ranges in ascending order (a fixed
+// order: the result does not depend on which workgroup finished first) and applies the ordinary epilogue.
+// One wave per 32x32 block; the partial buffer holds every wave's accumulator registers as they were.
+template <int DT, int OUT_PLAIN>
+__global__ void __launch_bounds__(256) ogc_splitk_reduce_kernel(const OgcLayerArgs a, int nb, int total_blocks) {
+    const int lane = threadIdx.x & 63;
+    const int blk = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (blk >= total_blocks) return;
+    const int bm = blk / nb, bn = blk - bm * nb;
+    const int ranges = 1 << a.ksplit_log2;
+    const size_t range_stride = (size_t)a.pmb * a.pnb * 4096;
+    const uint8_t* src = a.partial + ((size_t)bm * a.pnb + bn) * 4096 + lane * 16;
+    typename AccT<DT>::type acc;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if constexpr (DT == OGC_I8) {
+            v4i sum = *(const v4i*)(src + q * 1024);
+            for (int r = 1; r < ranges; ++r) sum += *(const v4i*)(src + r * range_stride + q * 1024);
+            acc[4 * q] = sum.x, acc[4 * q + 1] = sum.y, acc[4 * q + 2] = sum.z, acc[4 * q + 3] = sum.w;
+        } else {
+            v4f sum = *(const v4f*)(src + q * 1024);
+            for (int r = 1; r < ranges; ++r) sum += *(const v4f*)(src + r * range_stride + q * 1024);
+            acc[4 * q] = sum.x, acc[4 * q + 1] = sum.y, acc[4 * q + 2] = sum.z, acc[4 * q + 3] = sum.w;
+        }
+    }
+    if constexpr (OUT_PLAIN) epilogue_block<DT, 1>(acc, a, bn * 32, bm * 32, lane, (uint8_t*)nullptr);
+    else epilogue_block<DT, 0>(acc, a, bn * 32, bm * 32, lane, a.y + (size_t)bm * a.KC_out * 512);
+}
+
+template <int DT> static int launch_splitk_reduce(int op, const OgcLayerArgs* a, hipStream_t stream) {
+    const int nb = op ? (a->N + 31) / 32 : a->NB_out;
+    const int total = ((a->M + 31) / 32) * nb;
+    if (op) hipLaunchKernelGGL((ogc_splitk_reduce_kernel<DT, 1>), dim3((total + 3) / 4), dim3(256), 0, stream, *a, nb, total);
+    else hipLaunchKernelGGL((ogc_splitk_reduce_kernel<DT, 0>), dim3((total + 3) / 4), dim3(256), 0, stream, *a, nb, total);
+    return (int)hipGetLastError();
+}
+
 template <int DT, int TILE, int XP, int OP>
 static int launch_layer_t(const OgcLayerArgs* a, hipStream_t stream) {
     const OgcTileInfo ti = tile_info_t<TILE>();
@@ -660,8 +711,9 @@ static int launch_dma_t(const OgcLayerArgs* a, hipStream_t stream) {
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    const int nrows = OP ? a->N : a->NB_out * 32;
-    const int tiles_n = (nrows + C::BN - 1) / C::BN;
+    // (a split-K launch always writes partials; NB_out == 0 marks the chain's last layer, whose width is N)
+    const int nrows = (OP || (EPI == 2 && a->NB_out == 0)) ? a->N : a->NB_out * 32;
+    const int tiles_n = ((nrows + C::BN - 1) / C::BN) << (EPI == 2 ? a->ksplit_log2 : 0);  // x k ranges when split
     const int tiles_m = (a->M + C::BM - 1) / C::BM;
     const int total = tiles_n * tiles_m;
     const int per_xcd = (total + 7) / 8;
@@ -677,9 +729,18 @@ static int launch_dma_io(int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
     return op ? launch_dma_t<DT, SHAPE, 0, 1, EPI>(a, s) : launch_dma_t<DT, SHAPE, 0, 0, EPI>(a, s);
 }
 
-// EPI = 1: int8 layer with ReLU and a requantized result (the five-op epilogue only)
+// EPI = 1: int8 layer with ReLU and a requantized result (the five-op epilogue only); 2: split-K partials,
+// followed by the reduction pass that owns the epilogue
 template <int SHAPE>
 static int launch_dma_dtype(int dtype, int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
+    if (a->ksplit_log2 > 0) {
+        int rc;
+        if (dtype == OGC_BF16) rc = xp ? launch_dma_t<OGC_BF16, SHAPE, 1, 0, 2>(a, s) : launch_dma_t<OGC_BF16, SHAPE, 0, 0, 2>(a, s);
+        else if (dtype == OGC_I8) rc = xp ? launch_dma_t<OGC_I8, SHAPE, 1, 0, 2>(a, s) : launch_dma_t<OGC_I8, SHAPE, 0, 0, 2>(a, s);
+        else return (int)hipErrorInvalidValue;
+        if (rc != 0) return rc;
+        return dtype == OGC_BF16 ? launch_splitk_reduce<OGC_BF16>(op, a, s) : launch_splitk_reduce<OGC_I8>(op, a, s);
+    }
     if (dtype == OGC_BF16) return launch_dma_io<OGC_BF16, SHAPE, 0>(xp, op, a, s);
     if (dtype == OGC_I8) {
         if (a->act == OGC_ACT_RELU && !a->out_f32) return launch_dma_io<OGC_I8, SHAPE, 1>(xp, op, a, s);
@@ -749,11 +810,12 @@ extern "C" int ogc_launch_prepack_params(int dtype, const void* w, const float* 
 }
 
 // Kernel names with their template arguments, spelled the way a kernel trace prints them.
-extern "C" const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, int out_plain, int act, int out_f32) {
-    static char names[3][OGC_NUM_TILES][2][2][2][48];
+extern "C" const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, int out_plain, int act, int out_f32, int split) {
+    static char names[3][OGC_NUM_TILES][2][2][3][48];
     if (dtype < 0 || dtype > 2 || tile < 0 || tile >= OGC_NUM_TILES) return "?";
     const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8;
-    const int epi = stream && dtype == OGC_I8 && act == OGC_ACT_RELU && !out_f32;
+    const int epi = (stream && split) ? 2 : (stream && dtype == OGC_I8 && act == OGC_ACT_RELU && !out_f32);
+    if (epi == 2) out_plain = 0;
     char* n = names[dtype][tile][x_plain != 0][out_plain != 0][epi];
     if (!n[0]) {
         char tmp[48];

@@ -276,32 +276,31 @@ OGC_DEV void k_steps_run(uint32_t w_rd, uint32_t x_rd, uint64_t (&g)[6], uint32_
 #undef OGC_RUN_SHAPES
 }
 
-// Copies accumulator block B (v[128+16B ..]) into compiler-visible registers.  The block's last MFMA may
-// still be in flight: the caller has waited for it (see the s_nop before the epilogue).
+// Hands accumulator block B (v[128+16B ..]) to the compiler where it is: the empty statement declares the
+// sixteen registers as its output, and the epilogue then reads them as source operands (no copies; the
+// compiler cannot allocate, hence cannot write, registers above its cap).  The block's last MFMA may still be
+// in flight: the caller has waited for it (see the s_nop before the epilogue).  Every use feeds a store, and
+// the stores are ordered before the next k-step block, which overwrites the accumulators.
 template <int DT, int B> OGC_DEV typename AccT<DT>::type take_acc_block() {
-    int r[16];
-    asm volatile(
-        "v_mov_b32 %0, v[%c16+0]\n\tv_mov_b32 %1, v[%c16+1]\n\tv_mov_b32 %2, v[%c16+2]\n\tv_mov_b32 %3, v[%c16+3]\n\t"
-        "v_mov_b32 %4, v[%c16+4]\n\tv_mov_b32 %5, v[%c16+5]\n\tv_mov_b32 %6, v[%c16+6]\n\tv_mov_b32 %7, v[%c16+7]\n\t"
-        "v_mov_b32 %8, v[%c16+8]\n\tv_mov_b32 %9, v[%c16+9]\n\tv_mov_b32 %10, v[%c16+10]\n\tv_mov_b32 %11, v[%c16+11]\n\t"
-        "v_mov_b32 %12, v[%c16+12]\n\tv_mov_b32 %13, v[%c16+13]\n\tv_mov_b32 %14, v[%c16+14]\n\tv_mov_b32 %15, v[%c16+15]"
-        : "=v"(r[0]), "=v"(r[1]), "=v"(r[2]), "=v"(r[3]), "=v"(r[4]), "=v"(r[5]), "=v"(r[6]), "=v"(r[7]), "=v"(r[8]),
-          "=v"(r[9]), "=v"(r[10]), "=v"(r[11]), "=v"(r[12]), "=v"(r[13]), "=v"(r[14]), "=v"(r[15])
-        : "n"(128 + 16 * B));
-    typename AccT<DT>::type acc;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        if constexpr (DT == OGC_I8) acc[i] = r[i];
-        else acc[i] = __builtin_bit_cast(float, r[i]);
-    }
-    return acc;
+    v16i r;
+    if constexpr (B == 0) asm volatile("" : "={v[128:143]}"(r));
+    if constexpr (B == 1) asm volatile("" : "={v[144:159]}"(r));
+    if constexpr (B == 2) asm volatile("" : "={v[160:175]}"(r));
+    if constexpr (B == 3) asm volatile("" : "={v[176:191]}"(r));
+    if constexpr (B == 4) asm volatile("" : "={v[192:207]}"(r));
+    if constexpr (B == 5) asm volatile("" : "={v[208:223]}"(r));
+    if constexpr (B == 6) asm volatile("" : "={v[224:239]}"(r));
+    if constexpr (B == 7) asm volatile("" : "={v[240:255]}"(r));
+    if constexpr (DT == OGC_I8) return r;
+    else return __builtin_bit_cast(v16f, r);
 }
 
 // Grid: 8 * slots workgroups (slots <= tiles_per_xcd).  Workgroup wg belongs to XCD wg%8 and is slot wg/8 of
 // it; XCD x owns the contiguous tile range [x*tiles_per_xcd, (x+1)*tiles_per_xcd) and its slots walk that
 // range with stride `slots`, so the workgroups of one XCD always work on neighbouring tiles (the n-tiles of
 // one batch tile share its activations through that XCD's L2).
-// EPI: 1 = int8 ReLU + requantize epilogue only, 0 = every other combination
+// EPI: 1 = int8 ReLU + requantize epilogue only, 0 = every other combination, 2 = split-K: `tiles_n` counts
+// (channel tile, k range) pairs, a workgroup accumulates one k range of its tile and stores the raw accumulators
 template <int DT, int SHAPE, int X_PLAIN, int OUT_PLAIN, int EPI>
 __global__ void __launch_bounds__(StreamCfg<SHAPE>::NT, 2) __attribute__((amdgpu_num_vgpr(40)))
 ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_per_xcd, int slots) {
@@ -315,7 +314,8 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     asm volatile("; operand sets and accumulators live in v80..v255" ::: "v255");
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave % C::WAVES_N, wm = wave / C::WAVES_N;
-    const int KT = a.KC >> 2;
+    const int LS = EPI == 2 ? a.ksplit_log2 : 0;  // log2 of the number of k ranges
+    const int KT = (a.KC >> 2) >> LS;             // k-steps of one tile (of one k range of it)
     const int xcd = blockIdx.x & 7;
     int t_end = (xcd + 1) * tiles_per_xcd;
     t_end = t_end < tiles_total ? t_end : tiles_total;
@@ -352,13 +352,14 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     auto setup_src = [&]() {  // addresses of the cursor tile's first (rotated) k-step
         pf_kphys = __builtin_amdgcn_readfirstlane((int)((uint32_t)(pf_n * KT) / (uint32_t)tiles_n));
         pf_kt = 0;
-        const int n_base = pf_n * C::BN, m_base = pf_m * C::BM;
+        const int n_base = (pf_n >> LS) * C::BN, m_base = pf_m * C::BM;
+        const int k_first = (pf_n & ((1 << LS) - 1)) * KT + pf_kphys;  // physical k-step in the whole reduction axis
 #pragma unroll
         for (int i = 0; i < OPW; ++i) {
             const int o = i * C::WAVES + wave;
             const uint8_t* src;
             if (i < 2) {
-                src = a.w + ((size_t)((n_base >> 5) + (o >> 1)) * a.KC + (o & 1) * 2) * 512 + lane * 16 + (long long)pf_kphys * 2048;
+                src = a.w + ((size_t)((n_base >> 5) + (o >> 1)) * a.KC + (o & 1) * 2) * 512 + lane * 16 + (long long)k_first * 2048;
             } else {
                 const int ox = o - C::W_OPS;
                 if constexpr (X_PLAIN) {
@@ -368,7 +369,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                 } else {
                     src = a.x + ((size_t)((m_base >> 5) + (ox >> 1)) * a.KC + (ox & 1) * 2) * 512 + lane * 16;
                 }
-                src += (long long)pf_kphys * x_step;
+                src += (long long)k_first * x_step;
             }
             g[i] = (uint64_t)(uintptr_t)src;
         }
@@ -413,7 +414,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     typedef __attribute__((address_space(3))) uint8_t lds_u8;
     lds_u8* const params_lds = (lds_u8*)smem + C::RING;
     auto stage_params = [&](int n_tile, int buf) {
-        if (tid < C::BN) {
+        if (EPI != 2 && tid < C::BN) {
             const int n = n_tile * C::BN + tid;
             lds_u8* pb = params_lds + buf * C::PARAMS;
             ((__attribute__((address_space(3))) float*)pb)[tid] = (DT == OGC_I8) ? a.scale[n] : 0.0f;
@@ -423,7 +424,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     const bool late = SHAPE == 1 && wave >= 4;
     int cur_n = pf_n, cur_m = pf_m, tiles_left = my_tiles;
     int pbuf = 0;
-    stage_params(cur_n, 0);
+    stage_params(cur_n >> LS, 0);
     setup_src();
     int fetched = 0;  // k-steps whose loads this wave has issued
     {
@@ -507,7 +508,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             kt = 0;
             // the accumulators are read by ordinary vector instructions next: let the last MFMA drain first
             asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
-            const int n_base = cur_n * C::BN + wn * TN * 32, m_base = cur_m * C::BM + wm * TM * 32;
+            const int n_base = (cur_n >> LS) * C::BN + wn * TN * 32, m_base = cur_m * C::BM + wm * TM * 32;
             BlockParams prm;
             auto read_params = [&](int i) {  // the lane's parameters for weight block i of this wave
                 const lds_u8* pb = params_lds + pbuf * C::PARAMS;
@@ -522,7 +523,17 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             auto block = [&](auto tag) {
                 constexpr int B = decltype(tag)::value;
                 const int n0 = n_base + (B / 4) * 32, m0 = m_base + (B % 4) * 32;
-                if constexpr (OUT_PLAIN) {
+                if constexpr (EPI == 2) {
+                    const int range = cur_n & ((1 << LS) - 1);
+                    uint8_t* dst = a.partial + ((((size_t)range * a.pmb + (m0 >> 5)) * a.pnb + (n0 >> 5)) * 4) * 1024 + lane * 16;
+                    const auto acc = take_acc_block<DT, B>();
+                    v16i ai;
+                    if constexpr (DT == OGC_I8) ai = acc;
+                    else ai = __builtin_bit_cast(v16i, acc);
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq)
+                        *(v4i*)(dst + qq * 1024) = (v4i){ai[4 * qq], ai[4 * qq + 1], ai[4 * qq + 2], ai[4 * qq + 3]};
+                } else if constexpr (OUT_PLAIN) {
                     if (n0 < a.N && m0 < a.M)
                         epilogue_block<DT, 1, false, EPI>(take_acc_block<DT, B>(), a, prm, n0, m0, lane, (uint8_t*)nullptr);
                 } else {
@@ -531,12 +542,12 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                                                      a.y + (size_t)(m0 >> 5) * a.KC_out * 512);
                 }
             };
-            read_params(0);
+            if constexpr (EPI != 2) read_params(0);
             block(std::integral_constant<int, 0>());
             block(std::integral_constant<int, 1>());
             block(std::integral_constant<int, 2>());
             block(std::integral_constant<int, 3>());
-            read_params(1);
+            if constexpr (EPI != 2) read_params(1);
             block(std::integral_constant<int, 4>());
             block(std::integral_constant<int, 5>());
             block(std::integral_constant<int, 6>());
@@ -546,7 +557,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             // a one-step tile has no such barrier, hence the explicit one
             next_tile(cur_n, cur_m);
             if (--tiles_left > 0) {
-                stage_params(cur_n, pbuf ^ 1);
+                stage_params(cur_n >> LS, pbuf ^ 1);
                 if (KT == 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             }
             pbuf ^= 1;

@@ -30,20 +30,25 @@ def assert_close(got, ref, tol, what=""):
             what, int((err > bound).sum()), err.size, np.unravel_index(i, err.shape), got.flat[i], ref.flat[i], bound.flat[i]))
 
 
-def run_gpu(wl, mode, tile=None, **kw):
+def run_gpu(wl, mode, tile=None, ksplit=None, **kw):
+    """tile / ksplit: force the plan's tile configuration and the log2 of its split-K factor (read by
+    ogc_mlp_plan from the environment; both are otherwise chosen by its heuristic)."""
     from paper_2301_01333_amd.harness import DeviceMLP
 
-    old = os.environ.get("OGC_TILE")
-    if tile is not None:
-        os.environ["OGC_TILE"] = str(tile)
+    forced = {"OGC_TILE": tile, "OGC_KSPLIT": ksplit}
+    old = {k: os.environ.get(k) for k in forced}
+    for k, v in forced.items():
+        if v is not None:
+            os.environ[k] = str(v)
     try:
         d = DeviceMLP(wl, MODES[mode], **kw)
     finally:
-        if tile is not None:
-            if old is None:
-                os.environ.pop("OGC_TILE")
-            else:
-                os.environ["OGC_TILE"] = old
+        for k, v in forced.items():
+            if v is not None:
+                if old[k] is None:
+                    os.environ.pop(k)
+                else:
+                    os.environ[k] = old[k]
     d.run()
     y = d.result().copy()
     chosen = d.mlp.mode
@@ -51,9 +56,9 @@ def run_gpu(wl, mode, tile=None, **kw):
     return y, chosen
 
 
-def check(wl, mode, oracle_mod, tile=None, rows=None, **kw):
-    print("case:", wl.name, wl.dtype, "M=%d" % wl.m, wl.dims, "mode=%s tile=%s" % (mode, tile), kw, flush=True)
-    got, _ = run_gpu(wl, mode, tile, **kw)
+def check(wl, mode, oracle_mod, tile=None, rows=None, ksplit=None, **kw):
+    print("case:", wl.name, wl.dtype, "M=%d" % wl.m, wl.dims, "mode=%s tile=%s ksplit=%s" % (mode, tile, ksplit), kw, flush=True)
+    got, _ = run_gpu(wl, mode, tile, ksplit, **kw)
     n = wl.layers[-1].n
     pad = got[:, n:]
     got = got[:, :n]
@@ -147,6 +152,21 @@ def test_pipelined_kernel_plain_input(oracle_mod, dtype, tile):
           x_byte_offset=esz)
     check(synth.make_mlp(dtype, 300, [64, 70], [RELU], seed=704, name="dma-strided", ld_x=80), "per_layer", oracle_mod, tile=tile,
           ld_y=72)
+
+
+@pytest.mark.parametrize("tile", [3, 4])
+@pytest.mark.parametrize("dtype", ["i8", "bf16"])
+def test_split_k(oracle_mod, dtype, tile):
+    """The reduction axis cut into 2, 4 and 8 ranges (partial accumulators + the reduction pass that owns the
+    epilogue): middle layers (blocked output) and the last layer (plain output, ragged N and M), int8 bit-exact."""
+    k = {"i8": 512, "bf16": 256}[dtype]   # 8 k-steps of 64 bytes
+    for ls in (1, 2, 3):
+        wl = synth.make_mlp(dtype, 300, [k, 2 * k, 72], [RELU, RELU if dtype == "i8" else GELU], seed=720 + ls, name="split-k")
+        check(wl, "per_layer", oracle_mod, tile=tile, ksplit=ls)
+    wl = synth.make_mlp(dtype, 700, [k, 200], [NONE if dtype != "i8" else RELU], seed=724, name="split-k-1layer", has_bias=False)
+    check(wl, "per_layer", oracle_mod, tile=tile, ksplit=2)
+    if dtype == "bf16":  # residual + bias in the reduction pass
+        check(synth.make_config(4, m=300), "per_layer", oracle_mod, tile=tile, ksplit=2)
 
 
 # ---------------------------------------------------------------- edge cases
