@@ -145,6 +145,23 @@ OGC_DEV void epilogue_values(const typename AccT<DT>::type& acc, const OgcLayerA
     }
 }
 
+// 16-byte result stores.  Results that go to global memory are written through (system-scope bits on the store):
+// a layer's whole output otherwise sits dirty in the L2s until the kernel ends and is written back in one burst
+// that the kernel has to wait for; written through, it drains while the kernel computes.  GlobalY marks a
+// pointer that is known to be global memory; a plain uint8_t* may also point into LDS (fused chain kernel).
+struct GlobalY {
+    uint8_t* p;
+    __device__ __forceinline__ GlobalY operator+(size_t o) const { return GlobalY{p + o}; }
+};
+OGC_DEV void store16_through(uint8_t* p, const v4i& v) {
+    // the s_nop keeps the next instruction (which may overwrite the data registers) two wait states away from a
+    // store of more than 64 bits, as this target requires; the compiler inserts that for its own stores but
+    // does not look inside this one
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+}
+OGC_DEV void store16(uint8_t* p, const v4i& v) { *(v4i*)p = v; }
+OGC_DEV void store16(GlobalY g, const v4i& v) { store16_through(g.p, v); }
+
 // Converts the 16 values of a lane to the stored type, exchanges quads between the half-waves so that
 // each lane holds 16 CONSECUTIVE channels (n0 + 16*(lane/32) ...), and returns them as NDW 16-byte chunks.
 //   EO = bytes per stored element (1: u8/s8, 2: bf16, 4: fp32); NDW == EO.
@@ -223,7 +240,7 @@ OGC_DEV void store_plain(const v4i (&chunk)[EO], const OgcLayerArgs& a, int m, i
     uint8_t* p = a.y + (long long)m * a.ldy_bytes + (size_t)nl * EO;
     if (a.y_vec_ok && nl + 16 <= a.N) {
 #pragma unroll
-        for (int c = 0; c < EO; ++c) *(v4i*)(p + 16 * c) = chunk[c];
+        for (int c = 0; c < EO; ++c) store16_through(p + 16 * c, chunk[c]);
     } else {
         const int cnt = (a.N - nl < 16) ? (a.N - nl) : 16;
 #pragma unroll
@@ -282,7 +299,7 @@ OGC_DEV void epilogue_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, cons
         const v4i arr[1] = {ch};
         store_plain<1>(arr, a, m0 + mm, n0 + 16 * h);
     } else {
-        *(v4i*)(yblk + ((size_t)((n0 >> 5) * 2 + h) * 32 + mm) * 16) = ch;
+        store16(yblk + ((size_t)((n0 >> 5) * 2 + h) * 32 + mm) * 16, ch);
     }
 }
 
@@ -319,7 +336,7 @@ OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerAr
         pack_block<E>(out, DT == OGC_I8, ch);
         const int c0 = ((n0 >> 5) * 2 + h) * E;
 #pragma unroll
-        for (int c = 0; c < E; ++c) *(v4i*)(yblk + ((size_t)(c0 + c) * 32 + mm) * 16) = ch[c];
+        for (int c = 0; c < E; ++c) store16(yblk + ((size_t)(c0 + c) * 32 + mm) * 16, ch[c]);
     }
 }
 
@@ -473,7 +490,7 @@ ogc_layer_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_p
                 if (n0 < a.N && m0 < a.M) epilogue_block<DT, 1>(acc[i][j], a, n0, m0, lane, (uint8_t*)nullptr);
             } else {
                 if ((n0 >> 5) < a.NB_out)
-                    epilogue_block<DT, 0>(acc[i][j], a, n0, m0, lane, a.y + (size_t)(m0 >> 5) * a.KC_out * 512);
+                    epilogue_block<DT, 0>(acc[i][j], a, n0, m0, lane, GlobalY{a.y + (size_t)(m0 >> 5) * a.KC_out * 512});
             }
         }
     }
@@ -656,7 +673,7 @@ __global__ void __launch_bounds__(256) ogc_splitk_reduce_kernel(const OgcLayerAr
         }
     }
     if constexpr (OUT_PLAIN) epilogue_block<DT, 1>(acc, a, bn * 32, bm * 32, lane, (uint8_t*)nullptr);
-    else epilogue_block<DT, 0>(acc, a, bn * 32, bm * 32, lane, a.y + (size_t)bm * a.KC_out * 512);
+    else epilogue_block<DT, 0>(acc, a, bn * 32, bm * 32, lane, GlobalY{a.y + (size_t)bm * a.KC_out * 512});
 }
 
 template <int DT> static int launch_splitk_reduce(int op, const OgcLayerArgs* a, hipStream_t stream) {

@@ -532,14 +532,14 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                     else ai = __builtin_bit_cast(v16i, acc);
 #pragma unroll
                     for (int qq = 0; qq < 4; ++qq)
-                        *(v4i*)(dst + qq * 1024) = (v4i){ai[4 * qq], ai[4 * qq + 1], ai[4 * qq + 2], ai[4 * qq + 3]};
+                        store16_through(dst + qq * 1024, (v4i){ai[4 * qq], ai[4 * qq + 1], ai[4 * qq + 2], ai[4 * qq + 3]});
                 } else if constexpr (OUT_PLAIN) {
                     if (n0 < a.N && m0 < a.M)
                         epilogue_block<DT, 1, false, EPI>(take_acc_block<DT, B>(), a, prm, n0, m0, lane, (uint8_t*)nullptr);
                 } else {
                     if ((n0 >> 5) < a.NB_out)
                         epilogue_block<DT, 0, false, EPI>(take_acc_block<DT, B>(), a, prm, n0, m0, lane,
-                                                     a.y + (size_t)(m0 >> 5) * a.KC_out * 512);
+                                                     GlobalY{a.y + (size_t)(m0 >> 5) * a.KC_out * 512});
                 }
             };
             if constexpr (EPI != 2) read_params(0);
