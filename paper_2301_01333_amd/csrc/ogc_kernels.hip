@@ -508,32 +508,52 @@ ogc_layer_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int tiles_p
 #define OGC_FUSED_WAVES 8
 #define OGC_FUSED_THREADS (OGC_FUSED_WAVES * 64)
 
+// CNT output-channel blocks of one wave at a time: the activation operand read from LDS feeds CNT MFMAs, and
+// the CNT accumulator chains overlap (a single chain would wait out the full MFMA latency at every k-step).
+template <int DT, int OUT_PLAIN, int CNT>
+OGC_DEV void fused_blocks(const OgcLayerArgs& a, const uint8_t* xin, uint8_t* xout, int m0, int nb0, int lane) {
+    const int KP2 = a.KC >> 1;  // 32-byte k-steps
+    typename AccT<DT>::type acc[CNT];
+#pragma unroll
+    for (int i = 0; i < CNT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    const uint8_t* wp = a.w + (size_t)nb0 * a.KC * 512 + lane * 16;
+    const size_t wstep = (size_t)OGC_FUSED_WAVES * a.KC * 512;  // this wave's next block is OGC_FUSED_WAVES further
+    const uint8_t* xp = xin + lane * 16;
+    int kp = 0;
+    for (; kp + 4 <= KP2; kp += 4) {
+        v4i wf[CNT][4], xf[4];
+#pragma unroll
+        for (int i = 0; i < CNT; ++i)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) wf[i][u] = *(const v4i*)(wp + i * wstep + (size_t)(kp + u) * 1024);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) xf[u] = *(const v4i*)(xp + (size_t)(kp + u) * 1024);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < CNT; ++i) mma32<DT>(acc[i], wf[i][u], xf[u]);
+    }
+    for (; kp < KP2; ++kp) {
+        const v4i xf = *(const v4i*)(xp + (size_t)kp * 1024);
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) mma32<DT>(acc[i], *(const v4i*)(wp + i * wstep + (size_t)kp * 1024), xf);
+    }
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) epilogue_block<DT, OUT_PLAIN>(acc[i], a, (nb0 + i * OGC_FUSED_WAVES) * 32, m0, lane, xout);
+}
+
+// One layer of the fused chain for a 32-row tile: wave w owns the channel blocks w, w + 8, w + 16, ...
 template <int DT, int OUT_PLAIN>
 OGC_DEV void fused_layer(const OgcLayerArgs& a, const uint8_t* xin, uint8_t* xout, int m0, int wave, int lane) {
     const int nblocks = OUT_PLAIN ? ((a.N + 31) >> 5) : a.NB_out;
-    const int KP2 = a.KC >> 1;  // 32-byte k-steps
-    for (int nb = wave; nb < nblocks; nb += OGC_FUSED_WAVES) {
-        typename AccT<DT>::type acc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0;
-        const uint8_t* wp = a.w + (size_t)nb * a.KC * 512 + lane * 16;
-        const uint8_t* xp = xin + lane * 16;
-        int kp = 0;
-        for (; kp + 4 <= KP2; kp += 4) {
-            v4i wf[4], xf[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) wf[u] = *(const v4i*)(wp + (size_t)(kp + u) * 1024);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) xf[u] = *(const v4i*)(xp + (size_t)(kp + u) * 1024);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) mma32<DT>(acc, wf[u], xf[u]);
-        }
-        for (; kp < KP2; ++kp) {
-            const v4i wf = *(const v4i*)(wp + (size_t)kp * 1024);
-            const v4i xf = *(const v4i*)(xp + (size_t)kp * 1024);
-            mma32<DT>(acc, wf, xf);
-        }
-        epilogue_block<DT, OUT_PLAIN>(acc, a, nb * 32, m0, lane, xout);
+    for (int nb0 = wave; nb0 < nblocks; nb0 += 4 * OGC_FUSED_WAVES) {
+        const int cnt = (nblocks - nb0 + OGC_FUSED_WAVES - 1) / OGC_FUSED_WAVES;  // blocks of this wave from nb0 on
+        if (cnt >= 4) fused_blocks<DT, OUT_PLAIN, 4>(a, xin, xout, m0, nb0, lane);
+        else if (cnt == 3) fused_blocks<DT, OUT_PLAIN, 3>(a, xin, xout, m0, nb0, lane);
+        else if (cnt == 2) fused_blocks<DT, OUT_PLAIN, 2>(a, xin, xout, m0, nb0, lane);
+        else fused_blocks<DT, OUT_PLAIN, 1>(a, xin, xout, m0, nb0, lane);
     }
 }
 
