@@ -87,14 +87,17 @@ typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
  * and per-layer kernels with workspace buffer reuse (Section VI), picks tile shapes (the role of the
  * template-parameter heuristic, Section III) and lays out the packed blob and the workspace.
  * Host only: no device call is made.  *out_plan is written only on OGC_OK.
- * OGC_ERR_UNSUPPORTED: OGC_MODE_FUSED requested but a layer is too wide for the LDS activation tile. */
+ * OGC_ERR_UNSUPPORTED: OGC_MODE_FUSED requested but a layer is too wide for the LDS activation tile.
+ * For tests, two environment variables read here override the heuristic in per-layer mode: OGC_TILE (0..4:
+ * tile configuration of every layer) and OGC_KSPLIT (log2 of the number of k ranges, 0..3). */
 ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc /*host*/, ogc_mlp_plan_t* out_plan /*host*/);
 
 /* Size of the packed-weights blob (blocked weights + per-channel parameters of every layer). */
 ogc_status ogc_mlp_packed_bytes(ogc_mlp_plan_t plan, size_t* bytes /*host*/);
 
 /* Size of the workspace ogc_mlp_run needs (0 for the fused-chain kernel).  Per-layer mode: the
- * intermediate activations share slots assigned by life span; a chain needs two. */
+ * intermediate activations share slots assigned by life span (a chain needs two), followed by the partial
+ * accumulators of a layer whose reduction axis the plan splits into ranges (k-slicing, Section III). */
 ogc_status ogc_mlp_workspace_bytes(ogc_mlp_plan_t plan, size_t* bytes /*host*/);
 
 /* Which kernel family the plan chose: *mode is OGC_MODE_PER_LAYER or OGC_MODE_FUSED. */
@@ -124,7 +127,8 @@ ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, co
  * holds no state between calls. */
 ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream);
 
-/* Number of kernel launches one ogc_mlp_run makes: 1 for the fused-chain kernel, n_layers otherwise. */
+/* Number of timed launch steps of one ogc_mlp_run: 1 for the fused-chain kernel, n_layers otherwise (a layer
+ * whose reduction axis is split runs two kernels, the k ranges and the pass that adds them, and counts as one). */
 ogc_status ogc_mlp_num_launches(ogc_mlp_plan_t plan, int32_t* n /*host*/);
 
 /* ogc_mlp_run with a HIP event recorded on `stream` around every launch; waits for the last one and writes
@@ -140,8 +144,9 @@ void ogc_mlp_destroy(ogc_mlp_plan_t plan);
 /* Static, NUL-terminated description of a status code. */
 const char* ogc_status_string(ogc_status s);
 
-/* Name of the kernel that ogc_mlp_run launches for layer `layer` (fused mode: the same name for every
- * layer), for matching profiler output.  Returns NULL on a bad argument. */
+/* Name, with template arguments as a kernel trace prints them, of the kernel that ogc_mlp_run launches for
+ * layer `layer` (fused mode: the same name for every layer; a split layer: its first kernel), for matching
+ * profiler output.  Returns NULL on a bad argument. */
 const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer);
 
 #ifdef __cplusplus
