@@ -136,3 +136,38 @@ def test_buffer_reuse_is_ping_pong_for_a_chain():
     p = b.ogc_mlp_plan(b.OGC_F32, 64, [layer(32, 64)], 32, 64, 0, b.OGC_MODE_PER_LAYER)
     assert b.ogc_mlp_workspace_bytes(p) == 0
     b.ogc_mlp_destroy(p)
+
+
+def test_split_k_plan_sizes_and_kernel_names(monkeypatch):
+    """A layer with few 256x256 tiles and a long reduction axis is cut into k ranges (k-slicing, Section III):
+    the workspace then carries the partial accumulators behind the activation slots, the layer is still one
+    launch step, and kernel names carry their template arguments."""
+    monkeypatch.delenv("OGC_TILE", raising=False)
+    monkeypatch.delenv("OGC_KSPLIT", raising=False)
+    m, k0, hid = 4096, 1024, 4096
+    lay = [layer(k0, hid, act=b.OGC_ACT_GELU_TANH, has_bias=1), layer(hid, k0, act=b.OGC_ACT_NONE, has_bias=1)]
+    p = b.ogc_mlp_plan(b.OGC_BF16, m, lay, k0, k0, 1, b.OGC_MODE_AUTO)
+    assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_PER_LAYER
+    assert b.ogc_mlp_num_launches(p) == 2
+    hidden_slot = m * hid * 2
+    partial = 4 * m * k0 * 4          # 64 tiles of 256x256 -> four ranges of fp32 accumulators
+    assert b.ogc_mlp_workspace_bytes(p) == hidden_slot + partial
+    assert b.ogc_mlp_kernel_name(p, 0) == "ogc_layer_dma_kernel<1, 1, 1, 0, 0>"
+    assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 1, 0, 0, 2>"
+    b.ogc_mlp_destroy(p)
+    # forced off: no partial region, the second layer falls back to a register-staged tile
+    monkeypatch.setenv("OGC_KSPLIT", "0")
+    p = b.ogc_mlp_plan(b.OGC_BF16, m, lay, k0, k0, 1, b.OGC_MODE_AUTO)
+    assert b.ogc_mlp_workspace_bytes(p) == hidden_slot
+    assert b.ogc_mlp_kernel_name(p, 1).startswith("ogc_layer_kernel<1, ")
+    b.ogc_mlp_destroy(p)
+    # a forced split that does not divide the k-steps is ignored
+    monkeypatch.setenv("OGC_TILE", "4")
+    monkeypatch.setenv("OGC_KSPLIT", "3")
+    p = b.ogc_mlp_plan(b.OGC_I8, 300, [layer(64 * 4, 64)], 256, 64, 0, b.OGC_MODE_PER_LAYER)   # 4 k-steps
+    assert b.ogc_mlp_workspace_bytes(p) == 0
+    b.ogc_mlp_destroy(p)
+    monkeypatch.setenv("OGC_KSPLIT", "2")
+    p = b.ogc_mlp_plan(b.OGC_I8, 300, [layer(64 * 4, 64)], 256, 64, 0, b.OGC_MODE_PER_LAYER)
+    assert b.ogc_mlp_workspace_bytes(p) == 4 * 512 * 256 * 4      # ranges x padded rows x padded channels x 4 bytes
+    b.ogc_mlp_destroy(p)
