@@ -222,8 +222,9 @@ OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t soc, uint32_t son, ui
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                   \
     FL(104, 0) OGC_MFMA(OP, 104, 0, 0, 0) FL(104, 1) OGC_MFMA(OP, 104, 1, 0, 1)                                  \
     "s_waitcnt vmcnt(" #VMN ")\n\ts_barrier\n\t"                                                                 \
+    FL(104, 2) OGC_MFMA(OP, 104, 2, 0, 2)                                                                        \
     OGC_READ(80, "%[tw]", "%[tx]")                                                                               \
-    FL(104, 2) OGC_MFMA(OP, 104, 2, 0, 2) DB(0, 0, "incw") FL(104, 3) OGC_MFMA(OP, 104, 3, 0, 3)                 \
+    DB(0, 0, "incw") FL(104, 3) OGC_MFMA(OP, 104, 3, 0, 3)                                                       \
     DB(1, O1, "incw") OGC_MFMA(OP, 104, 4, 1, 0) DB(2, O2, "incx") OGC_MFMA(OP, 104, 5, 1, 1) DB(3, O3, "incx")  \
     OGC_MFMA(OP, 104, 6, 1, 2) D45(4, O4, "incx") OGC_MFMA(OP, 104, 7, 1, 3) D45(5, O5, "incx")                  \
     "s_mov_b32 %[sprev], %[sst]\n\t"                                                                             \
