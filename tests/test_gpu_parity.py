@@ -241,3 +241,58 @@ def test_run_before_prepack_is_refused():
         binding.ogc_mlp_run(m.plan, x.data_ptr(), x.data_ptr(), x.data_ptr(), 0, 0)
     assert e.value.status == -6
     m.close()
+
+
+# ---------------------------------------------------------------- limits and seeded random shapes
+def test_int8_longest_reduction_axis_with_extreme_values(oracle_mod):
+    """K = 65536, the longest int8 reduction axis the plan accepts, with every activation 255 and every weight
+    127 (and -128): the exact sums reach 65536*255*127 = 2 122 383 360, just inside int32."""
+    k = 65536
+    wl = synth.make_mlp("i8", 40, [k, 33], [RELU], seed=31, has_bias=False, a_z=0, c_z=0)
+    wl.x[:] = 255
+    wl.w[0][:, :17] = 127
+    wl.w[0][:, 17:] = -128
+    for ly in wl.layers:
+        ly.out_scale = float(np.float32(k * 255 * 127 * ly.in_scale * 0.02 / 200.0))  # keeps part of the range unsaturated
+    got = check(wl, "per_layer", oracle_mod)
+    assert (got[:, 17:] == 0).all()          # ReLU of the most negative sums
+    # the same through the stream kernel (needs zero point 128), whole and cut into eight k ranges
+    wl3 = synth.make_mlp("i8", 40, [k, 33], [RELU], seed=31, has_bias=False)
+    wl3.x[:] = 255
+    wl3.w[0][:, :17] = 127
+    wl3.w[0][:, 17:] = -128
+    wl3.layers[0].out_scale = float(np.float32(k * 127 * 127 * wl3.layers[0].in_scale * 0.02 / 120.0))
+    check(wl3, "per_layer", oracle_mod, tile=4)
+    check(wl3, "per_layer", oracle_mod, tile=4, ksplit=3)
+    wl2 = synth.make_mlp("i8", 40, [k, 33], [NONE], seed=32, has_bias=False, last_f32=True)
+    check(wl2, "per_layer", oracle_mod)
+
+
+def test_sixteen_layers(oracle_mod):
+    """The longest chain the descriptor allows, in both modes (ping-pong slots reused eight times)."""
+    for dtype in ("i8", "bf16", "f32"):
+        dims = [48, 64, 32, 96, 64, 32, 64, 96, 32, 64, 48, 64, 32, 64, 96, 32, 24]
+        wl = synth.make_mlp(dtype, 70, dims, [RELU] * 16, seed=40, name="16-layers")
+        check(wl, "fused", oracle_mod)
+        check(wl, "per_layer", oracle_mod)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f32"])
+def test_seeded_random_chains(oracle_mod, dtype):
+    """Twelve chains per dtype with seeded random depth, widths, batch, activations, bias, strides and mode."""
+    rng = np.random.default_rng({"i8": 9001, "bf16": 9002, "f32": 9003}[dtype])
+    for case in range(12):
+        nl = int(rng.integers(1, 5))
+        dims = [int(rng.integers(1, 300)) for _ in range(nl + 1)]
+        m = int(rng.integers(1, 400))
+        acts = [int(rng.choice([RELU, NONE] if dtype == "i8" else [RELU, NONE, GELU])) for _ in range(nl)]
+        if dtype == "i8":
+            acts = [RELU if a == NONE and i + 1 < nl else a for i, a in enumerate(acts)]
+        kw = dict(has_bias=bool(rng.integers(0, 2)))
+        if dtype == "i8":
+            kw.update(a_z=int(rng.choice([128, 128, 0, 77])), c_z=int(rng.choice([128, 128, 0, 200])))
+        ld_x = dims[0] + int(rng.integers(0, 9)) * int(rng.integers(0, 2))
+        wl = synth.make_mlp(dtype, m, dims, acts, seed=9100 + case, name="random-%d" % case, ld_x=ld_x, **kw)
+        mode = str(rng.choice(["fused", "per_layer", "auto"]))
+        tile = None if mode != "per_layer" else int(rng.integers(0, 5))
+        check(wl, mode, oracle_mod, tile=tile, ld_y=dims[-1] + int(rng.integers(0, 5)))
