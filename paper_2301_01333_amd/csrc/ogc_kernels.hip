@@ -359,10 +359,24 @@ template <int DT> OGC_DEV v4i load_plain_chunk(const OgcLayerArgs& a, int m, int
         if (a.x_vec_ok) {
             v = *(const v4i*)p;
         } else {
-            uint32_t d[4] = {0, 0, 0, 0};
+            // Rows that are not 16-byte aligned (K = 479 bytes, say): up to five aligned dwords that each hold at
+            // least one valid byte (so none lies outside the caller's allocation, whose end is dword aligned),
+            // shifted into place; bytes past the row's end are cleared.
+            const int n = kbytes - kb < 16 ? kbytes - kb : 16;
+            const uintptr_t addr = (uintptr_t)p;
+            const uint32_t sh = (uint32_t)(addr & 3);
+            const uint32_t* q = (const uint32_t*)(addr - sh);
+            const int count = (int)(sh + n + 3) >> 2;
+            uint32_t w[5];
 #pragma unroll
-            for (int j = 0; j < 16; ++j)
-                if (kb + j < kbytes) d[j >> 2] |= (uint32_t)p[j] << (8 * (j & 3));
+            for (int j = 0; j < 5; ++j) w[j] = j < count ? q[j] : 0u;
+            uint32_t d[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                d[j] = __builtin_amdgcn_alignbyte(w[j + 1], w[j], sh);
+                const int rem = n - 4 * j;
+                d[j] &= rem >= 4 ? 0xffffffffu : (rem <= 0 ? 0u : (0xffffffffu >> (8 * (4 - rem))));
+            }
             v = (v4i){(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
         }
         if constexpr (DT == OGC_I8) {
