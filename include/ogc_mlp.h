@@ -10,8 +10,9 @@
  *   - All shapes, dtypes, activations and quantization parameters are static: fixed when the plan is
  *     made (the paper specialises for static shapes and folds quantization constants, Sections I, V).
  *   - Tensors at the boundary are plain row-major ("input and output matrices are in plain layouts",
- *     Section VII).  Weights are [K,N] row-major (B[K,N] of Section III).  Blocked layouts exist only
- *     inside the packed blob and the workspace.
+ *     Section VII) unless the description asks for the blocked layout (ogc_layout), which lets chains hand
+ *     activations to each other the way the layers of one chain do.  Weights are [K,N] row-major (B[K,N] of
+ *     Section III).  Otherwise blocked layouts exist only inside the packed blob and the workspace.
  *   - "dev" pointers are device (HBM) addresses on the current HIP device; "host" pointers are ordinary
  *     process memory.  The library never allocates, frees or retains device memory: x, y, raw weights,
  *     packed and workspace are owned by the caller.  The plan is host memory owned by the library until
@@ -48,6 +49,12 @@ typedef enum { OGC_F32 = 0, OGC_BF16 = 1, OGC_I8 = 2 } ogc_dtype; /* OGC_I8: u8 
 typedef enum { OGC_ACT_NONE = 0, OGC_ACT_RELU = 1, OGC_ACT_GELU_TANH = 2, OGC_ACT_SIGMOID = 3 } ogc_act;
 typedef enum { OGC_OUT_SAME = 0, OGC_OUT_F32 = 1 } ogc_out_kind;
 typedef enum { OGC_MODE_AUTO = 0, OGC_MODE_PER_LAYER = 1, OGC_MODE_FUSED = 2 } ogc_mode;
+/* Layout of x / y at the boundary.  OGC_LAYOUT_BLOCKED is the library's operand layout (the blocked layout of
+ * Section III, as propagated between the layers of a chain, Section V): with it one chain's y is the next
+ * chain's x without the round trip through the plain layout.  A blocked tensor of m rows and c columns holds
+ * round_up(m,256) rows of c padded to a multiple of 64 (u8) or 32 (bf16, fp32) elements, as
+ * [rows/32][row bytes/16][32 rows][16 bytes]; u8 values are stored with 128 subtracted.  Its size is ogc_mlp_blocked_bytes(); only a chain of this library should write it. */
+typedef enum { OGC_LAYOUT_PLAIN = 0, OGC_LAYOUT_BLOCKED = 1 } ogc_layout;
 
 /* One layer: [M,k] x [k,n] -> [M,n].
  * Post-ops, in this order (fine-grain fusion of the matmul's successors, Section V):
@@ -78,6 +85,9 @@ typedef struct {
     int32_t ld_x, ld_y;            /* row strides of x and y in elements; ld_x >= k0, ld_y >= n_last */
     int32_t residual;              /* 1: last layer adds x (float dtypes only; requires n_last == k0) */
     int32_t mode;                  /* ogc_mode */
+    int32_t x_layout, y_layout;    /* ogc_layout.  Blocked: per-layer kernels only (OGC_MODE_FUSED is refused), no
+                                      residual with a blocked x, no OGC_OUT_F32 with a blocked y; ld_x / ld_y
+                                      are ignored for a blocked tensor */
 } ogc_mlp_desc;
 
 typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
@@ -94,6 +104,10 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc /*host*/, ogc_mlp_plan_t* out_p
 
 /* Size of the packed-weights blob (blocked weights + per-channel parameters of every layer). */
 ogc_status ogc_mlp_packed_bytes(ogc_mlp_plan_t plan, size_t* bytes /*host*/);
+
+/* Bytes of the blocked x (which = 0) or y (which = 1) of this plan; 0 if that tensor is plain.  The buffer
+ * must be 256-byte aligned. */
+ogc_status ogc_mlp_blocked_bytes(ogc_mlp_plan_t plan, int32_t which, size_t* bytes /*host*/);
 
 /* Size of the workspace ogc_mlp_run needs (0 for the fused-chain kernel).  Per-layer mode: the
  * intermediate activations share slots assigned by life span (a chain needs two), followed by the partial
@@ -122,6 +136,7 @@ ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, co
 
 /* Runs the chain: x[m, k0] (row stride ld_x) -> y[m, n_last] (row stride ld_y), both dev, plain row-major,
  * element type of the plan's dtype (u8 for OGC_I8; fp32 y if the last layer has OGC_OUT_F32).
+ * (A blocked x or y, see ogc_layout, is a buffer of ogc_mlp_blocked_bytes() bytes instead.)
  * x and y must not overlap.  packed is the blob written by ogc_mlp_prepack_weights for this plan;
  * workspace is dev, 256-byte aligned, ogc_mlp_workspace_bytes() bytes (may be NULL when that is 0) and
  * holds no state between calls. */

@@ -14,6 +14,7 @@ OGC_F32, OGC_BF16, OGC_I8 = 0, 1, 2
 OGC_ACT_NONE, OGC_ACT_RELU, OGC_ACT_GELU_TANH, OGC_ACT_SIGMOID = 0, 1, 2, 3
 OGC_OUT_SAME, OGC_OUT_F32 = 0, 1
 OGC_MODE_AUTO, OGC_MODE_PER_LAYER, OGC_MODE_FUSED = 0, 1, 2
+OGC_LAYOUT_PLAIN, OGC_LAYOUT_BLOCKED = 0, 1
 OGC_OK = 0
 DTYPES = {"f32": OGC_F32, "bf16": OGC_BF16, "i8": OGC_I8}
 
@@ -23,7 +24,7 @@ LIB_PATH = os.path.join(_HERE, "libogc_mlp.so")
 EXPORTS = [
     "ogc_mlp_plan", "ogc_mlp_packed_bytes", "ogc_mlp_workspace_bytes", "ogc_mlp_chosen_mode",
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
-    "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled",
+    "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes",
 ]
 
 
@@ -36,7 +37,8 @@ class ogc_layer_desc(ctypes.Structure):
 class ogc_mlp_desc(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("m", ctypes.c_int32), ("n_layers", ctypes.c_int32),
                 ("layers", ctypes.POINTER(ogc_layer_desc)), ("ld_x", ctypes.c_int32), ("ld_y", ctypes.c_int32),
-                ("residual", ctypes.c_int32), ("mode", ctypes.c_int32)]
+                ("residual", ctypes.c_int32), ("mode", ctypes.c_int32), ("x_layout", ctypes.c_int32),
+                ("y_layout", ctypes.c_int32)]
 
 
 class OgcError(RuntimeError):
@@ -63,6 +65,8 @@ def lib():
         l.ogc_mlp_packed_bytes.restype = i32
         l.ogc_mlp_workspace_bytes.argtypes = [vp, ctypes.POINTER(sz)]
         l.ogc_mlp_workspace_bytes.restype = i32
+        l.ogc_mlp_blocked_bytes.argtypes = [vp, i32, ctypes.POINTER(sz)]
+        l.ogc_mlp_blocked_bytes.restype = i32
         l.ogc_mlp_chosen_mode.argtypes = [vp, ctypes.POINTER(i32)]
         l.ogc_mlp_chosen_mode.restype = i32
         l.ogc_mlp_buffer_assignment.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(sz)]
@@ -95,14 +99,16 @@ def _check(status: int, what: str) -> None:
 
 
 # ---- one function per entry point, same names ---------------------------------------------------
-def ogc_mlp_plan(dtype: int, m: int, layers: Sequence[dict], ld_x: int, ld_y: int, residual: int = 0, mode: int = 0) -> int:
+def ogc_mlp_plan(dtype: int, m: int, layers: Sequence[dict], ld_x: int, ld_y: int, residual: int = 0, mode: int = 0,
+                 x_layout: int = 0, y_layout: int = 0) -> int:
     """layers: dicts with k, n, has_bias, act, in_scale, in_zp, out_scale, out_zp, out.  Returns the plan handle."""
     arr = (ogc_layer_desc * max(len(layers), 1))()
     for i, ly in enumerate(layers):
         arr[i] = ogc_layer_desc(int(ly["k"]), int(ly["n"]), int(ly.get("has_bias", 0)), int(ly.get("act", 0)),
                                 float(ly.get("in_scale", 0.0)), int(ly.get("in_zp", 0)), float(ly.get("out_scale", 0.0)),
                                 int(ly.get("out_zp", 0)), int(ly.get("out", 0)))
-    desc = ogc_mlp_desc(int(dtype), int(m), len(layers), arr, int(ld_x), int(ld_y), int(residual), int(mode))
+    desc = ogc_mlp_desc(int(dtype), int(m), len(layers), arr, int(ld_x), int(ld_y), int(residual), int(mode), int(x_layout),
+                        int(y_layout))
     handle = ctypes.c_void_p()
     _check(lib().ogc_mlp_plan(ctypes.byref(desc), ctypes.byref(handle)), "ogc_mlp_plan")
     return handle.value
@@ -117,6 +123,12 @@ def ogc_mlp_packed_bytes(plan: int) -> int:
 def ogc_mlp_workspace_bytes(plan: int) -> int:
     v = ctypes.c_size_t()
     _check(lib().ogc_mlp_workspace_bytes(plan, ctypes.byref(v)), "ogc_mlp_workspace_bytes")
+    return v.value
+
+
+def ogc_mlp_blocked_bytes(plan: int, which: int) -> int:
+    v = ctypes.c_size_t()
+    _check(lib().ogc_mlp_blocked_bytes(plan, int(which), ctypes.byref(v)), "ogc_mlp_blocked_bytes")
     return v.value
 
 
@@ -179,7 +191,8 @@ class FusedMLP:
     """plan + packed blob + workspace for one static MLP chain on the current CUDA/HIP device."""
 
     def __init__(self, dtype: str, m: int, layers: Sequence, ld_x: Optional[int] = None, ld_y: Optional[int] = None,
-                 residual: bool = False, mode: int = OGC_MODE_AUTO):
+                 residual: bool = False, mode: int = OGC_MODE_AUTO, x_layout: int = OGC_LAYOUT_PLAIN,
+                 y_layout: int = OGC_LAYOUT_PLAIN):
         import torch
 
         self.torch = torch
@@ -196,7 +209,7 @@ class FusedMLP:
         self.ld_x = ld_x or self.k0
         self.ld_y = ld_y or self.n_last
         self.out_f32 = self.layer_dicts[-1].get("out", 0) == OGC_OUT_F32
-        self.plan = ogc_mlp_plan(DTYPES[dtype], m, self.layer_dicts, self.ld_x, self.ld_y, int(residual), mode)
+        self.plan = ogc_mlp_plan(DTYPES[dtype], m, self.layer_dicts, self.ld_x, self.ld_y, int(residual), mode, x_layout, y_layout)
         self.mode = ogc_mlp_chosen_mode(self.plan)
         self.packed_bytes = ogc_mlp_packed_bytes(self.plan)
         self.workspace_bytes = ogc_mlp_workspace_bytes(self.plan)

@@ -113,6 +113,12 @@ ogc_status validate(const ogc_mlp_desc* d) {
     if (d->n_layers < 1 || d->n_layers > OGC_MAX_LAYERS) return OGC_ERR_SHAPE;
     if (d->m < 1) return OGC_ERR_SHAPE;
     if (d->residual != 0 && d->residual != 1) return OGC_ERR_INVALID_ARG;
+    if ((d->x_layout != OGC_LAYOUT_PLAIN && d->x_layout != OGC_LAYOUT_BLOCKED) ||
+        (d->y_layout != OGC_LAYOUT_PLAIN && d->y_layout != OGC_LAYOUT_BLOCKED))
+        return OGC_ERR_INVALID_ARG;
+    if (d->x_layout == OGC_LAYOUT_BLOCKED && d->residual) return OGC_ERR_UNSUPPORTED;  // the residual reads plain x
+    if ((d->x_layout == OGC_LAYOUT_BLOCKED || d->y_layout == OGC_LAYOUT_BLOCKED) && d->mode == OGC_MODE_FUSED)
+        return OGC_ERR_UNSUPPORTED;
     for (int l = 0; l < d->n_layers; ++l) {
         const ogc_layer_desc& y = d->layers[l];
         if (y.k < 1 || y.n < 1) return OGC_ERR_SHAPE;
@@ -121,6 +127,7 @@ ogc_status validate(const ogc_mlp_desc* d) {
         if (y.act < OGC_ACT_NONE || y.act > OGC_ACT_SIGMOID) return OGC_ERR_INVALID_ARG;
         if (y.out != OGC_OUT_SAME && y.out != OGC_OUT_F32) return OGC_ERR_INVALID_ARG;
         if (y.out == OGC_OUT_F32 && (d->dtype != OGC_I8 || l != d->n_layers - 1)) return OGC_ERR_INVALID_ARG;
+        if (y.out == OGC_OUT_F32 && d->y_layout == OGC_LAYOUT_BLOCKED) return OGC_ERR_INVALID_ARG;
         if (d->dtype == OGC_I8) {
             if (y.k > 65536) return OGC_ERR_SHAPE;
             if (!(y.in_scale > 0.0f) || !std::isfinite(y.in_scale)) return OGC_ERR_INVALID_ARG;
@@ -132,7 +139,8 @@ ogc_status validate(const ogc_mlp_desc* d) {
         }
     }
     const int k0 = d->layers[0].k, nl = d->layers[d->n_layers - 1].n;
-    if (d->ld_x < k0 || d->ld_y < nl) return OGC_ERR_SHAPE;
+    if (d->x_layout == OGC_LAYOUT_PLAIN && d->ld_x < k0) return OGC_ERR_SHAPE;
+    if (d->y_layout == OGC_LAYOUT_PLAIN && d->ld_y < nl) return OGC_ERR_SHAPE;
     if (d->residual) {
         if (d->dtype == OGC_I8) return OGC_ERR_INVALID_ARG;
         if (nl != k0) return OGC_ERR_SHAPE;
@@ -160,7 +168,8 @@ void fill_args(const ogc_mlp_plan_s* p, int l, const uint8_t* packed, OgcLayerAr
     a->zp_out = (float)lp.d.out_zp;
     a->has_bias = lp.d.has_bias;
     a->q_hi = 255.0f - (float)lp.d.out_zp;
-    const bool internal = l + 1 < (int)p->layers.size();  // result stays in the s8-with-128-subtracted form
+    // the result stays in the s8-with-128-subtracted form: every layer but the last, and a blocked y
+    const bool internal = l + 1 < (int)p->layers.size() || p->desc.y_layout == OGC_LAYOUT_BLOCKED;
     if (internal && lp.d.out_zp == 128) {
         a->q_add = 0;
         a->q_xor = 0;
@@ -202,6 +211,10 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         if (l + 1 < L) {
             lp.nb_out = p->layers[l + 1].kp / 32;
             lp.kc_out = p->layers[l + 1].kc;
+        } else if (desc->y_layout == OGC_LAYOUT_BLOCKED) {
+            const int kp_y = (int)round_up((size_t)lp.d.n, kgran);  // as the next chain's first layer will pad it
+            lp.nb_out = kp_y / 32;
+            lp.kc_out = kp_y * esz / 16;
         } else {
             lp.nb_out = 0;
             lp.kc_out = 0;
@@ -213,6 +226,8 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
     size_t wbytes = 0;
     for (int l = 0; l < L; ++l) wbytes += (size_t)p->layers[l].kp * esz * p->layers[l].d.n;
     int mode = desc->mode;
+    const bool blocked_io = desc->x_layout == OGC_LAYOUT_BLOCKED || desc->y_layout == OGC_LAYOUT_BLOCKED;
+    if (mode == OGC_MODE_AUTO && blocked_io) mode = OGC_MODE_PER_LAYER;
     if (mode == OGC_MODE_FUSED && !fused_fits) {
         delete p;
         return OGC_ERR_UNSUPPORTED;
@@ -234,7 +249,8 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
             // the stream kernel keeps its accumulators in fixed registers: no out-of-line calls (sigmoid) in it
             const bool dma_ok = desc->dtype != OGC_F32 && lp.d.act != OGC_ACT_SIGMOID &&
                                 !(desc->dtype == OGC_I8 && lp.d.in_zp != 128) &&
-                                (l > 0 || (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
+                                (l > 0 || desc->x_layout == OGC_LAYOUT_BLOCKED ||
+                                 (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
             lp.tile = choose_tile(desc->m, rows, dma_ok);
             lp.ksplit_log2 = 0;
             // Too few 256x256 tiles for the chip but a long reduction axis: cut K into ranges (the paper's
@@ -304,6 +320,15 @@ ogc_status ogc_mlp_packed_bytes(ogc_mlp_plan_t plan, size_t* bytes) {
     return OGC_OK;
 }
 
+ogc_status ogc_mlp_blocked_bytes(ogc_mlp_plan_t plan, int32_t which, size_t* bytes) {
+    if (!plan || !bytes || (which != 0 && which != 1)) return OGC_ERR_INVALID_ARG;
+    const LayerPlan& first = plan->layers.front();
+    const LayerPlan& last = plan->layers.back();
+    if (which == 0) *bytes = plan->desc.x_layout == OGC_LAYOUT_BLOCKED ? (size_t)plan->mp * first.kc * 16 : 0;
+    else *bytes = plan->desc.y_layout == OGC_LAYOUT_BLOCKED ? (size_t)plan->mp * last.kc_out * 16 : 0;
+    return OGC_OK;
+}
+
 ogc_status ogc_mlp_workspace_bytes(ogc_mlp_plan_t plan, size_t* bytes) {
     if (!plan || !bytes) return OGC_ERR_INVALID_ARG;
     *bytes = plan->workspace_bytes;
@@ -361,7 +386,8 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
     const int L = (int)plan->layers.size();
     const LayerPlan& last = plan->layers[L - 1];
     const int eo = (last.d.out == OGC_OUT_F32) ? 4 : esz;
-    if (((uintptr_t)x % esz) != 0 || ((uintptr_t)y % eo) != 0) return OGC_ERR_ALIGNMENT;
+    const bool x_blocked = plan->desc.x_layout == OGC_LAYOUT_BLOCKED, y_blocked = plan->desc.y_layout == OGC_LAYOUT_BLOCKED;
+    if (((uintptr_t)x % (x_blocked ? 256 : esz)) != 0 || ((uintptr_t)y % (y_blocked ? 256 : eo)) != 0) return OGC_ERR_ALIGNMENT;
     if (plan->workspace_bytes > 0) {
         if (!workspace) return OGC_ERR_WORKSPACE;
         if (((uintptr_t)workspace & 255) != 0) return OGC_ERR_ALIGNMENT;
@@ -415,7 +441,8 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
             a.pnb = plan->layers[l].npw / 32;
         }
         if (ev && hipEventRecord(ev[l], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
-        const int rc = ogc_launch_layer(plan->desc.dtype, plan->layers[l].tile, l == 0, l == L - 1, &a, stream);
+        const int rc = ogc_launch_layer(plan->desc.dtype, plan->layers[l].tile, l == 0 && !x_blocked, l == L - 1 && !y_blocked, &a,
+                                        stream);
         if (rc != 0) return OGC_ERR_DEVICE;
     }
     if (ev && hipEventRecord(ev[L], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
@@ -474,8 +501,10 @@ const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer) {
     if (plan->mode == OGC_MODE_FUSED) return ogc_fused_kernel_name(plan->desc.dtype);
     const int L = (int)plan->layers.size();
     const ogc_layer_desc& d = plan->layers[layer].d;
-    return ogc_layer_kernel_name(plan->desc.dtype, plan->layers[layer].tile, layer == 0, layer == L - 1, d.act,
-                                 d.out == OGC_OUT_F32, plan->layers[layer].ksplit_log2 > 0);
+    return ogc_layer_kernel_name(plan->desc.dtype, plan->layers[layer].tile,
+                                 layer == 0 && plan->desc.x_layout == OGC_LAYOUT_PLAIN,
+                                 layer == L - 1 && plan->desc.y_layout == OGC_LAYOUT_PLAIN, d.act, d.out == OGC_OUT_F32,
+                                 plan->layers[layer].ksplit_log2 > 0);
 }
 
 }  // extern "C"

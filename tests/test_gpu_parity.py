@@ -296,3 +296,51 @@ def test_seeded_random_chains(oracle_mod, dtype):
         mode = str(rng.choice(["fused", "per_layer", "auto"]))
         tile = None if mode != "per_layer" else int(rng.integers(0, 5))
         check(wl, mode, oracle_mod, tile=tile, ld_y=dims[-1] + int(rng.integers(0, 5)))
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f32"])
+def test_blocked_hand_off_between_two_chains(oracle_mod, dtype):
+    """Layout propagation across calls (Section V): chain A emits its y in the blocked operand layout, chain B
+    takes that buffer as its x; together they must equal the one five-layer chain the oracle computes.  Ragged
+    M, K and N; with the stream kernels (tile 4) and with the heuristic's choice."""
+    import torch
+
+    full = synth.make_mlp(dtype, 333, [96, 200, 72, 130, 50, 21], [RELU, RELU, RELU, GELU if dtype != "i8" else RELU, NONE if dtype != "i8" else RELU],
+                          seed=800, name="hand-off")
+    ref = oracle_mod.mlp(full)
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1).copy()).cuda()
+    for tile in (None, 4):
+        old = os.environ.get("OGC_TILE")
+        if tile is not None:
+            os.environ["OGC_TILE"] = str(tile)
+        try:
+            a = binding.FusedMLP(dtype, full.m, full.layers[:3], mode=binding.OGC_MODE_AUTO, y_layout=binding.OGC_LAYOUT_BLOCKED)
+            b = binding.FusedMLP(dtype, full.m, full.layers[3:], mode=binding.OGC_MODE_AUTO, x_layout=binding.OGC_LAYOUT_BLOCKED)
+        finally:
+            if tile is not None:
+                if old is None:
+                    os.environ.pop("OGC_TILE")
+                else:
+                    os.environ["OGC_TILE"] = old
+        assert a.mode == binding.OGC_MODE_PER_LAYER and b.mode == binding.OGC_MODE_PER_LAYER
+        nbytes = binding.ogc_mlp_blocked_bytes(a.plan, 1)
+        assert nbytes == binding.ogc_mlp_blocked_bytes(b.plan, 0) > 0
+        assert binding.ogc_mlp_blocked_bytes(a.plan, 0) == 0 and binding.ogc_mlp_blocked_bytes(b.plan, 1) == 0
+        for part, mlp in ((slice(0, 3), a), (slice(3, 5), b)):
+            ws = None if dtype != "i8" else [to_dev(s) for s in full.w_scale[part]]
+            mlp.prepack([to_dev(w) for w in full.w[part]], [None if v is None else to_dev(v) for v in full.bias[part]], ws)
+        x = to_dev(full.x)
+        mid = torch.full((nbytes,), 0xCD, dtype=torch.uint8, device="cuda")
+        y = torch.full((ref.nbytes,), 0xCD, dtype=torch.uint8, device="cuda")
+        a.run(x, mid)
+        b.run(mid, y)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy().view(ref.dtype).reshape(ref.shape)
+        if dtype == "i8":
+            assert np.array_equal(got, ref)
+        else:
+            assert_close(as_f32(full, got), as_f32(full, ref), TOL[dtype], "two chains with a blocked hand-off")
+        a.close()
+        b.close()
+    with pytest.raises(binding.OgcError):   # the fused-chain kernel does not take blocked tensors
+        binding.FusedMLP(dtype, 64, full.layers[:2], mode=binding.OGC_MODE_FUSED, y_layout=binding.OGC_LAYOUT_BLOCKED)

@@ -171,3 +171,36 @@ def test_split_k_plan_sizes_and_kernel_names(monkeypatch):
     p = b.ogc_mlp_plan(b.OGC_I8, 300, [layer(64 * 4, 64)], 256, 64, 0, b.OGC_MODE_PER_LAYER)
     assert b.ogc_mlp_workspace_bytes(p) == 4 * 512 * 256 * 4      # ranges x padded rows x padded channels x 4 bytes
     b.ogc_mlp_destroy(p)
+
+
+def test_blocked_layout_plan():
+    """Blocked x / y at the boundary: sizes, the forced per-layer mode, and what is refused."""
+    lay = [layer(100, 72), layer(72, 40)]
+    p = b.ogc_mlp_plan(b.OGC_I8, 300, lay, 100, 40, 0, b.OGC_MODE_AUTO, b.OGC_LAYOUT_BLOCKED, b.OGC_LAYOUT_BLOCKED)
+    assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_PER_LAYER      # small enough for the fused kernel, but blocked
+    assert b.ogc_mlp_blocked_bytes(p, 0) == 512 * 128            # rows to 256, 100 u8 columns to 128
+    assert b.ogc_mlp_blocked_bytes(p, 1) == 512 * 64
+    with pytest.raises(b.OgcError):
+        b.ogc_mlp_blocked_bytes(p, 2)
+    b.ogc_mlp_destroy(p)
+    p = b.ogc_mlp_plan(b.OGC_BF16, 10, [layer(33, 17)], 33, 17, 0, b.OGC_MODE_PER_LAYER, 0, b.OGC_LAYOUT_BLOCKED)
+    assert b.ogc_mlp_blocked_bytes(p, 0) == 0 and b.ogc_mlp_blocked_bytes(p, 1) == 256 * 32 * 2
+    b.ogc_mlp_destroy(p)
+    for kw, status in (
+            (dict(mode=b.OGC_MODE_FUSED, x_layout=1), -2),
+            (dict(mode=b.OGC_MODE_FUSED, y_layout=1), -2),
+            (dict(x_layout=2), -1),
+            (dict(y_layout=-1), -1)):
+        with pytest.raises(b.OgcError) as e:
+            b.ogc_mlp_plan(b.OGC_I8, 64, lay, 100, 40, 0, kw.get("mode", 0), kw.get("x_layout", 0), kw.get("y_layout", 0))
+        assert e.value.status == status, kw
+    with pytest.raises(b.OgcError) as e:      # the residual is read from a plain x
+        b.ogc_mlp_plan(b.OGC_BF16, 64, [layer(40, 40)], 40, 40, 1, 0, b.OGC_LAYOUT_BLOCKED, 0)
+    assert e.value.status == -2
+    with pytest.raises(b.OgcError) as e:      # an fp32 result is a plain tensor
+        b.ogc_mlp_plan(b.OGC_I8, 64, [layer(40, 8, out=b.OGC_OUT_F32)], 40, 8, 0, 0, 0, b.OGC_LAYOUT_BLOCKED)
+    assert e.value.status == -1
+    # strides of a blocked tensor are ignored
+    p = b.ogc_mlp_plan(b.OGC_F32, 64, [layer(40, 8)], 0, 0, 0, 0, b.OGC_LAYOUT_BLOCKED, b.OGC_LAYOUT_BLOCKED)
+    assert b.ogc_mlp_blocked_bytes(p, 0) == 256 * 64 * 4 and b.ogc_mlp_blocked_bytes(p, 1) == 256 * 32 * 4
+    b.ogc_mlp_destroy(p)
