@@ -159,6 +159,32 @@ def blocked_io_report(idx, steps, warmup):
             "ms_per_step_hip_events": ev_sec * 1e3, "tops_or_tflops": wl.ops / sec / 1e12, "frac_of_peak": wl.ops / sec / peak}
 
 
+def table1_sweep(steps, warmup):
+    """The MLP rows of the paper's Table I over its batch range, fp32 and int8 (seeded synthetic tensors of
+    those shapes): time per chain with the plan's own choice of kernels."""
+    from paper_2301_01333_amd import binding, synth
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    rows = []
+    shapes = {"MLP-1": [13, 512, 256, 128], "MLP-2": [479, 1024, 1024, 512, 256, 1]}
+    for name, dims in shapes.items():
+        for dtype in ("f32", "i8"):
+            for m in (32, 64, 128, 256, 512):
+                nl = len(dims) - 1
+                acts = [synth.ACT_RELU] * nl
+                kw = {}
+                if name == "MLP-2":
+                    acts[-1] = synth.ACT_SIGMOID if dtype == "i8" else synth.ACT_NONE
+                    kw = dict(last_f32=True) if dtype == "i8" else {}
+                wl = synth.make_mlp(dtype, m, dims, acts, seed=1000 + m, name="%s %s batch %d" % (name, dtype, m), **kw)
+                dev = DeviceMLP(wl)
+                sec, _ = time_steps(dev, steps, warmup)
+                rows.append({"workload": wl.name, "mode": "fused" if dev.mlp.mode == binding.OGC_MODE_FUSED else "per_layer",
+                             "us_per_chain": sec * 1e6, "gops": wl.ops / sec / 1e9})
+                dev.close()
+    return rows
+
+
 def read_traffic():
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if present."""
     path = os.path.join(ROOT, "profiles", "cfg5_layer_kernel_hbm_traffic.txt")
@@ -179,6 +205,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="headline configuration (1..5)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--only-headline", action="store_true", help="skip the per_config table")
+    ap.add_argument("--table1", action="store_true",
+                    help="instead of the benchmark line, print a JSON list of chain times for the MLP shapes of the paper's "
+                         "Table I over batch 32..512 in fp32 and int8")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference reading for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE runs of this same command)")
@@ -195,6 +224,9 @@ def main():
     from paper_2301_01333_amd import binding
 
     binding.lib()  # fail loudly if the HIP library is missing
+    if args.table1:
+        print(json.dumps({"table1_mlp_sweep": table1_sweep(args.steps, args.warmup)}))
+        return 0
     floor = launch_floor(args.steps, args.warmup)
     wl, dev, head, launches = config_report(args.config, args.steps, args.warmup)
     peak, unit = PEAK[wl.dtype]
