@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 PEAK = {"i8": (5.0e15, "TOP/s"), "bf16": (2.5e15, "TFLOP/s"), "f32": (157.3e12, "TFLOP/s")}
 HBM_PEAK = 8.0e12
 METRIC = "fused-MLP TFLOPS/TOPS + fraction of MFMA or HBM roofline, per config"
+MODE_NAMES = {1: "per_layer", 2: "fused", 3: "coop"}
 
 
 def _median(v):
@@ -72,7 +73,7 @@ def config_report(idx, steps, warmup, with_floor=None):
     ridge = peak / HBM_PEAK
     bound = "mfma" if ops / abytes > ridge else "hbm"
     rep = {
-        "config": idx, "workload": wl.name, "dtype": wl.dtype, "mode": "fused" if dev.mlp.mode == binding.OGC_MODE_FUSED else "per_layer",
+        "config": idx, "workload": wl.name, "dtype": wl.dtype, "mode": MODE_NAMES[dev.mlp.mode],
         "launches": nl, "ms_per_step": sec * 1e3, "ms_per_step_hip_events": ev_sec * 1e3,
         "ms_sum_of_per_launch_event_pairs": sum(launches) * 1e3,
         "tops_or_tflops": ops / sec / 1e12, "algorithmic_GBps": abytes / sec / 1e9, "bound": bound,
@@ -179,7 +180,7 @@ def table1_sweep(steps, warmup):
                 wl = synth.make_mlp(dtype, m, dims, acts, seed=1000 + m, name="%s %s batch %d" % (name, dtype, m), **kw)
                 dev = DeviceMLP(wl)
                 sec, _ = time_steps(dev, steps, warmup)
-                rows.append({"workload": wl.name, "mode": "fused" if dev.mlp.mode == binding.OGC_MODE_FUSED else "per_layer",
+                rows.append({"workload": wl.name, "mode": MODE_NAMES[dev.mlp.mode],
                              "us_per_chain": sec * 1e6, "gops": wl.ops / sec / 1e9})
                 dev.close()
     return rows

@@ -48,7 +48,7 @@ typedef enum {
 typedef enum { OGC_F32 = 0, OGC_BF16 = 1, OGC_I8 = 2 } ogc_dtype; /* OGC_I8: u8 activations x s8 weights */
 typedef enum { OGC_ACT_NONE = 0, OGC_ACT_RELU = 1, OGC_ACT_GELU_TANH = 2, OGC_ACT_SIGMOID = 3 } ogc_act;
 typedef enum { OGC_OUT_SAME = 0, OGC_OUT_F32 = 1 } ogc_out_kind;
-typedef enum { OGC_MODE_AUTO = 0, OGC_MODE_PER_LAYER = 1, OGC_MODE_FUSED = 2 } ogc_mode;
+typedef enum { OGC_MODE_AUTO = 0, OGC_MODE_PER_LAYER = 1, OGC_MODE_FUSED = 2, OGC_MODE_COOP = 3 } ogc_mode;
 /* Layout of x / y at the boundary.  OGC_LAYOUT_BLOCKED is the library's operand layout (the blocked layout of
  * Section III, as propagated between the layers of a chain, Section V): with it one chain's y is the next
  * chain's x without the round trip through the plain layout.  A blocked tensor of m rows and c columns holds
@@ -97,7 +97,14 @@ typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
  * and per-layer kernels with workspace buffer reuse (Section VI), picks tile shapes (the role of the
  * template-parameter heuristic, Section III) and lays out the packed blob and the workspace.
  * Host only: no device call is made.  *out_plan is written only on OGC_OK.
- * OGC_ERR_UNSUPPORTED: OGC_MODE_FUSED requested but a layer is too wide for the LDS activation tile.
+ * OGC_MODE_COOP is the small-batch kernel: one launch in which all CUs share each layer's output blocks and the
+ * waves of a workgroup split the reduction axis (multi-core loop and k-slicing, Section III), with a device-wide
+ * barrier between layers.  It needs the workspace and keeps two counters in the packed blob, so runs that share
+ * a packed blob must not overlap in time; all its workgroups must be resident at once (the grid is at most one
+ * per CU), so it is meant for a device that is not kept busy by other kernels for seconds: its barrier wait is
+ * bounded and a timeout yields wrong data, not a hang.  OGC_MODE_AUTO picks it for small batches with heavy layers.
+ * OGC_ERR_UNSUPPORTED: OGC_MODE_FUSED requested but a layer is too wide for the LDS activation tile; a blocked
+ * x or y with a mode other than per-layer.
  * For tests, two environment variables read here override the heuristic in per-layer mode: OGC_TILE (0..4:
  * tile configuration of every layer) and OGC_KSPLIT (log2 of the number of k ranges, 0..3). */
 ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc /*host*/, ogc_mlp_plan_t* out_plan /*host*/);
@@ -114,7 +121,7 @@ ogc_status ogc_mlp_blocked_bytes(ogc_mlp_plan_t plan, int32_t which, size_t* byt
  * accumulators of a layer whose reduction axis the plan splits into ranges (k-slicing, Section III). */
 ogc_status ogc_mlp_workspace_bytes(ogc_mlp_plan_t plan, size_t* bytes /*host*/);
 
-/* Which kernel family the plan chose: *mode is OGC_MODE_PER_LAYER or OGC_MODE_FUSED. */
+/* Which kernel family the plan chose: *mode is OGC_MODE_PER_LAYER, OGC_MODE_FUSED or OGC_MODE_COOP. */
 ogc_status ogc_mlp_chosen_mode(ogc_mlp_plan_t plan, int32_t* mode /*host*/);
 
 /* Buffer-reuse result for layer `layer`'s output (Section VI, memory buffer optimisation): *slot is the

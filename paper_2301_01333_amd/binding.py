@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence
 OGC_F32, OGC_BF16, OGC_I8 = 0, 1, 2
 OGC_ACT_NONE, OGC_ACT_RELU, OGC_ACT_GELU_TANH, OGC_ACT_SIGMOID = 0, 1, 2, 3
 OGC_OUT_SAME, OGC_OUT_F32 = 0, 1
-OGC_MODE_AUTO, OGC_MODE_PER_LAYER, OGC_MODE_FUSED = 0, 1, 2
+OGC_MODE_AUTO, OGC_MODE_PER_LAYER, OGC_MODE_FUSED, OGC_MODE_COOP = 0, 1, 2, 3
 OGC_LAYOUT_PLAIN, OGC_LAYOUT_BLOCKED = 0, 1
 OGC_OK = 0
 DTYPES = {"f32": OGC_F32, "bf16": OGC_BF16, "i8": OGC_I8}

@@ -42,6 +42,7 @@ struct ogc_mlp_plan_s {
     size_t packed_bytes, workspace_bytes;
     int lds_buf_bytes;  // fused mode
     size_t partial_off, partial_bytes;  // split-K partial accumulators, after the activation slots
+    size_t sync_off;                    // cooperative mode: two counters at the end of the packed blob
     std::vector<size_t> slot_off, slot_size;
     std::atomic<int> prepacked;
 };
@@ -109,7 +110,8 @@ int choose_tile(int m, int n, bool dma_ok) {
 ogc_status validate(const ogc_mlp_desc* d) {
     if (!d || !d->layers) return OGC_ERR_INVALID_ARG;
     if (d->dtype != OGC_F32 && d->dtype != OGC_BF16 && d->dtype != OGC_I8) return OGC_ERR_INVALID_ARG;
-    if (d->mode != OGC_MODE_AUTO && d->mode != OGC_MODE_PER_LAYER && d->mode != OGC_MODE_FUSED) return OGC_ERR_INVALID_ARG;
+    if (d->mode != OGC_MODE_AUTO && d->mode != OGC_MODE_PER_LAYER && d->mode != OGC_MODE_FUSED && d->mode != OGC_MODE_COOP)
+        return OGC_ERR_INVALID_ARG;
     if (d->n_layers < 1 || d->n_layers > OGC_MAX_LAYERS) return OGC_ERR_SHAPE;
     if (d->m < 1) return OGC_ERR_SHAPE;
     if (d->residual != 0 && d->residual != 1) return OGC_ERR_INVALID_ARG;
@@ -117,7 +119,8 @@ ogc_status validate(const ogc_mlp_desc* d) {
         (d->y_layout != OGC_LAYOUT_PLAIN && d->y_layout != OGC_LAYOUT_BLOCKED))
         return OGC_ERR_INVALID_ARG;
     if (d->x_layout == OGC_LAYOUT_BLOCKED && d->residual) return OGC_ERR_UNSUPPORTED;  // the residual reads plain x
-    if ((d->x_layout == OGC_LAYOUT_BLOCKED || d->y_layout == OGC_LAYOUT_BLOCKED) && d->mode == OGC_MODE_FUSED)
+    if ((d->x_layout == OGC_LAYOUT_BLOCKED || d->y_layout == OGC_LAYOUT_BLOCKED) &&
+        (d->mode == OGC_MODE_FUSED || d->mode == OGC_MODE_COOP))
         return OGC_ERR_UNSUPPORTED;
     for (int l = 0; l < d->n_layers; ++l) {
         const ogc_layer_desc& y = d->layers[l];
@@ -233,9 +236,22 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         return OGC_ERR_UNSUPPORTED;
     }
     if (mode == OGC_MODE_AUTO) {
-        // Every 32-row workgroup of the fused kernel streams all weights once: worth it while the batch is
-        // small (few workgroups, launch-latency bound) or the weights are small enough to sit in L2.
-        mode = (fused_fits && (desc->m <= 512 || wbytes <= (size_t)512 * 1024)) ? OGC_MODE_FUSED : OGC_MODE_PER_LAYER;
+        // Measured on the MLP shapes of the paper's Table I (batch 32..2048) and on the five configurations:
+        //  * the fused kernel streams every weight through each 32-row workgroup at what one CU gets from L2
+        //    (about 100 GB/s): best while the weights are small or the batch is small and the weights fit an L2;
+        //  * the cooperative kernel spreads a layer over all CUs but pays a device-wide barrier per layer (3-4 us):
+        //    best for small batches whose layers are heavy for one CU (fp32 at 0.6 TFLOP/s per CU; weights beyond
+        //    what one CU streams in the time of those barriers);
+        //  * per-layer kernels otherwise.
+        const bool small_w = wbytes <= (size_t)512 * 1024;
+        const bool fused_ok = fused_fits && (small_w || (desc->m <= 512 && wbytes <= (size_t)2560 * 1024));
+        bool coop = false;
+        if (!blocked_io && L > 1) {
+            if (desc->dtype == OGC_F32) coop = (desc->m <= 128 && wbytes >= (size_t)256 * 1024) || (desc->m <= 512 && wbytes > (size_t)4 << 20);
+            else if (desc->dtype == OGC_BF16) coop = desc->m <= 128 && wbytes > (size_t)2560 * 1024;
+            else coop = desc->m <= 32 && wbytes > (size_t)2 << 20;
+        }
+        mode = coop ? OGC_MODE_COOP : (fused_ok ? OGC_MODE_FUSED : OGC_MODE_PER_LAYER);
     }
     p->mode = mode;
     p->lds_buf_bytes = max_kc * 512;
@@ -288,9 +304,13 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         lp.ncomp_off = off;
         off += round_up((size_t)lp.npw * 4, 256);
     }
+    p->sync_off = off;
+    if (mode == OGC_MODE_COOP) off += 256;
     p->packed_bytes = off;
     p->partial_off = p->partial_bytes = 0;
-    if (mode == OGC_MODE_PER_LAYER) {
+    if (mode == OGC_MODE_COOP) {
+        assign_buffers(p);
+    } else if (mode == OGC_MODE_PER_LAYER) {
         assign_buffers(p);
         for (int l = 0; l < L; ++l) {
             const LayerPlan& lp = p->layers[l];
@@ -371,6 +391,7 @@ ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, co
                                        (float*)(blob + lp.bias_off), (int32_t*)(blob + lp.ncomp_off), stream);
         if (rc != 0) return OGC_ERR_DEVICE;
     }
+    if (plan->mode == OGC_MODE_COOP && ogc_launch_zero_sync(blob + plan->sync_off, stream) != 0) return OGC_ERR_DEVICE;
     plan->prepacked.store(1);
     return OGC_OK;
 }
@@ -429,6 +450,28 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
         return OGC_OK;
     }
     uint8_t* ws = (uint8_t*)workspace;
+    if (plan->mode == OGC_MODE_COOP) {
+        OgcChainArgs c;
+        std::memset(&c, 0, sizeof(c));
+        c.n_layers = L;
+        const int m_blocks = (plan->desc.m + 31) / 32;
+        long max_blocks = 1;
+        for (int l = 0; l < L; ++l) {
+            finish_args(l, &c.layer[l]);
+            if (l > 0) c.layer[l].x = ws + plan->layers[l - 1].out_off;
+            if (l < L - 1) c.layer[l].y = ws + plan->layers[l].out_off;
+            const long nb = l < L - 1 ? plan->layers[l].nb_out : (plan->layers[l].d.n + 31) / 32;
+            if ((long)m_blocks * nb > max_blocks) max_blocks = (long)m_blocks * nb;
+        }
+        int cus = ogc_device_cu_count();
+        if (cus <= 0) return OGC_ERR_DEVICE;
+        const int grid = (int)(max_blocks < cus ? max_blocks : cus);
+        if (ev && hipEventRecord(ev[0], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
+        const int rc = ogc_launch_coop(plan->desc.dtype, &c, m_blocks, grid, (void*)(blob + plan->sync_off), stream);
+        if (rc != 0) return OGC_ERR_DEVICE;
+        if (ev && hipEventRecord(ev[1], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
+        return OGC_OK;
+    }
     for (int l = 0; l < L; ++l) {
         OgcLayerArgs a;
         finish_args(l, &a);
@@ -455,14 +498,14 @@ ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* 
 
 ogc_status ogc_mlp_num_launches(ogc_mlp_plan_t plan, int32_t* n) {
     if (!plan || !n) return OGC_ERR_INVALID_ARG;
-    *n = plan->mode == OGC_MODE_FUSED ? 1 : (int32_t)plan->layers.size();
+    *n = plan->mode == OGC_MODE_PER_LAYER ? (int32_t)plan->layers.size() : 1;
     return OGC_OK;
 }
 
 ogc_status ogc_mlp_run_profiled(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace,
                                 void* stream, float* launch_ms) {
     if (!plan || !launch_ms) return OGC_ERR_INVALID_ARG;
-    const int n = plan->mode == OGC_MODE_FUSED ? 1 : (int)plan->layers.size();
+    const int n = plan->mode == OGC_MODE_PER_LAYER ? (int)plan->layers.size() : 1;
     hipEvent_t ev[OGC_MAX_LAYERS + 1];
     int made = 0;
     ogc_status st = OGC_OK;
@@ -499,6 +542,7 @@ const char* ogc_status_string(ogc_status s) {
 const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer) {
     if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return nullptr;
     if (plan->mode == OGC_MODE_FUSED) return ogc_fused_kernel_name(plan->desc.dtype);
+    if (plan->mode == OGC_MODE_COOP) return ogc_coop_kernel_name(plan->desc.dtype);
     const int L = (int)plan->layers.size();
     const ogc_layer_desc& d = plan->layers[layer].d;
     return ogc_layer_kernel_name(plan->desc.dtype, plan->layers[layer].tile,

@@ -78,6 +78,10 @@ extern "C" {
 OgcTileInfo ogc_tile_info(int tile);
 int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain, const OgcLayerArgs* a, void* stream);
 int ogc_launch_fused(int dtype, const OgcChainArgs* c, int m_blocks, void* stream);
+int ogc_launch_coop(int dtype, const OgcChainArgs* c, int m_blocks, int grid, void* sync, void* stream);
+int ogc_launch_zero_sync(void* sync, void* stream);
+int ogc_device_cu_count(void);
+const char* ogc_coop_kernel_name(int dtype);
 int ogc_launch_prepack_weights(const void* w, void* out, int K, int N, int KC, int NPw, int esz, void* stream);
 int ogc_launch_prepack_params(int dtype, const void* w, const float* w_scale, const float* bias, float in_scale, int in_zp,
                               int K, int N, int NPw, float* scale_out, float* bias_out, int32_t* ncomp_out, void* stream);

@@ -681,6 +681,125 @@ extern "C" OgcTileInfo ogc_tile_info(int tile) {
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Cooperative chain kernel for small batches (the multi-core loop and k-slicing of Section III applied to
+// shapes where one workgroup per row tile leaves most CUs idle).  One launch for the whole chain; every
+// resident workgroup takes 32x32 output blocks of the current layer (block b -> workgroup b mod G), its four
+// waves split the reduction axis between them (wave w takes the 32-byte k-steps w, w+4, ...) and add their
+// partial sums through LDS in a fixed order; between layers all workgroups meet at a barrier on a counter in
+// global memory.  Activations travel through the workspace buffers in the blocked layout.
+//
+// Cross-XCD visibility without cache maintenance: results are stored with write-through system-scope stores and
+// every wave waits for its stores before its workgroup arrives at the barrier (an agent-scope atomic add); a
+// workgroup leaves the barrier when an agent-scope atomic load shows all arrivals, and reads the other
+// workgroups' results with system-scope loads, which no stale cache line can serve.  (Agent-scope release /
+// acquire fences instead cost 4-5 us per barrier: they write back and invalidate whole L2s.)
+// All workgroups must be resident at once: the grid is at most one workgroup per CU.  A cooperative launch
+// would guarantee that but costs 18 us per call on this stack, more than the kernel saves, so the launch is
+// an ordinary one and the barrier wait is bounded instead (about 2^22 polls, seconds): a device kept busy by
+// another kernel for longer than that makes this chain finish with wrong data rather than hang.
+// sync[0]: barrier arrivals, sync[1]: workgroups finished.  Both are zero between runs: prepack zeroes them and
+// the last workgroup to finish a run zeroes them again (by then nobody waits on them).
+// ------------------------------------------------------------------------------------------------
+#define OGC_COOP_WAVES 4
+#define OGC_COOP_THREADS (OGC_COOP_WAVES * 64)
+
+OGC_DEV void coop_grid_barrier(unsigned long long* ctr, unsigned long long target, int tid) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's result stores (inline assembly) have completed
+    __syncthreads();
+    if (tid == 0) {
+        __hip_atomic_fetch_add(ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int budget = 1 << 22;
+        while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target && --budget > 0)
+            __builtin_amdgcn_s_sleep(1);
+    }
+    __syncthreads();
+}
+
+// 16 bytes of another workgroup's result, read coherently at system scope (two relaxed 64-bit atomic loads)
+OGC_DEV v4i load16_coherent(const uint8_t* p) {
+    const unsigned long long lo = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    const unsigned long long hi = __hip_atomic_load((const unsigned long long*)(p + 8), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    return (v4i){(int)(uint32_t)lo, (int)(uint32_t)(lo >> 32), (int)(uint32_t)hi, (int)(uint32_t)(hi >> 32)};
+}
+
+template <int DT>
+__global__ void __launch_bounds__(OGC_COOP_THREADS) ogc_coop_chain_kernel(const OgcChainArgs c, unsigned long long* sync, int m_blocks) {
+    __shared__ uint32_t red[OGC_COOP_WAVES - 1][16][64];  // partial accumulators of waves 1..3
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = gridDim.x, wg = blockIdx.x;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const OgcLayerArgs& a = c.layer[l];
+        const bool first = l == 0, last = l + 1 == c.n_layers;
+        const int nb = last ? ((a.N + 31) >> 5) : a.NB_out;
+        const int blocks = m_blocks * nb;
+        const int KP2 = a.KC >> 1;  // 32-byte k-steps
+        for (int b = wg; b < blocks; b += G) {
+            const int bm = b / nb, bn = b - bm * nb;
+            typename AccT<DT>::type acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0;
+            const uint8_t* wp = a.w + (size_t)bn * a.KC * 512 + lane * 16;
+            const uint8_t* xp = a.x + (size_t)bm * a.KC * 512 + lane * 16;  // blocked input (layers after the first)
+            const int row = bm * 32 + (lane & 31), kb0 = (lane >> 5) * 16;   // plain input (first layer)
+            int kp = wave;
+            for (; kp + 3 * OGC_COOP_WAVES < KP2; kp += 4 * OGC_COOP_WAVES) {  // four k-steps of this wave in flight
+                v4i wf[4], xf[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) wf[u] = *(const v4i*)(wp + (size_t)(kp + u * OGC_COOP_WAVES) * 1024);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    xf[u] = first ? load_plain_chunk<DT>(a, row, (kp + u * OGC_COOP_WAVES) * 32 + kb0)
+                                  : load16_coherent(xp + (size_t)(kp + u * OGC_COOP_WAVES) * 1024);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) mma32<DT>(acc, wf[u], xf[u]);
+            }
+            for (; kp < KP2; kp += OGC_COOP_WAVES) {
+                const v4i wf = *(const v4i*)(wp + (size_t)kp * 1024);
+                const v4i xf = first ? load_plain_chunk<DT>(a, row, kp * 32 + kb0)
+                                     : load16_coherent(xp + (size_t)kp * 1024);
+                mma32<DT>(acc, wf, xf);
+            }
+            // k-slices of waves 1..3 to LDS, wave 0 adds them in ascending order (a fixed order: deterministic)
+            if (wave > 0) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    if constexpr (DT == OGC_I8) red[wave - 1][r][lane] = (uint32_t)acc[r];
+                    else red[wave - 1][r][lane] = __builtin_bit_cast(uint32_t, (float)acc[r]);
+                }
+            }
+            __syncthreads();
+            if (wave == 0) {
+#pragma unroll
+                for (int w = 0; w < OGC_COOP_WAVES - 1; ++w)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        if constexpr (DT == OGC_I8) acc[r] += (int)red[w][r][lane];
+                        else acc[r] += __builtin_bit_cast(float, red[w][r][lane]);
+                    }
+                if (last) epilogue_block<DT, 1>(acc, a, bn * 32, bm * 32, lane, (uint8_t*)nullptr);
+                else epilogue_block<DT, 0>(acc, a, bn * 32, bm * 32, lane, GlobalY{a.y + (size_t)bm * a.KC_out * 512});
+            }
+            __syncthreads();  // red is reused by the next block
+        }
+        if (!last) coop_grid_barrier(sync, (unsigned long long)(l + 1) * G, tid);
+    }
+    // the last workgroup out resets the counters for the next run
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned long long done = __hip_atomic_fetch_add(sync + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (done == (unsigned long long)G - 1) {
+            __hip_atomic_store(sync, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(sync + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+__global__ void ogc_zero_sync_kernel(unsigned long long* sync) {
+    if (threadIdx.x < 32) sync[threadIdx.x] = 0;
+}
+
 // Second pass of a split-K layer: adds the partial accumulators of the k ranges in ascending order (a fixed
 // order: the result does not depend on which workgroup finished first) and applies the ordinary epilogue.
 // One wave per 32x32 block; the partial buffer holds every wave's accumulator registers as they were.
@@ -840,6 +959,37 @@ extern "C" int ogc_launch_fused(int dtype, const OgcChainArgs* c, int m_blocks, 
     case OGC_BF16: return launch_fused_t<OGC_BF16>(c, m_blocks, s);
     default: return launch_fused_t<OGC_I8>(c, m_blocks, s);
     }
+}
+
+template <int DT> static int launch_coop_t(const OgcChainArgs* c, int m_blocks, int grid, void* sync, hipStream_t stream) {
+    hipLaunchKernelGGL((ogc_coop_chain_kernel<DT>), dim3(grid), dim3(OGC_COOP_THREADS), 0, stream, *c, (unsigned long long*)sync, m_blocks);
+    return (int)hipGetLastError();
+}
+
+// grid: workgroups to launch (at most one per CU, at most the largest number of 32x32 blocks of any layer)
+extern "C" int ogc_launch_coop(int dtype, const OgcChainArgs* c, int m_blocks, int grid, void* sync, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    switch (dtype) {
+    case OGC_F32: return launch_coop_t<OGC_F32>(c, m_blocks, grid, sync, s);
+    case OGC_BF16: return launch_coop_t<OGC_BF16>(c, m_blocks, grid, sync, s);
+    default: return launch_coop_t<OGC_I8>(c, m_blocks, grid, sync, s);
+    }
+}
+
+extern "C" int ogc_launch_zero_sync(void* sync, void* stream) {
+    hipLaunchKernelGGL(ogc_zero_sync_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (unsigned long long*)sync);
+    return (int)hipGetLastError();
+}
+
+extern "C" int ogc_device_cu_count(void) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return n;
+}
+
+extern "C" const char* ogc_coop_kernel_name(int dtype) {
+    return dtype == OGC_F32 ? "ogc_coop_chain_kernel<0>" : dtype == OGC_BF16 ? "ogc_coop_chain_kernel<1>" : "ogc_coop_chain_kernel<2>";
 }
 
 extern "C" int ogc_launch_prepack_weights(const void* w, void* out, int K, int N, int KC, int NPw, int esz, void* stream) {

@@ -12,7 +12,8 @@ pytestmark = pytest.mark.gpu
 
 RELU, NONE, GELU, SIGM = synth.ACT_RELU, synth.ACT_NONE, synth.ACT_GELU_TANH, synth.ACT_SIGMOID
 TOL = {"f32": 1e-5, "bf16": 1e-2}
-MODES = {"fused": binding.OGC_MODE_FUSED, "per_layer": binding.OGC_MODE_PER_LAYER, "auto": binding.OGC_MODE_AUTO}
+MODES = {"fused": binding.OGC_MODE_FUSED, "per_layer": binding.OGC_MODE_PER_LAYER, "auto": binding.OGC_MODE_AUTO,
+         "coop": binding.OGC_MODE_COOP}
 
 
 def as_f32(wl, a):
@@ -344,3 +345,53 @@ def test_blocked_hand_off_between_two_chains(oracle_mod, dtype):
         b.close()
     with pytest.raises(binding.OgcError):   # the fused-chain kernel does not take blocked tensors
         binding.FusedMLP(dtype, 64, full.layers[:2], mode=binding.OGC_MODE_FUSED, y_layout=binding.OGC_LAYOUT_BLOCKED)
+
+
+# ---------------------------------------------------------------- cooperative small-batch kernel
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_coop_small_configs_full(oracle_mod, cfg):
+    check(synth.make_config(cfg), "coop", oracle_mod)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f32"])
+def test_coop_ragged_and_edges(oracle_mod, dtype):
+    """One cooperative launch for the chain: output blocks spread over all CUs, the reduction axis split between
+    the waves of a workgroup, a device-wide barrier between layers.  Ragged M / K / N, more blocks than CUs,
+    a single block, every post-op, strided and misaligned x."""
+    act2 = GELU if dtype != "i8" else RELU
+    check(synth.make_mlp(dtype, 77, [37, 130, 300, 9], [RELU, act2, RELU], seed=600, name="coop-ragged"), "coop", oracle_mod)
+    check(synth.make_mlp(dtype, 700, [100, 333, 72, 33], [RELU, RELU, NONE if dtype != "i8" else RELU], seed=601, name="coop-many-blocks"),
+          "coop", oracle_mod)
+    check(synth.make_mlp(dtype, 1, [1, 1], [NONE if dtype != "i8" else RELU], seed=602, name="coop-1x1"), "coop", oracle_mod)
+    check(synth.make_mlp(dtype, 50, [100, 48], [RELU], seed=603, ld_x=112), "coop", oracle_mod, ld_y=64)
+    esz = {"i8": 1, "bf16": 2, "f32": 4}[dtype]
+    check(synth.make_mlp(dtype, 50, [96, 48, 40], [RELU, RELU], seed=604), "coop", oracle_mod, x_byte_offset=esz)
+    dims = [48, 64, 32, 96, 64, 32, 64, 96, 32, 64, 48, 64, 32, 64, 96, 32, 24]
+    check(synth.make_mlp(dtype, 70, dims, [RELU] * 16, seed=40, name="coop-16-layers"), "coop", oracle_mod)
+    if dtype == "i8":
+        check(synth.make_mlp("i8", 33, [479, 65, 31], [RELU, RELU], seed=2, a_z=3, c_z=200, wq_lo=-128), "coop", oracle_mod)
+        check(synth.make_mlp("i8", 19, [70, 64, 5], [RELU, SIGM], seed=5, last_f32=True), "coop", oracle_mod)
+    else:
+        check(synth.make_mlp(dtype, 70, [40, 64, 40], [GELU, NONE], seed=13, residual=True), "coop", oracle_mod)
+        check(synth.make_mlp(dtype, 3, [13, 7, 1], [RELU, SIGM], seed=12), "coop", oracle_mod)
+
+
+def test_coop_runs_back_to_back(oracle_mod):
+    """The barrier counters live in the packed blob and are reset by the last workgroup of each run: many runs
+    in a row, on one stream, keep giving the same (correct) result."""
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    wl = synth.make_config(3)
+    ref = oracle_mod.mlp(wl)
+    d = DeviceMLP(wl, binding.OGC_MODE_COOP)
+    assert d.mlp.mode == binding.OGC_MODE_COOP
+    for _ in range(25):
+        d.run()
+    first = d.result().copy()
+    assert_close(first[:, :1], ref, 1e-5, "config 3, cooperative kernel")
+    for _ in range(3):
+        d.y.fill_(0xCD)
+        for _ in range(7):
+            d.run()
+        assert np.array_equal(d.result(), first)
+    d.close()

@@ -204,3 +204,41 @@ def test_blocked_layout_plan():
     p = b.ogc_mlp_plan(b.OGC_F32, 64, [layer(40, 8)], 0, 0, 0, 0, b.OGC_LAYOUT_BLOCKED, b.OGC_LAYOUT_BLOCKED)
     assert b.ogc_mlp_blocked_bytes(p, 0) == 256 * 64 * 4 and b.ogc_mlp_blocked_bytes(p, 1) == 256 * 32 * 4
     b.ogc_mlp_destroy(p)
+
+
+def test_auto_mode_choice_follows_the_measured_rules():
+    """fused: small weights, or a small batch whose weights fit an L2; cooperative: small batches with layers that
+    are heavy for one CU; per layer otherwise.  The five configurations keep their modes."""
+    def mode(dtype, m, dims, **kw):
+        lay = [layer(dims[i], dims[i + 1], **kw) for i in range(len(dims) - 1)]
+        p = b.ogc_mlp_plan(dtype, m, lay, dims[0], dims[-1], 0, b.OGC_MODE_AUTO)
+        r = b.ogc_mlp_chosen_mode(p)
+        b.ogc_mlp_destroy(p)
+        return r
+    mlp1, mlp2 = [13, 512, 256, 128], [479, 1024, 1024, 512, 256, 1]
+    assert mode(b.OGC_F32, 32, [13, 64, 32, 16]) == b.OGC_MODE_FUSED                   # config 1
+    assert mode(b.OGC_BF16, 128, [13, 512, 256, 128, 64]) == b.OGC_MODE_FUSED          # config 2
+    assert mode(b.OGC_I8, 256, mlp2) == b.OGC_MODE_FUSED                               # config 3
+    assert mode(b.OGC_BF16, 4096, [1024, 4096, 1024]) == b.OGC_MODE_PER_LAYER          # config 4
+    assert mode(b.OGC_I8, 32768, [1024] * 5) == b.OGC_MODE_PER_LAYER                   # config 5
+    assert mode(b.OGC_F32, 64, mlp1) == b.OGC_MODE_COOP and mode(b.OGC_F32, 512, mlp1) == b.OGC_MODE_FUSED
+    assert mode(b.OGC_F32, 512, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_F32, 2048, mlp2) == b.OGC_MODE_PER_LAYER
+    assert mode(b.OGC_BF16, 128, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_BF16, 512, mlp2) == b.OGC_MODE_PER_LAYER
+    assert mode(b.OGC_I8, 32, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_I8, 512, mlp2) == b.OGC_MODE_FUSED
+    assert mode(b.OGC_I8, 64, mlp1) == b.OGC_MODE_FUSED
+    # the cooperative kernel is never chosen for blocked tensors, and refuses them when asked for
+    p = b.ogc_mlp_plan(b.OGC_F32, 64, [layer(512, 512), layer(512, 512)], 512, 512, 0, b.OGC_MODE_AUTO, 0, b.OGC_LAYOUT_BLOCKED)
+    assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_PER_LAYER
+    b.ogc_mlp_destroy(p)
+    with pytest.raises(b.OgcError) as e:
+        b.ogc_mlp_plan(b.OGC_F32, 64, [layer(512, 512)], 512, 512, 0, b.OGC_MODE_COOP, b.OGC_LAYOUT_BLOCKED, 0)
+    assert e.value.status == -2
+    # one launch step, workspace slots as in per-layer mode, two counters behind the packed parameters
+    lay = [layer(64, 256), layer(256, 512), layer(512, 64)]
+    pc = b.ogc_mlp_plan(b.OGC_I8, 100, lay, 64, 64, 0, b.OGC_MODE_COOP)
+    pl = b.ogc_mlp_plan(b.OGC_I8, 100, lay, 64, 64, 0, b.OGC_MODE_FUSED)
+    assert b.ogc_mlp_num_launches(pc) == 1 and b.ogc_mlp_kernel_name(pc, 0) == "ogc_coop_chain_kernel<2>"
+    assert b.ogc_mlp_workspace_bytes(pc) == 256 * 256 + 256 * 512
+    assert b.ogc_mlp_packed_bytes(pc) == b.ogc_mlp_packed_bytes(pl) + 256
+    b.ogc_mlp_destroy(pc)
+    b.ogc_mlp_destroy(pl)
