@@ -101,8 +101,11 @@ int choose_tile(int m, int n, bool dma_ok) {
         const OgcTileInfo ti = ogc_tile_info(t);
         return (long)((m + ti.bm - 1) / ti.bm) * ((n + ti.bn - 1) / ti.bn);
     };
+    // Measured on 1024-wide int8 chains and on the bf16 FFN shape over batch 512..32768: the eight-wave stream
+    // shape once its 256x256 tiles fill the chip; the four-wave shape (128x256 tiles, two workgroups per CU) from
+    // 64 tiles up, where it beats the register-staged tiles; those below that.
     if (dma_ok && tiles(OGC_TILE_DMA8) >= 224) return OGC_TILE_DMA8;
-    if (dma_ok && tiles(OGC_TILE_DMA) >= 384) return OGC_TILE_DMA;
+    if (dma_ok && tiles(OGC_TILE_DMA) >= 64) return OGC_TILE_DMA;
     if (tiles(OGC_TILE_MID) >= 128) return OGC_TILE_MID;
     return OGC_TILE_SMALL;
 }
@@ -280,9 +283,12 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
                     if (forced_split > 0 && (lp.tile == OGC_TILE_DMA8 || lp.tile == OGC_TILE_DMA) && forced_split <= 3 &&
                         kt % (1 << forced_split) == 0)
                         lp.ksplit_log2 = forced_split;
-                } else if (dma_ok && forced_tile < 0 && lp.tile != OGC_TILE_DMA8 && lp.tile != OGC_TILE_DMA) {
+                } else if (dma_ok && forced_tile < 0 && lp.tile != OGC_TILE_DMA8) {
+                    // Worth it only for a long reduction axis: the partial accumulators cost (ranges + 1) x M x N x 4
+                    // bytes of traffic, the gain is a share of a GEMM time that grows with K.  At least 32 k-steps
+                    // per range (with 16 the pass over the partials took longer than the idle CUs cost).
                     for (int ls = 1; ls <= 3; ++ls)
-                        if (kt % (1 << ls) == 0 && (kt >> ls) >= 8 && (tiles8 << ls) >= 192) {
+                        if (kt % (1 << ls) == 0 && (kt >> ls) >= 32 && (tiles8 << ls) >= 192) {
                             lp.tile = OGC_TILE_DMA8;
                             lp.ksplit_log2 = ls;
                             break;

@@ -155,11 +155,11 @@ def test_split_k_plan_sizes_and_kernel_names(monkeypatch):
     assert b.ogc_mlp_kernel_name(p, 0) == "ogc_layer_dma_kernel<1, 1, 1, 0, 0>"
     assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 1, 0, 0, 2>"
     b.ogc_mlp_destroy(p)
-    # forced off: no partial region, the second layer falls back to a register-staged tile
+    # forced off: no partial region, the second layer takes the four-wave stream shape (128 tiles of 128x256)
     monkeypatch.setenv("OGC_KSPLIT", "0")
     p = b.ogc_mlp_plan(b.OGC_BF16, m, lay, k0, k0, 1, b.OGC_MODE_AUTO)
     assert b.ogc_mlp_workspace_bytes(p) == hidden_slot
-    assert b.ogc_mlp_kernel_name(p, 1).startswith("ogc_layer_kernel<1, ")
+    assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 0, 0, 1, 0>"
     b.ogc_mlp_destroy(p)
     # a forced split that does not divide the k-steps is ignored
     monkeypatch.setenv("OGC_TILE", "4")
