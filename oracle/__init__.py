@@ -1,4 +1,4 @@
-"""CPU oracle for the fused-MLP path.  TEST INFRASTRUCTURE ONLY.
+"""CPU oracle for the fused-MLP path and the attention subgraph.  TEST INFRASTRUCTURE ONLY.
 
 Only the tests, the smoke check and the cpu_baseline leg of the benchmark may import this
 package; the GPU library never does, and this package never imports the GPU library.
@@ -16,3 +16,4 @@ from .oracle import (  # noqa: F401
     mlp,
     num_threads,
 )
+from .mha import SOFTMAX_FAST, SOFTMAX_STABLE, attention  # noqa: F401,E402

@@ -179,3 +179,70 @@ def make_config(idx: int, m: Optional[int] = None) -> Workload:
     if idx == 5:
         return make_mlp("i8", m or 32768, [1024] * 5, [ACT_RELU] * 4, seed, has_bias=False, name=CONFIG_NAMES[5])
     raise ValueError("config index must be 1..5")
+
+
+# ---- scaled dot-product attention (Section VII, Table I rows MHA-1..4) ----------------------------------------
+# The paper takes sequence length, hidden size and head count from BERT models; no model or data is used here.
+# q, k, v are N(0,1) tensors of shape [batch, seq, hidden] (hidden = heads * head_dim, the plain layout a
+# projection layer leaves them in); the mask is a BERT-style padding mask: each batch entry has a valid length
+# drawn uniformly from [seq/2, seq], keys beyond it get -10000.
+MHA_TABLE1 = {  # name: (seq, hidden, heads)
+    "MHA-1": (128, 768, 8),
+    "MHA-2": (128, 768, 12),
+    "MHA-3": (384, 1024, 8),
+    "MHA-4": (512, 1024, 16),
+}
+
+
+@dataclass
+class MhaWorkload:
+    name: str
+    dtype: str           # "f32" | "bf16"
+    batch: int
+    seq: int
+    heads: int
+    head_dim: int
+    q: np.ndarray        # [batch, seq, heads*head_dim]; fp32, or bf16 bit patterns as uint16
+    k: np.ndarray
+    v: np.ndarray
+    mask: Optional[np.ndarray]  # [batch, seq] fp32 additive, or None
+    scale: float         # fp32 value of 1/sqrt(head_dim)
+    seed: int = 0
+
+    @property
+    def hidden(self) -> int:
+        return self.heads * self.head_dim
+
+    @property
+    def ops(self) -> int:
+        """Two batch matmuls: 2 * (2 * B * H * S * S * d)."""
+        return 4 * self.batch * self.heads * self.seq * self.seq * self.head_dim
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """q, k, v read once, o written once, the mask once; the S x S scores count zero."""
+        e = 4 if self.dtype == "f32" else 2
+        return 4 * self.batch * self.seq * self.hidden * e + (self.batch * self.seq * 4 if self.mask is not None else 0)
+
+
+def make_mha(dtype: str, batch: int, seq: int, hidden: int, heads: int, seed: int, *, has_mask: bool = True,
+             name: str = "custom", amplitude: float = 1.0) -> MhaWorkload:
+    """Draw order: q, k, v, then the valid lengths, from one default_rng(seed) stream."""
+    assert dtype in ("f32", "bf16") and hidden % heads == 0
+    rng = np.random.default_rng(seed)
+    d = hidden // heads
+    ts = []
+    for _ in range(3):
+        t = (rng.standard_normal((batch, seq, hidden)) * amplitude).astype(np.float32)
+        ts.append(t if dtype == "f32" else f32_to_bf16_bits(t))
+    mask = None
+    if has_mask:
+        lens = rng.integers(max(seq // 2, 1), seq + 1, size=(batch,))
+        mask = np.where(np.arange(seq)[None, :] < lens[:, None], np.float32(0.0), np.float32(-10000.0)).astype(np.float32)
+    return MhaWorkload(name, dtype, batch, seq, heads, d, ts[0], ts[1], ts[2], mask, float(np.float32(1.0 / math.sqrt(d))), seed)
+
+
+def make_mha_table1(row: str, dtype: str, batch: int) -> MhaWorkload:
+    seq, hidden, heads = MHA_TABLE1[row]
+    idx = sorted(MHA_TABLE1).index(row)
+    return make_mha(dtype, batch, seq, hidden, heads, BASE_SEED + 100 + idx, name="%s %s batch %d" % (row, dtype, batch))
