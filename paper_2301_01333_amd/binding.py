@@ -15,6 +15,7 @@ OGC_ACT_NONE, OGC_ACT_RELU, OGC_ACT_GELU_TANH, OGC_ACT_SIGMOID = 0, 1, 2, 3
 OGC_OUT_SAME, OGC_OUT_F32 = 0, 1
 OGC_MODE_AUTO, OGC_MODE_PER_LAYER, OGC_MODE_FUSED, OGC_MODE_COOP = 0, 1, 2, 3
 OGC_LAYOUT_PLAIN, OGC_LAYOUT_BLOCKED = 0, 1
+OGC_SOFTMAX_STABLE, OGC_SOFTMAX_FAST = 0, 1
 OGC_OK = 0
 DTYPES = {"f32": OGC_F32, "bf16": OGC_BF16, "i8": OGC_I8}
 
@@ -25,6 +26,7 @@ EXPORTS = [
     "ogc_mlp_plan", "ogc_mlp_packed_bytes", "ogc_mlp_workspace_bytes", "ogc_mlp_chosen_mode",
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
     "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes",
+    "ogc_mha_validate", "ogc_mha_run", "ogc_mha_kernel_name",
 ]
 
 
@@ -39,6 +41,13 @@ class ogc_mlp_desc(ctypes.Structure):
                 ("layers", ctypes.POINTER(ogc_layer_desc)), ("ld_x", ctypes.c_int32), ("ld_y", ctypes.c_int32),
                 ("residual", ctypes.c_int32), ("mode", ctypes.c_int32), ("x_layout", ctypes.c_int32),
                 ("y_layout", ctypes.c_int32)]
+
+
+class ogc_mha_desc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("seq", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("softmax", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
+                ("o_stride", ctypes.c_int64 * 3)]
 
 
 class OgcError(RuntimeError):
@@ -85,6 +94,12 @@ def lib():
         l.ogc_status_string.restype = ctypes.c_char_p
         l.ogc_mlp_kernel_name.argtypes = [vp, i32]
         l.ogc_mlp_kernel_name.restype = ctypes.c_char_p
+        l.ogc_mha_validate.argtypes = [ctypes.POINTER(ogc_mha_desc)]
+        l.ogc_mha_validate.restype = i32
+        l.ogc_mha_run.argtypes = [ctypes.POINTER(ogc_mha_desc), vp, vp, vp, vp, vp, vp]
+        l.ogc_mha_run.restype = i32
+        l.ogc_mha_kernel_name.argtypes = [ctypes.POINTER(ogc_mha_desc)]
+        l.ogc_mha_kernel_name.restype = ctypes.c_char_p
         _lib = l
     return _lib
 
@@ -183,6 +198,29 @@ def ogc_mlp_destroy(plan: int) -> None:
 
 def ogc_mlp_kernel_name(plan: int, layer: int) -> str:
     r = lib().ogc_mlp_kernel_name(plan, int(layer))
+    return r.decode() if r else ""
+
+
+def mha_desc(dtype: int, batch: int, heads: int, seq: int, head_dim: int, scale: float, softmax: int = OGC_SOFTMAX_STABLE,
+             q_stride=None, k_stride=None, v_stride=None, o_stride=None) -> ogc_mha_desc:
+    """Strides default to the [batch, seq, heads*head_dim] layout."""
+    plain = (seq * heads * head_dim, head_dim, heads * head_dim)
+    arrs = [(ctypes.c_int64 * 3)(*[int(v) for v in (st if st is not None else plain)])
+            for st in (q_stride, k_stride, v_stride, o_stride)]
+    return ogc_mha_desc(int(dtype), int(batch), int(heads), int(seq), int(head_dim), int(softmax), float(scale), *arrs)
+
+
+def ogc_mha_validate(desc: ogc_mha_desc) -> int:
+    return int(lib().ogc_mha_validate(ctypes.byref(desc)))
+
+
+def ogc_mha_run(desc: ogc_mha_desc, q_ptr: int, k_ptr: int, v_ptr: int, mask_ptr: int, o_ptr: int, stream: int = 0) -> None:
+    _check(lib().ogc_mha_run(ctypes.byref(desc), q_ptr or None, k_ptr or None, v_ptr or None, mask_ptr or None, o_ptr or None,
+                             stream), "ogc_mha_run")
+
+
+def ogc_mha_kernel_name(desc: ogc_mha_desc) -> str:
+    r = lib().ogc_mha_kernel_name(ctypes.byref(desc))
     return r.decode() if r else ""
 
 

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libogc_mlp.so")
-SOURCES = ["ogc_kernels.hip", "ogc_api.cpp"]
+SOURCES = ["ogc_kernels.hip", "ogc_mha.hip", "ogc_api.cpp"]
 
 
 def build_library(verbose: bool = True) -> str:

@@ -1,0 +1,398 @@
+// Fused scaled dot-product attention for gfx950 (the MHA subgraph of Section VII / Table I): both batch
+// matmuls, the scalar, the mask and the softmax in one kernel, scores never leaving the compute unit.
+//
+// One workgroup = 4 wavefronts = 128 queries of one (batch, head); a wavefront owns 32 queries.  Keys and
+// values stream through LDS in blocks of KB keys (bf16: 64, fp32: 32), prefetched one block ahead in
+// registers.  Both products are computed TRANSPOSED so that a lane owns one query:
+//
+//   S^T[key][query] = K * Q^T     first MFMA operand = 32 keys x k from LDS, second = Q^T, held in registers
+//   O^T[c][query]   = V^T * P^T   first operand = 32 channels x keys from LDS (V is transposed on its way into
+//                                 LDS), second = the softmax weights exactly where the first product left them
+//
+// In the 32x32 accumulator layout lane l holds column (query) l%32 and rows 8g + 4(l/32) + e, g,e = 0..3.  The
+// softmax reductions of a query are therefore 16 values inside a lane plus one exchange with lane l^32, the
+// running maximum / sum / rescale factors are per-lane scalars, and the weights feed the second product without
+// any data movement: the reduction axis of that product (keys) may be summed in any order, so V^T is simply
+// written to LDS with its key index permuted to the order in which the accumulator registers hold the keys.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "ogc_mha.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+
+#define MHA_DEV static __device__ __forceinline__
+
+struct MhaArgs {
+    const uint8_t* q;
+    const uint8_t* k;
+    const uint8_t* v;
+    const float* mask;
+    uint8_t* o;
+    long long sq[3], sk[3], sv[3], so[3];  // element strides: batch, head, token
+    int batch, heads, seq;
+    int q_tiles;       // ceil(seq / 128)
+    int xcd_order;     // 1: workgroups of one (batch, head) are placed on one XCD
+    float scale_log2;  // scale * log2(e)
+};
+
+constexpr float LOG2E = 1.44269504088896340736f;
+
+MHA_DEV void swap32(uint32_t& a, uint32_t& b) {
+    auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+    a = r[0];
+    b = r[1];
+}
+// value of x in the other half of the wavefront (lane ^ 32)
+MHA_DEV float other_half(float x) {
+    uint32_t a = __builtin_bit_cast(uint32_t, x), b = a;
+    swap32(a, b);
+    return __builtin_bit_cast(float, (threadIdx.x & 32) ? a : b);
+}
+MHA_DEV uint32_t pack_bf16(float lo, float hi) {  // round to nearest even, two values per register
+    v2bf r = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+template <int DT> struct Cfg;
+template <> struct Cfg<OGC_BF16> {
+    static constexpr int E = 2, KB = 64;
+};
+template <> struct Cfg<OGC_F32> {
+    static constexpr int E = 4, KB = 32;
+};
+
+// DT: OGC_F32 / OGC_BF16.  D32 = head_dim / 32.  FAST: softmax without the running maximum.
+template <int DT, int D32, int FAST> __global__ __launch_bounds__(256, 2) void ogc_mha_kernel(MhaArgs a) {
+    constexpr int E = Cfg<DT>::E, KB = Cfg<DT>::KB, D = D32 * 32;
+    constexpr int SB = KB / 32;                 // 32-key sub-blocks per block
+    constexpr int KSTR = D * E + 16;            // bytes per key row of K in LDS (padded)
+    constexpr int VSTR = KB * E + 16;           // bytes per channel row of V^T in LDS (padded)
+    constexpr int CH = D * E / 16;              // 16-byte chunks per token row
+    constexpr int VU = DT == OGC_BF16 ? (D32 + 1) / 2 : D32;  // V units per thread (bf16: a unit is two keys)
+    __shared__ __attribute__((aligned(16))) uint8_t k_lds[KB * KSTR];
+    __shared__ __attribute__((aligned(16))) uint8_t vt_lds[D * VSTR];
+    __shared__ __attribute__((aligned(16))) float m_lds[KB];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, col = lane & 31;
+    int bh, qt;
+    if (a.xcd_order) {  // consecutive workgroup ids go round the 8 XCDs: keep one (batch, head) on one of them
+        const int L = blockIdx.x, x = L & 7, r = L >> 3;
+        bh = x + 8 * (r / a.q_tiles);
+        qt = r % a.q_tiles;
+    } else {
+        bh = blockIdx.x / a.q_tiles;
+        qt = blockIdx.x % a.q_tiles;
+    }
+    const int b = bh / a.heads, hd = bh % a.heads, S = a.seq;
+    const uint8_t* kbase = a.k + (b * a.sk[0] + hd * a.sk[1]) * E;
+    const uint8_t* vbase = a.v + (b * a.sv[0] + hd * a.sv[1]) * E;
+    const long long kss = a.sk[2] * E, vss = a.sv[2] * E;
+
+    // ---- this lane's query row as the second MFMA operand, resident for the whole kernel
+    const int query = qt * 128 + wave * 32 + col;
+    const int qrow = query < S ? query : S - 1;
+    const uint8_t* qp = a.q + (b * a.sq[0] + hd * a.sq[1] + qrow * a.sq[2]) * E;
+    constexpr int QN = DT == OGC_BF16 ? D / 16 : D / 8;
+    v4i qreg[QN];
+#pragma unroll
+    for (int i = 0; i < QN; ++i) qreg[i] = *(const v4i*)(qp + i * 32 + h * 16);
+
+    v16f oacc[D32];
+#pragma unroll
+    for (int d = 0; d < D32; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[d][r] = 0.0f;
+    float run_max = -INFINITY, run_sum = 0.0f;  // run_sum: this lane's keys only, halves are added at the end
+
+    // ---- prefetch registers for one block of keys / values / mask
+    v4i kreg[D32], vreg[VU][DT == OGC_BF16 ? 2 : 1];
+    float mreg = 0.0f;
+    auto prefetch = [&](int key0) {
+#pragma unroll
+        for (int i = 0; i < D32; ++i) {
+            const int u = tid + 256 * i, key = key0 + u / CH, part = u % CH;
+            kreg[i] = key < S ? *(const v4i*)(kbase + key * kss + part * 16) : (v4i){0, 0, 0, 0};
+        }
+        if constexpr (DT == OGC_BF16) {
+#pragma unroll
+            for (int i = 0; i < VU; ++i) {
+                const int u = tid + 256 * i, kp = u & 31, c = u >> 5, key = key0 + 2 * kp;
+                const bool on = c < CH;
+                vreg[i][0] = (on && key < S) ? *(const v4i*)(vbase + key * vss + c * 16) : (v4i){0, 0, 0, 0};
+                vreg[i][1] = (on && key + 1 < S) ? *(const v4i*)(vbase + (key + 1) * vss + c * 16) : (v4i){0, 0, 0, 0};
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < VU; ++i) {
+                const int u = tid + 256 * i, key = key0 + (u & 31), c = u >> 5;
+                vreg[i][0] = key < S ? *(const v4i*)(vbase + key * vss + c * 16) : (v4i){0, 0, 0, 0};
+            }
+        }
+        if (tid < KB) {
+            const int key = key0 + tid;
+            mreg = key < S ? (a.mask ? a.mask[(long long)b * S + key] * LOG2E : 0.0f) : -INFINITY;
+        }
+    };
+    auto fill_lds = [&]() {
+#pragma unroll
+        for (int i = 0; i < D32; ++i) {
+            const int u = tid + 256 * i;
+            *(v4i*)(k_lds + (u / CH) * KSTR + (u % CH) * 16) = kreg[i];
+        }
+        if constexpr (DT == OGC_BF16) {
+            // two keys x eight channels per unit -> eight dwords (key, key+1) at the permuted key position:
+            // within a group of 16 keys, key offset 8*gg + 4*hh + e sits at 8*hh + 4*gg + e
+#pragma unroll
+            for (int i = 0; i < VU; ++i) {
+                const int u = tid + 256 * i, kp = u & 31, c = u >> 5, o = (2 * kp) & 15;
+                const int pos = ((2 * kp) & ~15) + ((o & 3) | ((o & 8) >> 1) | ((o & 4) << 1));
+                if (c < CH) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t lo = (uint32_t)vreg[i][0][j >> 1], hi = (uint32_t)vreg[i][1][j >> 1];
+                        const uint32_t w = __builtin_amdgcn_perm(hi, lo, (j & 1) ? 0x07060302u : 0x05040100u);
+                        *(uint32_t*)(vt_lds + (8 * c + j) * VSTR + pos * 2) = w;
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < VU; ++i) {
+                const int u = tid + 256 * i, kl = u & 31, c = u >> 5;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) *(int*)(vt_lds + (4 * c + j) * VSTR + kl * 4) = vreg[i][0][j];
+            }
+        }
+        if (tid < KB) m_lds[tid] = mreg;
+    };
+
+    const int nkb = (S + KB - 1) / KB;
+    prefetch(0);
+    for (int kb = 0; kb < nkb; ++kb) {
+        __syncthreads();  // every wavefront is done with the previous block
+        fill_lds();
+        __syncthreads();
+        if (kb + 1 < nkb) prefetch((kb + 1) * KB);
+
+        // ---- scores, transposed: rows = keys, columns = queries
+        v16f sacc[SB];
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[sb][r] = 0.0f;
+            const uint8_t* krow = k_lds + (sb * 32 + col) * KSTR + h * 16;
+#pragma unroll
+            for (int i = 0; i < QN; ++i) {
+                const v4i kv = *(const v4i*)(krow + i * 32);
+                if constexpr (DT == OGC_BF16) {
+                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, kv),
+                                                                       __builtin_bit_cast(v8bf, qreg[i]), sacc[sb], 0, 0, 0);
+                } else {
+                    const v4f kf = __builtin_bit_cast(v4f, kv), qf = __builtin_bit_cast(v4f, qreg[i]);
+                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, qf.x, sacc[sb], 0, 0, 0);
+                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, qf.y, sacc[sb], 0, 0, 0);
+                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, qf.z, sacc[sb], 0, 0, 0);
+                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, qf.w, sacc[sb], 0, 0, 0);
+                }
+            }
+        }
+        // ---- scalar, mask (base-2 logarithm domain; a key beyond the sequence carries -infinity)
+        float blk_max = -INFINITY;
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const v4f mk = *(const v4f*)(m_lds + sb * 32 + 8 * g + 4 * h);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float s = __builtin_fmaf(sacc[sb][4 * g + e], a.scale_log2, mk[e]);
+                    sacc[sb][4 * g + e] = s;
+                    if constexpr (!FAST) blk_max = fmaxf(blk_max, s);
+                }
+            }
+        float shift = 0.0f;
+        if constexpr (!FAST) {
+            blk_max = fmaxf(blk_max, other_half(blk_max));
+            const float new_max = fmaxf(run_max, blk_max);   // finite: key 0 of block 0 is always valid
+            const float alpha = __builtin_amdgcn_exp2f(run_max - new_max);
+            run_max = new_max;
+            run_sum *= alpha;
+#pragma unroll
+            for (int d = 0; d < D32; ++d)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
+            shift = new_max;
+        }
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(FAST ? sacc[sb][r] : sacc[sb][r] - shift);
+                sacc[sb][r] = p;
+                run_sum += p;
+            }
+        // ---- O^T += V^T P^T
+        if constexpr (DT == OGC_BF16) {
+#pragma unroll
+            for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const v16f& p = sacc[sb];
+                    const v4i pw = {(int)pack_bf16(p[8 * j], p[8 * j + 1]), (int)pack_bf16(p[8 * j + 2], p[8 * j + 3]),
+                                    (int)pack_bf16(p[8 * j + 4], p[8 * j + 5]), (int)pack_bf16(p[8 * j + 6], p[8 * j + 7])};
+#pragma unroll
+                    for (int d = 0; d < D32; ++d) {
+                        const v4i vv = *(const v4i*)(vt_lds + (d * 32 + col) * VSTR + (sb * 32 + 16 * j + 8 * h) * 2);
+                        oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vv),
+                                                                          __builtin_bit_cast(v8bf, pw), oacc[d], 0, 0, 0);
+                    }
+                }
+        } else {
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int d = 0; d < D32; ++d) {
+                    const v4f vv = *(const v4f*)(vt_lds + (d * 32 + col) * VSTR + (8 * g + 4 * h) * 4);
+                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.x, sacc[0][4 * g], oacc[d], 0, 0, 0);
+                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.y, sacc[0][4 * g + 1], oacc[d], 0, 0, 0);
+                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.z, sacc[0][4 * g + 2], oacc[d], 0, 0, 0);
+                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.w, sacc[0][4 * g + 3], oacc[d], 0, 0, 0);
+                }
+        }
+    }
+
+    // ---- normalise and store: after the half exchange a lane holds 16 consecutive channels of its query
+    const float total = run_sum + other_half(run_sum);
+    const float inv = 1.0f / total;
+    uint8_t* op = a.o + (b * a.so[0] + hd * a.so[1] + (long long)query * a.so[2]) * E;
+#pragma unroll
+    for (int d = 0; d < D32; ++d) {
+        if constexpr (DT == OGC_BF16) {
+            uint32_t dw[4][2];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                dw[g][0] = pack_bf16(oacc[d][4 * g] * inv, oacc[d][4 * g + 1] * inv);
+                dw[g][1] = pack_bf16(oacc[d][4 * g + 2] * inv, oacc[d][4 * g + 3] * inv);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                swap32(dw[0][j], dw[2][j]);
+                swap32(dw[1][j], dw[3][j]);
+            }
+            if (query < S) {
+                uint8_t* dst = op + (d * 32 + 16 * h) * 2;
+                *(v4i*)dst = (v4i){(int)dw[0][0], (int)dw[0][1], (int)dw[2][0], (int)dw[2][1]};
+                *(v4i*)(dst + 16) = (v4i){(int)dw[1][0], (int)dw[1][1], (int)dw[3][0], (int)dw[3][1]};
+            }
+        } else {
+            uint32_t dw[4][4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dw[g][e] = __builtin_bit_cast(uint32_t, oacc[d][4 * g + e] * inv);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                swap32(dw[0][e], dw[2][e]);
+                swap32(dw[1][e], dw[3][e]);
+            }
+            if (query < S) {
+                uint8_t* dst = op + (d * 32 + 16 * h) * 4;
+                const int order[4] = {0, 2, 1, 3};
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *(v4i*)(dst + 16 * g) = (v4i){(int)dw[order[g]][0], (int)dw[order[g]][1], (int)dw[order[g]][2], (int)dw[order[g]][3]};
+            }
+        }
+    }
+}
+
+template <int DT, int D32> hipError_t launch_fast(int fast, const MhaArgs& a, dim3 grid, hipStream_t st) {
+    if (fast) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 0>), grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+template <int DT> hipError_t launch_dim(int d32, int fast, const MhaArgs& a, dim3 grid, hipStream_t st) {
+    switch (d32) {
+    case 1: return launch_fast<DT, 1>(fast, a, grid, st);
+    case 2: return launch_fast<DT, 2>(fast, a, grid, st);
+    case 3: return launch_fast<DT, 3>(fast, a, grid, st);
+    default: return launch_fast<DT, 4>(fast, a, grid, st);
+    }
+}
+
+bool stride_ok(const int64_t s[3], int elt) {
+    for (int i = 0; i < 3; ++i)
+        if (s[i] < 0 || (s[i] * elt) % 16 != 0) return false;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+ogc_status ogc_mha_validate(const ogc_mha_desc* d) {
+    if (!d) return OGC_ERR_INVALID_ARG;
+    if (d->dtype != OGC_F32 && d->dtype != OGC_BF16 && d->dtype != OGC_I8) return OGC_ERR_INVALID_ARG;
+    if (d->softmax != OGC_SOFTMAX_STABLE && d->softmax != OGC_SOFTMAX_FAST) return OGC_ERR_INVALID_ARG;
+    if (!isfinite(d->scale)) return OGC_ERR_INVALID_ARG;
+    if (d->batch <= 0 || d->heads <= 0 || d->seq <= 0 || d->head_dim <= 0) return OGC_ERR_SHAPE;
+    if (d->seq > 65536 || (int64_t)d->batch * d->heads > 65535) return OGC_ERR_SHAPE;
+    if (d->dtype == OGC_I8) return OGC_ERR_UNSUPPORTED;
+    if (d->head_dim != 32 && d->head_dim != 64 && d->head_dim != 96 && d->head_dim != 128) return OGC_ERR_UNSUPPORTED;
+    const int e = d->dtype == OGC_F32 ? 4 : 2;
+    if (!stride_ok(d->q_stride, e) || !stride_ok(d->k_stride, e) || !stride_ok(d->v_stride, e) || !stride_ok(d->o_stride, e))
+        return OGC_ERR_ALIGNMENT;
+    return OGC_OK;
+}
+
+ogc_status ogc_mha_run(const ogc_mha_desc* d, const void* q, const void* k, const void* v, const float* mask, void* o,
+                       void* stream) {
+    const ogc_status st = ogc_mha_validate(d);
+    if (st != OGC_OK) return st;
+    if (!q || !k || !v || !o) return OGC_ERR_INVALID_ARG;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return OGC_ERR_ALIGNMENT;
+    if ((uintptr_t)mask & 3) return OGC_ERR_ALIGNMENT;
+    MhaArgs a;
+    a.q = (const uint8_t*)q;
+    a.k = (const uint8_t*)k;
+    a.v = (const uint8_t*)v;
+    a.mask = mask;
+    a.o = (uint8_t*)o;
+    for (int i = 0; i < 3; ++i) {
+        a.sq[i] = d->q_stride[i];
+        a.sk[i] = d->k_stride[i];
+        a.sv[i] = d->v_stride[i];
+        a.so[i] = d->o_stride[i];
+    }
+    a.batch = d->batch;
+    a.heads = d->heads;
+    a.seq = d->seq;
+    a.q_tiles = (d->seq + 127) / 128;
+    const int bh = d->batch * d->heads;
+    a.xcd_order = (bh % 8 == 0) ? 1 : 0;
+    a.scale_log2 = d->scale * 1.44269504088896340736f;
+    const dim3 grid((unsigned)(bh * a.q_tiles));
+    const hipError_t e = d->dtype == OGC_F32 ? launch_dim<OGC_F32>(d->head_dim / 32, d->softmax, a, grid, (hipStream_t)stream)
+                                             : launch_dim<OGC_BF16>(d->head_dim / 32, d->softmax, a, grid, (hipStream_t)stream);
+    return e == hipSuccess ? OGC_OK : OGC_ERR_DEVICE;
+}
+
+const char* ogc_mha_kernel_name(const ogc_mha_desc* d) {
+    if (ogc_mha_validate(d) != OGC_OK) return nullptr;
+    static char names[2][4][2][40];
+    char* s = names[d->dtype == OGC_BF16][d->head_dim / 32 - 1][d->softmax];
+    if (!s[0]) snprintf(s, 40, "ogc_mha_kernel<%d, %d, %d>", d->dtype, d->head_dim / 32, d->softmax);
+    return s;
+}
+
+}  // extern "C"

@@ -55,3 +55,28 @@ class DeviceMLP:
 
     def close(self):
         self.mlp.close()
+
+
+class DeviceMHA:
+    """An attention workload resident on the GPU (q, k, v, mask uploaded; o allocated and poisoned)."""
+
+    def __init__(self, wl, softmax: int = binding.OGC_SOFTMAX_STABLE, use_mask: bool = True):
+        import torch
+
+        self.torch = torch
+        self.wl = wl
+        self.np_dtype = np.float32 if wl.dtype == "f32" else np.uint16
+        self.q, self.k, self.v = (_to_device(torch, t) for t in (wl.q, wl.k, wl.v))
+        self.mask = _to_device(torch, wl.mask) if (use_mask and wl.mask is not None) else None
+        self.o = torch.full((wl.q.nbytes,), 0xCD, dtype=torch.uint8, device="cuda")
+        self.desc = binding.mha_desc(binding.DTYPES[wl.dtype], wl.batch, wl.heads, wl.seq, wl.head_dim, wl.scale, softmax)
+
+    def run(self) -> None:
+        binding.ogc_mha_run(self.desc, self.q.data_ptr(), self.k.data_ptr(), self.v.data_ptr(),
+                            self.mask.data_ptr() if self.mask is not None else 0, self.o.data_ptr(),
+                            int(self.torch.cuda.current_stream().cuda_stream))
+
+    def result(self) -> np.ndarray:
+        """o as [batch, seq, heads*head_dim] in the workload's storage dtype."""
+        self.torch.cuda.synchronize()
+        return self.o.cpu().numpy().view(self.np_dtype).reshape(self.wl.batch, self.wl.seq, self.wl.hidden)

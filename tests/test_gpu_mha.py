@@ -1,0 +1,139 @@
+"""GPU parity of the fused attention kernel, called through the C ABI, against the float64 oracle on the same
+seeded inputs: fp32 within 1e-5, bf16 within 1e-2, |gpu-ref| <= tol*|ref| + tol*max|ref| element by element."""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2301_01333_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+STABLE, FAST = binding.OGC_SOFTMAX_STABLE, binding.OGC_SOFTMAX_FAST
+
+
+def as_f64(a):
+    return (synth.bf16_bits_to_f32(a) if a.dtype == np.uint16 else a).astype(np.float64)
+
+
+def heads_view(t, wl):
+    """[batch, seq, hidden] -> [batch, heads, seq, head_dim]"""
+    return t.reshape(wl.batch, wl.seq, wl.heads, wl.head_dim).transpose(0, 2, 1, 3)
+
+
+def assert_close(got, ref, tol, what):
+    assert np.isfinite(got).all(), what + ": non-finite output"
+    bound = tol * np.abs(ref) + tol * np.abs(ref).max()
+    err = np.abs(got - ref)
+    if not (err <= bound).all():
+        i = int((err - bound).argmax())
+        raise AssertionError("%s: %d of %d outside tolerance; worst at %s: got %g ref %g bound %g" % (
+            what, int((err > bound).sum()), err.size, np.unravel_index(i, err.shape), got.flat[i], ref.flat[i], bound.flat[i]))
+
+
+def reference(oracle_mod, wl, softmax, use_mask=True, batches=None):
+    sel = slice(None) if batches is None else batches
+    q, k, v = (heads_view(as_f64(t), wl)[sel] for t in (wl.q, wl.k, wl.v))
+    mask = wl.mask[sel] if (use_mask and wl.mask is not None) else None
+    o = oracle_mod.attention(q, k, v, mask, wl.scale, softmax)          # [B,H,S,d]
+    return o.transpose(0, 2, 1, 3).reshape(o.shape[0], wl.seq, wl.hidden)
+
+
+def check(oracle_mod, wl, softmax=STABLE, use_mask=True, batches=None):
+    from paper_2301_01333_amd.harness import DeviceMHA
+
+    print("case:", wl.name, wl.dtype, "B=%d S=%d H=%d d=%d softmax=%d mask=%s" % (
+        wl.batch, wl.seq, wl.heads, wl.head_dim, softmax, use_mask and wl.mask is not None), flush=True)
+    dev = DeviceMHA(wl, softmax, use_mask)
+    dev.run()
+    got = as_f64(dev.result())
+    if batches is not None:
+        got = got[batches]
+    assert_close(got, reference(oracle_mod, wl, softmax, use_mask, batches), TOL[wl.dtype], wl.name)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("head_dim", [32, 64, 96, 128])
+@pytest.mark.parametrize("softmax", [STABLE, FAST])
+def test_head_dims_ragged_sequence(oracle_mod, dtype, head_dim, softmax):
+    """S = 200: two query tiles (the second ragged), four / seven key blocks with a ragged tail."""
+    wl = synth.make_mha(dtype, 2, 200, 3 * head_dim, 3, 4100 + head_dim, name="ragged d%d" % head_dim)
+    check(oracle_mod, wl, softmax)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("seq", [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 257])
+def test_sequence_lengths(oracle_mod, dtype, seq):
+    wl = synth.make_mha(dtype, 3, seq, 128, 2, 4300 + seq, name="S=%d" % seq)
+    check(oracle_mod, wl)
+    check(oracle_mod, wl, FAST, use_mask=False)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("row", ["MHA-1", "MHA-2", "MHA-3", "MHA-4"])
+def test_table1_shapes_small_batch(oracle_mod, dtype, row):
+    """The four MHA rows of Table I at batch 2 (the whole output is checked); 16 (batch, head) pairs or more, so
+    the XCD-aware workgroup order is the one in use."""
+    check(oracle_mod, synth.make_mha_table1(row, dtype, 2))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_table1_full_batch_sampled(oracle_mod, dtype):
+    """MHA-4 at batch 32, the launch bench.py times: the oracle checks three batch entries (all heads, all
+    tokens of each)."""
+    wl = synth.make_mha_table1("MHA-4", dtype, 32)
+    check(oracle_mod, wl, batches=[0, 13, 31])
+    check(oracle_mod, wl, FAST, batches=[7])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_workgroup_order_without_multiple_of_eight(oracle_mod, dtype):
+    wl = synth.make_mha(dtype, 3, 300, 5 * 64, 5, 4501, name="15 (batch, head) pairs")
+    check(oracle_mod, wl)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_head_major_layout_through_strides(oracle_mod, dtype):
+    """q in [batch, heads, seq, d], k and v in [batch, seq, hidden], o in [batch, heads, seq, d] with padding
+    between tokens: only the strides differ."""
+    import torch
+
+    wl = synth.make_mha(dtype, 2, 150, 4 * 64, 4, 4601, name="strided")
+    B, S, H, d = wl.batch, wl.seq, wl.heads, wl.head_dim
+    npdt = np.float32 if dtype == "f32" else np.uint16
+    qh = np.ascontiguousarray(heads_view(wl.q, wl))
+    pad = 16
+    q_dev = torch.from_numpy(qh.view(np.uint8).reshape(-1).copy()).cuda()
+    k_dev, v_dev = (torch.from_numpy(t.view(np.uint8).reshape(-1).copy()).cuda() for t in (wl.k, wl.v))
+    m_dev = torch.from_numpy(wl.mask.view(np.uint8).reshape(-1).copy()).cuda()
+    o_dev = torch.full((B * H * S * (d + pad) * np.dtype(npdt).itemsize,), 0xCD, dtype=torch.uint8, device="cuda")
+    desc = binding.mha_desc(binding.DTYPES[dtype], B, H, S, d, wl.scale, STABLE, q_stride=(H * S * d, S * d, d),
+                            o_stride=(H * S * (d + pad), S * (d + pad), d + pad))
+    binding.ogc_mha_run(desc, q_dev.data_ptr(), k_dev.data_ptr(), v_dev.data_ptr(), m_dev.data_ptr(), o_dev.data_ptr(),
+                        int(torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    o = o_dev.cpu().numpy().view(npdt).reshape(B, H, S, d + pad)
+    assert (o[..., d:].view(np.uint8) == 0xCD).all(), "padding between tokens was written"
+    got = as_f64(np.ascontiguousarray(o[..., :d])).transpose(0, 2, 1, 3).reshape(B, S, H * d)
+    assert_close(got, reference(oracle_mod, wl, STABLE), TOL[dtype], "strided layouts")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_large_scores_need_the_stable_form(oracle_mod, dtype):
+    """Scores up to a few hundred: exp overflows fp32 without the running maximum; the stable form must hold."""
+    wl = synth.make_mha(dtype, 1, 192, 2 * 64, 2, 4701, name="large scores", amplitude=6.0)
+    check(oracle_mod, wl, STABLE)
+
+
+def test_run_rejects_bad_pointers():
+    import torch
+
+    t = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    desc = binding.mha_desc(binding.OGC_F32, 1, 1, 4, 32, 1.0)
+    with pytest.raises(binding.OgcError) as e:
+        binding.ogc_mha_run(desc, 0, t.data_ptr(), t.data_ptr(), 0, t.data_ptr())
+    assert e.value.status == -1
+    with pytest.raises(binding.OgcError) as e:
+        binding.ogc_mha_run(desc, t.data_ptr() + 4, t.data_ptr(), t.data_ptr(), 0, t.data_ptr())
+    assert e.value.status == -4

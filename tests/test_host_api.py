@@ -25,10 +25,12 @@ def layer(k, n, **kw):
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "ogc_mlp.h")).read()
-    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(ogc_[a-z_0-9]+)\s*\(", hdr))
-    assert {"ogc_mlp_plan", "ogc_mlp_prepack_weights", "ogc_mlp_run"} <= declared
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        hdr = open(os.path.join(ROOT, "include", name)).read()
+        hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+        declared |= set(re.findall(r"\b(ogc_[a-z_0-9]+)\s*\(", hdr))
+    assert {"ogc_mlp_plan", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mha_run"} <= declared
     lib = ctypes.CDLL(b.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
@@ -242,3 +244,41 @@ def test_auto_mode_choice_follows_the_measured_rules():
     assert b.ogc_mlp_packed_bytes(pc) == b.ogc_mlp_packed_bytes(pl) + 256
     b.ogc_mlp_destroy(pc)
     b.ogc_mlp_destroy(pl)
+
+
+# ---- attention subgraph: description checks (host only) ---------------------------------------------------------
+@pytest.mark.parametrize("kw,status", [
+    (dict(), 0),
+    (dict(dtype=b.OGC_BF16, head_dim=96), 0),
+    (dict(dtype=7), -1),
+    (dict(softmax=2), -1),
+    (dict(scale=float("inf")), -1),
+    (dict(seq=0), -3),
+    (dict(batch=-1), -3),
+    (dict(batch=4096, heads=16), -3),
+    (dict(seq=65537), -3),
+    (dict(dtype=b.OGC_I8), -2),
+    (dict(head_dim=80), -2),
+    (dict(head_dim=256), -2),
+    (dict(q_stride=(1000, 64, 130)), -4),       # 130 fp32 elements: not a multiple of 16 bytes
+    (dict(o_stride=(-1024, 64, 128)), -4),
+])
+def test_mha_validate(kw, status):
+    args = dict(dtype=b.OGC_F32, batch=2, heads=2, seq=128, head_dim=64, scale=0.125)
+    args.update(kw)
+    assert b.ogc_mha_validate(b.mha_desc(**args)) == status
+
+
+def test_mha_kernel_names_and_null_checks():
+    d = b.mha_desc(b.OGC_BF16, 2, 8, 128, 96, 0.1, b.OGC_SOFTMAX_FAST)
+    assert b.ogc_mha_kernel_name(d) == "ogc_mha_kernel<1, 3, 1>"
+    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_F32, 2, 8, 128, 64, 0.1)) == "ogc_mha_kernel<0, 2, 0>"
+    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_F32, 2, 8, 128, 70, 0.1)) == ""
+    assert b.lib().ogc_mha_validate(None) == -1
+    # argument checks come before any device call: NULL tensors and misaligned bases are refused on the host
+    with pytest.raises(b.OgcError) as e:
+        b.ogc_mha_run(d, 0, 256, 256, 0, 256)
+    assert e.value.status == -1
+    with pytest.raises(b.OgcError) as e:
+        b.ogc_mha_run(d, 256, 256, 264, 0, 256)
+    assert e.value.status == -4
