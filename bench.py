@@ -186,6 +186,58 @@ def table1_sweep(steps, warmup):
     return rows
 
 
+def mha_report(steps, warmup, with_cpu=True):
+    """The attention subgraph on the MHA rows of the paper's Table I (seeded synthetic q, k, v and a padding
+    mask of those shapes): one fused launch per run, stable softmax.  The roofline object is for the fp32
+    kernel of the largest row (MHA-4, batch 128): both matmuls on the fp32 MFMA path."""
+    import dataclasses
+
+    import numpy as np
+    import torch
+
+    from paper_2301_01333_amd import binding, synth
+    from paper_2301_01333_amd.harness import DeviceMHA
+
+    rows, roof, cpu = [], None, None
+    for row in ("MHA-1", "MHA-2", "MHA-3", "MHA-4"):
+        big = synth.make_mha_table1(row, "f32", 128)
+        for dtype in ("f32", "bf16"):
+            conv = (lambda t: t) if dtype == "f32" else synth.f32_to_bf16_bits
+            for batch in (32, 128):
+                wl = dataclasses.replace(big, dtype=dtype, batch=batch, q=conv(big.q[:batch]), k=conv(big.k[:batch]),
+                                         v=conv(big.v[:batch]), mask=big.mask[:batch], name="%s %s batch %d" % (row, dtype, batch))
+                dev = DeviceMHA(wl)
+                sec, ev = time_steps(dev, max(steps // 3, 10), max(warmup // 3, 3))
+                peak = PEAK[dtype][0]
+                r = {"workload": wl.name, "seq": wl.seq, "heads": wl.heads, "head_dim": wl.head_dim,
+                     "kernel": binding.ogc_mha_kernel_name(dev.desc, True), "us_per_run": sec * 1e6,
+                     "tflops": wl.ops / sec / 1e12, "frac_of_mfma_peak": wl.ops / sec / peak,
+                     "gb_per_s_algorithmic": wl.algorithmic_bytes / sec / 1e9}
+                rows.append(r)
+                if row == "MHA-4" and dtype == "f32" and batch == 128:
+                    roof = {"bound": "mfma", "achieved": wl.ops / ev / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
+                            "frac": wl.ops / ev / peak, "traffic": None, "kernel": r["kernel"],
+                            "avg_launch_us": ev * 1e6, "workload": wl.name}
+                    if with_cpu:
+                        import oracle
+
+                        nb = 2  # batch entries the oracle computes (all heads, all tokens)
+                        hv = lambda t: t[:nb].reshape(nb, wl.seq, wl.heads, wl.head_dim).transpose(0, 2, 1, 3)
+                        t0 = time.perf_counter()
+                        reps = 0
+                        while time.perf_counter() - t0 < 5.0:
+                            oracle.attention(hv(wl.q), hv(wl.k), hv(wl.v), wl.mask[:nb], wl.scale)
+                            reps += 1
+                        dt = (time.perf_counter() - t0) / reps
+                        cpu = {"value": wl.ops * nb / wl.batch / dt / 1e12, "unit": "TFLOP/s", "cores": os.cpu_count(),
+                               "kind": "oracle", "sample": "%d of %d batch entries of %s, float64 numpy, %d passes" % (
+                                   nb, wl.batch, wl.name, reps)}
+                del dev
+        del big
+    torch.cuda.synchronize()
+    return {"rows": rows, "roofline": roof, "cpu_baseline": cpu}
+
+
 def read_traffic():
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if present."""
     path = os.path.join(ROOT, "profiles", "cfg5_layer_kernel_hbm_traffic.txt")
@@ -209,6 +261,9 @@ def main():
     ap.add_argument("--table1", action="store_true",
                     help="instead of the benchmark line, print a JSON list of chain times for the MLP shapes of the paper's "
                          "Table I over batch 32..512 in fp32 and int8")
+    ap.add_argument("--mha", action="store_true",
+                    help="instead of the benchmark line, print the attention-subgraph report alone (the MHA rows of Table I)")
+    ap.add_argument("--no-mha", action="store_true", help="skip the attention-subgraph report")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference reading for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE runs of this same command)")
@@ -227,6 +282,9 @@ def main():
     binding.lib()  # fail loudly if the HIP library is missing
     if args.table1:
         print(json.dumps({"table1_mlp_sweep": table1_sweep(args.steps, args.warmup)}))
+        return 0
+    if args.mha:
+        print(json.dumps({"mha": mha_report(args.steps, args.warmup, not args.no_cpu)}))
         return 0
     floor = launch_floor(args.steps, args.warmup)
     wl, dev, head, launches = config_report(args.config, args.steps, args.warmup)
@@ -300,6 +358,7 @@ def main():
         "launch_floor_us": floor * 1e6,
         "per_config": per,
         "blocked_io": blocked,
+        "mha": None if (args.only_headline or args.no_mha) else mha_report(args.steps, args.warmup, not args.no_cpu),
     }
     print(json.dumps(out))
     return 0

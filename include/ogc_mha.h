@@ -69,9 +69,11 @@ ogc_status ogc_mha_validate(const ogc_mha_desc* desc);
 ogc_status ogc_mha_run(const ogc_mha_desc* desc, const void* q, const void* k, const void* v, const float* mask, void* o,
                        void* stream);
 
-/* Name of the kernel instantiation ogc_mha_run launches for this description, as a profiler's kernel trace
- * prints it (static storage), or NULL for an invalid description. */
-const char* ogc_mha_kernel_name(const ogc_mha_desc* desc);
+/* Name of the kernel instantiation ogc_mha_run launches for this description (has_mask: whether the run passes a
+ * mask), as a profiler's kernel trace prints it (static storage), or NULL for an invalid description.  A run
+ * without a mask whose sequence is a whole number of key blocks (bf16: 64, fp32: 32) and whose scale is
+ * positive takes a variant that spends no per-key addend. */
+const char* ogc_mha_kernel_name(const ogc_mha_desc* desc, int32_t has_mask);
 
 #ifdef __cplusplus
 }

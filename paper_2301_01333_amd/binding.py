@@ -98,7 +98,7 @@ def lib():
         l.ogc_mha_validate.restype = i32
         l.ogc_mha_run.argtypes = [ctypes.POINTER(ogc_mha_desc), vp, vp, vp, vp, vp, vp]
         l.ogc_mha_run.restype = i32
-        l.ogc_mha_kernel_name.argtypes = [ctypes.POINTER(ogc_mha_desc)]
+        l.ogc_mha_kernel_name.argtypes = [ctypes.POINTER(ogc_mha_desc), i32]
         l.ogc_mha_kernel_name.restype = ctypes.c_char_p
         _lib = l
     return _lib
@@ -219,8 +219,8 @@ def ogc_mha_run(desc: ogc_mha_desc, q_ptr: int, k_ptr: int, v_ptr: int, mask_ptr
                              stream), "ogc_mha_run")
 
 
-def ogc_mha_kernel_name(desc: ogc_mha_desc) -> str:
-    r = lib().ogc_mha_kernel_name(ctypes.byref(desc))
+def ogc_mha_kernel_name(desc: ogc_mha_desc, has_mask: bool = True) -> str:
+    r = lib().ogc_mha_kernel_name(ctypes.byref(desc), int(bool(has_mask)))
     return r.decode() if r else ""
 
 

@@ -71,8 +71,9 @@ template <> struct Cfg<OGC_F32> {
     static constexpr int E = 4, KB = 32;
 };
 
-// DT: OGC_F32 / OGC_BF16.  D32 = head_dim / 32.  FAST: softmax without the running maximum.
-template <int DT, int D32, int FAST> __global__ __launch_bounds__(256, 2) void ogc_mha_kernel(MhaArgs a) {
+// DT: OGC_F32 / OGC_BF16.  D32 = head_dim / 32.  FAST: softmax without the running maximum.  PLAIN: no mask, the
+// sequence is a whole number of key blocks and the scalar is positive, so no key needs an addend.
+template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256, 2) void ogc_mha_kernel(MhaArgs a) {
     constexpr int E = Cfg<DT>::E, KB = Cfg<DT>::KB, D = D32 * 32;
     constexpr int SB = KB / 32;                 // 32-key sub-blocks per block
     constexpr int KSTR = D * E + 16;            // bytes per key row of K in LDS (padded)
@@ -118,24 +119,25 @@ template <int DT, int D32, int FAST> __global__ __launch_bounds__(256, 2) void o
     v4i kreg[D32], vreg[VU][DT == OGC_BF16 ? 2 : 1];
     float mreg = 0.0f;
     auto prefetch = [&](int key0) {
+        const bool full = key0 + KB <= S;  // uniform: every key of the block exists, no row needs a zero fill
 #pragma unroll
         for (int i = 0; i < D32; ++i) {
             const int u = tid + 256 * i, key = key0 + u / CH, part = u % CH;
-            kreg[i] = key < S ? *(const v4i*)(kbase + key * kss + part * 16) : (v4i){0, 0, 0, 0};
+            kreg[i] = (full || key < S) ? *(const v4i*)(kbase + key * kss + part * 16) : (v4i){0, 0, 0, 0};
         }
         if constexpr (DT == OGC_BF16) {
 #pragma unroll
             for (int i = 0; i < VU; ++i) {
                 const int u = tid + 256 * i, kp = u & 31, c = u >> 5, key = key0 + 2 * kp;
-                const bool on = c < CH;
-                vreg[i][0] = (on && key < S) ? *(const v4i*)(vbase + key * vss + c * 16) : (v4i){0, 0, 0, 0};
-                vreg[i][1] = (on && key + 1 < S) ? *(const v4i*)(vbase + (key + 1) * vss + c * 16) : (v4i){0, 0, 0, 0};
+                const bool on = (32 * CH) % 256 == 0 || 256 * (i + 1) <= 32 * CH || c < CH;
+                vreg[i][0] = (on && (full || key < S)) ? *(const v4i*)(vbase + key * vss + c * 16) : (v4i){0, 0, 0, 0};
+                vreg[i][1] = (on && (full || key + 1 < S)) ? *(const v4i*)(vbase + (key + 1) * vss + c * 16) : (v4i){0, 0, 0, 0};
             }
         } else {
 #pragma unroll
             for (int i = 0; i < VU; ++i) {
                 const int u = tid + 256 * i, key = key0 + (u & 31), c = u >> 5;
-                vreg[i][0] = key < S ? *(const v4i*)(vbase + key * vss + c * 16) : (v4i){0, 0, 0, 0};
+                vreg[i][0] = (full || key < S) ? *(const v4i*)(vbase + key * vss + c * 16) : (v4i){0, 0, 0, 0};
             }
         }
         if (tid < KB) {
@@ -188,59 +190,81 @@ template <int DT, int D32, int FAST> __global__ __launch_bounds__(256, 2) void o
         v16f sacc[SB];
 #pragma unroll
         for (int sb = 0; sb < SB; ++sb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[sb][r] = 0.0f;
+            const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
             const uint8_t* krow = k_lds + (sb * 32 + col) * KSTR + h * 16;
 #pragma unroll
             for (int i = 0; i < QN; ++i) {
                 const v4i kv = *(const v4i*)(krow + i * 32);
                 if constexpr (DT == OGC_BF16) {
                     sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, kv),
-                                                                       __builtin_bit_cast(v8bf, qreg[i]), sacc[sb], 0, 0, 0);
+                                                                       __builtin_bit_cast(v8bf, qreg[i]), i ? sacc[sb] : zero, 0, 0, 0);
                 } else {
                     const v4f kf = __builtin_bit_cast(v4f, kv), qf = __builtin_bit_cast(v4f, qreg[i]);
-                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, qf.x, sacc[sb], 0, 0, 0);
+                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, qf.x, i ? sacc[sb] : zero, 0, 0, 0);
                     sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, qf.y, sacc[sb], 0, 0, 0);
                     sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, qf.z, sacc[sb], 0, 0, 0);
                     sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, qf.w, sacc[sb], 0, 0, 0);
                 }
             }
         }
-        // ---- scalar, mask (base-2 logarithm domain; a key beyond the sequence carries -infinity)
-        float blk_max = -INFINITY;
+        // ---- scalar, mask, running maximum (base-2 logarithm domain; a key beyond the sequence carries
+        // -infinity).  A block of valid keys without a mask needs no per-key addend: the maximum is taken on
+        // the raw products and the scalar rides in the exponent's multiply-add.
+        const float c = a.scale_log2;
+        {
+            float cand = -INFINITY;
+            if constexpr (PLAIN) {
+                if constexpr (!FAST) {
 #pragma unroll
-        for (int sb = 0; sb < SB; ++sb)
+                    for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const v4f mk = *(const v4f*)(m_lds + sb * 32 + 8 * g + 4 * h);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float s = __builtin_fmaf(sacc[sb][4 * g + e], a.scale_log2, mk[e]);
-                    sacc[sb][4 * g + e] = s;
-                    if constexpr (!FAST) blk_max = fmaxf(blk_max, s);
+                        for (int r = 0; r < 16; ++r) cand = fmaxf(cand, sacc[sb][r]);
+                    cand *= c;
                 }
+            } else {
+#pragma unroll
+                for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const v4f mk = *(const v4f*)(m_lds + sb * 32 + 8 * g + 4 * h);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float t = __builtin_fmaf(sacc[sb][4 * g + e], c, mk[e]);
+                            sacc[sb][4 * g + e] = t;
+                            if constexpr (!FAST) cand = fmaxf(cand, t);
+                        }
+                    }
             }
-        float shift = 0.0f;
-        if constexpr (!FAST) {
-            blk_max = fmaxf(blk_max, other_half(blk_max));
-            const float new_max = fmaxf(run_max, blk_max);   // finite: key 0 of block 0 is always valid
-            const float alpha = __builtin_amdgcn_exp2f(run_max - new_max);
-            run_max = new_max;
-            run_sum *= alpha;
+            float off = 0.0f;
+            if constexpr (!FAST) {
+                // The reference point of the exponentials only has to be NEAR the maximum: it moves when a block
+                // exceeds it by more than 2^8, so most blocks skip the rescaling of the output accumulators.  The
+                // result is the same function (numerator and denominator carry the same factor); weights reach
+                // 256 at most, far from any overflow.  Key 0 of block 0 is always valid: the first block sets it.
+                cand = fmaxf(cand, other_half(cand));
+                const bool need = cand > run_max + 8.0f;
+                if (__builtin_amdgcn_ballot_w64(need) != 0) {
+                    const float new_max = need ? cand : run_max;
+                    const float alpha = __builtin_amdgcn_exp2f(run_max - new_max);
+                    run_max = new_max;
+                    run_sum *= alpha;
 #pragma unroll
-            for (int d = 0; d < D32; ++d)
+                    for (int d = 0; d < D32; ++d)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
-            shift = new_max;
+                        for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
+                }
+                off = -run_max;
+            }
+#pragma unroll
+            for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float x;
+                    if constexpr (PLAIN) x = __builtin_fmaf(sacc[sb][r], c, off);
+                    else x = FAST ? sacc[sb][r] : sacc[sb][r] + off;
+                    sacc[sb][r] = __builtin_amdgcn_exp2f(x);
+                }
         }
-#pragma unroll
-        for (int sb = 0; sb < SB; ++sb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(FAST ? sacc[sb][r] : sacc[sb][r] - shift);
-                sacc[sb][r] = p;
-                run_sum += p;
-            }
         // ---- O^T += V^T P^T
         if constexpr (DT == OGC_BF16) {
 #pragma unroll
@@ -248,8 +272,15 @@ template <int DT, int D32, int FAST> __global__ __launch_bounds__(256, 2) void o
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const v16f& p = sacc[sb];
-                    const v4i pw = {(int)pack_bf16(p[8 * j], p[8 * j + 1]), (int)pack_bf16(p[8 * j + 2], p[8 * j + 3]),
-                                    (int)pack_bf16(p[8 * j + 4], p[8 * j + 5]), (int)pack_bf16(p[8 * j + 6], p[8 * j + 7])};
+                    // the row sum takes the weights as rounded, the values the second product multiplies
+                    uint32_t w[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const v2bf pr = {(__bf16)p[8 * j + 2 * t], (__bf16)p[8 * j + 2 * t + 1]};
+                        run_sum = __builtin_amdgcn_fdot2_f32_bf16(pr, (v2bf){(__bf16)1.0f, (__bf16)1.0f}, run_sum, false);
+                        w[t] = __builtin_bit_cast(uint32_t, pr);
+                    }
+                    const v4i pw = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
 #pragma unroll
                     for (int d = 0; d < D32; ++d) {
                         const v4i vv = *(const v4i*)(vt_lds + (d * 32 + col) * VSTR + (sb * 32 + 16 * j + 8 * h) * 2);
@@ -258,6 +289,8 @@ template <int DT, int D32, int FAST> __global__ __launch_bounds__(256, 2) void o
                     }
                 }
         } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) run_sum += sacc[0][r];
 #pragma unroll
             for (int g = 0; g < 4; ++g)
 #pragma unroll
@@ -316,18 +349,26 @@ template <int DT, int D32, int FAST> __global__ __launch_bounds__(256, 2) void o
     }
 }
 
-template <int DT, int D32> hipError_t launch_fast(int fast, const MhaArgs& a, dim3 grid, hipStream_t st) {
-    if (fast) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 0>), grid, dim3(256), 0, st, a);
+template <int DT, int D32> hipError_t launch_fast(int fast, int plain, const MhaArgs& a, dim3 grid, hipStream_t st) {
+    if (fast && plain) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1, 1>), grid, dim3(256), 0, st, a);
+    else if (fast) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1, 0>), grid, dim3(256), 0, st, a);
+    else if (plain) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 0, 1>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 0, 0>), grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
-template <int DT> hipError_t launch_dim(int d32, int fast, const MhaArgs& a, dim3 grid, hipStream_t st) {
+template <int DT> hipError_t launch_dim(int d32, int fast, int plain, const MhaArgs& a, dim3 grid, hipStream_t st) {
     switch (d32) {
-    case 1: return launch_fast<DT, 1>(fast, a, grid, st);
-    case 2: return launch_fast<DT, 2>(fast, a, grid, st);
-    case 3: return launch_fast<DT, 3>(fast, a, grid, st);
-    default: return launch_fast<DT, 4>(fast, a, grid, st);
+    case 1: return launch_fast<DT, 1>(fast, plain, a, grid, st);
+    case 2: return launch_fast<DT, 2>(fast, plain, a, grid, st);
+    case 3: return launch_fast<DT, 3>(fast, plain, a, grid, st);
+    default: return launch_fast<DT, 4>(fast, plain, a, grid, st);
     }
+}
+
+// no mask, whole key blocks only, positive scalar
+bool plain_case(const ogc_mha_desc* d, const float* mask) {
+    const int kb = d->dtype == OGC_BF16 ? Cfg<OGC_BF16>::KB : Cfg<OGC_F32>::KB;
+    return mask == nullptr && d->seq % kb == 0 && d->scale > 0.0f;
 }
 
 bool stride_ok(const int64_t s[3], int elt) {
@@ -382,16 +423,18 @@ ogc_status ogc_mha_run(const ogc_mha_desc* d, const void* q, const void* k, cons
     a.xcd_order = (bh % 8 == 0) ? 1 : 0;
     a.scale_log2 = d->scale * 1.44269504088896340736f;
     const dim3 grid((unsigned)(bh * a.q_tiles));
-    const hipError_t e = d->dtype == OGC_F32 ? launch_dim<OGC_F32>(d->head_dim / 32, d->softmax, a, grid, (hipStream_t)stream)
-                                             : launch_dim<OGC_BF16>(d->head_dim / 32, d->softmax, a, grid, (hipStream_t)stream);
+    const int plain = plain_case(d, mask);
+    const hipError_t e = d->dtype == OGC_F32 ? launch_dim<OGC_F32>(d->head_dim / 32, d->softmax, plain, a, grid, (hipStream_t)stream)
+                                             : launch_dim<OGC_BF16>(d->head_dim / 32, d->softmax, plain, a, grid, (hipStream_t)stream);
     return e == hipSuccess ? OGC_OK : OGC_ERR_DEVICE;
 }
 
-const char* ogc_mha_kernel_name(const ogc_mha_desc* d) {
+const char* ogc_mha_kernel_name(const ogc_mha_desc* d, int32_t has_mask) {
     if (ogc_mha_validate(d) != OGC_OK) return nullptr;
-    static char names[2][4][2][40];
-    char* s = names[d->dtype == OGC_BF16][d->head_dim / 32 - 1][d->softmax];
-    if (!s[0]) snprintf(s, 40, "ogc_mha_kernel<%d, %d, %d>", d->dtype, d->head_dim / 32, d->softmax);
+    static char names[2][4][2][2][40];
+    const int plain = plain_case(d, has_mask ? (const float*)d : nullptr);
+    char* s = names[d->dtype == OGC_BF16][d->head_dim / 32 - 1][d->softmax][plain];
+    if (!s[0]) snprintf(s, 40, "ogc_mha_kernel<%d, %d, %d, %d>", d->dtype, d->head_dim / 32, d->softmax, plain);
     return s;
 }
 
