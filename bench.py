@@ -186,7 +186,7 @@ def table1_sweep(steps, warmup):
     return rows
 
 
-def mha_report(steps, warmup, with_cpu=True):
+def mha_report(steps, warmup, with_cpu=True, only=None):
     """The attention subgraph on the MHA rows of the paper's Table I (seeded synthetic q, k, v and a padding
     mask of those shapes): one fused launch per run, stable softmax.  The roofline object is for the fp32
     kernel of the largest row (MHA-4, batch 128): both matmuls on the fp32 MFMA path."""
@@ -200,10 +200,14 @@ def mha_report(steps, warmup, with_cpu=True):
 
     rows, roof, cpu = [], None, None
     for row in ("MHA-1", "MHA-2", "MHA-3", "MHA-4"):
+        if only and only[0] != row:
+            continue
         big = synth.make_mha_table1(row, "f32", 128)
         for dtype in ("f32", "bf16"):
             conv = (lambda t: t) if dtype == "f32" else synth.f32_to_bf16_bits
             for batch in (32, 128):
+                if only and (only[1] != dtype or int(only[2]) != batch):
+                    continue
                 wl = dataclasses.replace(big, dtype=dtype, batch=batch, q=conv(big.q[:batch]), k=conv(big.k[:batch]),
                                          v=conv(big.v[:batch]), mask=big.mask[:batch], name="%s %s batch %d" % (row, dtype, batch))
                 dev = DeviceMHA(wl)
@@ -216,7 +220,7 @@ def mha_report(steps, warmup, with_cpu=True):
                 rows.append(r)
                 if row == "MHA-4" and dtype == "f32" and batch == 128:
                     roof = {"bound": "mfma", "achieved": wl.ops / ev / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
-                            "frac": wl.ops / ev / peak, "traffic": None, "kernel": r["kernel"],
+                            "frac": wl.ops / ev / peak, "traffic": read_traffic("mha4_f32_kernel_hbm_traffic.txt"), "kernel": r["kernel"],
                             "avg_launch_us": ev * 1e6, "workload": wl.name}
                     if with_cpu:
                         import oracle
@@ -238,9 +242,18 @@ def mha_report(steps, warmup, with_cpu=True):
     return {"rows": rows, "roofline": roof, "cpu_baseline": cpu}
 
 
-def read_traffic():
+def copy_calibration(torch):
+    """Three plain 256 MiB device-to-device copies: the known-size reference for FETCH_SIZE / WRITE_SIZE runs."""
+    src = torch.full((256 << 20,), 7, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+
+
+def read_traffic(name="cfg5_layer_kernel_hbm_traffic.txt"):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if present."""
-    path = os.path.join(ROOT, "profiles", "cfg5_layer_kernel_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", name)
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -264,6 +277,8 @@ def main():
     ap.add_argument("--mha", action="store_true",
                     help="instead of the benchmark line, print the attention-subgraph report alone (the MHA rows of Table I)")
     ap.add_argument("--no-mha", action="store_true", help="skip the attention-subgraph report")
+    ap.add_argument("--mha-workload", default=None, metavar="ROW:DTYPE:BATCH",
+                    help="with --mha: only this workload, e.g. MHA-4:f32:128 (the one the report's roofline is for)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference reading for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE runs of this same command)")
@@ -284,7 +299,10 @@ def main():
         print(json.dumps({"table1_mlp_sweep": table1_sweep(args.steps, args.warmup)}))
         return 0
     if args.mha:
-        print(json.dumps({"mha": mha_report(args.steps, args.warmup, not args.no_cpu)}))
+        only = args.mha_workload.split(":") if args.mha_workload else None
+        print(json.dumps({"mha": mha_report(args.steps, args.warmup, not args.no_cpu, only)}))
+        if args.copy_calibration:
+            copy_calibration(torch)
         return 0
     floor = launch_floor(args.steps, args.warmup)
     wl, dev, head, launches = config_report(args.config, args.steps, args.warmup)
@@ -323,12 +341,7 @@ def main():
     roof.update(dom)
     dev.close()
     if args.copy_calibration:
-        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        copy_calibration(torch)
 
     per = []
     if not args.only_headline:

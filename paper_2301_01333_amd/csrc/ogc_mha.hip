@@ -22,8 +22,6 @@
 
 #include "ogc_mha.h"
 
-namespace {
-
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -63,18 +61,18 @@ MHA_DEV uint32_t pack_bf16(float lo, float hi) {  // round to nearest even, two 
     return __builtin_bit_cast(uint32_t, r);
 }
 
-template <int DT> struct Cfg;
-template <> struct Cfg<OGC_BF16> {
+template <int DT> struct MhaCfg;
+template <> struct MhaCfg<OGC_BF16> {
     static constexpr int E = 2, KB = 64;
 };
-template <> struct Cfg<OGC_F32> {
+template <> struct MhaCfg<OGC_F32> {
     static constexpr int E = 4, KB = 32;
 };
 
 // DT: OGC_F32 / OGC_BF16.  D32 = head_dim / 32.  FAST: softmax without the running maximum.  PLAIN: no mask, the
 // sequence is a whole number of key blocks and the scalar is positive, so no key needs an addend.
 template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256, 2) void ogc_mha_kernel(MhaArgs a) {
-    constexpr int E = Cfg<DT>::E, KB = Cfg<DT>::KB, D = D32 * 32;
+    constexpr int E = MhaCfg<DT>::E, KB = MhaCfg<DT>::KB, D = D32 * 32;
     constexpr int SB = KB / 32;                 // 32-key sub-blocks per block
     constexpr int KSTR = D * E + 16;            // bytes per key row of K in LDS (padded)
     constexpr int VSTR = KB * E + 16;           // bytes per channel row of V^T in LDS (padded)
@@ -349,6 +347,8 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
     }
 }
 
+namespace {
+
 template <int DT, int D32> hipError_t launch_fast(int fast, int plain, const MhaArgs& a, dim3 grid, hipStream_t st) {
     if (fast && plain) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1, 1>), grid, dim3(256), 0, st, a);
     else if (fast) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1, 0>), grid, dim3(256), 0, st, a);
@@ -367,7 +367,7 @@ template <int DT> hipError_t launch_dim(int d32, int fast, int plain, const MhaA
 
 // no mask, whole key blocks only, positive scalar
 bool plain_case(const ogc_mha_desc* d, const float* mask) {
-    const int kb = d->dtype == OGC_BF16 ? Cfg<OGC_BF16>::KB : Cfg<OGC_F32>::KB;
+    const int kb = d->dtype == OGC_BF16 ? MhaCfg<OGC_BF16>::KB : MhaCfg<OGC_F32>::KB;
     return mask == nullptr && d->seq % kb == 0 && d->scale > 0.0f;
 }
 
