@@ -166,6 +166,13 @@ void ogc_mlp_destroy(ogc_mlp_plan_t plan);
 /* Static, NUL-terminated description of a status code. */
 const char* ogc_status_string(ogc_status s);
 
+/* The plan's cost-model estimate, in microseconds, of layer `layer`'s launch (both launches of a layer whose
+ * reduction axis is split), the figure by which ogc_mlp_plan chose that layer's tile and split (Section III: the
+ * heuristic scores candidate template parameters, no tuning run).  *us = -1 when the layer was not chosen by the
+ * model: fused / cooperative mode, OGC_F32, a forced tile of a kind the model does not cover.  Host only.
+ * OGC_ERR_INVALID_ARG: NULL plan or us, layer out of range. */
+ogc_status ogc_mlp_estimated_us(ogc_mlp_plan_t plan, int32_t layer, float* us);
+
 /* Name, with template arguments as a kernel trace prints them, of the kernel that ogc_mlp_run launches for
  * layer `layer` (fused mode: the same name for every layer; a split layer: its first kernel), for matching
  * profiler output.  Returns NULL on a bad argument. */

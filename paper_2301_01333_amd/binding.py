@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(_HERE, "libogc_mlp.so")
 EXPORTS = [
     "ogc_mlp_plan", "ogc_mlp_packed_bytes", "ogc_mlp_workspace_bytes", "ogc_mlp_chosen_mode",
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
-    "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes",
+    "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes", "ogc_mlp_estimated_us",
     "ogc_mha_validate", "ogc_mha_run", "ogc_mha_kernel_name",
 ]
 
@@ -94,6 +94,8 @@ def lib():
         l.ogc_status_string.restype = ctypes.c_char_p
         l.ogc_mlp_kernel_name.argtypes = [vp, i32]
         l.ogc_mlp_kernel_name.restype = ctypes.c_char_p
+        l.ogc_mlp_estimated_us.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
+        l.ogc_mlp_estimated_us.restype = i32
         l.ogc_mha_validate.argtypes = [ctypes.POINTER(ogc_mha_desc)]
         l.ogc_mha_validate.restype = i32
         l.ogc_mha_run.argtypes = [ctypes.POINTER(ogc_mha_desc), vp, vp, vp, vp, vp, vp]
@@ -190,6 +192,12 @@ def ogc_mlp_run_profiled(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, wor
     ms = (ctypes.c_float * n)()
     _check(lib().ogc_mlp_run_profiled(plan, x_ptr, y_ptr, packed_ptr, workspace_ptr or None, stream, ms), "ogc_mlp_run_profiled")
     return [float(v) for v in ms]
+
+
+def ogc_mlp_estimated_us(plan: int, layer: int) -> float:
+    v = ctypes.c_float()
+    _check(lib().ogc_mlp_estimated_us(plan, int(layer), ctypes.byref(v)), "ogc_mlp_estimated_us")
+    return v.value
 
 
 def ogc_mlp_destroy(plan: int) -> None:

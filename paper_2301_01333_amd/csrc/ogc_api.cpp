@@ -1,6 +1,7 @@
 // Host side of the fused-MLP library: plan construction (validation, kernel-family and tile choice,
 // packed-blob and workspace layout, buffer reuse) and the C ABI declared in include/ogc_mlp.h.
 // No device memory is allocated here and no device call is made outside prepack / run.
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdlib>
@@ -25,6 +26,7 @@ struct LayerPlan {
     int kc_out;       // chunks per row of the KB16 output
     int tile;         // per-layer mode: tile configuration
     int ksplit_log2;  // stream tiles only: the reduction axis is cut into 1 << ksplit_log2 ranges (0: not split)
+    double est_us;    // the cost model's estimate for this layer's launch(es); < 0: not modelled
     size_t w_off, scale_off, bias_off, ncomp_off;  // offsets in the packed blob
     int out_slot;     // workspace slot of the output (-1: caller's y / LDS)
     size_t out_off;   // byte offset of that slot in the workspace
@@ -89,25 +91,101 @@ int env_int(const char* name, int dflt) {
     return (v && *v) ? std::atoi(v) : dflt;
 }
 
-// Tile choice for a per-layer launch (the role of the template-parameter heuristic of Section III:
-// balance the number of workgroups against the 256 CUs, prefer the largest tile for operand reuse).
-// dma_ok: the pipelined global->LDS kernel can read this layer's input (always true for KB16 workspace
-// inputs; for the caller's plain x it needs 16-byte aligned rows and no K padding).
-int choose_tile(int m, int n, bool dma_ok) {
-    const int forced = env_int("OGC_TILE", -1);
-    if (forced >= 0 && forced < OGC_NUM_TILES)
-        return ((forced == OGC_TILE_DMA || forced == OGC_TILE_DMA8) && !dma_ok) ? OGC_TILE_MID : forced;
+// ---- Plan-time cost model for a per-layer launch (the role of the template-parameter heuristic of Section III:
+// propose a split of the output among the cores for load balance and a tile for kernel efficiency, score, take the
+// best; no tuning run).  A candidate is a tile configuration and, for the stream tiles, a cut of the reduction
+// axis into 1 << ks ranges (the paper's k-slicing).  Its time in microseconds is modelled as
+//
+//     W      = tiles * 2^ks workgroups of k = KT >> ks steps (a step is 64 bytes of K per row)
+//     lone   = (c + d*k) * (1 + g*min(1, W/CUs))        one workgroup's latency, stretched as the chip fills up
+//     stream = l0 + rounds * (a + b*k [+ px if split])   a CU's share of the work at full load,
+//              rounds = (ceil(W/CUs) + W/CUs) / 2        (between whole rounds and perfect balance)
+//     t      = max(lone, stream) [+ r0 + r2*2^ks + r1*(2^ks + 1)*Mp*Np*4 bytes/1e6 for the pass over the partials]
+//
+// with the constants fitted (least squares on log time, candidates near the fastest weighted double, 8 % rms) to
+// 1570 timed launches of mid-chain layers on an
+// MI355X: K and N from 256 to 8192, batch 32 to 32768, every tile, splits 1 to 8, int8 and bf16.  On those shapes
+// the model's pick is within 1 % (geometric mean; 36 % worst case, one 8192x256 layer) of the fastest
+// candidate measured.  The constants include the launch; activation and bias costs are left out (the same for
+// every candidate to first order).
+struct TileCost {
+    float c, d, a, b, g;
+};
+struct CostTable {
+    TileCost t[OGC_NUM_TILES];  // indexed by tile id; OGC_TILE_BIG is not a candidate
+    float r0, r1, r2, px, l0;
+};
+const CostTable kCostI8 = {{{0, 0, 0, 0, 0},
+                            {7.354f, 0.452f, 2.362f, 0.349f, 0.097f},
+                            {4.896f, 0.339f, 0.479f, 0.086f, 0.102f},
+                            {7.931f, 0.289f, 0.051f, 0.565f, 0.260f},
+                            {9.489f, 0.486f, 4.848f, 0.805f, 0.115f}},
+                           0.933f, 0.160f, 0.981f, 3.013f, 2.651f};
+const CostTable kCostBf16 = {{{0, 0, 0, 0, 0},
+                              {6.767f, 0.452f, 2.365f, 0.327f, 0.171f},
+                              {4.596f, 0.337f, 0.517f, 0.081f, 0.133f},
+                              {8.151f, 0.289f, 0.756f, 0.579f, 0.277f},
+                              {9.995f, 0.480f, 8.036f, 0.829f, 0.244f}},
+                             0.889f, 0.119f, 0.922f, 4.469f, 0.061f};
+
+// m rows x n channels, kt = 64-byte steps of the (padded) reduction axis.  dtype OGC_I8 or OGC_BF16.
+double estimate_layer_us(int dtype, int m, int n, int kt, int tile, int ks) {
+    const CostTable& ct = dtype == OGC_I8 ? kCostI8 : kCostBf16;
+    const TileCost& tc = ct.t[tile];
+    const OgcTileInfo ti = ogc_tile_info(tile);
+    const double cus = 256.0;
+    const double tiles = (double)((m + ti.bm - 1) / ti.bm) * ((n + ti.bn - 1) / ti.bn);
+    const double w = tiles * (1 << ks), k = (double)(kt >> ks);
+    const double lone = (tc.c + tc.d * k) * (1.0 + tc.g * std::min(1.0, w / cus));
+    const double rounds = 0.5 * (std::ceil(w / cus) + w / cus);
+    double t = std::max(lone, ct.l0 + rounds * (tc.a + tc.b * k + (ks ? ct.px : 0.0f)));
+    if (ks) {
+        const double mp = (double)round_up((size_t)m, 256), np = (double)round_up((size_t)n, 256);
+        t += ct.r0 + ct.r2 * (1 << ks) + ct.r1 * ((1 << ks) + 1) * mp * np * 4.0 / 1e6;
+    }
+    return t;
+}
+
+// Picks tile and split for one layer.  dma_ok: the stream kernel can run this layer (int8 / bf16, no sigmoid,
+// input zero point 128, and a first layer whose plain rows are 16-byte aligned without K padding).  Layers it
+// cannot run keep the rule measured for the register-staged tiles.  OGC_TILE / OGC_KSPLIT in the environment
+// force a choice (tests, sweeps).
+void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int* tile_out, int* ks_out, double* us_out) {
     auto tiles = [&](int t) {
         const OgcTileInfo ti = ogc_tile_info(t);
         return (long)((m + ti.bm - 1) / ti.bm) * ((n + ti.bn - 1) / ti.bn);
     };
-    // Measured on 1024-wide int8 chains and on the bf16 FFN shape over batch 512..32768: the eight-wave stream
-    // shape once its 256x256 tiles fill the chip; the four-wave shape (128x256 tiles, two workgroups per CU) from
-    // 64 tiles up, where it beats the register-staged tiles; those below that.
-    if (dma_ok && tiles(OGC_TILE_DMA8) >= 224) return OGC_TILE_DMA8;
-    if (dma_ok && tiles(OGC_TILE_DMA) >= 64) return OGC_TILE_DMA;
-    if (tiles(OGC_TILE_MID) >= 128) return OGC_TILE_MID;
-    return OGC_TILE_SMALL;
+    auto split_ok = [&](int ks) { return ks >= 0 && ks <= 3 && kt % (1 << ks) == 0 && (kt >> ks) >= 4; };
+    const int forced = env_int("OGC_TILE", -1), forced_split = env_int("OGC_KSPLIT", -1);
+    const bool modelled = dtype != OGC_F32;
+    int tile = -1, ks = 0;
+    if (forced >= 0 && forced < OGC_NUM_TILES) {
+        tile = ((forced == OGC_TILE_DMA || forced == OGC_TILE_DMA8) && !dma_ok) ? OGC_TILE_MID : forced;
+    } else if (!dma_ok) {
+        tile = tiles(OGC_TILE_MID) >= 128 ? OGC_TILE_MID : OGC_TILE_SMALL;
+    }
+    const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8;
+    if (tile >= 0) {
+        if (stream && forced_split > 0 && forced_split <= 3 && kt % (1 << forced_split) == 0) ks = forced_split;
+        else if (stream && forced_split < 0 && forced >= 0) ks = 0;
+    } else {
+        double best = 0.0;
+        const int cands[4] = {OGC_TILE_SMALL, OGC_TILE_MID, OGC_TILE_DMA, OGC_TILE_DMA8};
+        for (int c = 0; c < 4; ++c) {
+            const bool st = cands[c] == OGC_TILE_DMA || cands[c] == OGC_TILE_DMA8;
+            if (forced_split > 0 && !st) continue;  // a forced split needs a stream tile
+            for (int s = 0; s <= (st ? 3 : 0); ++s) {
+                if (forced_split >= 0 && st && s != forced_split) continue;
+                if (s > 0 && !(forced_split > 0 ? kt % (1 << s) == 0 : split_ok(s))) continue;
+                const double us = estimate_layer_us(dtype, m, n, kt, cands[c], s);
+                if (tile < 0 || us < best) best = us, tile = cands[c], ks = s;
+            }
+        }
+    }
+    if (tile < 0) tile = tiles(OGC_TILE_MID) >= 128 ? OGC_TILE_MID : OGC_TILE_SMALL;  // nothing admissible was forced
+    *tile_out = tile;
+    *ks_out = ks;
+    *us_out = (modelled && tile != OGC_TILE_BIG) ? estimate_layer_us(dtype, m, n, kt, tile, ks) : -1.0;
 }
 
 ogc_status validate(const ogc_mlp_desc* d) {
@@ -270,35 +348,12 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
                                 !(desc->dtype == OGC_I8 && lp.d.in_zp != 128) &&
                                 (l > 0 || desc->x_layout == OGC_LAYOUT_BLOCKED ||
                                  (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
-            lp.tile = choose_tile(desc->m, rows, dma_ok);
-            lp.ksplit_log2 = 0;
-            // Too few 256x256 tiles for the chip but a long reduction axis: cut K into ranges (the paper's
-            // k-slicing, Section III) so that tiles x ranges fill the CUs; a second pass adds the ranges.
-            {
-                const OgcTileInfo t8 = ogc_tile_info(OGC_TILE_DMA8);
-                const long tiles8 = (long)((desc->m + t8.bm - 1) / t8.bm) * ((rows + t8.bn - 1) / t8.bn);
-                const int kt = lp.kc / 4;
-                const int forced_tile = env_int("OGC_TILE", -1), forced_split = env_int("OGC_KSPLIT", -1);
-                if (forced_split >= 0) {
-                    if (forced_split > 0 && (lp.tile == OGC_TILE_DMA8 || lp.tile == OGC_TILE_DMA) && forced_split <= 3 &&
-                        kt % (1 << forced_split) == 0)
-                        lp.ksplit_log2 = forced_split;
-                } else if (dma_ok && forced_tile < 0 && lp.tile != OGC_TILE_DMA8) {
-                    // Worth it only for a long reduction axis: the partial accumulators cost (ranges + 1) x M x N x 4
-                    // bytes of traffic, the gain is a share of a GEMM time that grows with K.  At least 32 k-steps
-                    // per range (with 16 the pass over the partials took longer than the idle CUs cost).
-                    for (int ls = 1; ls <= 3; ++ls)
-                        if (kt % (1 << ls) == 0 && (kt >> ls) >= 32 && (tiles8 << ls) >= 192) {
-                            lp.tile = OGC_TILE_DMA8;
-                            lp.ksplit_log2 = ls;
-                            break;
-                        }
-                }
-            }
+            choose_tile_and_split(desc->dtype, desc->m, rows, lp.kc / 4, dma_ok, &lp.tile, &lp.ksplit_log2, &lp.est_us);
             lp.npw = (int)round_up((size_t)rows, ogc_tile_info(lp.tile).bn);
         } else {
             lp.tile = -1;
             lp.ksplit_log2 = 0;
+            lp.est_us = -1.0;
             lp.npw = (int)round_up((size_t)rows, 32);
         }
         lp.w_off = off;
@@ -543,6 +598,12 @@ const char* ogc_status_string(ogc_status s) {
     case OGC_ERR_DEVICE: return "HIP runtime error";
     }
     return "unknown status";
+}
+
+ogc_status ogc_mlp_estimated_us(ogc_mlp_plan_t plan, int32_t layer, float* us) {
+    if (!plan || !us || layer < 0 || layer >= (int)plan->layers.size()) return OGC_ERR_INVALID_ARG;
+    *us = (plan->mode == OGC_MODE_PER_LAYER) ? (float)plan->layers[layer].est_us : -1.0f;
+    return OGC_OK;
 }
 
 const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer) {

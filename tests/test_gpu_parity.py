@@ -170,6 +170,19 @@ def test_split_k(oracle_mod, dtype, tile):
         check(synth.make_config(4, m=300), "per_layer", oracle_mod, tile=tile, ksplit=2)
 
 
+@pytest.mark.parametrize("dtype", ["i8", "bf16"])
+def test_cost_model_choices(oracle_mod, dtype):
+    """Per-layer chains whose tiles and splits the plan's cost model picks by itself: long reduction axes at small
+    batch (four-wave stream tile cut along K), mid-size layers (small register-staged tile), a ragged batch that
+    fills the chip (eight-wave tile).  int8 bit-exact against the oracle."""
+    for m, dims, seed in ((256, [256, 8192, 256, 512], 731), (500, [1024, 4096, 1024], 732), (1536, [768, 3072, 768], 733),
+                          (2048, [1024, 1024, 1024], 734), (96, [2048, 2048, 320], 735), (16500, [512, 1024, 512], 736)):
+        acts = [RELU] * (len(dims) - 1)
+        wl = synth.make_mlp(dtype, m, dims, acts, seed=seed, name="model-chosen", has_bias=(seed % 2 == 0))
+        rows = None if m * max(dims) <= (1 << 22) else [slice(0, 300), slice(m - 260, m)]
+        check(wl, "per_layer", oracle_mod, rows=rows)
+
+
 # ---------------------------------------------------------------- edge cases
 @pytest.mark.parametrize("mode", ["fused", "per_layer"])
 def test_edges_int8(oracle_mod, mode):

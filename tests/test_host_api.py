@@ -152,10 +152,12 @@ def test_split_k_plan_sizes_and_kernel_names(monkeypatch):
     assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_PER_LAYER
     assert b.ogc_mlp_num_launches(p) == 2
     hidden_slot = m * hid * 2
-    partial = 4 * m * k0 * 4          # 64 tiles of 256x256 -> four ranges of fp32 accumulators
+    partial = 2 * m * k0 * 4          # 128 tiles of 128x256 -> two ranges of fp32 accumulators, 256 workgroups
     assert b.ogc_mlp_workspace_bytes(p) == hidden_slot + partial
     assert b.ogc_mlp_kernel_name(p, 0) == "ogc_layer_dma_kernel<1, 1, 1, 0, 0>"
-    assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 1, 0, 0, 2>"
+    assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 0, 0, 0, 2>"
+    # the figures the choice was made by: the estimate of the chosen candidate, in microseconds
+    assert 25.0 < b.ogc_mlp_estimated_us(p, 0) < 45.0 and 40.0 < b.ogc_mlp_estimated_us(p, 1) < 65.0
     b.ogc_mlp_destroy(p)
     # forced off: no partial region, the second layer takes the four-wave stream shape (128 tiles of 128x256)
     monkeypatch.setenv("OGC_KSPLIT", "0")
@@ -287,3 +289,34 @@ def test_mha_kernel_names_and_null_checks():
     with pytest.raises(b.OgcError) as e:
         b.ogc_mha_run(d, 256, 256, 264, 0, 256)
     assert e.value.status == -4
+
+
+def test_cost_model_choices(monkeypatch):
+    """The plan's cost model (Section III: score candidate template parameters, no tuning run) on shapes whose
+    fastest candidate was measured: big batches take the eight-wave stream tile, a short wide layer with a long
+    reduction axis is cut along K on the four-wave tile, mid-size layers take the small register-staged tile."""
+    monkeypatch.delenv("OGC_TILE", raising=False)
+    monkeypatch.delenv("OGC_KSPLIT", raising=False)
+
+    def mid_layer(dtype, m, dims):
+        lay = [layer(dims[i], dims[i + 1], has_bias=0) for i in range(3)]
+        p = b.ogc_mlp_plan(dtype, m, lay, dims[0], dims[3], 0, b.OGC_MODE_PER_LAYER)
+        r = b.ogc_mlp_kernel_name(p, 1), b.ogc_mlp_estimated_us(p, 1)
+        b.ogc_mlp_destroy(p)
+        return r
+
+    assert mid_layer(b.OGC_I8, 32768, [1024] * 4)[0] == "ogc_layer_dma_kernel<2, 1, 0, 0, 1>"
+    assert mid_layer(b.OGC_I8, 256, [256, 8192, 256, 8192])[0] == "ogc_layer_dma_kernel<2, 0, 0, 0, 2>"   # K = 8192, split
+    assert mid_layer(b.OGC_BF16, 512, [1024, 4096, 1024, 4096])[0] == "ogc_layer_dma_kernel<1, 0, 0, 0, 2>"
+    assert mid_layer(b.OGC_I8, 2048, [1024] * 4)[0] == "ogc_layer_kernel<2, 2, 0, 0>"
+    # estimates grow with the batch once the chip is full, and a forced worse candidate is estimated slower
+    e1, e2 = mid_layer(b.OGC_I8, 16384, [1024] * 4)[1], mid_layer(b.OGC_I8, 32768, [1024] * 4)[1]
+    assert 0 < e1 < e2 < 2.5 * e1
+    best = mid_layer(b.OGC_I8, 256, [256, 8192, 256, 8192])[1]
+    monkeypatch.setenv("OGC_TILE", "4")
+    monkeypatch.setenv("OGC_KSPLIT", "0")
+    assert mid_layer(b.OGC_I8, 256, [256, 8192, 256, 8192])[1] > 2 * best
+    # fp32 layers are not modelled
+    monkeypatch.delenv("OGC_TILE")
+    monkeypatch.delenv("OGC_KSPLIT")
+    assert mid_layer(b.OGC_F32, 4096, [512] * 4)[1] == -1.0
