@@ -173,6 +173,13 @@ const char* ogc_status_string(ogc_status s);
  * OGC_ERR_INVALID_ARG: NULL plan or us, layer out of range. */
 ogc_status ogc_mlp_estimated_us(ogc_mlp_plan_t plan, int32_t layer, float* us);
 
+/* The cost models' estimates of the whole chain in microseconds, by which OGC_MODE_AUTO chose the mode:
+ * us[0] layer by layer (sum of the layers' estimates), us[1] the fused whole-chain kernel, us[2] the cooperative
+ * kernel; -1 where a mode is not admissible (fused: the widest layer does not fit LDS, or bf16 / fp32 weights
+ * beyond 2.5 MB; cooperative: a single layer, blocked tensors at the boundary) or not modelled.  Host only.
+ * OGC_ERR_INVALID_ARG: NULL plan or us. */
+ogc_status ogc_mlp_mode_estimates(ogc_mlp_plan_t plan, float us[3]);
+
 /* Name, with template arguments as a kernel trace prints them, of the kernel that ogc_mlp_run launches for
  * layer `layer` (fused mode: the same name for every layer; a split layer: its first kernel), for matching
  * profiler output.  Returns NULL on a bad argument. */

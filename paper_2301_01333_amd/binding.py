@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(_HERE, "libogc_mlp.so")
 EXPORTS = [
     "ogc_mlp_plan", "ogc_mlp_packed_bytes", "ogc_mlp_workspace_bytes", "ogc_mlp_chosen_mode",
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
-    "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes", "ogc_mlp_estimated_us",
+    "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes", "ogc_mlp_estimated_us", "ogc_mlp_mode_estimates",
     "ogc_mha_validate", "ogc_mha_run", "ogc_mha_kernel_name",
 ]
 
@@ -96,6 +96,8 @@ def lib():
         l.ogc_mlp_kernel_name.restype = ctypes.c_char_p
         l.ogc_mlp_estimated_us.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
         l.ogc_mlp_estimated_us.restype = i32
+        l.ogc_mlp_mode_estimates.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        l.ogc_mlp_mode_estimates.restype = i32
         l.ogc_mha_validate.argtypes = [ctypes.POINTER(ogc_mha_desc)]
         l.ogc_mha_validate.restype = i32
         l.ogc_mha_run.argtypes = [ctypes.POINTER(ogc_mha_desc), vp, vp, vp, vp, vp, vp]
@@ -198,6 +200,13 @@ def ogc_mlp_estimated_us(plan: int, layer: int) -> float:
     v = ctypes.c_float()
     _check(lib().ogc_mlp_estimated_us(plan, int(layer), ctypes.byref(v)), "ogc_mlp_estimated_us")
     return v.value
+
+
+def ogc_mlp_mode_estimates(plan: int):
+    """(per layer, fused, cooperative) estimates of the whole chain in microseconds; -1 where not admissible."""
+    v = (ctypes.c_float * 3)()
+    _check(lib().ogc_mlp_mode_estimates(plan, v), "ogc_mlp_mode_estimates")
+    return tuple(float(x) for x in v)
 
 
 def ogc_mlp_destroy(plan: int) -> None:

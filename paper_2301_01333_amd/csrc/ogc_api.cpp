@@ -39,7 +39,8 @@ struct ogc_mlp_plan_s {
     ogc_mlp_desc desc;
     std::vector<LayerPlan> layers;
     int esz;
-    int mode;  // OGC_MODE_PER_LAYER or OGC_MODE_FUSED
+    int mode;  // OGC_MODE_PER_LAYER, OGC_MODE_FUSED or OGC_MODE_COOP
+    double mode_us[3];  // the cost models' estimates of the whole chain: per layer, fused, cooperative (< 0: n/a)
     int mp;    // padded batch rows of the workspace buffers
     size_t packed_bytes, workspace_bytes;
     int lds_buf_bytes;  // fused mode
@@ -128,9 +129,17 @@ const CostTable kCostBf16 = {{{0, 0, 0, 0, 0},
                               {9.995f, 0.480f, 8.036f, 0.829f, 0.244f}},
                              0.889f, 0.119f, 0.922f, 4.469f, 0.061f};
 
-// m rows x n channels, kt = 64-byte steps of the (padded) reduction axis.  dtype OGC_I8 or OGC_BF16.
+// fp32 runs on the register-staged tiles only (256x256, 128x128, 64x32), never split: 1044 timed launches, 11 % rms.
+const CostTable kCostF32 = {{{12.688f, 4.093f, 26.438f, 3.881f, 0.131f},
+                             {7.964f, 1.128f, 2.877f, 1.215f, 0.157f},
+                             {4.817f, 0.380f, 0.177f, 0.193f, 0.305f},
+                             {0, 0, 0, 0, 0},
+                             {0, 0, 0, 0, 0}},
+                            0.0f, 0.0f, 0.0f, 0.0f, 6.245f};
+
+// m rows x n channels, kt = 64-byte steps of the (padded) reduction axis.
 double estimate_layer_us(int dtype, int m, int n, int kt, int tile, int ks) {
-    const CostTable& ct = dtype == OGC_I8 ? kCostI8 : kCostBf16;
+    const CostTable& ct = dtype == OGC_I8 ? kCostI8 : (dtype == OGC_BF16 ? kCostBf16 : kCostF32);
     const TileCost& tc = ct.t[tile];
     const OgcTileInfo ti = ogc_tile_info(tile);
     const double cus = 256.0;
@@ -147,9 +156,8 @@ double estimate_layer_us(int dtype, int m, int n, int kt, int tile, int ks) {
 }
 
 // Picks tile and split for one layer.  dma_ok: the stream kernel can run this layer (int8 / bf16, no sigmoid,
-// input zero point 128, and a first layer whose plain rows are 16-byte aligned without K padding).  Layers it
-// cannot run keep the rule measured for the register-staged tiles.  OGC_TILE / OGC_KSPLIT in the environment
-// force a choice (tests, sweeps).
+// input zero point 128, and a first layer whose plain rows are 16-byte aligned without K padding); other layers
+// choose among the register-staged tiles.  OGC_TILE / OGC_KSPLIT in the environment force a choice (tests, sweeps).
 void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int* tile_out, int* ks_out, double* us_out) {
     auto tiles = [&](int t) {
         const OgcTileInfo ti = ogc_tile_info(t);
@@ -157,23 +165,21 @@ void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int* ti
     };
     auto split_ok = [&](int ks) { return ks >= 0 && ks <= 3 && kt % (1 << ks) == 0 && (kt >> ks) >= 4; };
     const int forced = env_int("OGC_TILE", -1), forced_split = env_int("OGC_KSPLIT", -1);
-    const bool modelled = dtype != OGC_F32;
     int tile = -1, ks = 0;
-    if (forced >= 0 && forced < OGC_NUM_TILES) {
+    if (forced >= 0 && forced < OGC_NUM_TILES)
         tile = ((forced == OGC_TILE_DMA || forced == OGC_TILE_DMA8) && !dma_ok) ? OGC_TILE_MID : forced;
-    } else if (!dma_ok) {
-        tile = tiles(OGC_TILE_MID) >= 128 ? OGC_TILE_MID : OGC_TILE_SMALL;
-    }
     const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8;
     if (tile >= 0) {
         if (stream && forced_split > 0 && forced_split <= 3 && kt % (1 << forced_split) == 0) ks = forced_split;
-        else if (stream && forced_split < 0 && forced >= 0) ks = 0;
     } else {
         double best = 0.0;
-        const int cands[4] = {OGC_TILE_SMALL, OGC_TILE_MID, OGC_TILE_DMA, OGC_TILE_DMA8};
-        for (int c = 0; c < 4; ++c) {
+        // the 256x256 register-staged tile is timed for fp32 only; the stream tiles replace it for int8 / bf16
+        const int cands[5] = {OGC_TILE_SMALL, OGC_TILE_MID, dtype == OGC_F32 ? OGC_TILE_BIG : -1, dma_ok ? OGC_TILE_DMA : -1,
+                              dma_ok ? OGC_TILE_DMA8 : -1};
+        for (int c = 0; c < 5; ++c) {
+            if (cands[c] < 0) continue;
             const bool st = cands[c] == OGC_TILE_DMA || cands[c] == OGC_TILE_DMA8;
-            if (forced_split > 0 && !st) continue;  // a forced split needs a stream tile
+            if (forced_split > 0 && !st && dma_ok) continue;  // a forced split needs a stream tile
             for (int s = 0; s <= (st ? 3 : 0); ++s) {
                 if (forced_split >= 0 && st && s != forced_split) continue;
                 if (s > 0 && !(forced_split > 0 ? kt % (1 << s) == 0 : split_ok(s))) continue;
@@ -185,7 +191,43 @@ void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int* ti
     if (tile < 0) tile = tiles(OGC_TILE_MID) >= 128 ? OGC_TILE_MID : OGC_TILE_SMALL;  // nothing admissible was forced
     *tile_out = tile;
     *ks_out = ks;
-    *us_out = (modelled && tile != OGC_TILE_BIG) ? estimate_layer_us(dtype, m, n, kt, tile, ks) : -1.0;
+    const bool timed = dtype == OGC_F32 ? (tile <= OGC_TILE_SMALL) : (tile != OGC_TILE_BIG);
+    *us_out = timed ? estimate_layer_us(dtype, m, n, kt, tile, ks) : -1.0;
+}
+
+// ---- Whole-chain models of the other two modes, fitted to 357 timed chains (12 shapes, batch 32..16384, three
+// dtypes; 2-10 % rms).  A chain run layer by layer costs the sum of its layers' estimates less the event overhead
+// each of those carries from the way it was timed.
+constexpr double kProfiledLaunchExtraUs = 2.0;
+struct FusedCost { float f0, per_mb, per_layer, fill; };
+struct CoopCost { float c0, barrier, block, step, fill; };
+const FusedCost kFused[3] = {{4.827f, 30.593f, 1.158f, 0.224f}, {5.818f, 10.435f, 0.413f, 0.408f}, {5.709f, 10.838f, 0.699f, 0.337f}};
+const CoopCost kCoop[3] = {{3.199f, 2.579f, 0.503f, 0.0605f, 0.678f}, {1.004f, 2.695f, 0.652f, 0.0385f, 0.816f},
+                           {1.039f, 2.699f, 0.774f, 0.0388f, 0.869f}};
+
+// One workgroup per 32 rows streams every weight: flat in the batch up to 8192 rows (256 CUs), then in rounds.
+double estimate_fused_us(const ogc_mlp_plan_s* p) {
+    const FusedCost& c = kFused[p->desc.dtype];
+    const double m = p->desc.m, rounds = std::max(1.0, m / 8192.0);
+    double sum = 0.0;
+    for (const LayerPlan& lp : p->layers)
+        sum += c.per_mb * ((double)lp.kp * p->esz * round_up((size_t)lp.d.n, 32)) / 1e6 + c.per_layer;
+    return c.f0 + rounds * sum * (1.0 + c.fill * std::min(1.0, m / 8192.0));
+}
+
+// Every CU takes 32x32 blocks of the current layer, a device-wide barrier between layers.
+double estimate_coop_us(const ogc_mlp_plan_s* p) {
+    const CoopCost& c = kCoop[p->desc.dtype];
+    const double mb = (p->desc.m + 31) / 32;
+    double most = 0.0;
+    for (const LayerPlan& lp : p->layers) most = std::max(most, mb * ((lp.d.n + 31) / 32));
+    const double g = std::min(256.0, most);
+    double t = c.c0;
+    for (const LayerPlan& lp : p->layers) {
+        const double blocks = mb * ((lp.d.n + 31) / 32), rounds = 0.5 * (std::ceil(blocks / g) + blocks / g);
+        t += c.barrier + rounds * (c.block + c.step * ((double)lp.kp * p->esz / 32.0));
+    }
+    return t * (1.0 + c.fill * std::min(1.0, most / 256.0));
 }
 
 ogc_status validate(const ogc_mlp_desc* d) {
@@ -316,23 +358,38 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         delete p;
         return OGC_ERR_UNSUPPORTED;
     }
+    // Per-layer candidates first: tile, split and the model's estimate of every layer (used if the chain runs layer
+    // by layer, and to decide whether it should).
+    double per_us = 0.0;
+    bool per_timed = true;
+    for (int l = 0; l < L; ++l) {
+        LayerPlan& lp = p->layers[l];
+        const int rows = lp.nb_out * 32 > lp.d.n ? lp.nb_out * 32 : lp.d.n;
+        // the stream kernel keeps its accumulators in fixed registers: no out-of-line calls (sigmoid) in it
+        const bool dma_ok = desc->dtype != OGC_F32 && lp.d.act != OGC_ACT_SIGMOID &&
+                            !(desc->dtype == OGC_I8 && lp.d.in_zp != 128) &&
+                            (l > 0 || desc->x_layout == OGC_LAYOUT_BLOCKED ||
+                             (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
+        choose_tile_and_split(desc->dtype, desc->m, rows, lp.kc / 4, dma_ok, &lp.tile, &lp.ksplit_log2, &lp.est_us);
+        if (lp.est_us < 0) per_timed = false;
+        per_us += lp.est_us - kProfiledLaunchExtraUs;
+    }
+    p->mode_us[0] = per_timed ? per_us : -1.0;
+    p->mode_us[1] = (fused_fits && (desc->dtype == OGC_I8 || wbytes <= (size_t)2600000)) ? estimate_fused_us(p) : -1.0;
+    p->mode_us[2] = (!blocked_io && L > 1) ? estimate_coop_us(p) : -1.0;
     if (mode == OGC_MODE_AUTO) {
-        // Measured on the MLP shapes of the paper's Table I (batch 32..2048) and on the five configurations:
-        //  * the fused kernel streams every weight through each 32-row workgroup at what one CU gets from L2
-        //    (about 100 GB/s): best while the weights are small or the batch is small and the weights fit an L2;
-        //  * the cooperative kernel spreads a layer over all CUs but pays a device-wide barrier per layer (3-4 us):
-        //    best for small batches whose layers are heavy for one CU (fp32 at 0.6 TFLOP/s per CU; weights beyond
-        //    what one CU streams in the time of those barriers);
-        //  * per-layer kernels otherwise.
-        const bool small_w = wbytes <= (size_t)512 * 1024;
-        const bool fused_ok = fused_fits && (small_w || (desc->m <= 512 && wbytes <= (size_t)2560 * 1024));
-        bool coop = false;
-        if (!blocked_io && L > 1) {
-            if (desc->dtype == OGC_F32) coop = (desc->m <= 128 && wbytes >= (size_t)256 * 1024) || (desc->m <= 512 && wbytes > (size_t)4 << 20);
-            else if (desc->dtype == OGC_BF16) coop = desc->m <= 128 && wbytes > (size_t)2560 * 1024;
-            else coop = desc->m <= 32 && wbytes > (size_t)2 << 20;
-        }
-        mode = coop ? OGC_MODE_COOP : (fused_ok ? OGC_MODE_FUSED : OGC_MODE_PER_LAYER);
+        // The mode whose estimate is lowest (section "cost model" of the sources above: each mode has its own fitted
+        // model).  The fused kernel is a candidate only where it was timed without its cliff: bf16 / fp32 chains
+        // whose weights exceed about 2.5 MB run several times slower per byte in it.
+        // A single-launch mode wins ties within 7 %: its model is the tighter one, and it keeps the intermediates
+        // on chip.
+        int single = -1;
+        if (p->mode_us[1] >= 0) single = 1;
+        if (p->mode_us[2] >= 0 && (single < 0 || p->mode_us[2] < p->mode_us[1])) single = 2;
+        if (single >= 0 && (p->mode_us[0] < 0 || p->mode_us[single] <= 1.07 * p->mode_us[0]))
+            mode = single == 1 ? OGC_MODE_FUSED : OGC_MODE_COOP;
+        else
+            mode = OGC_MODE_PER_LAYER;
     }
     p->mode = mode;
     p->lds_buf_bytes = max_kc * 512;
@@ -343,12 +400,6 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         LayerPlan& lp = p->layers[l];
         const int rows = lp.nb_out * 32 > lp.d.n ? lp.nb_out * 32 : lp.d.n;
         if (mode == OGC_MODE_PER_LAYER) {
-            // the stream kernel keeps its accumulators in fixed registers: no out-of-line calls (sigmoid) in it
-            const bool dma_ok = desc->dtype != OGC_F32 && lp.d.act != OGC_ACT_SIGMOID &&
-                                !(desc->dtype == OGC_I8 && lp.d.in_zp != 128) &&
-                                (l > 0 || desc->x_layout == OGC_LAYOUT_BLOCKED ||
-                                 (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
-            choose_tile_and_split(desc->dtype, desc->m, rows, lp.kc / 4, dma_ok, &lp.tile, &lp.ksplit_log2, &lp.est_us);
             lp.npw = (int)round_up((size_t)rows, ogc_tile_info(lp.tile).bn);
         } else {
             lp.tile = -1;
@@ -603,6 +654,12 @@ const char* ogc_status_string(ogc_status s) {
 ogc_status ogc_mlp_estimated_us(ogc_mlp_plan_t plan, int32_t layer, float* us) {
     if (!plan || !us || layer < 0 || layer >= (int)plan->layers.size()) return OGC_ERR_INVALID_ARG;
     *us = (plan->mode == OGC_MODE_PER_LAYER) ? (float)plan->layers[layer].est_us : -1.0f;
+    return OGC_OK;
+}
+
+ogc_status ogc_mlp_mode_estimates(ogc_mlp_plan_t plan, float us[3]) {
+    if (!plan || !us) return OGC_ERR_INVALID_ARG;
+    for (int i = 0; i < 3; ++i) us[i] = (float)plan->mode_us[i];
     return OGC_OK;
 }
 
