@@ -102,10 +102,13 @@ typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
  * barrier between layers.  It needs the workspace and keeps two counters in the packed blob, so runs that share
  * a packed blob must not overlap in time; all its workgroups must be resident at once (the grid is at most one
  * per CU), so it is meant for a device that is not kept busy by other kernels for seconds: its barrier wait is
- * bounded and a timeout yields wrong data, not a hang.  OGC_MODE_AUTO picks it for small batches with heavy layers.
+ * bounded and a timeout yields wrong data, not a hang.
+ * OGC_MODE_AUTO takes the mode with the lowest estimate of three fitted cost models (ogc_mlp_mode_estimates); a
+ * single-launch mode wins ties within 7 %.  In per-layer mode each layer's tile and k-split are the candidate with
+ * the lowest estimate (ogc_mlp_estimated_us): the scoring heuristic of Section III, no tuning run.
  * OGC_ERR_UNSUPPORTED: OGC_MODE_FUSED requested but a layer is too wide for the LDS activation tile; a blocked
  * x or y with a mode other than per-layer.
- * For tests, two environment variables read here override the heuristic in per-layer mode: OGC_TILE (0..4:
+ * For tests, two environment variables read here override the cost model in per-layer mode: OGC_TILE (0..4:
  * tile configuration of every layer) and OGC_KSPLIT (log2 of the number of k ranges, 0..3). */
 ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc /*host*/, ogc_mlp_plan_t* out_plan /*host*/);
 
