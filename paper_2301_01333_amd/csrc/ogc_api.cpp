@@ -201,9 +201,9 @@ void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int* ti
 constexpr double kProfiledLaunchExtraUs = 2.0;
 struct FusedCost { float f0, per_mb, per_layer, fill; };
 struct CoopCost { float c0, barrier, block, step, fill; };
-const FusedCost kFused[3] = {{4.827f, 30.593f, 1.158f, 0.224f}, {5.818f, 10.435f, 0.413f, 0.408f}, {5.709f, 10.838f, 0.699f, 0.337f}};
-const CoopCost kCoop[3] = {{3.199f, 2.579f, 0.503f, 0.0605f, 0.678f}, {1.004f, 2.695f, 0.652f, 0.0385f, 0.816f},
-                           {1.039f, 2.699f, 0.774f, 0.0388f, 0.869f}};
+const FusedCost kFused[3] = {{4.706f, 30.663f, 1.174f, 0.225f}, {6.228f, 10.346f, 0.328f, 0.433f}, {5.824f, 10.761f, 0.669f, 0.357f}};
+const CoopCost kCoop[3] = {{2.837f, 2.769f, 0.725f, 0.0399f, 0.767f}, {0.951f, 2.838f, 0.949f, 0.0211f, 0.871f},
+                           {0.610f, 2.891f, 0.956f, 0.0215f, 0.859f}};
 
 // One workgroup per 32 rows streams every weight: flat in the batch up to 8192 rows (256 CUs), then in rounds.
 double estimate_fused_us(const ogc_mlp_plan_s* p) {
