@@ -18,6 +18,7 @@
 #include <math.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "ogc_mha.h"
@@ -38,7 +39,7 @@ struct MhaArgs {
     uint8_t* o;
     long long sq[3], sk[3], sv[3], so[3];  // element strides: batch, head, token
     int batch, heads, seq;
-    int q_tiles;       // ceil(seq / 128)
+    int q_tiles;       // ceil(seq / queries per workgroup)
     int xcd_order;     // 1: workgroups of one (batch, head) are placed on one XCD
     float scale_log2;  // scale * log2(e)
 };
@@ -71,7 +72,9 @@ template <> struct MhaCfg<OGC_F32> {
 
 // DT: OGC_F32 / OGC_BF16.  D32 = head_dim / 32.  FAST: softmax without the running maximum.  PLAIN: no mask, the
 // sequence is a whole number of key blocks and the scalar is positive, so no key needs an addend.
-template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256, 2) void ogc_mha_kernel(MhaArgs a) {
+// QS: 32-query groups per wavefront (1 or 2).  With 2, every key / value operand read from LDS feeds two matrix
+// instructions (one per group): the bf16 kernel is bound by LDS reads, one KiB per instruction, otherwise.
+template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_bounds__(256, 2) void ogc_mha_kernel(MhaArgs a) {
     constexpr int E = MhaCfg<DT>::E, KB = MhaCfg<DT>::KB, D = D32 * 32;
     constexpr int SB = KB / 32;                 // 32-key sub-blocks per block
     constexpr int KSTR = D * E + 16;            // bytes per key row of K in LDS (padded)
@@ -98,20 +101,25 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
     const long long kss = a.sk[2] * E, vss = a.sv[2] * E;
 
     // ---- this lane's query row as the second MFMA operand, resident for the whole kernel
-    const int query = qt * 128 + wave * 32 + col;
-    const int qrow = query < S ? query : S - 1;
-    const uint8_t* qp = a.q + (b * a.sq[0] + hd * a.sq[1] + qrow * a.sq[2]) * E;
     constexpr int QN = DT == OGC_BF16 ? D / 16 : D / 8;
-    v4i qreg[QN];
+    int query[QS];
+    v4i qreg[QS][QN];
+    v16f oacc[QS][D32];
+    float run_max[QS], run_sum[QS];  // run_sum: this lane's keys only, halves are added at the end
 #pragma unroll
-    for (int i = 0; i < QN; ++i) qreg[i] = *(const v4i*)(qp + i * 32 + h * 16);
-
-    v16f oacc[D32];
+    for (int qs = 0; qs < QS; ++qs) {
+        query[qs] = (qt * 4 + wave) * (32 * QS) + qs * 32 + col;
+        const int qrow = query[qs] < S ? query[qs] : S - 1;
+        const uint8_t* qp = a.q + (b * a.sq[0] + hd * a.sq[1] + qrow * a.sq[2]) * E;
 #pragma unroll
-    for (int d = 0; d < D32; ++d)
+        for (int i = 0; i < QN; ++i) qreg[qs][i] = *(const v4i*)(qp + i * 32 + h * 16);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[d][r] = 0.0f;
-    float run_max = -INFINITY, run_sum = 0.0f;  // run_sum: this lane's keys only, halves are added at the end
+        for (int d = 0; d < D32; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[qs][d][r] = 0.0f;
+        run_max[qs] = -INFINITY;
+        run_sum[qs] = 0.0f;
+    }
 
     // ---- prefetch registers for one block of keys / values / mask
     v4i kreg[D32], vreg[VU][DT == OGC_BF16 ? 2 : 1];
@@ -185,7 +193,7 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
         if (kb + 1 < nkb) prefetch((kb + 1) * KB);
 
         // ---- scores, transposed: rows = keys, columns = queries
-        v16f sacc[SB];
+        v16f sacc[QS][SB];
 #pragma unroll
         for (int sb = 0; sb < SB; ++sb) {
             const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
@@ -193,15 +201,18 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
 #pragma unroll
             for (int i = 0; i < QN; ++i) {
                 const v4i kv = *(const v4i*)(krow + i * 32);
-                if constexpr (DT == OGC_BF16) {
-                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, kv),
-                                                                       __builtin_bit_cast(v8bf, qreg[i]), i ? sacc[sb] : zero, 0, 0, 0);
-                } else {
-                    const v4f kf = __builtin_bit_cast(v4f, kv), qf = __builtin_bit_cast(v4f, qreg[i]);
-                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, qf.x, i ? sacc[sb] : zero, 0, 0, 0);
-                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, qf.y, sacc[sb], 0, 0, 0);
-                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, qf.z, sacc[sb], 0, 0, 0);
-                    sacc[sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, qf.w, sacc[sb], 0, 0, 0);
+#pragma unroll
+                for (int qs = 0; qs < QS; ++qs) {
+                    if constexpr (DT == OGC_BF16) {
+                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(v8bf, kv), __builtin_bit_cast(v8bf, qreg[qs][i]), i ? sacc[qs][sb] : zero, 0, 0, 0);
+                    } else {
+                        const v4f kf = __builtin_bit_cast(v4f, kv), qf = __builtin_bit_cast(v4f, qreg[qs][i]);
+                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, qf.x, i ? sacc[qs][sb] : zero, 0, 0, 0);
+                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, qf.y, sacc[qs][sb], 0, 0, 0);
+                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, qf.z, sacc[qs][sb], 0, 0, 0);
+                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, qf.w, sacc[qs][sb], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -209,14 +220,15 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
         // -infinity).  A block of valid keys without a mask needs no per-key addend: the maximum is taken on
         // the raw products and the scalar rides in the exponent's multiply-add.
         const float c = a.scale_log2;
-        {
+#pragma unroll
+        for (int qs = 0; qs < QS; ++qs) {
             float cand = -INFINITY;
             if constexpr (PLAIN) {
                 if constexpr (!FAST) {
 #pragma unroll
                     for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) cand = fmaxf(cand, sacc[sb][r]);
+                        for (int r = 0; r < 16; ++r) cand = fmaxf(cand, sacc[qs][sb][r]);
                     cand *= c;
                 }
             } else {
@@ -227,8 +239,8 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
                         const v4f mk = *(const v4f*)(m_lds + sb * 32 + 8 * g + 4 * h);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const float t = __builtin_fmaf(sacc[sb][4 * g + e], c, mk[e]);
-                            sacc[sb][4 * g + e] = t;
+                            const float t = __builtin_fmaf(sacc[qs][sb][4 * g + e], c, mk[e]);
+                            sacc[qs][sb][4 * g + e] = t;
                             if constexpr (!FAST) cand = fmaxf(cand, t);
                         }
                     }
@@ -240,27 +252,27 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
                 // result is the same function (numerator and denominator carry the same factor); weights reach
                 // 256 at most, far from any overflow.  Key 0 of block 0 is always valid: the first block sets it.
                 cand = fmaxf(cand, other_half(cand));
-                const bool need = cand > run_max + 8.0f;
+                const bool need = cand > run_max[qs] + 8.0f;
                 if (__builtin_amdgcn_ballot_w64(need) != 0) {
-                    const float new_max = need ? cand : run_max;
-                    const float alpha = __builtin_amdgcn_exp2f(run_max - new_max);
-                    run_max = new_max;
-                    run_sum *= alpha;
+                    const float new_max = need ? cand : run_max[qs];
+                    const float alpha = __builtin_amdgcn_exp2f(run_max[qs] - new_max);
+                    run_max[qs] = new_max;
+                    run_sum[qs] *= alpha;
 #pragma unroll
                     for (int d = 0; d < D32; ++d)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
+                        for (int r = 0; r < 16; ++r) oacc[qs][d][r] *= alpha;
                 }
-                off = -run_max;
+                off = -run_max[qs];
             }
 #pragma unroll
             for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float x;
-                    if constexpr (PLAIN) x = __builtin_fmaf(sacc[sb][r], c, off);
-                    else x = FAST ? sacc[sb][r] : sacc[sb][r] + off;
-                    sacc[sb][r] = __builtin_amdgcn_exp2f(x);
+                    if constexpr (PLAIN) x = __builtin_fmaf(sacc[qs][sb][r], c, off);
+                    else x = FAST ? sacc[qs][sb][r] : sacc[qs][sb][r] + off;
+                    sacc[qs][sb][r] = __builtin_amdgcn_exp2f(x);
                 }
         }
         // ---- O^T += V^T P^T
@@ -269,58 +281,71 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
             for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const v16f& p = sacc[sb];
                     // the row sum takes the weights as rounded, the values the second product multiplies
-                    uint32_t w[4];
+                    v4i pw[QS];
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const v2bf pr = {(__bf16)p[8 * j + 2 * t], (__bf16)p[8 * j + 2 * t + 1]};
-                        run_sum = __builtin_amdgcn_fdot2_f32_bf16(pr, (v2bf){(__bf16)1.0f, (__bf16)1.0f}, run_sum, false);
-                        w[t] = __builtin_bit_cast(uint32_t, pr);
+                    for (int qs = 0; qs < QS; ++qs) {
+                        const v16f& p = sacc[qs][sb];
+                        uint32_t w[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const v2bf pr = {(__bf16)p[8 * j + 2 * t], (__bf16)p[8 * j + 2 * t + 1]};
+                            run_sum[qs] = __builtin_amdgcn_fdot2_f32_bf16(pr, (v2bf){(__bf16)1.0f, (__bf16)1.0f}, run_sum[qs], false);
+                            w[t] = __builtin_bit_cast(uint32_t, pr);
+                        }
+                        pw[qs] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
                     }
-                    const v4i pw = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
 #pragma unroll
                     for (int d = 0; d < D32; ++d) {
                         const v4i vv = *(const v4i*)(vt_lds + (d * 32 + col) * VSTR + (sb * 32 + 16 * j + 8 * h) * 2);
-                        oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vv),
-                                                                          __builtin_bit_cast(v8bf, pw), oacc[d], 0, 0, 0);
+#pragma unroll
+                        for (int qs = 0; qs < QS; ++qs)
+                            oacc[qs][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vv),
+                                                                                  __builtin_bit_cast(v8bf, pw[qs]), oacc[qs][d], 0, 0, 0);
                     }
                 }
         } else {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) run_sum += sacc[0][r];
+            for (int r = 0; r < 16; ++r)
+#pragma unroll
+                for (int qs = 0; qs < QS; ++qs) run_sum[qs] += sacc[qs][0][r];
 #pragma unroll
             for (int g = 0; g < 4; ++g)
 #pragma unroll
                 for (int d = 0; d < D32; ++d) {
                     const v4f vv = *(const v4f*)(vt_lds + (d * 32 + col) * VSTR + (8 * g + 4 * h) * 4);
-                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.x, sacc[0][4 * g], oacc[d], 0, 0, 0);
-                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.y, sacc[0][4 * g + 1], oacc[d], 0, 0, 0);
-                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.z, sacc[0][4 * g + 2], oacc[d], 0, 0, 0);
-                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.w, sacc[0][4 * g + 3], oacc[d], 0, 0, 0);
+#pragma unroll
+                    for (int qs = 0; qs < QS; ++qs) {
+                        oacc[qs][d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.x, sacc[qs][0][4 * g], oacc[qs][d], 0, 0, 0);
+                        oacc[qs][d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.y, sacc[qs][0][4 * g + 1], oacc[qs][d], 0, 0, 0);
+                        oacc[qs][d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.z, sacc[qs][0][4 * g + 2], oacc[qs][d], 0, 0, 0);
+                        oacc[qs][d] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv.w, sacc[qs][0][4 * g + 3], oacc[qs][d], 0, 0, 0);
+                    }
                 }
         }
     }
 
     // ---- normalise and store: after the half exchange a lane holds 16 consecutive channels of its query
-    const float total = run_sum + other_half(run_sum);
+#pragma unroll
+    for (int qs = 0; qs < QS; ++qs) {
+    const float total = run_sum[qs] + other_half(run_sum[qs]);
     const float inv = 1.0f / total;
-    uint8_t* op = a.o + (b * a.so[0] + hd * a.so[1] + (long long)query * a.so[2]) * E;
+    uint8_t* op = a.o + (b * a.so[0] + hd * a.so[1] + (long long)query[qs] * a.so[2]) * E;
 #pragma unroll
     for (int d = 0; d < D32; ++d) {
         if constexpr (DT == OGC_BF16) {
             uint32_t dw[4][2];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                dw[g][0] = pack_bf16(oacc[d][4 * g] * inv, oacc[d][4 * g + 1] * inv);
-                dw[g][1] = pack_bf16(oacc[d][4 * g + 2] * inv, oacc[d][4 * g + 3] * inv);
+                dw[g][0] = pack_bf16(oacc[qs][d][4 * g] * inv, oacc[qs][d][4 * g + 1] * inv);
+                dw[g][1] = pack_bf16(oacc[qs][d][4 * g + 2] * inv, oacc[qs][d][4 * g + 3] * inv);
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 swap32(dw[0][j], dw[2][j]);
                 swap32(dw[1][j], dw[3][j]);
             }
-            if (query < S) {
+            if (query[qs] < S) {
                 uint8_t* dst = op + (d * 32 + 16 * h) * 2;
                 *(v4i*)dst = (v4i){(int)dw[0][0], (int)dw[0][1], (int)dw[2][0], (int)dw[2][1]};
                 *(v4i*)(dst + 16) = (v4i){(int)dw[1][0], (int)dw[1][1], (int)dw[3][0], (int)dw[3][1]};
@@ -330,13 +355,13 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
 #pragma unroll
             for (int g = 0; g < 4; ++g)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) dw[g][e] = __builtin_bit_cast(uint32_t, oacc[d][4 * g + e] * inv);
+                for (int e = 0; e < 4; ++e) dw[g][e] = __builtin_bit_cast(uint32_t, oacc[qs][d][4 * g + e] * inv);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 swap32(dw[0][e], dw[2][e]);
                 swap32(dw[1][e], dw[3][e]);
             }
-            if (query < S) {
+            if (query[qs] < S) {
                 uint8_t* dst = op + (d * 32 + 16 * h) * 4;
                 const int order[4] = {0, 2, 1, 3};
 #pragma unroll
@@ -345,24 +370,37 @@ template <int DT, int D32, int FAST, int PLAIN> __global__ __launch_bounds__(256
             }
         }
     }
+    }
 }
 
 namespace {
 
-template <int DT, int D32> hipError_t launch_fast(int fast, int plain, const MhaArgs& a, dim3 grid, hipStream_t st) {
-    if (fast && plain) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1, 1>), grid, dim3(256), 0, st, a);
-    else if (fast) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1, 0>), grid, dim3(256), 0, st, a);
-    else if (plain) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 0, 1>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 0, 0>), grid, dim3(256), 0, st, a);
+template <int DT, int D32, int QS> hipError_t launch_fast(int fast, int plain, const MhaArgs& a, dim3 grid, hipStream_t st) {
+    if (fast && plain) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1, 1, QS>), grid, dim3(256), 0, st, a);
+    else if (fast) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 1, 0, QS>), grid, dim3(256), 0, st, a);
+    else if (plain) hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 0, 1, QS>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((ogc_mha_kernel<DT, D32, 0, 0, QS>), grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
-template <int DT> hipError_t launch_dim(int d32, int fast, int plain, const MhaArgs& a, dim3 grid, hipStream_t st) {
-    switch (d32) {
-    case 1: return launch_fast<DT, 1>(fast, plain, a, grid, st);
-    case 2: return launch_fast<DT, 2>(fast, plain, a, grid, st);
-    case 3: return launch_fast<DT, 3>(fast, plain, a, grid, st);
-    default: return launch_fast<DT, 4>(fast, plain, a, grid, st);
+template <int DT> hipError_t launch_dim(int d32, int qs, int fast, int plain, const MhaArgs& a, dim3 grid, hipStream_t st) {
+    if (qs == 2) {  // bf16 with head_dim <= 64 only (query_groups)
+        if constexpr (DT == OGC_BF16) return d32 == 1 ? launch_fast<DT, 1, 2>(fast, plain, a, grid, st) : launch_fast<DT, 2, 2>(fast, plain, a, grid, st);
     }
+    switch (d32) {
+    case 1: return launch_fast<DT, 1, 1>(fast, plain, a, grid, st);
+    case 2: return launch_fast<DT, 2, 1>(fast, plain, a, grid, st);
+    case 3: return launch_fast<DT, 3, 1>(fast, plain, a, grid, st);
+    default: return launch_fast<DT, 4, 1>(fast, plain, a, grid, st);
+    }
+}
+
+// 32-query groups per wavefront.  Two where the registers allow it (bf16, head_dim <= 64) and the sequence is long
+// enough to keep the four wavefronts of a workgroup busy: the bf16 kernel is then no longer bound by LDS reads.
+int query_groups(const ogc_mha_desc* d) {
+    const char* e = getenv("OGC_MHA_QS");
+    const bool can = d->dtype == OGC_BF16 && d->head_dim <= 64;
+    if (e && *e) return (atoi(e) == 2 && can) ? 2 : 1;
+    return (can && d->seq >= 256) ? 2 : 1;
 }
 
 // no mask, whole key blocks only, positive scalar
@@ -418,23 +456,24 @@ ogc_status ogc_mha_run(const ogc_mha_desc* d, const void* q, const void* k, cons
     a.batch = d->batch;
     a.heads = d->heads;
     a.seq = d->seq;
-    a.q_tiles = (d->seq + 127) / 128;
+    const int qs = query_groups(d);
+    a.q_tiles = (d->seq + 128 * qs - 1) / (128 * qs);
     const int bh = d->batch * d->heads;
     a.xcd_order = (bh % 8 == 0) ? 1 : 0;
     a.scale_log2 = d->scale * 1.44269504088896340736f;
     const dim3 grid((unsigned)(bh * a.q_tiles));
     const int plain = plain_case(d, mask);
-    const hipError_t e = d->dtype == OGC_F32 ? launch_dim<OGC_F32>(d->head_dim / 32, d->softmax, plain, a, grid, (hipStream_t)stream)
-                                             : launch_dim<OGC_BF16>(d->head_dim / 32, d->softmax, plain, a, grid, (hipStream_t)stream);
+    const hipError_t e = d->dtype == OGC_F32 ? launch_dim<OGC_F32>(d->head_dim / 32, qs, d->softmax, plain, a, grid, (hipStream_t)stream)
+                                             : launch_dim<OGC_BF16>(d->head_dim / 32, qs, d->softmax, plain, a, grid, (hipStream_t)stream);
     return e == hipSuccess ? OGC_OK : OGC_ERR_DEVICE;
 }
 
 const char* ogc_mha_kernel_name(const ogc_mha_desc* d, int32_t has_mask) {
     if (ogc_mha_validate(d) != OGC_OK) return nullptr;
-    static char names[2][4][2][2][40];
-    const int plain = plain_case(d, has_mask ? (const float*)d : nullptr);
-    char* s = names[d->dtype == OGC_BF16][d->head_dim / 32 - 1][d->softmax][plain];
-    if (!s[0]) snprintf(s, 40, "ogc_mha_kernel<%d, %d, %d, %d>", d->dtype, d->head_dim / 32, d->softmax, plain);
+    static char names[2][4][2][2][2][48];
+    const int plain = plain_case(d, has_mask ? (const float*)d : nullptr), qs = query_groups(d);
+    char* s = names[d->dtype == OGC_BF16][d->head_dim / 32 - 1][d->softmax][plain][qs - 1];
+    if (!s[0]) snprintf(s, 48, "ogc_mha_kernel<%d, %d, %d, %d, %d>", d->dtype, d->head_dim / 32, d->softmax, plain, qs);
     return s;
 }
 

@@ -87,6 +87,11 @@ def test_table1_full_batch_sampled(oracle_mod, dtype):
     check(oracle_mod, wl, FAST, batches=[7])
 
 
+def test_roofline_workload_sampled(oracle_mod):
+    """MHA-4 fp32 at batch 128, the launch the benchmark's attention roofline is quoted on: two batch entries."""
+    check(oracle_mod, synth.make_mha_table1("MHA-4", "f32", 128), batches=[5, 127])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_workgroup_order_without_multiple_of_eight(oracle_mod, dtype):
     wl = synth.make_mha(dtype, 3, 300, 5 * 64, 5, 4501, name="15 (batch, head) pairs")

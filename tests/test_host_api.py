@@ -281,13 +281,16 @@ def test_mha_validate(kw, status):
 
 def test_mha_kernel_names_and_null_checks():
     d = b.mha_desc(b.OGC_BF16, 2, 8, 128, 96, 0.1, b.OGC_SOFTMAX_FAST)
-    assert b.ogc_mha_kernel_name(d) == "ogc_mha_kernel<1, 3, 1, 0>"
-    assert b.ogc_mha_kernel_name(d, has_mask=False) == "ogc_mha_kernel<1, 3, 1, 1>"
-    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_F32, 2, 8, 128, 64, 0.1)) == "ogc_mha_kernel<0, 2, 0, 0>"
+    assert b.ogc_mha_kernel_name(d) == "ogc_mha_kernel<1, 3, 1, 0, 1>"
+    assert b.ogc_mha_kernel_name(d, has_mask=False) == "ogc_mha_kernel<1, 3, 1, 1, 1>"
+    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_F32, 2, 8, 128, 64, 0.1)) == "ogc_mha_kernel<0, 2, 0, 0, 1>"
     # the variant without per-key addends needs whole key blocks (bf16: 64 keys) and a positive scale
-    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_BF16, 2, 8, 96, 64, 0.1), False) == "ogc_mha_kernel<1, 2, 0, 0>"
-    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_F32, 2, 8, 96, 64, 0.1), False) == "ogc_mha_kernel<0, 2, 0, 1>"
-    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_F32, 2, 8, 96, 64, -0.1), False) == "ogc_mha_kernel<0, 2, 0, 0>"
+    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_BF16, 2, 8, 96, 64, 0.1), False) == "ogc_mha_kernel<1, 2, 0, 0, 1>"
+    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_F32, 2, 8, 96, 64, 0.1), False) == "ogc_mha_kernel<0, 2, 0, 1, 1>"
+    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_F32, 2, 8, 96, 64, -0.1), False) == "ogc_mha_kernel<0, 2, 0, 0, 1>"
+    # bf16 with head_dim <= 64 and a sequence of 256 or more: two 32-query groups per wavefront
+    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_BF16, 2, 8, 512, 64, 0.1)) == "ogc_mha_kernel<1, 2, 0, 0, 2>"
+    assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_BF16, 2, 8, 512, 128, 0.1)) == "ogc_mha_kernel<1, 4, 0, 0, 1>"
     assert b.ogc_mha_kernel_name(b.mha_desc(b.OGC_F32, 2, 8, 128, 70, 0.1)) == ""
     assert b.lib().ogc_mha_validate(None) == -1
     # argument checks come before any device call: NULL tensors and misaligned bases are refused on the host
