@@ -80,7 +80,9 @@ template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_boun
     constexpr int KSTR = D * E + 16;            // bytes per key row of K in LDS (padded)
     constexpr int VSTR = KB * E + 16;           // bytes per channel row of V^T in LDS (padded)
     constexpr int CH = D * E / 16;              // 16-byte chunks per token row
-    constexpr int VU = DT == OGC_BF16 ? (D32 + 1) / 2 : D32;  // V units per thread (bf16: a unit is two keys)
+    constexpr int KU = KB * CH / 256;                          // 16-byte chunks of K per thread
+    constexpr int KP = KB / 2;                                 // bf16: key pairs per block
+    constexpr int VU = DT == OGC_BF16 ? (KP * CH + 255) / 256 : D32;  // V units per thread (bf16: a unit is two keys)
     __shared__ __attribute__((aligned(16))) uint8_t k_lds[KB * KSTR];
     __shared__ __attribute__((aligned(16))) uint8_t vt_lds[D * VSTR];
     __shared__ __attribute__((aligned(16))) float m_lds[KB];
@@ -122,20 +124,20 @@ template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_boun
     }
 
     // ---- prefetch registers for one block of keys / values / mask
-    v4i kreg[D32], vreg[VU][DT == OGC_BF16 ? 2 : 1];
+    v4i kreg[KU], vreg[VU][DT == OGC_BF16 ? 2 : 1];
     float mreg = 0.0f;
     auto prefetch = [&](int key0) {
         const bool full = key0 + KB <= S;  // uniform: every key of the block exists, no row needs a zero fill
 #pragma unroll
-        for (int i = 0; i < D32; ++i) {
+        for (int i = 0; i < KU; ++i) {
             const int u = tid + 256 * i, key = key0 + u / CH, part = u % CH;
             kreg[i] = (full || key < S) ? *(const v4i*)(kbase + key * kss + part * 16) : (v4i){0, 0, 0, 0};
         }
         if constexpr (DT == OGC_BF16) {
 #pragma unroll
             for (int i = 0; i < VU; ++i) {
-                const int u = tid + 256 * i, kp = u & 31, c = u >> 5, key = key0 + 2 * kp;
-                const bool on = (32 * CH) % 256 == 0 || 256 * (i + 1) <= 32 * CH || c < CH;
+                const int u = tid + 256 * i, kp = u % KP, c = u / KP, key = key0 + 2 * kp;
+                const bool on = (KP * CH) % 256 == 0 || 256 * (i + 1) <= KP * CH || c < CH;
                 vreg[i][0] = (on && (full || key < S)) ? *(const v4i*)(vbase + key * vss + c * 16) : (v4i){0, 0, 0, 0};
                 vreg[i][1] = (on && (full || key + 1 < S)) ? *(const v4i*)(vbase + (key + 1) * vss + c * 16) : (v4i){0, 0, 0, 0};
             }
@@ -153,7 +155,7 @@ template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_boun
     };
     auto fill_lds = [&]() {
 #pragma unroll
-        for (int i = 0; i < D32; ++i) {
+        for (int i = 0; i < KU; ++i) {
             const int u = tid + 256 * i;
             *(v4i*)(k_lds + (u / CH) * KSTR + (u % CH) * 16) = kreg[i];
         }
@@ -162,7 +164,7 @@ template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_boun
             // within a group of 16 keys, key offset 8*gg + 4*hh + e sits at 8*hh + 4*gg + e
 #pragma unroll
             for (int i = 0; i < VU; ++i) {
-                const int u = tid + 256 * i, kp = u & 31, c = u >> 5, o = (2 * kp) & 15;
+                const int u = tid + 256 * i, kp = u % KP, c = u / KP, o = (2 * kp) & 15;
                 const int pos = ((2 * kp) & ~15) + ((o & 3) | ((o & 8) >> 1) | ((o & 4) << 1));
                 if (c < CH) {
 #pragma unroll
@@ -194,26 +196,35 @@ template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_boun
 
         // ---- scores, transposed: rows = keys, columns = queries
         v16f sacc[QS][SB];
-#pragma unroll
-        for (int sb = 0; sb < SB; ++sb) {
+        {
+            // bf16: the operand reads of a 32-key group go out before its first matrix instruction (the compiler
+            // would otherwise issue each read just ahead of its use and wait for it)
             const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-            const uint8_t* krow = k_lds + (sb * 32 + col) * KSTR + h * 16;
 #pragma unroll
-            for (int i = 0; i < QN; ++i) {
-                const v4i kv = *(const v4i*)(krow + i * 32);
+            for (int sb = 0; sb < SB; ++sb) {
+                const uint8_t* krow = k_lds + (sb * 32 + col) * KSTR + h * 16;
+                v4i kfrag[QN];
+                if constexpr (DT == OGC_BF16) {
 #pragma unroll
-                for (int qs = 0; qs < QS; ++qs) {
-                    if constexpr (DT == OGC_BF16) {
-                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(v8bf, kv), __builtin_bit_cast(v8bf, qreg[qs][i]), i ? sacc[qs][sb] : zero, 0, 0, 0);
-                    } else {
-                        const v4f kf = __builtin_bit_cast(v4f, kv), qf = __builtin_bit_cast(v4f, qreg[qs][i]);
-                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, qf.x, i ? sacc[qs][sb] : zero, 0, 0, 0);
-                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, qf.y, sacc[qs][sb], 0, 0, 0);
-                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, qf.z, sacc[qs][sb], 0, 0, 0);
-                        sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, qf.w, sacc[qs][sb], 0, 0, 0);
-                    }
+                    for (int i = 0; i < QN; ++i) kfrag[i] = *(const v4i*)(krow + i * 32);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+#pragma unroll
+                for (int i = 0; i < QN; ++i)
+#pragma unroll
+                    for (int qs = 0; qs < QS; ++qs) {
+                        const v4i kv = DT == OGC_BF16 ? kfrag[i] : *(const v4i*)(krow + i * 32);
+                        if constexpr (DT == OGC_BF16) {
+                            sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(v8bf, kv), __builtin_bit_cast(v8bf, qreg[qs][i]), i ? sacc[qs][sb] : zero, 0, 0, 0);
+                        } else {
+                            const v4f kf = __builtin_bit_cast(v4f, kv), qf = __builtin_bit_cast(v4f, qreg[qs][i]);
+                            sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, qf.x, i ? sacc[qs][sb] : zero, 0, 0, 0);
+                            sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, qf.y, sacc[qs][sb], 0, 0, 0);
+                            sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, qf.z, sacc[qs][sb], 0, 0, 0);
+                            sacc[qs][sb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, qf.w, sacc[qs][sb], 0, 0, 0);
+                        }
+                    }
             }
         }
         // ---- scalar, mask, running maximum (base-2 logarithm domain; a key beyond the sequence carries
