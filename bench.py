@@ -51,6 +51,30 @@ def time_steps(dev, steps, warmup):
     return wall, e0.elapsed_time(e1) * 1e-3 / steps
 
 
+def time_graph_replay(dev, runs_per_graph=50, replays=6):
+    """The same runs recorded once into a HIP graph (stream capture of `runs_per_graph` calls) and replayed: what a
+    caller whose loop is bound by the launch path of the host gets.  Returns seconds per run."""
+    import torch
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dev.run()                      # plan-time work (kernel attributes) happens outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(runs_per_graph):
+            dev.run()                  # the launches go to the capturing stream (torch's current stream)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(replays):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / (replays * runs_per_graph)
+
+
 def profile_launches(dev, reps=30):
     """Per-launch durations (seconds), median over reps, from HIP events recorded around every launch."""
     dev.run_profiled()
@@ -83,6 +107,10 @@ def config_report(idx, steps, warmup, with_floor=None):
     if with_floor is not None:
         rep["launch_floor_ms"] = with_floor * 1e3
         rep["frac_of_latency_aware_bound"] = (with_floor + abytes / HBM_PEAK) / sec
+        # the small configurations are bound by the host's launch path: the same calls replayed from a HIP graph
+        g = time_graph_replay(dev)
+        rep["ms_per_step_hip_graph_replay"] = g * 1e3
+        rep["algorithmic_GBps_hip_graph_replay"] = abytes / g / 1e9
     return wl, dev, rep, launches
 
 

@@ -408,3 +408,33 @@ def test_coop_runs_back_to_back(oracle_mod):
             d.run()
         assert np.array_equal(d.result(), first)
     d.close()
+
+
+@pytest.mark.parametrize("idx,mode", [(1, "fused"), (3, "fused"), (2, "coop"), (5, "per_layer")])
+def test_runs_recorded_in_a_hip_graph_replay_correctly(oracle_mod, idx, mode):
+    """ogc_mlp_run under stream capture: the graph is replayed several times with eager work and synchronisations
+    in between, and every replay must reproduce the eager result (the library records kernels only, no memsets)."""
+    import torch
+
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    wl = synth.make_config(idx, m={1: 32, 2: 128, 3: 256, 5: 512}[idx])
+    dev = DeviceMLP(wl, MODES[mode])
+    dev.run()
+    eager = dev.result().copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dev.run()
+        dev.run()
+    for rep in range(3):
+        dev.y.fill_(0xCD)
+        torch.cuda.synchronize()
+        graph.replay()
+        got = dev.result().copy()
+        assert np.array_equal(got.view(np.uint8), eager.view(np.uint8)), "replay %d differs from the eager run" % rep
+        dev.run()                       # eager work between the replays
+        torch.cuda.synchronize()
+    dev.close()
