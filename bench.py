@@ -240,9 +240,13 @@ def mha_report(steps, warmup, with_cpu=True, only=None):
                                          v=conv(big.v[:batch]), mask=big.mask[:batch], name="%s %s batch %d" % (row, dtype, batch))
                 dev = DeviceMHA(wl)
                 sec, ev = time_steps(dev, max(steps // 3, 10), max(warmup // 3, 3))
+                fast_dev = DeviceMHA(wl, binding.OGC_SOFTMAX_FAST)   # the softmax without the max reduction (Section VII)
+                fast_sec, _ = time_steps(fast_dev, max(steps // 6, 10), 3)
+                del fast_dev
                 peak = PEAK[dtype][0]
                 r = {"workload": wl.name, "seq": wl.seq, "heads": wl.heads, "head_dim": wl.head_dim,
                      "kernel": binding.ogc_mha_kernel_name(dev.desc, True), "us_per_run": sec * 1e6,
+                     "us_per_run_fast_softmax": fast_sec * 1e6,
                      "tflops": wl.ops / sec / 1e12, "frac_of_mfma_peak": wl.ops / sec / peak,
                      "gb_per_s_algorithmic": wl.algorithmic_bytes / sec / 1e9}
                 rows.append(r)
