@@ -1,7 +1,8 @@
 // Fused scaled dot-product attention for gfx950 (the MHA subgraph of Section VII / Table I): both batch
 // matmuls, the scalar, the mask and the softmax in one kernel, scores never leaving the compute unit.
 //
-// One workgroup = 4 wavefronts = 128 queries of one (batch, head); a wavefront owns 32 queries.  Keys and
+// One workgroup = 4 wavefronts = 128 queries of one (batch, head); a wavefront owns 32 queries (64, as two
+// groups of 32, in the bf16 variant for head dimensions up to 64).  Keys and
 // values stream through LDS in blocks of KB keys (bf16: 64, fp32: 32), prefetched one block ahead in
 // registers.  Both products are computed TRANSPOSED so that a lane owns one query:
 //
@@ -339,48 +340,48 @@ template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_boun
     // ---- normalise and store: after the half exchange a lane holds 16 consecutive channels of its query
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
-    const float total = run_sum[qs] + other_half(run_sum[qs]);
-    const float inv = 1.0f / total;
-    uint8_t* op = a.o + (b * a.so[0] + hd * a.so[1] + (long long)query[qs] * a.so[2]) * E;
+        const float total = run_sum[qs] + other_half(run_sum[qs]);
+        const float inv = 1.0f / total;
+        uint8_t* op = a.o + (b * a.so[0] + hd * a.so[1] + (long long)query[qs] * a.so[2]) * E;
 #pragma unroll
-    for (int d = 0; d < D32; ++d) {
-        if constexpr (DT == OGC_BF16) {
-            uint32_t dw[4][2];
+        for (int d = 0; d < D32; ++d) {
+            if constexpr (DT == OGC_BF16) {
+                uint32_t dw[4][2];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                dw[g][0] = pack_bf16(oacc[qs][d][4 * g] * inv, oacc[qs][d][4 * g + 1] * inv);
-                dw[g][1] = pack_bf16(oacc[qs][d][4 * g + 2] * inv, oacc[qs][d][4 * g + 3] * inv);
-            }
+                for (int g = 0; g < 4; ++g) {
+                    dw[g][0] = pack_bf16(oacc[qs][d][4 * g] * inv, oacc[qs][d][4 * g + 1] * inv);
+                    dw[g][1] = pack_bf16(oacc[qs][d][4 * g + 2] * inv, oacc[qs][d][4 * g + 3] * inv);
+                }
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                swap32(dw[0][j], dw[2][j]);
-                swap32(dw[1][j], dw[3][j]);
-            }
-            if (query[qs] < S) {
-                uint8_t* dst = op + (d * 32 + 16 * h) * 2;
-                *(v4i*)dst = (v4i){(int)dw[0][0], (int)dw[0][1], (int)dw[2][0], (int)dw[2][1]};
-                *(v4i*)(dst + 16) = (v4i){(int)dw[1][0], (int)dw[1][1], (int)dw[3][0], (int)dw[3][1]};
-            }
-        } else {
-            uint32_t dw[4][4];
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) dw[g][e] = __builtin_bit_cast(uint32_t, oacc[qs][d][4 * g + e] * inv);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                swap32(dw[0][e], dw[2][e]);
-                swap32(dw[1][e], dw[3][e]);
-            }
-            if (query[qs] < S) {
-                uint8_t* dst = op + (d * 32 + 16 * h) * 4;
-                const int order[4] = {0, 2, 1, 3};
+                for (int j = 0; j < 2; ++j) {
+                    swap32(dw[0][j], dw[2][j]);
+                    swap32(dw[1][j], dw[3][j]);
+                }
+                if (query[qs] < S) {
+                    uint8_t* dst = op + (d * 32 + 16 * h) * 2;
+                    *(v4i*)dst = (v4i){(int)dw[0][0], (int)dw[0][1], (int)dw[2][0], (int)dw[2][1]};
+                    *(v4i*)(dst + 16) = (v4i){(int)dw[1][0], (int)dw[1][1], (int)dw[3][0], (int)dw[3][1]};
+                }
+            } else {
+                uint32_t dw[4][4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
-                    *(v4i*)(dst + 16 * g) = (v4i){(int)dw[order[g]][0], (int)dw[order[g]][1], (int)dw[order[g]][2], (int)dw[order[g]][3]};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dw[g][e] = __builtin_bit_cast(uint32_t, oacc[qs][d][4 * g + e] * inv);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    swap32(dw[0][e], dw[2][e]);
+                    swap32(dw[1][e], dw[3][e]);
+                }
+                if (query[qs] < S) {
+                    uint8_t* dst = op + (d * 32 + 16 * h) * 4;
+                    const int order[4] = {0, 2, 1, 3};
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        *(v4i*)(dst + 16 * g) = (v4i){(int)dw[order[g]][0], (int)dw[order[g]][1], (int)dw[order[g]][2], (int)dw[order[g]][3]};
+                }
             }
         }
-    }
     }
 }
 
