@@ -75,6 +75,26 @@ def time_graph_replay(dev, runs_per_graph=50, replays=6):
     return (time.perf_counter() - t0) / (replays * runs_per_graph)
 
 
+def time_cold(dev, reps=9):
+    """One run at a time with the caches flushed before it (a 512 MiB fill goes through L2 and the memory-side
+    cache first): median of HIP-event times around the single call.  Returns seconds."""
+    import torch
+
+    junk = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    times = []
+    for i in range(reps):
+        junk.fill_(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dev.run()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) * 1e-3)
+    del junk
+    return _median(times)
+
+
 def profile_launches(dev, reps=30):
     """Per-launch durations (seconds), median over reps, from HIP events recorded around every launch."""
     dev.run_profiled()
@@ -111,6 +131,7 @@ def config_report(idx, steps, warmup, with_floor=None):
         g = time_graph_replay(dev)
         rep["ms_per_step_hip_graph_replay"] = g * 1e3
         rep["algorithmic_GBps_hip_graph_replay"] = abytes / g / 1e9
+        rep["ms_per_step_cold_caches"] = time_cold(dev) * 1e3   # weights and input come from HBM
     return wl, dev, rep, launches
 
 
