@@ -73,7 +73,8 @@ ogc_status ogc_mha_run(const ogc_mha_desc* desc, const void* q, const void* k, c
  * mask), as a profiler's kernel trace prints it (static storage), or NULL for an invalid description.  A run
  * without a mask whose sequence is a whole number of key blocks (bf16: 64, fp32: 32) and whose scale is
  * positive takes a variant that spends no per-key addend; bf16 with head_dim <= 64 and seq >= 256 takes one in
- * which a wavefront owns 64 queries instead of 32 (the last template argument). */
+ * which a wavefront owns 64 queries instead of 32 (the last template argument; the environment variable
+ * OGC_MHA_QS = 1 or 2, read by ogc_mha_run and by this function, overrides that choice for tests and sweeps). */
 const char* ogc_mha_kernel_name(const ogc_mha_desc* desc, int32_t has_mask);
 
 #ifdef __cplusplus
