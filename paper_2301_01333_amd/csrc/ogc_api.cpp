@@ -45,7 +45,9 @@ struct ogc_mlp_plan_s {
     size_t packed_bytes, workspace_bytes;
     int lds_buf_bytes;  // fused mode
     size_t partial_off, partial_bytes;  // split-K partial accumulators, after the activation slots
-    size_t sync_off;                    // cooperative mode: two counters at the end of the packed blob
+    size_t sync_off;                    // cooperative mode: counters at the end of the packed blob
+    int cluster_split;                  // cooperative mode: 0 = blocks dealt to all workgroups, n = n workgroups per row tile
+    int cluster_spread;                 // cluster kernel: a tile's members on different XCDs (weights beyond one L2)
     std::vector<size_t> slot_off, slot_size;
     std::atomic<int> prepacked;
 };
@@ -230,6 +232,35 @@ double estimate_coop_us(const ogc_mlp_plan_s* p) {
     return t * (1.0 + c.fill * std::min(1.0, most / 256.0));
 }
 
+// The cluster kernel: `split` workgroups per 32-row tile, each streaming 1/split of the weights; after every layer
+// but the last, a barrier of the tile's members and a copy of the whole tile back into LDS.  Fitted like the other
+// mode models (chains of 2-5 layers, 64-4096 wide, 32-2048 rows, splits 2-16; rms error 6 % int8, 8 % bf16).  No
+// fp32 entry: the kernel has no split along K, and the fp32 chains are bound by one CU's MFMA rate in it.
+struct ClusterCost { float c0, per_mb, group, per_layer, barrier, copy_mb, fill, all_mb; };
+const ClusterCost kCluster[3] = {{0, 0, 0, 0, 0, 0, 0, 0},
+                                 {4.202f, 8.072f, 0.0659f, 0.0f, 2.330f, 10.52f, 0.0603f, 0.0357f},
+                                 {4.996f, 10.156f, 0.0f, 0.030f, 2.235f, 30.50f, 0.0103f, 0.0226f}};
+double estimate_cluster_us(const ogc_mlp_plan_s* p, int split) {
+    const ClusterCost& c = kCluster[p->desc.dtype];
+    const int L = (int)p->layers.size(), waves = 8 * split;
+    const double tiles = (p->desc.m + 31) / 32;
+    double t = c.c0, all_mb = 0.0;
+    for (int l = 0; l < L; ++l) {
+        const LayerPlan& lp = p->layers[l];
+        const bool last = l == L - 1;
+        const int nb = last ? (lp.d.n + 31) / 32 : lp.nb_out;
+        const double kb = (double)lp.kp * p->esz;  // bytes of a row of the layer's input
+        int wg = 0;                                // channel blocks of the busiest member
+        for (int w = 0; w < 8 && w < nb; ++w) wg += (nb - w + waves - 1) / waves;
+        const int per_wave = (nb + waves - 1) / waves;
+        t += c.per_mb * kb * 32.0 * wg / 1e6 + c.group * std::ceil(kb / 128.0) * ((per_wave + 3) / 4) + c.per_layer;
+        if (!last) t += c.barrier + c.copy_mb * ((double)p->layers[l + 1].kp * p->esz * 32.0) / 1e6;
+        all_mb += kb * 32.0 * nb / 1e6;
+    }
+    // every tile streams all the weights through the L2s: the aggregate term counts beyond a few dozen tiles
+    return t * (1.0 + c.fill * std::min(1.0, tiles * split / 256.0)) + c.all_mb * tiles * all_mb;
+}
+
 ogc_status validate(const ogc_mlp_desc* d) {
     if (!d || !d->layers) return OGC_ERR_INVALID_ARG;
     if (d->dtype != OGC_F32 && d->dtype != OGC_BF16 && d->dtype != OGC_I8) return OGC_ERR_INVALID_ARG;
@@ -377,6 +408,29 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
     p->mode_us[0] = per_timed ? per_us : -1.0;
     p->mode_us[1] = (fused_fits && (desc->dtype == OGC_I8 || wbytes <= (size_t)2600000)) ? estimate_fused_us(p) : -1.0;
     p->mode_us[2] = (!blocked_io && L > 1) ? estimate_coop_us(p) : -1.0;
+    // The cooperative mode has two kernels: blocks dealt to all workgroups (above), or a few workgroups per row tile
+    // (the cluster kernel).  The split with the lowest estimate competes; OGC_CLUSTER_SPLIT overrides (0: never).
+    p->cluster_split = 0;
+    p->cluster_spread = wbytes > (size_t)3000000;  // weights beyond one XCD's L2: a tile's members on different XCDs
+    if (p->mode_us[2] >= 0 && fused_fits) {
+        const int m_blocks = (desc->m + 31) / 32;
+        const int forced = env_int("OGC_CLUSTER_SPLIT", -1);
+        if (forced > 0) {
+            if (ogc_cluster_xcds(m_blocks, forced, p->cluster_spread) >= 0) {
+                p->cluster_split = forced;
+                if (desc->dtype != OGC_F32) p->mode_us[2] = estimate_cluster_us(p, forced);
+            }
+        } else if (forced < 0 && desc->dtype != OGC_F32) {
+            for (int split = 2; split <= 16; split *= 2) {
+                if (ogc_cluster_xcds(m_blocks, split, p->cluster_spread) < 0) continue;
+                const double e = estimate_cluster_us(p, split);
+                if (e < p->mode_us[2]) {
+                    p->mode_us[2] = e;
+                    p->cluster_split = split;
+                }
+            }
+        }
+    }
     if (mode == OGC_MODE_AUTO) {
         // The mode whose estimate is lowest (section "cost model" of the sources above: each mode has its own fitted
         // model).  The fused kernel is a candidate only where it was timed without its cliff: bf16 / fp32 chains
@@ -417,9 +471,10 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         off += round_up((size_t)lp.npw * 4, 256);
     }
     p->sync_off = off;
-    if (mode == OGC_MODE_COOP) off += 256;
+    if (mode == OGC_MODE_COOP) off += (size_t)OGC_SYNC_WORDS * 8;
     p->packed_bytes = off;
     p->partial_off = p->partial_bytes = 0;
+    if (mode != OGC_MODE_COOP) p->cluster_split = 0;
     if (mode == OGC_MODE_COOP) {
         assign_buffers(p);
     } else if (mode == OGC_MODE_PER_LAYER) {
@@ -575,6 +630,14 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
             const long nb = l < L - 1 ? plan->layers[l].nb_out : (plan->layers[l].d.n + 31) / 32;
             if ((long)m_blocks * nb > max_blocks) max_blocks = (long)m_blocks * nb;
         }
+        if (plan->cluster_split > 0) {
+            c.lds_buf_bytes = plan->lds_buf_bytes;
+            if (ev && hipEventRecord(ev[0], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
+            const int rc = ogc_launch_cluster(plan->desc.dtype, &c, m_blocks, plan->cluster_split, plan->cluster_spread, (void*)(blob + plan->sync_off), stream);
+            if (rc != 0) return OGC_ERR_DEVICE;
+            if (ev && hipEventRecord(ev[1], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
+            return OGC_OK;
+        }
         int cus = ogc_device_cu_count();
         if (cus <= 0) return OGC_ERR_DEVICE;
         const int grid = (int)(max_blocks < cus ? max_blocks : cus);
@@ -666,7 +729,8 @@ ogc_status ogc_mlp_mode_estimates(ogc_mlp_plan_t plan, float us[3]) {
 const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer) {
     if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return nullptr;
     if (plan->mode == OGC_MODE_FUSED) return ogc_fused_kernel_name(plan->desc.dtype);
-    if (plan->mode == OGC_MODE_COOP) return ogc_coop_kernel_name(plan->desc.dtype);
+    if (plan->mode == OGC_MODE_COOP)
+        return plan->cluster_split > 0 ? ogc_cluster_kernel_name(plan->desc.dtype) : ogc_coop_kernel_name(plan->desc.dtype);
     const int L = (int)plan->layers.size();
     const ogc_layer_desc& d = plan->layers[layer].d;
     return ogc_layer_kernel_name(plan->desc.dtype, plan->layers[layer].tile,

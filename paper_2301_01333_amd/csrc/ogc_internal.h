@@ -61,8 +61,14 @@ struct OgcLayerArgs {
 struct OgcChainArgs {
     int32_t n_layers;
     int32_t lds_buf_bytes;  // size of one LDS activation buffer
+    int32_t fused_xcds;     // fused kernel: row tiles are dealt to this many of the 8 XCDs (workgroup b runs on XCD b%8)
+    int32_t fused_tiles;    // fused kernel: number of 32-row tiles
+    int32_t cluster_split;  // cluster kernel: workgroups that share a row tile
     OgcLayerArgs layer[OGC_MAX_LAYERS];
 };
+
+#define OGC_SYNC_STRIDE 16    // 64-bit words between the counters of two row tiles: a 128-byte line each
+#define OGC_SYNC_WORDS 2048   // 64-bit words at the end of the packed blob (cooperative and cluster kernels)
 
 enum { OGC_TILE_BIG = 0, OGC_TILE_MID = 1, OGC_TILE_SMALL = 2, OGC_TILE_DMA = 3, OGC_TILE_DMA8 = 4, OGC_NUM_TILES = 5 };
 
@@ -80,8 +86,11 @@ int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain, const OgcL
 int ogc_launch_fused(int dtype, const OgcChainArgs* c, int m_blocks, void* stream);
 int ogc_launch_coop(int dtype, const OgcChainArgs* c, int m_blocks, int grid, void* sync, void* stream);
 int ogc_launch_zero_sync(void* sync, void* stream);
+int ogc_cluster_xcds(int m_blocks, int split, int spread);
+int ogc_launch_cluster(int dtype, const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync, void* stream);
 int ogc_device_cu_count(void);
 const char* ogc_coop_kernel_name(int dtype);
+const char* ogc_cluster_kernel_name(int dtype);
 int ogc_launch_prepack_weights(const void* w, void* out, int K, int N, int KC, int NPw, int esz, void* stream);
 int ogc_launch_prepack_params(int dtype, const void* w, const float* w_scale, const float* bias, float in_scale, int in_zp,
                               int K, int N, int NPw, float* scale_out, float* bias_out, int32_t* ncomp_out, void* stream);

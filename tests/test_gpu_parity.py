@@ -410,6 +410,63 @@ def test_coop_runs_back_to_back(oracle_mod):
     d.close()
 
 
+# ---------------------------------------------------------------- cluster kernel (a few workgroups per row tile)
+@pytest.mark.parametrize("split", [0, 2, 4, 8])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "i8"])
+def test_cluster_kernel_ragged_and_edges(oracle_mod, monkeypatch, dtype, split):
+    """The cooperative mode's second kernel: `split` workgroups share a 32-row tile, each computes every split-th
+    group of channel blocks, and the tile travels through the workspace between layers.  OGC_CLUSTER_SPLIT forces
+    the split (0: the block-dealing kernel), so every split is checked against the oracle on every dtype."""
+    monkeypatch.setenv("OGC_CLUSTER_SPLIT", str(split))
+    act2 = GELU if dtype != "i8" else RELU
+    wl = synth.make_mlp(dtype, 77, [37, 130, 300, 9], [RELU, act2, RELU], seed=600, name="cluster-ragged")
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    d = DeviceMLP(wl, binding.OGC_MODE_COOP)
+    assert binding.ogc_mlp_kernel_name(d.mlp.plan, 0).startswith("ogc_cluster_chain_kernel" if split else "ogc_coop_chain_kernel")
+    d.close()
+    check(wl, "coop", oracle_mod)
+    check(synth.make_mlp(dtype, 700, [100, 333, 72, 33], [RELU, RELU, NONE if dtype != "i8" else RELU], seed=601, name="cluster-22-tiles"),
+          "coop", oracle_mod)
+    check(synth.make_mlp(dtype, 1, [1, 1], [NONE if dtype != "i8" else RELU], seed=602, name="cluster-1x1"), "coop", oracle_mod)
+    check(synth.make_mlp(dtype, 50, [100, 48, 24], [RELU, RELU], seed=603, ld_x=112), "coop", oracle_mod, ld_y=64)
+    check(synth.make_mlp(dtype, 70, [32] + [40, 24] * 8, [RELU] * 16, seed=40, name="cluster-16-layers"), "coop", oracle_mod)
+    if dtype == "i8":
+        check(synth.make_mlp("i8", 33, [479, 65, 31], [RELU, RELU], seed=2, a_z=3, c_z=200, wq_lo=-128), "coop", oracle_mod)
+        check(synth.make_mlp("i8", 19, [70, 64, 5], [RELU, SIGM], seed=5, last_f32=True), "coop", oracle_mod)
+    else:
+        check(synth.make_mlp(dtype, 70, [40, 64, 40], [GELU, NONE], seed=13, residual=True), "coop", oracle_mod)
+
+
+@pytest.mark.parametrize("dtype,m,split", [("i8", 256, 4), ("i8", 520, 8), ("bf16", 200, 4), ("bf16", 64, 16), ("i8", 2048, 4)])
+def test_cluster_kernel_table1_mlp2(oracle_mod, monkeypatch, dtype, m, split):
+    """Table I's MLP-2 through the cluster kernel: int8 weights fit one XCD's L2 (a tile's members share an XCD), the
+    bf16 weights do not (members on different XCDs); many runs in a row keep giving the first run's result (each
+    tile's members reset their counters at the end of a run)."""
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    monkeypatch.setenv("OGC_CLUSTER_SPLIT", str(split))
+    dims = [479, 1024, 1024, 512, 256, 1]
+    acts = [RELU] * 4 + [SIGM if dtype == "i8" else NONE]
+    wl = synth.make_mlp(dtype, m, dims, acts, seed=77, last_f32=(dtype == "i8"), name="cluster-mlp2")
+    d = DeviceMLP(wl, binding.OGC_MODE_COOP)
+    assert binding.ogc_mlp_kernel_name(d.mlp.plan, 0).startswith("ogc_cluster_chain_kernel")
+    d.run()
+    first = d.result().copy()
+    rows = slice(0, m) if m <= 520 else slice(m - 300, m)
+    ref = oracle_mod.mlp(wl, rows=rows)
+    if dtype == "i8":
+        assert_close(first[rows, :1], ref, 1e-5, "MLP-2 int8, cluster kernel")
+    else:
+        assert_close(as_f32(wl, first[rows, :1]), as_f32(wl, ref), TOL[dtype], "MLP-2 bf16, cluster kernel")
+    for _ in range(3):
+        d.y.fill_(0xCD)
+        for _ in range(9):
+            d.run()
+        assert np.array_equal(d.result().view(np.uint8), first.view(np.uint8))
+    d.close()
+
+
 @pytest.mark.parametrize("idx,mode", [(1, "fused"), (3, "fused"), (2, "coop"), (5, "per_layer")])
 def test_runs_recorded_in_a_hip_graph_replay_correctly(oracle_mod, idx, mode):
     """ogc_mlp_run under stream capture: the graph is replayed several times with eager work and synchronisations

@@ -95,22 +95,55 @@ def test_run_and_prepack_argument_checks_need_no_device():
 
 
 def test_mode_choice_and_sizes():
-    # config 3 shape: small batch -> fused chain kernel, no workspace
+    # config 3 shape: small batch, 2.2 MB of weights -> one launch, a few workgroups per row tile (cluster kernel),
+    # intermediates through two workspace slots of 256 rows x 1024 bytes
     dims = [479, 1024, 1024, 512, 256, 1]
     ls = [layer(dims[i], dims[i + 1]) for i in range(5)]
     ls[-1].update(out=1, act=b.OGC_ACT_SIGMOID)
     p = b.ogc_mlp_plan(b.OGC_I8, 256, ls, 479, 1, 0, 0)
-    assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_FUSED
-    assert b.ogc_mlp_workspace_bytes(p) == 0 and b.ogc_mlp_num_launches(p) == 1
+    assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_COOP
+    assert b.ogc_mlp_kernel_name(p, 0) == "ogc_cluster_chain_kernel<2>"
+    assert b.ogc_mlp_workspace_bytes(p) == 2 * 256 * 1024 and b.ogc_mlp_num_launches(p) == 1
     # packed weights: K padded to 64 (479 -> 512), rows padded to 32/64; per-channel params on top
     assert b.ogc_mlp_packed_bytes(p) >= 512 * 1024 + 1024 * 1024 + 1024 * 512 + 512 * 256 + 256 * 32
     assert b.ogc_mlp_packed_bytes(p) < 1.1 * (512 * 1024 + 1024 * 1024 + 1024 * 512 + 512 * 256 + 256 * 64) + 5 * 3 * 4096
+    b.ogc_mlp_destroy(p)
+    # a narrow chain (config 2's shape): the fused chain kernel, no workspace
+    dims2 = [13, 512, 256, 128, 64]
+    p = b.ogc_mlp_plan(b.OGC_BF16, 128, [layer(dims2[i], dims2[i + 1]) for i in range(4)], 13, 64, 0, 0)
+    assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_FUSED
+    assert b.ogc_mlp_workspace_bytes(p) == 0 and b.ogc_mlp_num_launches(p) == 1
     b.ogc_mlp_destroy(p)
     # config 5 shape: large batch, wide layers -> per-layer kernels
     p = b.ogc_mlp_plan(b.OGC_I8, 32768, [layer(1024, 1024, has_bias=0)] * 4, 1024, 1024, 0, 0)
     assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_PER_LAYER and b.ogc_mlp_num_launches(p) == 4
     assert b.ogc_mlp_kernel_name(p, 0)
     b.ogc_mlp_destroy(p)
+
+
+def test_cluster_split_override(monkeypatch):
+    """OGC_CLUSTER_SPLIT picks the cooperative mode's kernel: 0 = blocks dealt to all workgroups, n = n workgroups
+    per row tile, where they fit one per CU; unset = the cost model's choice."""
+    dims = [479, 1024, 1024, 512, 256]
+    ls = [layer(dims[i], dims[i + 1]) for i in range(4)]
+
+    narrow = [layer(256, 512), layer(512, 256)]  # fp32 rows of 1024 values do not fit the two LDS buffers
+
+    def name(m, dtype=b.OGC_I8):
+        p = b.ogc_mlp_plan(dtype, m, narrow if dtype == b.OGC_F32 else ls, 256 if dtype == b.OGC_F32 else 479, 256, 0, b.OGC_MODE_COOP)
+        n = b.ogc_mlp_kernel_name(p, 0)
+        b.ogc_mlp_destroy(p)
+        return n
+
+    monkeypatch.setenv("OGC_CLUSTER_SPLIT", "0")
+    assert name(256) == "ogc_coop_chain_kernel<2>"
+    monkeypatch.setenv("OGC_CLUSTER_SPLIT", "4")
+    assert name(256) == "ogc_cluster_chain_kernel<2>"
+    assert name(256, b.OGC_F32) == "ogc_cluster_chain_kernel<0>"
+    assert name(32 * 65) == "ogc_coop_chain_kernel<2>"      # 65 tiles x 4 members do not fit 256 CUs
+    monkeypatch.delenv("OGC_CLUSTER_SPLIT")
+    assert name(256) == "ogc_cluster_chain_kernel<2>"
+    assert name(256, b.OGC_F32) == "ogc_coop_chain_kernel<0>"  # never the model's choice for fp32
 
 
 def test_buffer_reuse_is_ping_pong_for_a_chain():
@@ -212,7 +245,7 @@ def test_blocked_layout_plan():
 
 def test_auto_mode_choice_follows_the_cost_models():
     """OGC_MODE_AUTO takes the mode whose fitted model gives the lowest estimate for the chain (a single-launch
-    mode wins near ties).  Checked on shapes whose fastest mode was measured; the five configurations keep theirs."""
+    mode wins near ties).  Checked on shapes whose fastest mode was measured."""
     def mode(dtype, m, dims, **kw):
         lay = [layer(dims[i], dims[i + 1], **kw) for i in range(len(dims) - 1)]
         p = b.ogc_mlp_plan(dtype, m, lay, dims[0], dims[-1], 0, b.OGC_MODE_AUTO)
@@ -224,13 +257,16 @@ def test_auto_mode_choice_follows_the_cost_models():
     mlp1, mlp2 = [13, 512, 256, 128], [479, 1024, 1024, 512, 256, 1]
     assert mode(b.OGC_F32, 32, [13, 64, 32, 16]) == b.OGC_MODE_FUSED                   # config 1
     assert mode(b.OGC_BF16, 128, [13, 512, 256, 128, 64]) == b.OGC_MODE_FUSED          # config 2
-    assert mode(b.OGC_I8, 256, mlp2) == b.OGC_MODE_FUSED                               # config 3
+    assert mode(b.OGC_I8, 256, mlp2) == b.OGC_MODE_COOP                                # config 3 (cluster kernel)
     assert mode(b.OGC_BF16, 4096, [1024, 4096, 1024]) == b.OGC_MODE_PER_LAYER          # config 4
     assert mode(b.OGC_I8, 32768, [1024] * 5) == b.OGC_MODE_PER_LAYER                   # config 5
     assert mode(b.OGC_F32, 64, mlp1) == b.OGC_MODE_COOP and mode(b.OGC_F32, 8192, mlp1) == b.OGC_MODE_FUSED
     assert mode(b.OGC_F32, 512, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_F32, 2048, mlp2) == b.OGC_MODE_PER_LAYER
-    assert mode(b.OGC_BF16, 128, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_BF16, 2048, mlp2) == b.OGC_MODE_PER_LAYER
-    assert mode(b.OGC_I8, 32, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_I8, 2048, mlp2) == b.OGC_MODE_FUSED
+    # 2048 rows of MLP-2: four workgroups per row tile (measured 48 us bf16, 29 us int8) beat a launch per layer (63)
+    # and the fused kernel (34.5, int8 only)
+    assert mode(b.OGC_BF16, 128, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_BF16, 2048, mlp2) == b.OGC_MODE_COOP
+    assert mode(b.OGC_I8, 32, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_I8, 2048, mlp2) == b.OGC_MODE_COOP
+    assert mode(b.OGC_BF16, 8192, mlp2) == b.OGC_MODE_PER_LAYER
     assert mode(b.OGC_I8, 64, mlp1) == b.OGC_MODE_FUSED
     # wide int8 layers at a small batch: every CU on each layer beats one launch per layer (measured 33 against 51 us)
     assert mode(b.OGC_I8, 128, [2048] * 4) == b.OGC_MODE_COOP and mode(b.OGC_I8, 2048, [2048] * 4) == b.OGC_MODE_PER_LAYER
@@ -245,13 +281,13 @@ def test_auto_mode_choice_follows_the_cost_models():
     with pytest.raises(b.OgcError) as e:
         b.ogc_mlp_plan(b.OGC_F32, 64, [layer(512, 512)], 512, 512, 0, b.OGC_MODE_COOP, b.OGC_LAYOUT_BLOCKED, 0)
     assert e.value.status == -2
-    # one launch step, workspace slots as in per-layer mode, two counters behind the packed parameters
+    # one launch step, workspace slots as in per-layer mode, the barrier counters behind the packed parameters
     lay = [layer(64, 256), layer(256, 512), layer(512, 64)]
     pc = b.ogc_mlp_plan(b.OGC_I8, 100, lay, 64, 64, 0, b.OGC_MODE_COOP)
     pl = b.ogc_mlp_plan(b.OGC_I8, 100, lay, 64, 64, 0, b.OGC_MODE_FUSED)
-    assert b.ogc_mlp_num_launches(pc) == 1 and b.ogc_mlp_kernel_name(pc, 0) == "ogc_coop_chain_kernel<2>"
+    assert b.ogc_mlp_num_launches(pc) == 1 and b.ogc_mlp_kernel_name(pc, 0) in ("ogc_coop_chain_kernel<2>", "ogc_cluster_chain_kernel<2>")
     assert b.ogc_mlp_workspace_bytes(pc) == 256 * 256 + 256 * 512
-    assert b.ogc_mlp_packed_bytes(pc) == b.ogc_mlp_packed_bytes(pl) + 256
+    assert b.ogc_mlp_packed_bytes(pc) == b.ogc_mlp_packed_bytes(pl) + 2048 * 8
     b.ogc_mlp_destroy(pc)
     b.ogc_mlp_destroy(pl)
 
