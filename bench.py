@@ -118,6 +118,7 @@ def config_report(idx, steps, warmup, with_floor=None):
     bound = "mfma" if ops / abytes > ridge else "hbm"
     rep = {
         "config": idx, "workload": wl.name, "dtype": wl.dtype, "mode": MODE_NAMES[dev.mlp.mode],
+        "kernels": sorted({binding.ogc_mlp_kernel_name(dev.mlp.plan, j) for j in range(nl)}),
         "launches": nl, "ms_per_step": sec * 1e3, "ms_per_step_hip_events": ev_sec * 1e3,
         "ms_sum_of_per_launch_event_pairs": sum(launches) * 1e3,
         "tops_or_tflops": ops / sec / 1e12, "algorithmic_GBps": abytes / sec / 1e9, "bound": bound,
@@ -230,6 +231,7 @@ def table1_sweep(steps, warmup):
                 dev = DeviceMLP(wl)
                 sec, _ = time_steps(dev, steps, warmup)
                 rows.append({"workload": wl.name, "mode": MODE_NAMES[dev.mlp.mode],
+                             "kernel": binding.ogc_mlp_kernel_name(dev.mlp.plan, 0).split("<")[0],
                              "us_per_chain": sec * 1e6, "gops": wl.ops / sec / 1e9})
                 dev.close()
     return rows

@@ -97,19 +97,25 @@ typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
  * and per-layer kernels with workspace buffer reuse (Section VI), picks tile shapes (the role of the
  * template-parameter heuristic, Section III) and lays out the packed blob and the workspace.
  * Host only: no device call is made.  *out_plan is written only on OGC_OK.
- * OGC_MODE_COOP is the small-batch kernel: one launch in which all CUs share each layer's output blocks and the
- * waves of a workgroup split the reduction axis (multi-core loop and k-slicing, Section III), with a device-wide
- * barrier between layers.  It needs the workspace and keeps two counters in the packed blob, so runs that share
- * a packed blob must not overlap in time; all its workgroups must be resident at once (the grid is at most one
- * per CU), so it is meant for a device that is not kept busy by other kernels for seconds: its barrier wait is
- * bounded and a timeout yields wrong data, not a hang.
+ * OGC_MODE_COOP is the small-batch mode: one launch in which several workgroups share the work of a row tile
+ * (multi-core loop and k-slicing, Section III) and meet at barriers between layers.  It has two kernels, and the
+ * plan takes the one with the lower estimate: (a) all CUs share each layer's 32x32 output blocks, the waves of a
+ * workgroup split the reduction axis, device-wide barrier; (b) the cluster kernel: 2, 4, 8 or 16 workgroups per
+ * 32-row tile, each keeps the tile in LDS and streams its share of the weights, the tile's members exchange their
+ * channel blocks through the workspace at a barrier of their own (int8 and bf16 chains whose widest row fits LDS).
+ * The mode needs the workspace and keeps barrier counters in the packed blob (16 KiB at its end), so runs that
+ * share a packed blob must not overlap in time; all its workgroups must be resident at once (the grid is at most
+ * one per CU), so it is meant for a device that is not kept busy by other kernels for seconds: the barrier wait
+ * is bounded and a timeout yields wrong data, not a hang.
  * OGC_MODE_AUTO takes the mode with the lowest estimate of three fitted cost models (ogc_mlp_mode_estimates); a
  * single-launch mode wins ties within 7 %.  In per-layer mode each layer's tile and k-split are the candidate with
  * the lowest estimate (ogc_mlp_estimated_us): the scoring heuristic of Section III, no tuning run.
  * OGC_ERR_UNSUPPORTED: OGC_MODE_FUSED requested but a layer is too wide for the LDS activation tile; a blocked
  * x or y with a mode other than per-layer.
- * For tests, two environment variables read here override the cost model in per-layer mode: OGC_TILE (0..4:
- * tile configuration of every layer) and OGC_KSPLIT (log2 of the number of k ranges, 0..3). */
+ * For tests, environment variables read here override the cost model: in per-layer mode OGC_TILE (0..4: tile
+ * configuration of every layer) and OGC_KSPLIT (log2 of the number of k ranges, 0..3); in cooperative mode
+ * OGC_CLUSTER_SPLIT (0: kernel (a); n: kernel (b) with n workgroups per tile where they fit, any dtype) and
+ * OGC_CLUSTER_WHOLE=0 (kernel (b) exchanges after every layer, also the small ones it would compute whole). */
 ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc /*host*/, ogc_mlp_plan_t* out_plan /*host*/);
 
 /* Size of the packed-weights blob (blocked weights + per-channel parameters of every layer). */
@@ -178,7 +184,7 @@ ogc_status ogc_mlp_estimated_us(ogc_mlp_plan_t plan, int32_t layer, float* us);
 
 /* The cost models' estimates of the whole chain in microseconds, by which OGC_MODE_AUTO chose the mode:
  * us[0] layer by layer (sum of the layers' estimates), us[1] the fused whole-chain kernel, us[2] the cooperative
- * kernel; -1 where a mode is not admissible (fused: the widest layer does not fit LDS, or bf16 / fp32 weights
+ * mode (the lower of its two kernels' estimates); -1 where a mode is not admissible (fused: the widest layer does not fit LDS, or bf16 / fp32 weights
  * beyond 2.5 MB; cooperative: a single layer, blocked tensors at the boundary) or not modelled.  Host only.
  * OGC_ERR_INVALID_ARG: NULL plan or us. */
 ogc_status ogc_mlp_mode_estimates(ogc_mlp_plan_t plan, float us[3]);

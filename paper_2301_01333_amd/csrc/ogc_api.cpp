@@ -234,28 +234,53 @@ double estimate_coop_us(const ogc_mlp_plan_s* p) {
 
 // The cluster kernel: `split` workgroups per 32-row tile, each streaming 1/split of the weights; after every layer
 // but the last, a barrier of the tile's members and a copy of the whole tile back into LDS.  Fitted like the other
-// mode models (chains of 2-5 layers, 64-4096 wide, 32-2048 rows, splits 2-16; rms error 6 % int8, 8 % bf16).  No
-// fp32 entry: the kernel has no split along K, and the fp32 chains are bound by one CU's MFMA rate in it.
+// mode models (chains of 2-5 layers, 64-4096 wide, 32-2048 rows, splits 2-16; rms error 8 %, worst 37 %: wide bf16
+// layers at 1024 rows, underestimated).  The fp32 row serves forced splits only: the kernel has no split along K,
+// an fp32 chain is bound by one CU's MFMA rate in it, and the plan does not offer it fp32 chains.
 struct ClusterCost { float c0, per_mb, group, per_layer, barrier, copy_mb, fill, all_mb; };
-const ClusterCost kCluster[3] = {{0, 0, 0, 0, 0, 0, 0, 0},
-                                 {4.202f, 8.072f, 0.0659f, 0.0f, 2.330f, 10.52f, 0.0603f, 0.0357f},
-                                 {4.996f, 10.156f, 0.0f, 0.030f, 2.235f, 30.50f, 0.0103f, 0.0226f}};
+const ClusterCost kCluster[3] = {{0.051f, 31.81f, 0.0f, 2.819f, 2.310f, 26.20f, 0.0922f, 0.0069f},
+                                 {3.808f, 7.503f, 0.0543f, 1.079f, 2.720f, 0.0f, 0.0820f, 0.0181f},
+                                 {3.370f, 8.906f, 0.1855f, 1.102f, 1.000f, 0.0f, 0.0753f, 0.0107f}};
+
+// One layer of the cluster kernel: the busiest member's weight stream, and the exchange if the layer is split.
+double cluster_layer_us(const ogc_mlp_plan_s* p, int l, int split, bool whole) {
+    const ClusterCost& c = kCluster[p->desc.dtype];
+    const int L = (int)p->layers.size(), waves = 8 * (whole ? 1 : split);
+    const LayerPlan& lp = p->layers[l];
+    const bool last = l == L - 1;
+    const int nb = last ? (lp.d.n + 31) / 32 : lp.nb_out;
+    const double kb = (double)lp.kp * p->esz;  // bytes of a row of the layer's input
+    int wg = 0;                                // channel blocks of the busiest member
+    for (int w = 0; w < 8 && w < nb; ++w) wg += (nb - w + waves - 1) / waves;
+    const int per_wave = (nb + waves - 1) / waves;
+    double t = c.per_mb * kb * 32.0 * wg / 1e6 + c.group * std::ceil(kb / 128.0) * ((per_wave + 3) / 4) + c.per_layer;
+    if (!last && !whole) t += c.barrier + c.copy_mb * ((double)p->layers[l + 1].kp * p->esz * 32.0) / 1e6;
+    return t;
+}
+
+// Bit l set: layer l is so small that every member computing all of it costs less than splitting it and
+// exchanging the result.  The last layer is always split (nothing follows it, so no exchange either).
+uint32_t cluster_whole_layers(const ogc_mlp_plan_s* p, int split) {
+    uint32_t mask = 0;
+    const int L = (int)p->layers.size();
+    if (env_int("OGC_CLUSTER_WHOLE", 1) == 0) return 0;  // test override: split every layer
+    for (int l = 0; l + 1 < L; ++l)
+        if (cluster_layer_us(p, l, split, true) < cluster_layer_us(p, l, split, false)) mask |= 1u << l;
+    return mask;
+}
+
 double estimate_cluster_us(const ogc_mlp_plan_s* p, int split) {
     const ClusterCost& c = kCluster[p->desc.dtype];
-    const int L = (int)p->layers.size(), waves = 8 * split;
+    const int L = (int)p->layers.size();
     const double tiles = (p->desc.m + 31) / 32;
+    const uint32_t whole = cluster_whole_layers(p, split);
     double t = c.c0, all_mb = 0.0;
     for (int l = 0; l < L; ++l) {
         const LayerPlan& lp = p->layers[l];
-        const bool last = l == L - 1;
-        const int nb = last ? (lp.d.n + 31) / 32 : lp.nb_out;
-        const double kb = (double)lp.kp * p->esz;  // bytes of a row of the layer's input
-        int wg = 0;                                // channel blocks of the busiest member
-        for (int w = 0; w < 8 && w < nb; ++w) wg += (nb - w + waves - 1) / waves;
-        const int per_wave = (nb + waves - 1) / waves;
-        t += c.per_mb * kb * 32.0 * wg / 1e6 + c.group * std::ceil(kb / 128.0) * ((per_wave + 3) / 4) + c.per_layer;
-        if (!last) t += c.barrier + c.copy_mb * ((double)p->layers[l + 1].kp * p->esz * 32.0) / 1e6;
-        all_mb += kb * 32.0 * nb / 1e6;
+        const int nb = l == L - 1 ? (lp.d.n + 31) / 32 : lp.nb_out;
+        const bool w = (whole >> l) & 1;
+        t += cluster_layer_us(p, l, split, w);
+        all_mb += (double)lp.kp * p->esz * 32.0 * nb / 1e6 * (w ? split : 1);
     }
     // every tile streams all the weights through the L2s: the aggregate term counts beyond a few dozen tiles
     return t * (1.0 + c.fill * std::min(1.0, tiles * split / 256.0)) + c.all_mb * tiles * all_mb;
@@ -423,6 +448,8 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
         } else if (forced < 0 && desc->dtype != OGC_F32) {
             for (int split = 2; split <= 16; split *= 2) {
                 if (ogc_cluster_xcds(m_blocks, split, p->cluster_spread) < 0) continue;
+                // no layer worth an exchange: the members would all run the fused kernel's work
+                if (cluster_whole_layers(p, split) == (1u << (L - 1)) - 1u) continue;
                 const double e = estimate_cluster_us(p, split);
                 if (e < p->mode_us[2]) {
                     p->mode_us[2] = e;
@@ -632,6 +659,7 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
         }
         if (plan->cluster_split > 0) {
             c.lds_buf_bytes = plan->lds_buf_bytes;
+            c.cluster_whole_mask = cluster_whole_layers(plan, plan->cluster_split);
             if (ev && hipEventRecord(ev[0], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
             const int rc = ogc_launch_cluster(plan->desc.dtype, &c, m_blocks, plan->cluster_split, plan->cluster_spread, (void*)(blob + plan->sync_off), stream);
             if (rc != 0) return OGC_ERR_DEVICE;

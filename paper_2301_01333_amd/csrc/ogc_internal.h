@@ -64,6 +64,7 @@ struct OgcChainArgs {
     int32_t fused_xcds;     // fused kernel: row tiles are dealt to this many of the 8 XCDs (workgroup b runs on XCD b%8)
     int32_t fused_tiles;    // fused kernel: number of 32-row tiles
     int32_t cluster_split;  // cluster kernel: workgroups that share a row tile
+    uint32_t cluster_whole_mask;  // cluster kernel: bit l set = every member computes the whole of layer l (no exchange)
     OgcLayerArgs layer[OGC_MAX_LAYERS];
 };
 

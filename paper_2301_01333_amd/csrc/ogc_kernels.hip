@@ -857,14 +857,19 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_chain_kernel(co
     }
     __syncthreads();
     unsigned long long* ctr = sync + (size_t)tile * OGC_SYNC_STRIDE;  // [0] arrivals, [1] members finished
+    int barriers = 0;
     for (int l = 0; l < c.n_layers; ++l) {
         const OgcLayerArgs& a = c.layer[l];
         const uint8_t* xin = (l & 1) ? buf1 : buf0;
         uint8_t* xout = (l & 1) ? buf0 : buf1;
-        if (l + 1 < c.n_layers) {
+        if (l + 1 < c.n_layers && ((c.cluster_whole_mask >> l) & 1)) {
+            // a layer too small to be worth an exchange: every member computes all of it, as the fused kernel does
+            fused_layer<DT, 0>(a, xin, xout, m0, wave, OGC_FUSED_WAVES, lane);
+            __syncthreads();
+        } else if (l + 1 < c.n_layers) {
             uint8_t* ytile = a.y + (size_t)tile * a.KC_out * 512;  // the tile in blocked layout = its LDS image
             fused_layer<DT, 0>(a, xin, GlobalY{ytile}, m0, vwave, vwaves, lane);
-            coop_grid_barrier(ctr, (unsigned long long)(l + 1) * S, tid);
+            coop_grid_barrier(ctr, (unsigned long long)(++barriers) * S, tid);
             const int pieces = a.KC_out * 32;
             int p = tid;
             for (; p + 3 * OGC_FUSED_THREADS < pieces; p += 4 * OGC_FUSED_THREADS) {
@@ -881,7 +886,7 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_chain_kernel(co
         }
     }
     // the last member out resets its tile's counters for the next run (by then nobody waits on them)
-    if (c.n_layers > 1) {
+    if (barriers > 0) {
         __syncthreads();
         if (tid == 0) {
             const unsigned long long done = __hip_atomic_fetch_add(ctr + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
