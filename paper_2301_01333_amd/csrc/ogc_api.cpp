@@ -204,8 +204,8 @@ constexpr double kProfiledLaunchExtraUs = 2.0;
 struct FusedCost { float f0, per_mb, per_layer, fill; };
 struct CoopCost { float c0, barrier, block, step, fill; };
 const FusedCost kFused[3] = {{4.706f, 30.663f, 1.174f, 0.225f}, {6.228f, 10.346f, 0.328f, 0.433f}, {5.824f, 10.761f, 0.669f, 0.357f}};
-const CoopCost kCoop[3] = {{2.837f, 2.769f, 0.725f, 0.0399f, 0.767f}, {0.951f, 2.838f, 0.949f, 0.0211f, 0.871f},
-                           {0.610f, 2.891f, 0.956f, 0.0215f, 0.859f}};
+const CoopCost kCoop[3] = {{3.243f, 2.691f, 0.809f, 0.0321f, 0.821f}, {1.153f, 2.756f, 1.005f, 0.0130f, 0.957f},
+                           {0.611f, 2.886f, 1.007f, 0.0172f, 0.867f}};
 
 // One workgroup per 32 rows streams every weight: flat in the batch up to 8192 rows (256 CUs), then in rounds.
 double estimate_fused_us(const ogc_mlp_plan_s* p) {

@@ -731,6 +731,18 @@ OGC_DEV v4i load16_coherent(const uint8_t* p) {
     return (v4i){(int)(uint32_t)lo, (int)(uint32_t)(lo >> 32), (int)(uint32_t)hi, (int)(uint32_t)(hi >> 32)};
 }
 
+// four 16-byte pieces of other workgroups' results, read at system scope, in flight together
+OGC_DEV void load16x4_coherent(const uint8_t* p0, const uint8_t* p1, const uint8_t* p2, const uint8_t* p3, v4i (&v)[4]) {
+    asm volatile("global_load_dwordx4 %0, %4, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %1, %5, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %2, %6, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %3, %7, off sc0 sc1\n\t"
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+                 : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+                 : "memory");
+}
+
 template <int DT>
 __global__ void __launch_bounds__(OGC_COOP_THREADS) ogc_coop_chain_kernel(const OgcChainArgs c, unsigned long long* sync, int m_blocks) {
     __shared__ uint32_t red[OGC_COOP_WAVES - 1][16][64];  // partial accumulators of waves 1..7
@@ -755,10 +767,14 @@ __global__ void __launch_bounds__(OGC_COOP_THREADS) ogc_coop_chain_kernel(const 
                 v4i wf[OGC_COOP_U], xf[OGC_COOP_U];
 #pragma unroll
                 for (int u = 0; u < OGC_COOP_U; ++u) wf[u] = *(const v4i*)(wp + (size_t)(kp + u * OGC_COOP_WAVES) * 1024);
+                if (first) {
 #pragma unroll
-                for (int u = 0; u < OGC_COOP_U; ++u)
-                    xf[u] = first ? load_plain_chunk<DT>(a, row, (kp + u * OGC_COOP_WAVES) * 32 + kb0)
-                                  : load16_coherent(xp + (size_t)(kp + u * OGC_COOP_WAVES) * 1024);
+                    for (int u = 0; u < OGC_COOP_U; ++u) xf[u] = load_plain_chunk<DT>(a, row, (kp + u * OGC_COOP_WAVES) * 32 + kb0);
+                } else {
+                    static_assert(OGC_COOP_U == 4, "the coherent load below takes four pieces");
+                    const uint8_t* g = xp + (size_t)kp * 1024;
+                    load16x4_coherent(g, g + OGC_COOP_WAVES * 1024, g + 2 * OGC_COOP_WAVES * 1024, g + 3 * OGC_COOP_WAVES * 1024, xf);
+                }
 #pragma unroll
                 for (int u = 0; u < OGC_COOP_U; ++u) mma32<DT>(acc, wf[u], xf[u]);
             }
@@ -818,18 +834,6 @@ __global__ void ogc_zero_sync_kernel(unsigned long long* sync) {
 // written through and the copy back uses system-scope loads, as in the cooperative kernel above, whose bounded
 // barrier wait and counter reset this kernel shares.  sync[1]: workgroups finished; sync[2 + tile]: arrivals.
 // ------------------------------------------------------------------------------------------------
-// four 16-byte pieces of other workgroups' results, read at system scope, in flight together
-OGC_DEV void load16x4_coherent(const uint8_t* p0, const uint8_t* p1, const uint8_t* p2, const uint8_t* p3, v4i (&v)[4]) {
-    asm volatile("global_load_dwordx4 %0, %4, off sc0 sc1\n\t"
-                 "global_load_dwordx4 %1, %5, off sc0 sc1\n\t"
-                 "global_load_dwordx4 %2, %6, off sc0 sc1\n\t"
-                 "global_load_dwordx4 %3, %7, off sc0 sc1\n\t"
-                 "s_waitcnt vmcnt(0)"
-                 : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
-                 : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
-                 : "memory");
-}
-
 template <int DT>
 __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_chain_kernel(const OgcChainArgs c, unsigned long long* sync) {
     extern __shared__ __align__(16) uint8_t smem[];

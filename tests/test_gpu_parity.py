@@ -467,7 +467,7 @@ def test_cluster_kernel_table1_mlp2(oracle_mod, monkeypatch, dtype, m, split):
     d.close()
 
 
-@pytest.mark.parametrize("idx,mode", [(1, "fused"), (3, "fused"), (2, "coop"), (5, "per_layer")])
+@pytest.mark.parametrize("idx,mode", [(1, "fused"), (3, "fused"), (2, "coop"), (3, "auto"), (5, "per_layer")])
 def test_runs_recorded_in_a_hip_graph_replay_correctly(oracle_mod, idx, mode):
     """ogc_mlp_run under stream capture: the graph is replayed several times with eager work and synchronisations
     in between, and every replay must reproduce the eager result (the library records kernels only, no memsets)."""
