@@ -61,8 +61,9 @@ struct OgcLayerArgs {
 struct OgcChainArgs {
     int32_t n_layers;
     int32_t lds_buf_bytes;  // size of one LDS activation buffer
-    int32_t fused_xcds;     // fused kernel: row tiles are dealt to this many of the 8 XCDs (workgroup b runs on XCD b%8)
-    int32_t fused_tiles;    // fused kernel: number of 32-row tiles
+    int32_t fused_xcds;     // fused and cluster kernels: row tiles are dealt to this many of the 8 XCDs (workgroup b runs on
+                            // XCD b%8); cluster kernel, 0: a tile's members are consecutive workgroups instead
+    int32_t fused_tiles;    // fused and cluster kernels: number of 32-row tiles
     int32_t cluster_split;  // cluster kernel: workgroups that share a row tile
     uint32_t cluster_whole_mask;  // cluster kernel: bit l set = every member computes the whole of layer l (no exchange)
     OgcLayerArgs layer[OGC_MAX_LAYERS];
