@@ -48,6 +48,7 @@ struct ogc_mlp_plan_s {
     size_t sync_off;                    // cooperative mode: counters at the end of the packed blob
     int cluster_split;                  // cooperative mode: 0 = blocks dealt to all workgroups, n = n workgroups per row tile
     int cluster_spread;                 // cluster kernel: a tile's members on different XCDs (weights beyond one L2)
+    int cluster_ksplit;                 // cluster kernel: the waves of a member split K (one LDS buffer) instead of the channel blocks
     std::vector<size_t> slot_off, slot_size;
     std::atomic<int> prepacked;
 };
@@ -286,6 +287,30 @@ double estimate_cluster_us(const ogc_mlp_plan_s* p, int split) {
     return t * (1.0 + c.fill * std::min(1.0, tiles * split / 256.0)) + c.all_mb * tiles * all_mb;
 }
 
+// The cluster kernel whose waves split K inside a member: member j of S takes the channel blocks j, j + S, ... one
+// after the other (rounds), each over the whole of K on its eight waves; every layer but the last is exchanged.
+// 899 timed chains (the 12 calibration shapes, batch 32-2048, splits 2-32, three dtypes): 4-7 % rms, worst 18 %.
+struct KsplitCost { float c0, block, step, barrier, copy_mb, fill, all_mb; };
+const KsplitCost kKsplit[3] = {{3.809f, 0.956f, 0.3723f, 2.226f, 11.90f, 0.0524f, 0.0362f},
+                               {4.556f, 1.067f, 0.1953f, 1.669f, 12.54f, 0.0527f, 0.0202f},
+                               {3.929f, 1.221f, 0.1804f, 1.674f, 15.91f, 0.0784f, 0.0119f}};
+double estimate_cluster_ksplit_us(const ogc_mlp_plan_s* p, int split) {
+    const KsplitCost& c = kKsplit[p->desc.dtype];
+    const int L = (int)p->layers.size();
+    const double tiles = (p->desc.m + 31) / 32;
+    double t = c.c0, all_mb = 0.0;
+    for (int l = 0; l < L; ++l) {
+        const LayerPlan& lp = p->layers[l];
+        const bool last = l == L - 1;
+        const int nb = last ? (lp.d.n + 31) / 32 : lp.nb_out;
+        const double kb = (double)lp.kp * p->esz;
+        t += ((nb + split - 1) / split) * (c.block + c.step * kb / 256.0);  // kb/32 k-steps over eight waves
+        if (!last) t += c.barrier + c.copy_mb * ((double)p->layers[l + 1].kp * p->esz * 32.0) / 1e6;
+        all_mb += kb * 32.0 * nb / 1e6;
+    }
+    return t * (1.0 + c.fill * std::min(1.0, tiles * split / 256.0)) + c.all_mb * tiles * all_mb;
+}
+
 ogc_status validate(const ogc_mlp_desc* d) {
     if (!d || !d->layers) return OGC_ERR_INVALID_ARG;
     if (d->dtype != OGC_F32 && d->dtype != OGC_BF16 && d->dtype != OGC_I8) return OGC_ERR_INVALID_ARG;
@@ -435,17 +460,23 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
     p->mode_us[2] = (!blocked_io && L > 1) ? estimate_coop_us(p) : -1.0;
     // The cooperative mode has two kernels: blocks dealt to all workgroups (above), or a few workgroups per row tile
     // (the cluster kernel).  The split with the lowest estimate competes; OGC_CLUSTER_SPLIT overrides (0: never).
-    p->cluster_split = 0;
+    p->cluster_split = p->cluster_ksplit = 0;
     p->cluster_spread = wbytes > (size_t)3000000;  // weights beyond one XCD's L2: a tile's members on different XCDs
-    if (p->mode_us[2] >= 0 && fused_fits) {
+    const bool ksplit_fits = ogc_cluster_ksplit_lds_bytes((size_t)max_kc * 512) <= ogc_fused_lds_limit();
+    const int forced = env_int("OGC_CLUSTER_SPLIT", -1);
+    const int forced_ks = env_int("OGC_CLUSTER_KSPLIT", -1);
+    if (p->mode_us[2] >= 0 && forced > 0 && forced_ks == 1) {
+        // test override: the k-split variant with this many members per tile
+        if (ksplit_fits && ogc_cluster_xcds((desc->m + 31) / 32, forced, p->cluster_spread) >= 0) {
+            p->cluster_split = forced;
+            p->cluster_ksplit = 1;
+            p->mode_us[2] = estimate_cluster_ksplit_us(p, forced);
+        }
+    } else if (p->mode_us[2] >= 0 && forced < 0) {
+        // the model's choice among the cooperative kernel, the cluster kernel (channel blocks split over the waves
+        // of all members) and its k-split variant, each with its best split
         const int m_blocks = (desc->m + 31) / 32;
-        const int forced = env_int("OGC_CLUSTER_SPLIT", -1);
-        if (forced > 0) {
-            if (ogc_cluster_xcds(m_blocks, forced, p->cluster_spread) >= 0) {
-                p->cluster_split = forced;
-                if (desc->dtype != OGC_F32) p->mode_us[2] = estimate_cluster_us(p, forced);
-            }
-        } else if (forced < 0 && desc->dtype != OGC_F32) {
+        if (fused_fits && desc->dtype != OGC_F32) {
             for (int split = 2; split <= 16; split *= 2) {
                 if (ogc_cluster_xcds(m_blocks, split, p->cluster_spread) < 0) continue;
                 // no layer worth an exchange: the members would all run the fused kernel's work
@@ -454,7 +485,27 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
                 if (e < p->mode_us[2]) {
                     p->mode_us[2] = e;
                     p->cluster_split = split;
+                    p->cluster_ksplit = 0;
                 }
+            }
+        }
+        if (ksplit_fits && forced_ks != 0) {
+            for (int split = 2; split <= 32; split *= 2) {
+                if (ogc_cluster_xcds(m_blocks, split, p->cluster_spread) < 0) continue;
+                const double e = estimate_cluster_ksplit_us(p, split);
+                if (e < p->mode_us[2]) {
+                    p->mode_us[2] = e;
+                    p->cluster_split = split;
+                    p->cluster_ksplit = 1;
+                }
+            }
+        }
+    } else if (p->mode_us[2] >= 0 && fused_fits) {
+        const int m_blocks = (desc->m + 31) / 32;
+        if (forced > 0) {
+            if (ogc_cluster_xcds(m_blocks, forced, p->cluster_spread) >= 0) {
+                p->cluster_split = forced;
+                if (desc->dtype != OGC_F32) p->mode_us[2] = estimate_cluster_us(p, forced);
             }
         }
     }
@@ -501,7 +552,7 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
     if (mode == OGC_MODE_COOP) off += (size_t)OGC_SYNC_WORDS * 8;
     p->packed_bytes = off;
     p->partial_off = p->partial_bytes = 0;
-    if (mode != OGC_MODE_COOP) p->cluster_split = 0;
+    if (mode != OGC_MODE_COOP) p->cluster_split = p->cluster_ksplit = 0;
     if (mode == OGC_MODE_COOP) {
         assign_buffers(p);
     } else if (mode == OGC_MODE_PER_LAYER) {
@@ -659,9 +710,10 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
         }
         if (plan->cluster_split > 0) {
             c.lds_buf_bytes = plan->lds_buf_bytes;
-            c.cluster_whole_mask = cluster_whole_layers(plan, plan->cluster_split);
+            c.cluster_whole_mask = plan->cluster_ksplit ? 0u : cluster_whole_layers(plan, plan->cluster_split);
             if (ev && hipEventRecord(ev[0], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
-            const int rc = ogc_launch_cluster(plan->desc.dtype, &c, m_blocks, plan->cluster_split, plan->cluster_spread, (void*)(blob + plan->sync_off), stream);
+            const int rc = ogc_launch_cluster(plan->desc.dtype, plan->cluster_ksplit, &c, m_blocks, plan->cluster_split, plan->cluster_spread,
+                                              (void*)(blob + plan->sync_off), stream);
             if (rc != 0) return OGC_ERR_DEVICE;
             if (ev && hipEventRecord(ev[1], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
             return OGC_OK;
@@ -758,7 +810,7 @@ const char* ogc_mlp_kernel_name(ogc_mlp_plan_t plan, int32_t layer) {
     if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return nullptr;
     if (plan->mode == OGC_MODE_FUSED) return ogc_fused_kernel_name(plan->desc.dtype);
     if (plan->mode == OGC_MODE_COOP)
-        return plan->cluster_split > 0 ? ogc_cluster_kernel_name(plan->desc.dtype) : ogc_coop_kernel_name(plan->desc.dtype);
+        return plan->cluster_split > 0 ? ogc_cluster_kernel_name(plan->desc.dtype, plan->cluster_ksplit) : ogc_coop_kernel_name(plan->desc.dtype);
     const int L = (int)plan->layers.size();
     const ogc_layer_desc& d = plan->layers[layer].d;
     return ogc_layer_kernel_name(plan->desc.dtype, plan->layers[layer].tile,

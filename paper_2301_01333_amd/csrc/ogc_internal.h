@@ -89,10 +89,11 @@ int ogc_launch_fused(int dtype, const OgcChainArgs* c, int m_blocks, void* strea
 int ogc_launch_coop(int dtype, const OgcChainArgs* c, int m_blocks, int grid, void* sync, void* stream);
 int ogc_launch_zero_sync(void* sync, void* stream);
 int ogc_cluster_xcds(int m_blocks, int split, int spread);
-int ogc_launch_cluster(int dtype, const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync, void* stream);
+int ogc_launch_cluster(int dtype, int ksplit, const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync, void* stream);
+size_t ogc_cluster_ksplit_lds_bytes(size_t lds_buf_bytes);
 int ogc_device_cu_count(void);
 const char* ogc_coop_kernel_name(int dtype);
-const char* ogc_cluster_kernel_name(int dtype);
+const char* ogc_cluster_kernel_name(int dtype, int ksplit);
 int ogc_launch_prepack_weights(const void* w, void* out, int K, int N, int KC, int NPw, int esz, void* stream);
 int ogc_launch_prepack_params(int dtype, const void* w, const float* w_scale, const float* bias, float in_scale, int in_zp,
                               int K, int N, int NPw, float* scale_out, float* bias_out, int32_t* ncomp_out, void* stream);

@@ -902,6 +902,117 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_chain_kernel(co
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Cluster chain kernel with the reduction axis split inside a workgroup: the members of a tile take whole channel
+// blocks (member j: blocks j, j + split, ...) and the eight waves of a member split K between them, as in the
+// cooperative kernel, but with the activations read from the member's LDS copy of the tile instead of global
+// memory.  For chains whose matrix work per block is large against its weight stream (fp32: a 32x32 block over
+// K = 1024 is 3.4 us of one CU's MFMA rate), where splitting the channel blocks alone leaves most waves idle.
+// One LDS activation buffer: a layer's input is dead once its members have met at the barrier, and the copy of the
+// layer's output takes its place; the reduction scratch (waves 1..7, 28 KiB) follows it.  Every layer but the
+// last is exchanged.
+// ------------------------------------------------------------------------------------------------
+#define OGC_KS_RED_BYTES ((OGC_FUSED_WAVES - 1) * 16 * 64 * 4)
+
+template <int DT>
+__global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_ksplit_chain_kernel(const OgcChainArgs c, unsigned long long* sync) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int S = c.cluster_split;
+    int tile, member;
+    if (c.fused_xcds == 0) {
+        tile = blockIdx.x / S, member = blockIdx.x % S;
+    } else {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        tile = (slot / S) * c.fused_xcds + xcd, member = slot % S;
+        if (xcd >= c.fused_xcds || tile >= c.fused_tiles) return;
+    }
+    const int m0 = tile * 32;
+    uint8_t* buf = smem;
+    uint32_t(*red)[16][64] = (uint32_t(*)[16][64])(smem + c.lds_buf_bytes);
+    {
+        const OgcLayerArgs& a = c.layer[0];
+        const int pieces = a.KC * 32;
+        for (int p = tid; p < pieces; p += OGC_FUSED_THREADS) {
+            const int mr = p & 31, kc = p >> 5;
+            *(v4i*)(buf + (size_t)p * 16) = load_plain_chunk<DT>(a, m0 + mr, kc * 16);
+        }
+    }
+    __syncthreads();
+    unsigned long long* ctr = sync + (size_t)tile * OGC_SYNC_STRIDE;  // [0] arrivals, [1] members finished
+    int barriers = 0;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const OgcLayerArgs& a = c.layer[l];
+        const bool last = l + 1 == c.n_layers;
+        const int nb = last ? ((a.N + 31) >> 5) : a.NB_out;
+        const int KP2 = a.KC >> 1;  // 32-byte k-steps
+        uint8_t* ytile = last ? nullptr : a.y + (size_t)tile * a.KC_out * 512;
+        for (int bn = member; bn < nb; bn += S) {
+            typename AccT<DT>::type acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0;
+            const uint8_t* wp = a.w + (size_t)bn * a.KC * 512 + lane * 16;
+            const uint8_t* xp = buf + lane * 16;
+            int kp = wave;
+            for (; kp + 3 * OGC_FUSED_WAVES < KP2; kp += 4 * OGC_FUSED_WAVES) {  // four k-steps of this wave in flight
+                v4i wf[4], xf[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) wf[u] = *(const v4i*)(wp + (size_t)(kp + u * OGC_FUSED_WAVES) * 1024);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) xf[u] = *(const v4i*)(xp + (size_t)(kp + u * OGC_FUSED_WAVES) * 1024);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) mma32<DT>(acc, wf[u], xf[u]);
+            }
+            for (; kp < KP2; kp += OGC_FUSED_WAVES) mma32<DT>(acc, *(const v4i*)(wp + (size_t)kp * 1024), *(const v4i*)(xp + (size_t)kp * 1024));
+            // k-slices of waves 1..7 to LDS, wave 0 adds them in ascending order (a fixed order: deterministic)
+            if (wave > 0) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    if constexpr (DT == OGC_I8) red[wave - 1][r][lane] = (uint32_t)acc[r];
+                    else red[wave - 1][r][lane] = __builtin_bit_cast(uint32_t, (float)acc[r]);
+                }
+            }
+            __syncthreads();
+            if (wave == 0) {
+#pragma unroll
+                for (int w = 0; w < OGC_FUSED_WAVES - 1; ++w)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        if constexpr (DT == OGC_I8) acc[r] += (int)red[w][r][lane];
+                        else acc[r] += __builtin_bit_cast(float, red[w][r][lane]);
+                    }
+                if (last) epilogue_block<DT, 1>(acc, a, bn * 32, m0, lane, (uint8_t*)nullptr);
+                else epilogue_block<DT, 0>(acc, a, bn * 32, m0, lane, GlobalY{ytile});
+            }
+            __syncthreads();  // red is reused by the next block
+        }
+        if (!last) {
+            coop_grid_barrier(ctr, (unsigned long long)(++barriers) * S, tid);
+            const int pieces = a.KC_out * 32;
+            int p = tid;
+            for (; p + 3 * OGC_FUSED_THREADS < pieces; p += 4 * OGC_FUSED_THREADS) {
+                v4i v[4];
+                const uint8_t* g = ytile + (size_t)p * 16;
+                load16x4_coherent(g, g + OGC_FUSED_THREADS * 16, g + 2 * OGC_FUSED_THREADS * 16, g + 3 * OGC_FUSED_THREADS * 16, v);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) *(v4i*)(buf + ((size_t)p + u * OGC_FUSED_THREADS) * 16) = v[u];
+            }
+            for (; p < pieces; p += OGC_FUSED_THREADS) *(v4i*)(buf + (size_t)p * 16) = load16_coherent(ytile + (size_t)p * 16);
+            __syncthreads();
+        }
+    }
+    if (barriers > 0) {
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned long long done = __hip_atomic_fetch_add(ctr + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (done == (unsigned long long)S - 1) {
+                __hip_atomic_store(ctr, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(ctr + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
 // Second pass of a split-K layer: adds the partial accumulators of the k ranges in ascending order (a fixed
 // order: the result does not depend on which workgroup finished first) and applies the ordinary epilogue.
 // One wave per 32x32 block; the partial buffer holds every wave's accumulator registers as they were.
@@ -1105,9 +1216,9 @@ extern "C" int ogc_cluster_xcds(int m_blocks, int split, int spread) {
     return -1;
 }
 
-template <int DT> static int launch_cluster_t(const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync, hipStream_t stream) {
-    auto kern = ogc_cluster_chain_kernel<DT>;
-    const size_t lds = (size_t)2 * c->lds_buf_bytes;
+template <int DT, int KSPLIT> static int launch_cluster_t(const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync, hipStream_t stream) {
+    auto kern = KSPLIT ? ogc_cluster_ksplit_chain_kernel<DT> : ogc_cluster_chain_kernel<DT>;
+    const size_t lds = KSPLIT ? (size_t)c->lds_buf_bytes + OGC_KS_RED_BYTES : (size_t)2 * c->lds_buf_bytes;
     static size_t attr_max = 0;
     if (lds > attr_max) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1125,12 +1236,24 @@ template <int DT> static int launch_cluster_t(const OgcChainArgs* c, int m_block
     return (int)hipGetLastError();
 }
 
-extern "C" int ogc_launch_cluster(int dtype, const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync, void* stream) {
+extern "C" size_t ogc_cluster_ksplit_lds_bytes(size_t lds_buf_bytes) { return lds_buf_bytes + OGC_KS_RED_BYTES; }
+
+// ksplit: the kernel whose waves split K inside a member (one LDS buffer + reduction scratch) instead of the one
+// whose waves take different channel blocks (two LDS buffers)
+extern "C" int ogc_launch_cluster(int dtype, int ksplit, const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync,
+                                  void* stream) {
     hipStream_t s = (hipStream_t)stream;
+    if (ksplit) {
+        switch (dtype) {
+        case OGC_F32: return launch_cluster_t<OGC_F32, 1>(c, m_blocks, split, spread, sync, s);
+        case OGC_BF16: return launch_cluster_t<OGC_BF16, 1>(c, m_blocks, split, spread, sync, s);
+        default: return launch_cluster_t<OGC_I8, 1>(c, m_blocks, split, spread, sync, s);
+        }
+    }
     switch (dtype) {
-    case OGC_F32: return launch_cluster_t<OGC_F32>(c, m_blocks, split, spread, sync, s);
-    case OGC_BF16: return launch_cluster_t<OGC_BF16>(c, m_blocks, split, spread, sync, s);
-    default: return launch_cluster_t<OGC_I8>(c, m_blocks, split, spread, sync, s);
+    case OGC_F32: return launch_cluster_t<OGC_F32, 0>(c, m_blocks, split, spread, sync, s);
+    case OGC_BF16: return launch_cluster_t<OGC_BF16, 0>(c, m_blocks, split, spread, sync, s);
+    default: return launch_cluster_t<OGC_I8, 0>(c, m_blocks, split, spread, sync, s);
     }
 }
 
@@ -1144,7 +1267,10 @@ extern "C" int ogc_device_cu_count(void) {
 extern "C" const char* ogc_coop_kernel_name(int dtype) {
     return dtype == OGC_F32 ? "ogc_coop_chain_kernel<0>" : dtype == OGC_BF16 ? "ogc_coop_chain_kernel<1>" : "ogc_coop_chain_kernel<2>";
 }
-extern "C" const char* ogc_cluster_kernel_name(int dtype) {
+extern "C" const char* ogc_cluster_kernel_name(int dtype, int ksplit) {
+    if (ksplit)
+        return dtype == OGC_F32 ? "ogc_cluster_ksplit_chain_kernel<0>"
+                                : dtype == OGC_BF16 ? "ogc_cluster_ksplit_chain_kernel<1>" : "ogc_cluster_ksplit_chain_kernel<2>";
     return dtype == OGC_F32 ? "ogc_cluster_chain_kernel<0>" : dtype == OGC_BF16 ? "ogc_cluster_chain_kernel<1>" : "ogc_cluster_chain_kernel<2>";
 }
 

@@ -411,19 +411,23 @@ def test_coop_runs_back_to_back(oracle_mod):
 
 
 # ---------------------------------------------------------------- cluster kernel (a few workgroups per row tile)
-@pytest.mark.parametrize("split", [0, 2, 4, 8])
+@pytest.mark.parametrize("split", [0, 2, 4, 8, -2, -8, -32])
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "i8"])
 def test_cluster_kernel_ragged_and_edges(oracle_mod, monkeypatch, dtype, split):
     """The cooperative mode's second kernel: `split` workgroups share a 32-row tile, each computes every split-th
     group of channel blocks, and the tile travels through the workspace between layers.  OGC_CLUSTER_SPLIT forces
-    the split (0: the block-dealing kernel), so every split is checked against the oracle on every dtype."""
+    the split (0: the block-dealing kernel; negative here: the variant whose waves split K inside a member, forced
+    with OGC_CLUSTER_KSPLIT), so every variant is checked against the oracle on every dtype."""
+    ksplit, split = split < 0, abs(split)   # negative: the variant whose waves split K inside a member
     monkeypatch.setenv("OGC_CLUSTER_SPLIT", str(split))
+    monkeypatch.setenv("OGC_CLUSTER_KSPLIT", "1" if ksplit else "0")
     act2 = GELU if dtype != "i8" else RELU
     wl = synth.make_mlp(dtype, 77, [37, 130, 300, 9], [RELU, act2, RELU], seed=600, name="cluster-ragged")
     from paper_2301_01333_amd.harness import DeviceMLP
 
     d = DeviceMLP(wl, binding.OGC_MODE_COOP)
-    assert binding.ogc_mlp_kernel_name(d.mlp.plan, 0).startswith("ogc_cluster_chain_kernel" if split else "ogc_coop_chain_kernel")
+    want = "ogc_cluster_ksplit_chain_kernel" if ksplit else "ogc_cluster_chain_kernel" if split else "ogc_coop_chain_kernel"
+    assert binding.ogc_mlp_kernel_name(d.mlp.plan, 0).startswith(want)
     d.close()
     check(wl, "coop", oracle_mod)
     check(synth.make_mlp(dtype, 700, [100, 333, 72, 33], [RELU, RELU, NONE if dtype != "i8" else RELU], seed=601, name="cluster-22-tiles"),
@@ -438,19 +442,21 @@ def test_cluster_kernel_ragged_and_edges(oracle_mod, monkeypatch, dtype, split):
         check(synth.make_mlp(dtype, 70, [40, 64, 40], [GELU, NONE], seed=13, residual=True), "coop", oracle_mod)
 
 
-@pytest.mark.parametrize("dtype,m,split", [("i8", 256, 4), ("i8", 520, 8), ("bf16", 200, 4), ("bf16", 64, 16), ("i8", 2048, 4)])
+@pytest.mark.parametrize("dtype,m,split", [("i8", 256, 4), ("i8", 520, 8), ("bf16", 200, 4), ("bf16", 64, 16), ("i8", 2048, 4),
+                                           ("f32", 512, -16), ("f32", 200, -32), ("i8", 256, -32), ("bf16", 1024, -8)])
 def test_cluster_kernel_table1_mlp2(oracle_mod, monkeypatch, dtype, m, split):
     """Table I's MLP-2 through the cluster kernel: int8 weights fit one XCD's L2 (a tile's members share an XCD), the
     bf16 weights do not (members on different XCDs); many runs in a row keep giving the first run's result (each
     tile's members reset their counters at the end of a run)."""
     from paper_2301_01333_amd.harness import DeviceMLP
 
-    monkeypatch.setenv("OGC_CLUSTER_SPLIT", str(split))
-    dims = [479, 1024, 1024, 512, 256, 1]
+    monkeypatch.setenv("OGC_CLUSTER_SPLIT", str(abs(split)))
+    monkeypatch.setenv("OGC_CLUSTER_KSPLIT", "1" if split < 0 else "0")   # negative: the k-split variant (fp32 rows of
+    dims = [479, 1024, 1024, 512, 256, 1]                                  # 1024 values fit only its single LDS buffer)
     acts = [RELU] * 4 + [SIGM if dtype == "i8" else NONE]
     wl = synth.make_mlp(dtype, m, dims, acts, seed=77, last_f32=(dtype == "i8"), name="cluster-mlp2")
     d = DeviceMLP(wl, binding.OGC_MODE_COOP)
-    assert binding.ogc_mlp_kernel_name(d.mlp.plan, 0).startswith("ogc_cluster_chain_kernel")
+    assert binding.ogc_mlp_kernel_name(d.mlp.plan, 0).startswith("ogc_cluster_ksplit_chain_kernel" if split < 0 else "ogc_cluster_chain_kernel")
     d.run()
     first = d.result().copy()
     rows = slice(0, m) if m <= 520 else slice(m - 300, m)
@@ -458,7 +464,7 @@ def test_cluster_kernel_table1_mlp2(oracle_mod, monkeypatch, dtype, m, split):
     if dtype == "i8":
         assert_close(first[rows, :1], ref, 1e-5, "MLP-2 int8, cluster kernel")
     else:
-        assert_close(as_f32(wl, first[rows, :1]), as_f32(wl, ref), TOL[dtype], "MLP-2 bf16, cluster kernel")
+        assert_close(as_f32(wl, first[rows, :1]), as_f32(wl, ref), TOL[dtype], "MLP-2 %s, cluster kernel" % dtype)
     for _ in range(3):
         d.y.fill_(0xCD)
         for _ in range(9):

@@ -102,7 +102,7 @@ def test_mode_choice_and_sizes():
     ls[-1].update(out=1, act=b.OGC_ACT_SIGMOID)
     p = b.ogc_mlp_plan(b.OGC_I8, 256, ls, 479, 1, 0, 0)
     assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_COOP
-    assert b.ogc_mlp_kernel_name(p, 0) == "ogc_cluster_chain_kernel<2>"
+    assert b.ogc_mlp_kernel_name(p, 0) in ("ogc_cluster_chain_kernel<2>", "ogc_cluster_ksplit_chain_kernel<2>")
     assert b.ogc_mlp_workspace_bytes(p) == 2 * 256 * 1024 and b.ogc_mlp_num_launches(p) == 1
     # packed weights: K padded to 64 (479 -> 512), rows padded to 32/64; per-channel params on top
     assert b.ogc_mlp_packed_bytes(p) >= 512 * 1024 + 1024 * 1024 + 1024 * 512 + 512 * 256 + 256 * 32
@@ -141,9 +141,19 @@ def test_cluster_split_override(monkeypatch):
     assert name(256) == "ogc_cluster_chain_kernel<2>"
     assert name(256, b.OGC_F32) == "ogc_cluster_chain_kernel<0>"
     assert name(32 * 65) == "ogc_coop_chain_kernel<2>"      # 65 tiles x 4 members do not fit 256 CUs
+    # the variant whose waves split K inside a member
+    monkeypatch.setenv("OGC_CLUSTER_KSPLIT", "1")
+    assert name(256) == "ogc_cluster_ksplit_chain_kernel<2>"
+    assert name(256, b.OGC_F32) == "ogc_cluster_ksplit_chain_kernel<0>"
+    assert name(32 * 65) == "ogc_coop_chain_kernel<2>"
+    # unset: the cost model's choice; OGC_CLUSTER_KSPLIT=0 keeps the k-split variant out of it
     monkeypatch.delenv("OGC_CLUSTER_SPLIT")
+    monkeypatch.setenv("OGC_CLUSTER_KSPLIT", "0")
     assert name(256) == "ogc_cluster_chain_kernel<2>"
-    assert name(256, b.OGC_F32) == "ogc_coop_chain_kernel<0>"  # never the model's choice for fp32
+    assert name(256, b.OGC_F32) == "ogc_coop_chain_kernel<0>"  # the channel-split kernel is never the model's choice for fp32
+    monkeypatch.delenv("OGC_CLUSTER_KSPLIT")
+    assert name(256).startswith("ogc_cluster_")
+    assert name(256, b.OGC_F32) == "ogc_cluster_ksplit_chain_kernel<0>"
 
 
 def test_buffer_reuse_is_ping_pong_for_a_chain():
@@ -285,7 +295,8 @@ def test_auto_mode_choice_follows_the_cost_models():
     lay = [layer(64, 256), layer(256, 512), layer(512, 64)]
     pc = b.ogc_mlp_plan(b.OGC_I8, 100, lay, 64, 64, 0, b.OGC_MODE_COOP)
     pl = b.ogc_mlp_plan(b.OGC_I8, 100, lay, 64, 64, 0, b.OGC_MODE_FUSED)
-    assert b.ogc_mlp_num_launches(pc) == 1 and b.ogc_mlp_kernel_name(pc, 0) in ("ogc_coop_chain_kernel<2>", "ogc_cluster_chain_kernel<2>")
+    assert b.ogc_mlp_num_launches(pc) == 1 and b.ogc_mlp_kernel_name(pc, 0) in (
+        "ogc_coop_chain_kernel<2>", "ogc_cluster_chain_kernel<2>", "ogc_cluster_ksplit_chain_kernel<2>")
     assert b.ogc_mlp_workspace_bytes(pc) == 256 * 256 + 256 * 512
     assert b.ogc_mlp_packed_bytes(pc) == b.ogc_mlp_packed_bytes(pl) + 2048 * 8
     b.ogc_mlp_destroy(pc)
