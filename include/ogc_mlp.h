@@ -98,11 +98,14 @@ typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
  * template-parameter heuristic, Section III) and lays out the packed blob and the workspace.
  * Host only: no device call is made.  *out_plan is written only on OGC_OK.
  * OGC_MODE_COOP is the small-batch mode: one launch in which several workgroups share the work of a row tile
- * (multi-core loop and k-slicing, Section III) and meet at barriers between layers.  It has two kernels, and the
- * plan takes the one with the lower estimate: (a) all CUs share each layer's 32x32 output blocks, the waves of a
+ * (multi-core loop and k-slicing, Section III) and meet at barriers between layers.  It has three kernels, and the
+ * plan takes the one with the lowest estimate: (a) all CUs share each layer's 32x32 output blocks, the waves of a
  * workgroup split the reduction axis, device-wide barrier; (b) the cluster kernel: 2, 4, 8 or 16 workgroups per
  * 32-row tile, each keeps the tile in LDS and streams its share of the weights, the tile's members exchange their
- * channel blocks through the workspace at a barrier of their own (int8 and bf16 chains whose widest row fits LDS).
+ * channel blocks through the workspace at a barrier of their own (int8 and bf16 chains whose widest row fits LDS
+ * twice); (c) its k-split variant: 2 to 32 members per tile take whole channel blocks, the waves of a member split
+ * the reduction axis as in (a) but read the activations from the member's LDS copy of the tile (any dtype; the
+ * widest row has to fit LDS once).
  * The mode needs the workspace and keeps barrier counters in the packed blob (16 KiB at its end), so runs that
  * share a packed blob must not overlap in time; all its workgroups must be resident at once (the grid is at most
  * one per CU), so it is meant for a device that is not kept busy by other kernels for seconds: the barrier wait
@@ -114,7 +117,8 @@ typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
  * x or y with a mode other than per-layer.
  * For tests, environment variables read here override the cost model: in per-layer mode OGC_TILE (0..4: tile
  * configuration of every layer) and OGC_KSPLIT (log2 of the number of k ranges, 0..3); in cooperative mode
- * OGC_CLUSTER_SPLIT (0: kernel (a); n: kernel (b) with n workgroups per tile where they fit, any dtype) and
+ * OGC_CLUSTER_SPLIT (0: kernel (a); n: kernel (b) with n workgroups per tile where they fit, any dtype),
+ * OGC_CLUSTER_KSPLIT (1 together with OGC_CLUSTER_SPLIT=n: kernel (c) with n members; 0: never kernel (c)) and
  * OGC_CLUSTER_WHOLE=0 (kernel (b) exchanges after every layer, also the small ones it would compute whole). */
 ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc /*host*/, ogc_mlp_plan_t* out_plan /*host*/);
 
@@ -184,7 +188,7 @@ ogc_status ogc_mlp_estimated_us(ogc_mlp_plan_t plan, int32_t layer, float* us);
 
 /* The cost models' estimates of the whole chain in microseconds, by which OGC_MODE_AUTO chose the mode:
  * us[0] layer by layer (sum of the layers' estimates), us[1] the fused whole-chain kernel, us[2] the cooperative
- * mode (the lower of its two kernels' estimates); -1 where a mode is not admissible (fused: the widest layer does not fit LDS, or bf16 / fp32 weights
+ * mode (the lowest of its kernels' estimates); -1 where a mode is not admissible (fused: the widest layer does not fit LDS, or bf16 / fp32 weights
  * beyond 2.5 MB; cooperative: a single layer, blocked tensors at the boundary) or not modelled.  Host only.
  * OGC_ERR_INVALID_ARG: NULL plan or us. */
 ogc_status ogc_mlp_mode_estimates(ogc_mlp_plan_t plan, float us[3]);
