@@ -1226,7 +1226,8 @@ template <int DT, int KSPLIT> static int launch_cluster_t(const OgcChainArgs* c,
         attr_max = lds;
     }
     const int xcds = ogc_cluster_xcds(m_blocks, split, spread);
-    if (xcds < 0) return (int)hipErrorInvalidValue;
+    // every member waits for the others of its tile: all of them need a CU at once (the plan assumed 256 CUs)
+    if (xcds < 0 || (long)m_blocks * split > ogc_device_cu_count()) return (int)hipErrorInvalidValue;
     OgcChainArgs args = *c;
     args.fused_xcds = xcds;  // 0: spread
     args.fused_tiles = m_blocks;
