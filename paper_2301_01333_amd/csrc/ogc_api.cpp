@@ -289,11 +289,11 @@ double estimate_cluster_us(const ogc_mlp_plan_s* p, int split) {
 
 // The cluster kernel whose waves split K inside a member: member j of S takes the channel blocks j, j + S, ... one
 // after the other (rounds), each over the whole of K on its eight waves; every layer but the last is exchanged.
-// 899 timed chains (the 12 calibration shapes, batch 32-2048, splits 2-32, three dtypes): 4-7 % rms, worst 18 %.
+// 899 timed chains (the 12 calibration shapes, batch 32-2048, splits 2-32, three dtypes): 4-6 % rms, worst 22 %.
 struct KsplitCost { float c0, block, step, barrier, copy_mb, fill, all_mb; };
-const KsplitCost kKsplit[3] = {{3.809f, 0.956f, 0.3723f, 2.226f, 11.90f, 0.0524f, 0.0362f},
-                               {4.556f, 1.067f, 0.1953f, 1.669f, 12.54f, 0.0527f, 0.0202f},
-                               {3.929f, 1.221f, 0.1804f, 1.674f, 15.91f, 0.0784f, 0.0119f}};
+const KsplitCost kKsplit[3] = {{4.405f, 1.028f, 0.3281f, 1.861f, 17.28f, 0.0529f, 0.0214f},
+                               {4.530f, 1.151f, 0.1613f, 1.583f, 12.22f, 0.0737f, 0.0132f},
+                               {3.661f, 1.266f, 0.1496f, 1.823f, 13.51f, 0.0859f, 0.0067f}};
 double estimate_cluster_ksplit_us(const ogc_mlp_plan_s* p, int split) {
     const KsplitCost& c = kKsplit[p->desc.dtype];
     const int L = (int)p->layers.size();

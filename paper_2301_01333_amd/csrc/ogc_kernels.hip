@@ -941,6 +941,8 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_ksplit_chain_ke
     __syncthreads();
     unsigned long long* ctr = sync + (size_t)tile * OGC_SYNC_STRIDE;  // [0] arrivals, [1] members finished
     int barriers = 0;
+    v4i wfirst[4];
+    bool have_first = false;
     for (int l = 0; l < c.n_layers; ++l) {
         const OgcLayerArgs& a = c.layer[l];
         const bool last = l + 1 == c.n_layers;
@@ -954,6 +956,15 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_ksplit_chain_ke
             const uint8_t* wp = a.w + (size_t)bn * a.KC * 512 + lane * 16;
             const uint8_t* xp = buf + lane * 16;
             int kp = wave;
+            if (have_first) {  // this member's first block of the layer: its first weight group came in under the barrier
+                have_first = false;
+                v4i xf[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) xf[u] = *(const v4i*)(xp + (size_t)(kp + u * OGC_FUSED_WAVES) * 1024);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) mma32<DT>(acc, wfirst[u], xf[u]);
+                kp += 4 * OGC_FUSED_WAVES;
+            }
             for (; kp + 3 * OGC_FUSED_WAVES < KP2; kp += 4 * OGC_FUSED_WAVES) {  // four k-steps of this wave in flight
                 v4i wf[4], xf[4];
 #pragma unroll
@@ -987,7 +998,30 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_ksplit_chain_ke
             __syncthreads();  // red is reused by the next block
         }
         if (!last) {
-            coop_grid_barrier(ctr, (unsigned long long)(++barriers) * S, tid);
+            // The barrier of the tile's members, with the next layer's first weight loads of this wave issued before it:
+            // they do not depend on the exchange and arrive while the members wait for each other.  Only wave 0
+            // has result stores to wait for; it issues its loads after that wait.
+            if (wave == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            {
+                const OgcLayerArgs& an = c.layer[l + 1];
+                const int nbn = (l + 2 == c.n_layers) ? ((an.N + 31) >> 5) : an.NB_out;
+                have_first = member < nbn && wave + 3 * OGC_FUSED_WAVES < (an.KC >> 1);
+                if (have_first) {
+                    const uint8_t* wn = an.w + (size_t)member * an.KC * 512 + lane * 16;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) wfirst[u] = *(const v4i*)(wn + (size_t)(wave + u * OGC_FUSED_WAVES) * 1024);
+                }
+            }
+            ++barriers;
+            __syncthreads();
+            if (tid == 0) {
+                __hip_atomic_fetch_add(ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned long long target = (unsigned long long)barriers * S;
+                int budget = 1 << 22;  // bounded, as in the cooperative kernel's barrier
+                while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target && --budget > 0)
+                    __builtin_amdgcn_s_sleep(1);
+            }
+            __syncthreads();
             const int pieces = a.KC_out * 32;
             int p = tid;
             for (; p + 3 * OGC_FUSED_THREADS < pieces; p += 4 * OGC_FUSED_THREADS) {

@@ -271,7 +271,7 @@ def test_auto_mode_choice_follows_the_cost_models():
     assert mode(b.OGC_BF16, 4096, [1024, 4096, 1024]) == b.OGC_MODE_PER_LAYER          # config 4
     assert mode(b.OGC_I8, 32768, [1024] * 5) == b.OGC_MODE_PER_LAYER                   # config 5
     assert mode(b.OGC_F32, 64, mlp1) == b.OGC_MODE_COOP and mode(b.OGC_F32, 8192, mlp1) == b.OGC_MODE_FUSED
-    assert mode(b.OGC_F32, 512, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_F32, 2048, mlp2) == b.OGC_MODE_PER_LAYER
+    assert mode(b.OGC_F32, 512, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_F32, 8192, mlp2) == b.OGC_MODE_PER_LAYER
     # 2048 rows of MLP-2: four workgroups per row tile (measured 48 us bf16, 29 us int8) beat a launch per layer (63)
     # and the fused kernel (34.5, int8 only)
     assert mode(b.OGC_BF16, 128, mlp2) == b.OGC_MODE_COOP and mode(b.OGC_BF16, 2048, mlp2) == b.OGC_MODE_COOP
