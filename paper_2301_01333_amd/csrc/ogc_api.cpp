@@ -202,9 +202,10 @@ void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int* ti
 // dtypes; 2-10 % rms).  A chain run layer by layer costs the sum of its layers' estimates less the event overhead
 // each of those carries from the way it was timed.
 constexpr double kProfiledLaunchExtraUs = 2.0;
-struct FusedCost { float f0, per_mb, per_layer, fill; };
+struct FusedCost { float f0, per_mb, per_layer, fill, per_block; };
 struct CoopCost { float c0, barrier, block, step, fill; };
-const FusedCost kFused[3] = {{4.706f, 30.663f, 1.174f, 0.225f}, {6.228f, 10.346f, 0.328f, 0.433f}, {5.824f, 10.761f, 0.669f, 0.357f}};
+const FusedCost kFused[3] = {{4.706f, 30.663f, 1.174f, 0.225f, 0.0f}, {6.163f, 9.580f, 0.0f, 0.429f, 0.363f},
+                             {4.515f, 9.308f, 0.474f, 0.288f, 0.496f}};
 const CoopCost kCoop[3] = {{3.243f, 2.691f, 0.809f, 0.0321f, 0.821f}, {1.153f, 2.756f, 1.005f, 0.0130f, 0.957f},
                            {0.611f, 2.886f, 1.007f, 0.0172f, 0.867f}};
 
@@ -213,8 +214,12 @@ double estimate_fused_us(const ogc_mlp_plan_s* p) {
     const FusedCost& c = kFused[p->desc.dtype];
     const double m = p->desc.m, rounds = std::max(1.0, m / 8192.0);
     double sum = 0.0;
-    for (const LayerPlan& lp : p->layers)
-        sum += c.per_mb * ((double)lp.kp * p->esz * round_up((size_t)lp.d.n, 32)) / 1e6 + c.per_layer;
+    for (const LayerPlan& lp : p->layers) {
+        // a wave takes every eighth 32-channel block: per_block is what a block costs besides its weight stream
+        // (first loads, epilogue), which counts for wide layers over a short K
+        const int nb = lp.nb_out > 0 ? lp.nb_out : (lp.d.n + 31) / 32;
+        sum += c.per_mb * ((double)lp.kp * p->esz * nb * 32.0) / 1e6 + c.per_layer + c.per_block * ((nb + 7) / 8);
+    }
     return c.f0 + rounds * sum * (1.0 + c.fill * std::min(1.0, m / 8192.0));
 }
 
