@@ -109,8 +109,9 @@ typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
  * The mode needs the workspace and keeps barrier counters in the packed blob (16 KiB at its end), so runs that
  * share a packed blob must not overlap in time; all its workgroups must be resident at once (the grid is at most
  * one per CU), so it is meant for a device that is not kept busy by other kernels for seconds: the barrier wait
- * is bounded and a timeout yields wrong data, not a hang.
- * OGC_MODE_AUTO takes the mode with the lowest estimate of three fitted cost models (ogc_mlp_mode_estimates); a
+ * is bounded and a timeout yields wrong data, not a hang.  The plan sizes the cluster kernels for the 256 CUs of
+ * this part; on a device with fewer CUs than a launch has workgroups ogc_mlp_run returns OGC_ERR_DEVICE.
+ * OGC_MODE_AUTO takes the mode with the lowest estimate of the modes' fitted cost models (ogc_mlp_mode_estimates); a
  * single-launch mode wins ties within 7 %.  In per-layer mode each layer's tile and k-split are the candidate with
  * the lowest estimate (ogc_mlp_estimated_us): the scoring heuristic of Section III, no tuning run.
  * OGC_ERR_UNSUPPORTED: OGC_MODE_FUSED requested but a layer is too wide for the LDS activation tile; a blocked
