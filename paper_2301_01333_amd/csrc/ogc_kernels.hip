@@ -708,6 +708,32 @@ extern "C" OgcTileInfo ogc_tile_info(int tile) {
 // sync[0]: barrier arrivals, sync[1]: workgroups finished.  Both are zero between runs: prepack zeroes them and
 // the last workgroup to finish a run zeroes them again (by then nobody waits on them).
 // ------------------------------------------------------------------------------------------------
+// Partial accumulators of the k-slices of a workgroup's waves travel through LDS as four 16-byte pieces per lane
+// ([wave][piece][lane]: consecutive lanes, consecutive 16 bytes, so the 128-bit LDS accesses are conflict-free).
+template <int DT> OGC_DEV void partial_store(v4i (*red)[4][64], int slot, int lane, const typename AccT<DT>::type& acc) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if constexpr (DT == OGC_I8) {
+            red[slot][q][lane] = (v4i){acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        } else {
+            const v4f t = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+            red[slot][q][lane] = __builtin_bit_cast(v4i, t);
+        }
+    }
+}
+template <int DT> OGC_DEV void partial_add(v4i (*red)[4][64], int slot, int lane, typename AccT<DT>::type& acc) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const v4i v = red[slot][q][lane];
+        if constexpr (DT == OGC_I8) {
+            acc[4 * q] += v[0], acc[4 * q + 1] += v[1], acc[4 * q + 2] += v[2], acc[4 * q + 3] += v[3];
+        } else {
+            const v4f t = __builtin_bit_cast(v4f, v);
+            acc[4 * q] += t[0], acc[4 * q + 1] += t[1], acc[4 * q + 2] += t[2], acc[4 * q + 3] += t[3];
+        }
+    }
+}
+
 #define OGC_COOP_WAVES 8  // measured against 4 and 16: 10-25 % faster than 4 on 1024- and 2048-wide layers
 #define OGC_COOP_U 4      // k-steps a wave keeps in flight (8 measured: no better)
 #define OGC_COOP_THREADS (OGC_COOP_WAVES * 64)
@@ -745,7 +771,7 @@ OGC_DEV void load16x4_coherent(const uint8_t* p0, const uint8_t* p1, const uint8
 
 template <int DT>
 __global__ void __launch_bounds__(OGC_COOP_THREADS) ogc_coop_chain_kernel(const OgcChainArgs c, unsigned long long* sync, int m_blocks) {
-    __shared__ uint32_t red[OGC_COOP_WAVES - 1][16][64];  // partial accumulators of waves 1..7
+    __shared__ v4i red[OGC_COOP_WAVES - 1][4][64];  // partial accumulators of waves 1..7
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int G = gridDim.x, wg = blockIdx.x;
     for (int l = 0; l < c.n_layers; ++l) {
@@ -785,22 +811,11 @@ __global__ void __launch_bounds__(OGC_COOP_THREADS) ogc_coop_chain_kernel(const 
                 mma32<DT>(acc, wf, xf);
             }
             // k-slices of waves 1..7 to LDS, wave 0 adds them in ascending order (a fixed order: deterministic)
-            if (wave > 0) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    if constexpr (DT == OGC_I8) red[wave - 1][r][lane] = (uint32_t)acc[r];
-                    else red[wave - 1][r][lane] = __builtin_bit_cast(uint32_t, (float)acc[r]);
-                }
-            }
+            if (wave > 0) partial_store<DT>(red, wave - 1, lane, acc);
             __syncthreads();
             if (wave == 0) {
 #pragma unroll
-                for (int w = 0; w < OGC_COOP_WAVES - 1; ++w)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        if constexpr (DT == OGC_I8) acc[r] += (int)red[w][r][lane];
-                        else acc[r] += __builtin_bit_cast(float, red[w][r][lane]);
-                    }
+                for (int w = 0; w < OGC_COOP_WAVES - 1; ++w) partial_add<DT>(red, w, lane, acc);
                 if (last) epilogue_block<DT, 1>(acc, a, bn * 32, bm * 32, lane, (uint8_t*)nullptr);
                 else epilogue_block<DT, 0>(acc, a, bn * 32, bm * 32, lane, GlobalY{a.y + (size_t)bm * a.KC_out * 512});
             }
@@ -929,7 +944,7 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_ksplit_chain_ke
     }
     const int m0 = tile * 32;
     uint8_t* buf = smem;
-    uint32_t(*red)[16][64] = (uint32_t(*)[16][64])(smem + c.lds_buf_bytes);
+    v4i(*red)[4][64] = (v4i(*)[4][64])(smem + c.lds_buf_bytes);
     {
         const OgcLayerArgs& a = c.layer[0];
         const int pieces = a.KC * 32;
@@ -976,22 +991,11 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_ksplit_chain_ke
             }
             for (; kp < KP2; kp += OGC_FUSED_WAVES) mma32<DT>(acc, *(const v4i*)(wp + (size_t)kp * 1024), *(const v4i*)(xp + (size_t)kp * 1024));
             // k-slices of waves 1..7 to LDS, wave 0 adds them in ascending order (a fixed order: deterministic)
-            if (wave > 0) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    if constexpr (DT == OGC_I8) red[wave - 1][r][lane] = (uint32_t)acc[r];
-                    else red[wave - 1][r][lane] = __builtin_bit_cast(uint32_t, (float)acc[r]);
-                }
-            }
+            if (wave > 0) partial_store<DT>(red, wave - 1, lane, acc);
             __syncthreads();
             if (wave == 0) {
 #pragma unroll
-                for (int w = 0; w < OGC_FUSED_WAVES - 1; ++w)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        if constexpr (DT == OGC_I8) acc[r] += (int)red[w][r][lane];
-                        else acc[r] += __builtin_bit_cast(float, red[w][r][lane]);
-                    }
+                for (int w = 0; w < OGC_FUSED_WAVES - 1; ++w) partial_add<DT>(red, w, lane, acc);
                 if (last) epilogue_block<DT, 1>(acc, a, bn * 32, m0, lane, (uint8_t*)nullptr);
                 else epilogue_block<DT, 0>(acc, a, bn * 32, m0, lane, GlobalY{ytile});
             }
