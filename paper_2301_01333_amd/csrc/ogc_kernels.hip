@@ -769,6 +769,44 @@ OGC_DEV void load16x4_coherent(const uint8_t* p0, const uint8_t* p1, const uint8
                  : "memory");
 }
 
+// eight pieces in flight: the copy of a wide tile back into LDS is a few such batches, each one round trip
+OGC_DEV void load16x8_coherent(const uint8_t* p, size_t stride, v4i (&v)[8]) {
+    const uint8_t *p1 = p + stride, *p2 = p + 2 * stride, *p3 = p + 3 * stride, *p4 = p + 4 * stride, *p5 = p + 5 * stride,
+                  *p6 = p + 6 * stride, *p7 = p + 7 * stride;
+    asm volatile("global_load_dwordx4 %0, %8, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %1, %9, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %2, %10, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %3, %11, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %4, %12, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %5, %13, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %6, %14, off sc0 sc1\n\t"
+                 "global_load_dwordx4 %7, %15, off sc0 sc1\n\t"
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+                 : "v"(p), "v"(p1), "v"(p2), "v"(p3), "v"(p4), "v"(p5), "v"(p6), "v"(p7)
+                 : "memory");
+}
+
+// Copies a tile's image (pieces x 16 bytes, written by other workgroups) from global memory into LDS.
+OGC_DEV void copy_tile_coherent(uint8_t* lds, const uint8_t* g, int pieces, int tid) {
+    constexpr size_t T = OGC_FUSED_THREADS;
+    int p = tid;
+    for (; p + 7 * (int)T < pieces; p += 8 * (int)T) {
+        v4i v[8];
+        load16x8_coherent(g + (size_t)p * 16, T * 16, v);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) *(v4i*)(lds + ((size_t)p + u * T) * 16) = v[u];
+    }
+    for (; p + 3 * (int)T < pieces; p += 4 * (int)T) {
+        v4i v[4];
+        const uint8_t* q = g + (size_t)p * 16;
+        load16x4_coherent(q, q + T * 16, q + 2 * T * 16, q + 3 * T * 16, v);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) *(v4i*)(lds + ((size_t)p + u * T) * 16) = v[u];
+    }
+    for (; p < pieces; p += (int)T) *(v4i*)(lds + (size_t)p * 16) = load16_coherent(g + (size_t)p * 16);
+}
+
 template <int DT>
 __global__ void __launch_bounds__(OGC_COOP_THREADS) ogc_coop_chain_kernel(const OgcChainArgs c, unsigned long long* sync, int m_blocks) {
     __shared__ v4i red[OGC_COOP_WAVES - 1][4][64];  // partial accumulators of waves 1..7
@@ -889,16 +927,7 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_chain_kernel(co
             uint8_t* ytile = a.y + (size_t)tile * a.KC_out * 512;  // the tile in blocked layout = its LDS image
             fused_layer<DT, 0>(a, xin, GlobalY{ytile}, m0, vwave, vwaves, lane);
             coop_grid_barrier(ctr, (unsigned long long)(++barriers) * S, tid);
-            const int pieces = a.KC_out * 32;
-            int p = tid;
-            for (; p + 3 * OGC_FUSED_THREADS < pieces; p += 4 * OGC_FUSED_THREADS) {
-                v4i v[4];
-                const uint8_t* g = ytile + (size_t)p * 16;
-                load16x4_coherent(g, g + OGC_FUSED_THREADS * 16, g + 2 * OGC_FUSED_THREADS * 16, g + 3 * OGC_FUSED_THREADS * 16, v);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) *(v4i*)(xout + ((size_t)p + u * OGC_FUSED_THREADS) * 16) = v[u];
-            }
-            for (; p < pieces; p += OGC_FUSED_THREADS) *(v4i*)(xout + (size_t)p * 16) = load16_coherent(ytile + (size_t)p * 16);
+            copy_tile_coherent(xout, ytile, a.KC_out * 32, tid);
             __syncthreads();
         } else {
             fused_layer<DT, 1>(a, xin, (uint8_t*)nullptr, m0, vwave, vwaves, lane);
@@ -1026,16 +1055,7 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_ksplit_chain_ke
                     __builtin_amdgcn_s_sleep(1);
             }
             __syncthreads();
-            const int pieces = a.KC_out * 32;
-            int p = tid;
-            for (; p + 3 * OGC_FUSED_THREADS < pieces; p += 4 * OGC_FUSED_THREADS) {
-                v4i v[4];
-                const uint8_t* g = ytile + (size_t)p * 16;
-                load16x4_coherent(g, g + OGC_FUSED_THREADS * 16, g + 2 * OGC_FUSED_THREADS * 16, g + 3 * OGC_FUSED_THREADS * 16, v);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) *(v4i*)(buf + ((size_t)p + u * OGC_FUSED_THREADS) * 16) = v[u];
-            }
-            for (; p < pieces; p += OGC_FUSED_THREADS) *(v4i*)(buf + (size_t)p * 16) = load16_coherent(ytile + (size_t)p * 16);
+            copy_tile_coherent(buf, ytile, a.KC_out * 32, tid);
             __syncthreads();
         }
     }
