@@ -427,6 +427,8 @@ def main():
         "per_config": per,
         "blocked_io": blocked,
         "mha": None if (args.only_headline or args.no_mha) else mha_report(args.steps, args.warmup, not args.no_cpu),
+        # the MLP rows of the paper's Table I over its batch range, each with the plan's own choice of kernel
+        "table1_mlp_sweep": None if args.only_headline else table1_sweep(min(args.steps, 200), min(args.warmup, 20)),
     }
     print(json.dumps(out))
     return 0
