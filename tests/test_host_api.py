@@ -156,6 +156,28 @@ def test_cluster_split_override(monkeypatch):
     assert name(256, b.OGC_F32) == "ogc_cluster_ksplit_chain_kernel<0>"
 
 
+def test_cooperative_estimate_is_the_lowest_of_its_kernels(monkeypatch):
+    """ogc_mlp_mode_estimates()[2] is the estimate of the kernel the cooperative mode would launch: never above the
+    block-dealing kernel's own estimate (what OGC_CLUSTER_SPLIT=0 leaves), equal to it where no cluster kernel fits."""
+    def coop_est(dtype, m, dims):
+        p = b.ogc_mlp_plan(dtype, m, [layer(dims[i], dims[i + 1]) for i in range(len(dims) - 1)], dims[0], dims[-1], 0, 0)
+        e, name = b.ogc_mlp_mode_estimates(p)[2], b.ogc_mlp_kernel_name(p, 0) if b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_COOP else ""
+        b.ogc_mlp_destroy(p)
+        return e, name
+    cases = [(b.OGC_I8, 256, [479, 1024, 1024, 512, 256]), (b.OGC_F32, 512, [479, 1024, 1024, 512, 256]),
+             (b.OGC_BF16, 128, [1024, 1024, 1024]), (b.OGC_I8, 64, [64, 64, 64]), (b.OGC_F32, 32 * 300, [512, 512, 512])]
+    for dtype, m, dims in cases:
+        monkeypatch.setenv("OGC_CLUSTER_SPLIT", "0")
+        base, _ = coop_est(dtype, m, dims)
+        monkeypatch.delenv("OGC_CLUSTER_SPLIT")
+        best, name = coop_est(dtype, m, dims)
+        assert 0 < best <= base
+        if m > 32 * 128:                      # 300 row tiles: no cluster kernel has a CU for every member
+            assert best == base and "cluster" not in name
+        if name.startswith("ogc_cluster"):
+            assert best < base
+
+
 def test_buffer_reuse_is_ping_pong_for_a_chain():
     """Life-span reuse: layer l's output may take the buffer of layer l-2's output (dead once layer l-1 has
     run), never that of layer l-1's (live as the input).  Peak = two slots of the largest intermediate."""
