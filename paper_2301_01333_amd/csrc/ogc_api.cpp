@@ -240,13 +240,13 @@ double estimate_coop_us(const ogc_mlp_plan_s* p) {
 
 // The cluster kernel: `split` workgroups per 32-row tile, each streaming 1/split of the weights; after every layer
 // but the last, a barrier of the tile's members and a copy of the whole tile back into LDS.  Fitted like the other
-// mode models (chains of 2-5 layers, 64-4096 wide, 32-2048 rows, splits 2-16; rms error 8 %, worst 37 %: wide bf16
+// mode models (chains of 2-5 layers, 64-4096 wide, 32-2048 rows, splits 2-16; rms error 8 %, worst 34 %: wide bf16
 // layers at 1024 rows, underestimated).  The fp32 row serves forced splits only: the kernel has no split along K,
 // an fp32 chain is bound by one CU's MFMA rate in it, and the plan does not offer it fp32 chains.
 struct ClusterCost { float c0, per_mb, group, per_layer, barrier, copy_mb, fill, all_mb; };
-const ClusterCost kCluster[3] = {{0.051f, 31.81f, 0.0f, 2.819f, 2.310f, 26.20f, 0.0922f, 0.0069f},
-                                 {3.808f, 7.503f, 0.0543f, 1.079f, 2.720f, 0.0f, 0.0820f, 0.0181f},
-                                 {3.370f, 8.906f, 0.1855f, 1.102f, 1.000f, 0.0f, 0.0753f, 0.0107f}};
+const ClusterCost kCluster[3] = {{0.0f, 15.37f, 0.4852f, 2.127f, 1.000f, 11.72f, 0.1019f, 0.0310f},
+                                 {5.620f, 7.110f, 0.0477f, 0.744f, 1.000f, 55.68f, 0.0466f, 0.0233f},
+                                 {3.045f, 8.420f, 0.2833f, 1.272f, 1.000f, 0.0f, 0.0614f, 0.0106f}};
 
 // One layer of the cluster kernel: the busiest member's weight stream, and the exchange if the layer is split.
 double cluster_layer_us(const ogc_mlp_plan_s* p, int l, int split, bool whole) {
@@ -256,8 +256,9 @@ double cluster_layer_us(const ogc_mlp_plan_s* p, int l, int split, bool whole) {
     const bool last = l == L - 1;
     const int nb = last ? (lp.d.n + 31) / 32 : lp.nb_out;
     const double kb = (double)lp.kp * p->esz;  // bytes of a row of the layer's input
-    int wg = 0;                                // channel blocks of the busiest member
-    for (int w = 0; w < 8 && w < nb; ++w) wg += (nb - w + waves - 1) / waves;
+    int wg = 0;                                // channel blocks of the busiest member (its wave w is wave w*stride)
+    const int stride = whole ? 1 : split;
+    for (int w = 0; w < 8 && w * stride < nb; ++w) wg += (nb - w * stride + waves - 1) / waves;
     const int per_wave = (nb + waves - 1) / waves;
     double t = c.per_mb * kb * 32.0 * wg / 1e6 + c.group * std::ceil(kb / 128.0) * ((per_wave + 3) / 4) + c.per_layer;
     if (!last && !whole) t += c.barrier + c.copy_mb * ((double)p->layers[l + 1].kp * p->esz * 32.0) / 1e6;
@@ -495,16 +496,10 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
             }
         }
         if (ksplit_fits && forced_ks != 0) {
-            // against the channel-split kernel the k-split variant has to win clearly (15 %): it uses up to 32
-            // members per tile, each of which copies the whole tile back after every layer (config 3: 19 MB of
-            // fabric traffic per run against 6 MB), and where the two were timed within a few per cent of each
-            // other its model was the optimistic one
-            const double bar = p->cluster_split > 0 ? 0.85 : 1.0;
-            double best = p->mode_us[2];
             for (int split = 2; split <= 32; split *= 2) {
                 if (ogc_cluster_xcds(m_blocks, split, p->cluster_spread) < 0) continue;
                 const double e = estimate_cluster_ksplit_us(p, split);
-                if (e < bar * best && e < p->mode_us[2]) {
+                if (e < p->mode_us[2]) {
                     p->mode_us[2] = e;
                     p->cluster_split = split;
                     p->cluster_ksplit = 1;

@@ -901,7 +901,9 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_chain_kernel(co
         if (xcd >= c.fused_xcds || tile >= c.fused_tiles) return;
     }
     const int m0 = tile * 32;
-    const int vwave = member * OGC_FUSED_WAVES + wave, vwaves = S * OGC_FUSED_WAVES;
+    // the members' waves are numbered member-fastest: a layer with fewer channel blocks than waves still gives every
+    // member its share (wave w of member j is wave w*S + j of the tile)
+    const int vwave = wave * S + member, vwaves = S * OGC_FUSED_WAVES;
     uint8_t* buf0 = smem;
     uint8_t* buf1 = smem + c.lds_buf_bytes;
     {
