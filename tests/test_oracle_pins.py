@@ -304,6 +304,45 @@ def test_residual_and_bias_terms(oracle_mod):
     assert np.allclose(oracle_mod.layer_f32(x, w, b, RELU, residual=x), ref, rtol=1e-4, atol=1e-5)
 
 
+def test_bf16_residual_is_added_in_fp32_before_the_single_rounding(oracle_mod):
+    """Hand case from the fixture: rounding to bf16 before the residual add gives 1.0 where the
+    reading taken (fp32 add, one rounding) gives 1.0078125."""
+    d = _float_fixture()
+    x = synth.f32_to_bf16_bits(np.array([d["RESX"]], np.float32))
+    assert np.array_equal(synth.bf16_bits_to_f32(x)[0], np.array(d["RESX"], np.float32))   # operands are bf16-exact
+    w = synth.f32_to_bf16_bits(np.array(d["RESW"], np.float32).reshape(2, 2))
+    want = np.array([d["RESY"]], np.float32)
+    for dbl in (False, True):
+        y = oracle_mod.layer_bf16(x, w, None, NONE, residual=x, accum_double=dbl)
+        assert np.array_equal(synth.bf16_bits_to_f32(y), want), (dbl, synth.bf16_bits_to_f32(y))
+    # without the residual the same layer gives [2^-8, bf16(1 + 2^-8) = 1]
+    y0 = synth.bf16_bits_to_f32(oracle_mod.layer_bf16(x, w, None, NONE))
+    assert np.array_equal(y0, np.array([[2.0 ** -8, 1.0]], np.float32))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_chain_residual_is_the_first_input_on_the_last_layer_only(oracle_mod, dtype):
+    """Two-layer chain from the fixture: the last layer adds the chain's first input x0 (not its own
+    input), and layer 0 adds nothing."""
+    d = _float_fixture()
+    conv = synth.f32_to_bf16_bits if dtype == "bf16" else (lambda a: np.ascontiguousarray(a, np.float32))
+    back = synth.bf16_bits_to_f32 if dtype == "bf16" else (lambda a: a)
+    x0 = conv(np.array([d["CHX"]], np.float32))
+    ws = [conv(np.array(d[t], np.float32).reshape(2, 2)) for t in ("CHW0", "CHW1")]
+    layers = [synth.Layer(2, 2, False, NONE), synth.Layer(2, 2, False, NONE)]
+    wl = synth.Workload("hand chain", dtype, 1, layers, True, x0, ws, [None, None], [None, None])
+    outs = oracle_mod.mlp(wl, keep=True)
+    assert np.array_equal(back(outs[0]), np.array([[2.0, 2.0 ** -7]], np.float32))          # no residual on layer 0
+    if dtype == "bf16":
+        want = np.array([d["CHY"]], np.float32)
+    else:   # the same sums without the bf16 rounding: [2^-7 + 1, 1 + 2^-7 + 2^-8], exact in fp32
+        want = np.array([[1.0 + 2.0 ** -7, 1.0 + 2.0 ** -7 + 2.0 ** -8]], np.float32)
+    assert np.array_equal(back(outs[1]), want), back(outs[1])
+    wl.residual = False
+    plain = back(oracle_mod.mlp(wl))
+    assert np.array_equal(plain, np.array([[2.0 ** -7, 1.0 + 2.0 ** -7]], np.float32))
+
+
 def test_activation_closed_forms(oracle_mod):
     from oracle import oracle as o
 
