@@ -9,8 +9,8 @@
  * Conventions common to every entry point
  *   - All shapes, dtypes, activations and quantization parameters are static: fixed when the plan is
  *     made (the paper specialises for static shapes and folds quantization constants, Sections I, V).
- *   - Tensors at the boundary are plain row-major ("input and output matrices are in plain layouts",
- *     Section VII) unless the description asks for the blocked layout (ogc_layout), which lets chains hand
+ *   - Tensors at the boundary are plain row-major (as in the evaluation set-up of Section VII, where the
+ *     graph's inputs and outputs keep the plain layout) unless the description asks for the blocked layout (ogc_layout), which lets chains hand
  *     activations to each other the way the layers of one chain do.  Weights are [K,N] row-major (B[K,N] of
  *     Section III).  Otherwise blocked layouts exist only inside the packed blob and the workspace.
  *   - "dev" pointers are device (HBM) addresses on the current HIP device; "host" pointers are ordinary
@@ -42,7 +42,8 @@ typedef enum {
     OGC_ERR_ALIGNMENT = -4,     /* packed / workspace pointer not 256-byte aligned, x / y not element aligned */
     OGC_ERR_WORKSPACE = -5,     /* workspace is NULL although ogc_mlp_workspace_bytes() > 0 */
     OGC_ERR_NOT_PREPACKED = -6, /* ogc_mlp_run before any ogc_mlp_prepack_weights on this plan */
-    OGC_ERR_DEVICE = -7         /* the HIP runtime reported an error at launch */
+    OGC_ERR_DEVICE = -7,        /* the HIP runtime reported an error at launch */
+    OGC_ERR_TIMEOUT = -8        /* ogc_mlp_check / ogc_mlp_run_profiled: a barrier wait of the cooperative mode gave up */
 } ogc_status;
 
 typedef enum { OGC_F32 = 0, OGC_BF16 = 1, OGC_I8 = 2 } ogc_dtype; /* OGC_I8: u8 activations x s8 weights */
@@ -109,19 +110,38 @@ typedef struct ogc_mlp_plan_s* ogc_mlp_plan_t;
  * The mode needs the workspace and keeps barrier counters in the packed blob (16 KiB at its end), so runs that
  * share a packed blob must not overlap in time; all its workgroups must be resident at once (the grid is at most
  * one per CU), so it is meant for a device that is not kept busy by other kernels for seconds: the barrier wait
- * is bounded and a timeout yields wrong data, not a hang.  The plan sizes the cluster kernels for the 256 CUs of
+ * is bounded (about 2^22 polls).  A wait that gives up does not hang: the workgroup records the fact in the packed
+ * blob's sync area and abandons the rest of the chain, and so do the workgroups that wait for it; y is then invalid.
+ * ogc_mlp_run cannot report that (it returns before the kernel runs): call ogc_mlp_check after the run, or use
+ * ogc_mlp_run_profiled, which includes the check.  The plan sizes the cluster kernels for the 256 CUs of
  * this part; on a device with fewer CUs than a launch has workgroups ogc_mlp_run returns OGC_ERR_DEVICE.
  * OGC_MODE_AUTO takes the mode with the lowest estimate of the modes' fitted cost models (ogc_mlp_mode_estimates); a
  * single-launch mode wins ties within 7 %.  In per-layer mode each layer's tile and k-split are the candidate with
  * the lowest estimate (ogc_mlp_estimated_us): the scoring heuristic of Section III, no tuning run.
  * OGC_ERR_UNSUPPORTED: OGC_MODE_FUSED requested but a layer is too wide for the LDS activation tile; a blocked
  * x or y with a mode other than per-layer.
- * For tests, environment variables read here override the cost model: in per-layer mode OGC_TILE (0..4: tile
- * configuration of every layer) and OGC_KSPLIT (log2 of the number of k ranges, 0..3); in cooperative mode
- * OGC_CLUSTER_SPLIT (0: kernel (a); n: kernel (b) with n workgroups per tile where they fit, any dtype),
- * OGC_CLUSTER_KSPLIT (1 together with OGC_CLUSTER_SPLIT=n: kernel (c) with n members; 0: never kernel (c)) and
- * OGC_CLUSTER_WHOLE=0 (kernel (b) exchanges after every layer, also the small ones it would compute whole). */
+ * The plan depends on the description alone (nothing is read from the process environment). */
 ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc /*host*/, ogc_mlp_plan_t* out_plan /*host*/);
+
+/* Forced choices for ogc_mlp_plan_with_overrides; -1 in a field leaves that choice to the cost model.  For tests,
+ * sweeps and the calibration of the cost models (every candidate of Section III's heuristic can be timed by itself). */
+typedef struct {
+    int32_t tile;            /* per-layer mode: tile configuration of every layer, 0..4 (0-2 register-staged 256x256 /
+                                128x128 / 64x32 channels x rows, 3 / 4 the four- / eight-wave stream tile); a stream tile
+                                falls back to 1 on a layer the stream kernel cannot run */
+    int32_t ksplit_log2;     /* per-layer mode: log2 of the number of k ranges of every stream-tile layer, 0..3 */
+    int32_t cluster_split;   /* cooperative mode: 0 = kernel (a); n = kernel (b) with n workgroups per row tile where
+                                they fit (any dtype) */
+    int32_t cluster_ksplit;  /* cooperative mode: 1 together with cluster_split = n: kernel (c) with n members;
+                                0: kernel (c) is never chosen */
+    int32_t cluster_whole;   /* kernel (b): 0 = exchange after every layer, also the small ones the model would have
+                                every member compute whole */
+} ogc_plan_overrides;
+
+/* ogc_mlp_plan with forced choices (overrides may be NULL: identical to ogc_mlp_plan).
+ * OGC_ERR_INVALID_ARG also for a field outside its range. */
+ogc_status ogc_mlp_plan_with_overrides(const ogc_mlp_desc* desc /*host*/, const ogc_plan_overrides* overrides /*host*/,
+                                       ogc_mlp_plan_t* out_plan /*host*/);
 
 /* Size of the packed-weights blob (blocked weights + per-channel parameters of every layer). */
 ogc_status ogc_mlp_packed_bytes(ogc_mlp_plan_t plan, size_t* bytes /*host*/);
@@ -160,7 +180,8 @@ ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, co
  * (A blocked x or y, see ogc_layout, is a buffer of ogc_mlp_blocked_bytes() bytes instead.)
  * x and y must not overlap.  packed is the blob written by ogc_mlp_prepack_weights for this plan;
  * workspace is dev, 256-byte aligned, ogc_mlp_workspace_bytes() bytes (may be NULL when that is 0) and
- * holds no state between calls. */
+ * holds no state between calls.  In the cooperative mode a run can come out invalid without an error here
+ * (see ogc_mlp_plan and ogc_mlp_check). */
 ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream);
 
 /* Number of timed launch steps of one ogc_mlp_run: 1 for the fused-chain kernel, n_layers otherwise (a layer
@@ -170,9 +191,33 @@ ogc_status ogc_mlp_num_launches(ogc_mlp_plan_t plan, int32_t* n /*host*/);
 /* ogc_mlp_run with a HIP event recorded on `stream` around every launch; waits for the last one and writes
  * each launch's duration in milliseconds to launch_ms[0 .. ogc_mlp_num_launches()-1] (host).  This is the
  * per-operation measurement of Section VII (layers timed separately while still run back to back as a
- * chain).  Unlike ogc_mlp_run it synchronises with the stream and creates/destroys HIP events. */
+ * chain).  Unlike ogc_mlp_run it synchronises with the stream and creates/destroys HIP events, and it ends with
+ * ogc_mlp_check (OGC_ERR_TIMEOUT if a barrier wait gave up). */
 ogc_status ogc_mlp_run_profiled(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace,
                                 void* stream, float* launch_ms /*host*/);
+
+/* Tells whether a barrier wait of the cooperative mode gave up in any run on `packed` since the last check
+ * (Section III's multi-core template needs all cores at the barrier; on a shared device they may not all be resident
+ * in time).  Waits for `stream`, reads one word of the packed blob's sync area, and, if it is set, clears the sync
+ * area and returns OGC_ERR_TIMEOUT: the y of that run is invalid and the run may simply be repeated.  OGC_OK
+ * otherwise, and at once for plans in another mode.  packed: dev, the blob this plan's runs used.
+ * OGC_ERR_INVALID_ARG: NULL plan or packed.  OGC_ERR_DEVICE: the runtime failed. */
+ogc_status ogc_mlp_check(ogc_mlp_plan_t plan, const void* packed, void* stream);
+
+/* Test hook for the give-up path of the cooperative mode's barriers: later runs of this plan poll `budget` times
+ * (>= 1; default about 2^22) and wait for `extra_target` arrivals more than will ever come (default 0).  With
+ * extra_target = 1 every workgroup gives up at its first barrier after `budget` polls and exits normally, which is
+ * what ogc_mlp_check must then report.  Host only. */
+ogc_status ogc_mlp_test_barrier(ogc_mlp_plan_t plan, int32_t budget, int32_t extra_target);
+
+/* Cooperative mode, cluster kernels: *members = workgroups per 32-row tile (0: not a cluster kernel), *ksplit = 1 for
+ * kernel (c), *whole_mask bit l = layer l is computed whole by every member (no exchange), *tile_stride = bytes
+ * between the exchange regions of two row tiles inside a workspace slot.  Together with ogc_mlp_buffer_assignment
+ * this is the workspace layout of Section VI's buffer reuse as the cluster kernels use it: every tile owns
+ * [slot offset + tile*tile_stride, + row-block bytes of the layer) and consecutive exchanged layers alternate
+ * between two slots.  Host only; all pointers host, none NULL. */
+ogc_status ogc_mlp_cluster_layout(ogc_mlp_plan_t plan, int32_t* members, int32_t* ksplit, uint32_t* whole_mask,
+                                  size_t* tile_stride);
 
 /* Releases the plan (NULL is ignored). */
 void ogc_mlp_destroy(ogc_mlp_plan_t plan);

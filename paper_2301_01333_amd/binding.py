@@ -26,8 +26,10 @@ EXPORTS = [
     "ogc_mlp_plan", "ogc_mlp_packed_bytes", "ogc_mlp_workspace_bytes", "ogc_mlp_chosen_mode",
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
     "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes", "ogc_mlp_estimated_us", "ogc_mlp_mode_estimates",
+    "ogc_mlp_plan_with_overrides", "ogc_mlp_check", "ogc_mlp_test_barrier", "ogc_mlp_cluster_layout",
     "ogc_mha_validate", "ogc_mha_run", "ogc_mha_kernel_name",
 ]
+OGC_ERR_TIMEOUT = -8
 
 
 class ogc_layer_desc(ctypes.Structure):
@@ -41,6 +43,11 @@ class ogc_mlp_desc(ctypes.Structure):
                 ("layers", ctypes.POINTER(ogc_layer_desc)), ("ld_x", ctypes.c_int32), ("ld_y", ctypes.c_int32),
                 ("residual", ctypes.c_int32), ("mode", ctypes.c_int32), ("x_layout", ctypes.c_int32),
                 ("y_layout", ctypes.c_int32)]
+
+
+class ogc_plan_overrides(ctypes.Structure):
+    _fields_ = [("tile", ctypes.c_int32), ("ksplit_log2", ctypes.c_int32), ("cluster_split", ctypes.c_int32),
+                ("cluster_ksplit", ctypes.c_int32), ("cluster_whole", ctypes.c_int32)]
 
 
 class ogc_mha_desc(ctypes.Structure):
@@ -70,6 +77,14 @@ def lib():
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         l.ogc_mlp_plan.argtypes = [ctypes.POINTER(ogc_mlp_desc), ctypes.POINTER(vp)]
         l.ogc_mlp_plan.restype = i32
+        l.ogc_mlp_plan_with_overrides.argtypes = [ctypes.POINTER(ogc_mlp_desc), ctypes.POINTER(ogc_plan_overrides), ctypes.POINTER(vp)]
+        l.ogc_mlp_plan_with_overrides.restype = i32
+        l.ogc_mlp_check.argtypes = [vp, vp, vp]
+        l.ogc_mlp_check.restype = i32
+        l.ogc_mlp_test_barrier.argtypes = [vp, i32, i32]
+        l.ogc_mlp_test_barrier.restype = i32
+        l.ogc_mlp_cluster_layout.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(sz)]
+        l.ogc_mlp_cluster_layout.restype = i32
         l.ogc_mlp_packed_bytes.argtypes = [vp, ctypes.POINTER(sz)]
         l.ogc_mlp_packed_bytes.restype = i32
         l.ogc_mlp_workspace_bytes.argtypes = [vp, ctypes.POINTER(sz)]
@@ -118,9 +133,7 @@ def _check(status: int, what: str) -> None:
 
 
 # ---- one function per entry point, same names ---------------------------------------------------
-def ogc_mlp_plan(dtype: int, m: int, layers: Sequence[dict], ld_x: int, ld_y: int, residual: int = 0, mode: int = 0,
-                 x_layout: int = 0, y_layout: int = 0) -> int:
-    """layers: dicts with k, n, has_bias, act, in_scale, in_zp, out_scale, out_zp, out.  Returns the plan handle."""
+def _desc(dtype, m, layers, ld_x, ld_y, residual, mode, x_layout, y_layout):
     arr = (ogc_layer_desc * max(len(layers), 1))()
     for i, ly in enumerate(layers):
         arr[i] = ogc_layer_desc(int(ly["k"]), int(ly["n"]), int(ly.get("has_bias", 0)), int(ly.get("act", 0)),
@@ -128,9 +141,53 @@ def ogc_mlp_plan(dtype: int, m: int, layers: Sequence[dict], ld_x: int, ld_y: in
                                 int(ly.get("out_zp", 0)), int(ly.get("out", 0)))
     desc = ogc_mlp_desc(int(dtype), int(m), len(layers), arr, int(ld_x), int(ld_y), int(residual), int(mode), int(x_layout),
                         int(y_layout))
+    return desc, arr
+
+
+def ogc_mlp_plan(dtype: int, m: int, layers: Sequence[dict], ld_x: int, ld_y: int, residual: int = 0, mode: int = 0,
+                 x_layout: int = 0, y_layout: int = 0) -> int:
+    """layers: dicts with k, n, has_bias, act, in_scale, in_zp, out_scale, out_zp, out.  Returns the plan handle."""
+    desc, _keep = _desc(dtype, m, layers, ld_x, ld_y, residual, mode, x_layout, y_layout)
     handle = ctypes.c_void_p()
     _check(lib().ogc_mlp_plan(ctypes.byref(desc), ctypes.byref(handle)), "ogc_mlp_plan")
     return handle.value
+
+
+def ogc_mlp_plan_with_overrides(dtype: int, m: int, layers: Sequence[dict], ld_x: int, ld_y: int, residual: int = 0,
+                                mode: int = 0, x_layout: int = 0, y_layout: int = 0, overrides: Optional[dict] = None) -> int:
+    """overrides: dict with any of tile, ksplit_log2, cluster_split, cluster_ksplit, cluster_whole (missing or None = -1,
+    the cost model's choice); None passes a NULL pointer."""
+    desc, _keep = _desc(dtype, m, layers, ld_x, ld_y, residual, mode, x_layout, y_layout)
+    ov = None
+    if overrides is not None:
+        unknown = set(overrides) - {f for f, _ in ogc_plan_overrides._fields_}
+        if unknown:
+            raise KeyError("unknown plan overrides: %s" % sorted(unknown))
+        ov = ogc_plan_overrides(*[-1 if overrides.get(f) is None else int(overrides[f]) for f, _ in ogc_plan_overrides._fields_])
+    handle = ctypes.c_void_p()
+    _check(lib().ogc_mlp_plan_with_overrides(ctypes.byref(desc), ctypes.byref(ov) if ov is not None else None,
+                                             ctypes.byref(handle)), "ogc_mlp_plan_with_overrides")
+    return handle.value
+
+
+def ogc_mlp_check(plan: int, packed_ptr: int, stream: int = 0) -> int:
+    """Returns the status (OGC_OK or OGC_ERR_TIMEOUT); raises on any other error."""
+    st = int(lib().ogc_mlp_check(plan, packed_ptr, stream))
+    if st not in (OGC_OK, OGC_ERR_TIMEOUT):
+        raise OgcError(st, "ogc_mlp_check")
+    return st
+
+
+def ogc_mlp_test_barrier(plan: int, budget: int, extra_target: int) -> None:
+    _check(lib().ogc_mlp_test_barrier(plan, int(budget), int(extra_target)), "ogc_mlp_test_barrier")
+
+
+def ogc_mlp_cluster_layout(plan: int):
+    """(members per row tile, k-split variant?, whole-layer mask, tile stride in bytes)."""
+    m, k, w, st = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_uint32(), ctypes.c_size_t()
+    _check(lib().ogc_mlp_cluster_layout(plan, ctypes.byref(m), ctypes.byref(k), ctypes.byref(w), ctypes.byref(st)),
+           "ogc_mlp_cluster_layout")
+    return m.value, k.value, w.value, st.value
 
 
 def ogc_mlp_packed_bytes(plan: int) -> int:
@@ -247,7 +304,7 @@ class FusedMLP:
 
     def __init__(self, dtype: str, m: int, layers: Sequence, ld_x: Optional[int] = None, ld_y: Optional[int] = None,
                  residual: bool = False, mode: int = OGC_MODE_AUTO, x_layout: int = OGC_LAYOUT_PLAIN,
-                 y_layout: int = OGC_LAYOUT_PLAIN):
+                 y_layout: int = OGC_LAYOUT_PLAIN, overrides: Optional[dict] = None):
         import torch
 
         self.torch = torch
@@ -264,7 +321,11 @@ class FusedMLP:
         self.ld_x = ld_x or self.k0
         self.ld_y = ld_y or self.n_last
         self.out_f32 = self.layer_dicts[-1].get("out", 0) == OGC_OUT_F32
-        self.plan = ogc_mlp_plan(DTYPES[dtype], m, self.layer_dicts, self.ld_x, self.ld_y, int(residual), mode, x_layout, y_layout)
+        if overrides:
+            self.plan = ogc_mlp_plan_with_overrides(DTYPES[dtype], m, self.layer_dicts, self.ld_x, self.ld_y, int(residual), mode,
+                                                    x_layout, y_layout, overrides)
+        else:
+            self.plan = ogc_mlp_plan(DTYPES[dtype], m, self.layer_dicts, self.ld_x, self.ld_y, int(residual), mode, x_layout, y_layout)
         self.mode = ogc_mlp_chosen_mode(self.plan)
         self.packed_bytes = ogc_mlp_packed_bytes(self.plan)
         self.workspace_bytes = ogc_mlp_workspace_bytes(self.plan)
@@ -299,6 +360,10 @@ class FusedMLP:
     def run(self, x, y) -> None:
         ogc_mlp_run(self.plan, x.data_ptr(), y.data_ptr(), self.packed.data_ptr(),
                     self.workspace.data_ptr() if self.workspace_bytes else 0, self._stream())
+
+    def check(self) -> int:
+        """OGC_OK, or OGC_ERR_TIMEOUT if a barrier wait of the cooperative mode gave up since the last check."""
+        return ogc_mlp_check(self.plan, self.packed.data_ptr(), self._stream())
 
     def run_profiled(self, x, y):
         return ogc_mlp_run_profiled(self.plan, x.data_ptr(), y.data_ptr(), self.packed.data_ptr(),

@@ -12,26 +12,42 @@ LIB = os.path.join(HERE, "libogc_mlp.so")
 SOURCES = ["ogc_kernels.hip", "ogc_mha.hip", "ogc_api.cpp"]
 
 
-def build_library(verbose: bool = True) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [
-        hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
-        # packed fp32 VALU ops are kept off for every HIP translation unit in this repository
-        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-Wall", "-Wno-unused-function",
-        "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-    ] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", tmp]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
+         # packed fp32 VALU ops are kept off for every HIP translation unit in this repository
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
-    if out.strip() and verbose:
-        print(out, flush=True)
     if r.returncode != 0:
-        if os.path.exists(tmp):
-            os.remove(tmp)
         raise RuntimeError("hipcc failed (%d)\n%s" % (r.returncode, out))
+    return out
+
+
+def build_library(verbose: bool = True) -> str:
+    """Compiles every source to an object (in parallel, one hipcc each) and links the shared library."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    with tempfile.TemporaryDirectory() as td:
+        objs = [os.path.join(td, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+        cmds = [[hipcc] + FLAGS + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+        with ThreadPoolExecutor(len(cmds)) as pool:
+            outs = list(pool.map(lambda c: _run(c, verbose), cmds))
+        try:
+            outs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp], verbose))
+        except RuntimeError:
+            if os.path.exists(tmp):
+                os.remove(tmp)
+            raise
+    if verbose and os.environ.get("OGC_BUILD_WARNINGS"):
+        print("\n".join(o for o in outs if o.strip()), flush=True)
     os.replace(tmp, LIB)
     return LIB
 

@@ -49,8 +49,13 @@ struct ogc_mlp_plan_s {
     int cluster_split;                  // cooperative mode: 0 = blocks dealt to all workgroups, n = n workgroups per row tile
     int cluster_spread;                 // cluster kernel: a tile's members on different XCDs (weights beyond one L2)
     int cluster_ksplit;                 // cluster kernel: the waves of a member split K (one LDS buffer) instead of the channel blocks
+    uint32_t cluster_whole_mask;        // channel-split cluster kernel: layers every member computes whole (no exchange)
+    size_t cluster_tile_stride;         // cluster kernels: bytes between two row tiles' regions inside an exchange slot
+    ogc_plan_overrides ov;              // forced choices (-1: the cost model's)
     std::vector<size_t> slot_off, slot_size;
     std::atomic<int> prepacked;
+    std::atomic<int> cu_count;          // compute units of the device, asked once at the first cooperative run (0: not yet)
+    std::atomic<int> barrier_budget, barrier_extra;  // cooperative barriers: polls before giving up, test-only target offset
 };
 
 namespace {
@@ -88,11 +93,6 @@ void assign_buffers(ogc_mlp_plan_s* p) {
     }
     p->workspace_bytes = off;
     for (int l = 0; l + 1 < L; ++l) p->layers[l].out_off = p->slot_off[p->layers[l].out_slot];
-}
-
-int env_int(const char* name, int dflt) {
-    const char* v = std::getenv(name);
-    return (v && *v) ? std::atoi(v) : dflt;
 }
 
 // ---- Plan-time cost model for a per-layer launch (the role of the template-parameter heuristic of Section III:
@@ -160,14 +160,14 @@ double estimate_layer_us(int dtype, int m, int n, int kt, int tile, int ks) {
 
 // Picks tile and split for one layer.  dma_ok: the stream kernel can run this layer (int8 / bf16, no sigmoid,
 // input zero point 128, and a first layer whose plain rows are 16-byte aligned without K padding); other layers
-// choose among the register-staged tiles.  OGC_TILE / OGC_KSPLIT in the environment force a choice (tests, sweeps).
-void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int* tile_out, int* ks_out, double* us_out) {
+// choose among the register-staged tiles.  forced / forced_split (-1: none) come from ogc_mlp_plan_with_overrides.
+void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int forced, int forced_split, int* tile_out, int* ks_out,
+                           double* us_out) {
     auto tiles = [&](int t) {
         const OgcTileInfo ti = ogc_tile_info(t);
         return (long)((m + ti.bm - 1) / ti.bm) * ((n + ti.bn - 1) / ti.bn);
     };
     auto split_ok = [&](int ks) { return ks >= 0 && ks <= 3 && kt % (1 << ks) == 0 && (kt >> ks) >= 4; };
-    const int forced = env_int("OGC_TILE", -1), forced_split = env_int("OGC_KSPLIT", -1);
     int tile = -1, ks = 0;
     if (forced >= 0 && forced < OGC_NUM_TILES)
         tile = ((forced == OGC_TILE_DMA || forced == OGC_TILE_DMA8) && !dma_ok) ? OGC_TILE_MID : forced;
@@ -270,7 +270,7 @@ double cluster_layer_us(const ogc_mlp_plan_s* p, int l, int split, bool whole) {
 uint32_t cluster_whole_layers(const ogc_mlp_plan_s* p, int split) {
     uint32_t mask = 0;
     const int L = (int)p->layers.size();
-    if (env_int("OGC_CLUSTER_WHOLE", 1) == 0) return 0;  // test override: split every layer
+    if (p->ov.cluster_whole == 0) return 0;  // override: split every layer
     for (int l = 0; l + 1 < L; ++l)
         if (cluster_layer_us(p, l, split, true) < cluster_layer_us(p, l, split, false)) mask |= 1u << l;
     return mask;
@@ -315,6 +315,37 @@ double estimate_cluster_ksplit_us(const ogc_mlp_plan_s* p, int split) {
         all_mb += kb * 32.0 * nb / 1e6;
     }
     return t * (1.0 + c.fill * std::min(1.0, tiles * split / 256.0)) + c.all_mb * tiles * all_mb;
+}
+
+// Workspace of the cluster kernels.  The members of a row tile exchange a layer's output through the workspace and are
+// synchronised only among themselves, so two tiles may be several layers apart.  Every tile therefore owns a private
+// region at a fixed stride (the widest exchanged row block) in each of two slots, and the slots alternate per EXCHANGED
+// layer (a layer that every member computes whole needs no slot and no barrier).  Inside a tile two slots suffice: a
+// member writes exchange e+2 only after the barrier of exchange e+1, which every member reaches only after it has
+// copied exchange e out of the slot that e+2 reuses.  (Life-span reuse as in assign_buffers, Section VI, applied per tile.)
+void assign_cluster_buffers(ogc_mlp_plan_s* p) {
+    const int L = (int)p->layers.size();
+    p->cluster_whole_mask = p->cluster_ksplit ? 0u : cluster_whole_layers(p, p->cluster_split);
+    size_t stride = 0;
+    for (int l = 0; l + 1 < L; ++l)
+        if (!((p->cluster_whole_mask >> l) & 1)) stride = std::max(stride, (size_t)p->layers[l].kc_out * 512);
+    stride = round_up(stride, 256);
+    const size_t tiles = (size_t)(p->desc.m + 31) / 32, slot_bytes = tiles * stride;
+    p->cluster_tile_stride = stride;
+    p->slot_off.assign({0, slot_bytes});
+    p->slot_size.assign({slot_bytes, slot_bytes});
+    int exchanges = 0;
+    for (int l = 0; l < L; ++l) {
+        LayerPlan& lp = p->layers[l];
+        if (l + 1 < L && !((p->cluster_whole_mask >> l) & 1)) {
+            lp.out_slot = exchanges++ & 1;
+            lp.out_off = p->slot_off[lp.out_slot];
+        } else {
+            lp.out_slot = -1;
+            lp.out_off = 0;
+        }
+    }
+    p->workspace_bytes = exchanges > 1 ? 2 * slot_bytes : (exchanges == 1 ? slot_bytes : 0);
 }
 
 ogc_status validate(const ogc_mlp_desc* d) {
@@ -397,14 +428,27 @@ void fill_args(const ogc_mlp_plan_s* p, int l, const uint8_t* packed, OgcLayerAr
 extern "C" {
 
 ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
+    return ogc_mlp_plan_with_overrides(desc, nullptr, out_plan);
+}
+
+ogc_status ogc_mlp_plan_with_overrides(const ogc_mlp_desc* desc, const ogc_plan_overrides* overrides, ogc_mlp_plan_t* out_plan) {
     if (!out_plan) return OGC_ERR_INVALID_ARG;
     ogc_status st = validate(desc);
     if (st != OGC_OK) return st;
+    const ogc_plan_overrides none = {-1, -1, -1, -1, -1};
+    const ogc_plan_overrides ov = overrides ? *overrides : none;
+    if (ov.tile < -1 || ov.tile >= OGC_NUM_TILES || ov.ksplit_log2 < -1 || ov.ksplit_log2 > 3 || ov.cluster_split < -1 ||
+        ov.cluster_split > 32 || ov.cluster_ksplit < -1 || ov.cluster_ksplit > 1 || ov.cluster_whole < -1 || ov.cluster_whole > 1)
+        return OGC_ERR_INVALID_ARG;
     ogc_mlp_plan_s* p = new (std::nothrow) ogc_mlp_plan_s();
     if (!p) return OGC_ERR_INVALID_ARG;
     p->desc = *desc;
     p->desc.layers = nullptr;
+    p->ov = ov;
     p->prepacked.store(0);
+    p->cu_count.store(0);
+    p->barrier_budget.store(OGC_BARRIER_BUDGET);
+    p->barrier_extra.store(0);
     const int L = desc->n_layers;
     const int esz = desc->dtype == OGC_F32 ? 4 : (desc->dtype == OGC_BF16 ? 2 : 1);
     p->esz = esz;
@@ -457,7 +501,8 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
                             !(desc->dtype == OGC_I8 && lp.d.in_zp != 128) &&
                             (l > 0 || desc->x_layout == OGC_LAYOUT_BLOCKED ||
                              (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
-        choose_tile_and_split(desc->dtype, desc->m, rows, lp.kc / 4, dma_ok, &lp.tile, &lp.ksplit_log2, &lp.est_us);
+        choose_tile_and_split(desc->dtype, desc->m, rows, lp.kc / 4, dma_ok, p->ov.tile, p->ov.ksplit_log2, &lp.tile, &lp.ksplit_log2,
+                              &lp.est_us);
         if (lp.est_us < 0) per_timed = false;
         per_us += lp.est_us - kProfiledLaunchExtraUs;
     }
@@ -465,12 +510,12 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
     p->mode_us[1] = (fused_fits && (desc->dtype == OGC_I8 || wbytes <= (size_t)2600000)) ? estimate_fused_us(p) : -1.0;
     p->mode_us[2] = (!blocked_io && L > 1) ? estimate_coop_us(p) : -1.0;
     // The cooperative mode has two kernels: blocks dealt to all workgroups (above), or a few workgroups per row tile
-    // (the cluster kernel).  The split with the lowest estimate competes; OGC_CLUSTER_SPLIT overrides (0: never).
+    // (the cluster kernel).  The split with the lowest estimate competes; the cluster_split override forces one (0: never).
     p->cluster_split = p->cluster_ksplit = 0;
     p->cluster_spread = wbytes > (size_t)3000000;  // weights beyond one XCD's L2: a tile's members on different XCDs
     const bool ksplit_fits = ogc_cluster_ksplit_lds_bytes((size_t)max_kc * 512) <= ogc_fused_lds_limit();
-    const int forced = env_int("OGC_CLUSTER_SPLIT", -1);
-    const int forced_ks = env_int("OGC_CLUSTER_KSPLIT", -1);
+    const int forced = p->ov.cluster_split;
+    const int forced_ks = p->ov.cluster_ksplit;
     if (p->mode_us[2] >= 0 && forced > 0 && forced_ks == 1) {
         // test override: the k-split variant with this many members per tile
         if (ksplit_fits && ogc_cluster_xcds((desc->m + 31) / 32, forced, p->cluster_spread) >= 0) {
@@ -559,7 +604,11 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc, ogc_mlp_plan_t* out_plan) {
     p->packed_bytes = off;
     p->partial_off = p->partial_bytes = 0;
     if (mode != OGC_MODE_COOP) p->cluster_split = p->cluster_ksplit = 0;
-    if (mode == OGC_MODE_COOP) {
+    p->cluster_whole_mask = 0;
+    p->cluster_tile_stride = 0;
+    if (mode == OGC_MODE_COOP && p->cluster_split > 0) {
+        assign_cluster_buffers(p);
+    } else if (mode == OGC_MODE_COOP) {
         assign_buffers(p);
     } else if (mode == OGC_MODE_PER_LAYER) {
         assign_buffers(p);
@@ -709,23 +758,30 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
         long max_blocks = 1;
         for (int l = 0; l < L; ++l) {
             finish_args(l, &c.layer[l]);
-            if (l > 0) c.layer[l].x = ws + plan->layers[l - 1].out_off;
-            if (l < L - 1) c.layer[l].y = ws + plan->layers[l].out_off;
+            if (l > 0 && plan->layers[l - 1].out_slot >= 0) c.layer[l].x = ws + plan->layers[l - 1].out_off;
+            if (l < L - 1 && plan->layers[l].out_slot >= 0) c.layer[l].y = ws + plan->layers[l].out_off;
             const long nb = l < L - 1 ? plan->layers[l].nb_out : (plan->layers[l].d.n + 31) / 32;
             if ((long)m_blocks * nb > max_blocks) max_blocks = (long)m_blocks * nb;
         }
+        c.barrier_budget = plan->barrier_budget.load();
+        c.barrier_extra = plan->barrier_extra.load();
+        int cus = plan->cu_count.load();
+        if (cus <= 0) {  // asked once per plan: two runtime calls
+            cus = ogc_device_cu_count();
+            if (cus <= 0) return OGC_ERR_DEVICE;
+            plan->cu_count.store(cus);
+        }
         if (plan->cluster_split > 0) {
             c.lds_buf_bytes = plan->lds_buf_bytes;
-            c.cluster_whole_mask = plan->cluster_ksplit ? 0u : cluster_whole_layers(plan, plan->cluster_split);
+            c.cluster_whole_mask = plan->cluster_whole_mask;
+            c.cluster_tile_stride = (uint32_t)plan->cluster_tile_stride;
             if (ev && hipEventRecord(ev[0], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
             const int rc = ogc_launch_cluster(plan->desc.dtype, plan->cluster_ksplit, &c, m_blocks, plan->cluster_split, plan->cluster_spread,
-                                              (void*)(blob + plan->sync_off), stream);
+                                              cus, (void*)(blob + plan->sync_off), stream);
             if (rc != 0) return OGC_ERR_DEVICE;
             if (ev && hipEventRecord(ev[1], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
             return OGC_OK;
         }
-        int cus = ogc_device_cu_count();
-        if (cus <= 0) return OGC_ERR_DEVICE;
         const int grid = (int)(max_blocks < cus ? max_blocks : cus);
         if (ev && hipEventRecord(ev[0], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
         const int rc = ogc_launch_coop(plan->desc.dtype, &c, m_blocks, grid, (void*)(blob + plan->sync_off), stream);
@@ -781,7 +837,38 @@ ogc_status ogc_mlp_run_profiled(ogc_mlp_plan_t plan, const void* x, void* y, con
         for (int i = 0; i < n; ++i)
             if (hipEventElapsedTime(&launch_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = OGC_ERR_DEVICE;
     for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    if (st == OGC_OK) st = ogc_mlp_check(plan, packed, stream);
     return st;
+}
+
+ogc_status ogc_mlp_check(ogc_mlp_plan_t plan, const void* packed, void* stream) {
+    if (!plan || !packed) return OGC_ERR_INVALID_ARG;
+    if (plan->mode != OGC_MODE_COOP) return OGC_OK;  // the other modes have no waits that can give up
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
+    uint8_t* word = (uint8_t*)packed + plan->sync_off + (size_t)OGC_SYNC_ERR_WORD * 8;
+    unsigned long long v = 0;
+    if (hipMemcpy(&v, word, sizeof v, hipMemcpyDeviceToHost) != hipSuccess) return OGC_ERR_DEVICE;
+    if (v == 0) return OGC_OK;
+    // reported once: the word and the counters start the next run from zero
+    if (ogc_launch_zero_sync((uint8_t*)packed + plan->sync_off, stream) != 0) return OGC_ERR_DEVICE;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
+    return OGC_ERR_TIMEOUT;
+}
+
+ogc_status ogc_mlp_test_barrier(ogc_mlp_plan_t plan, int32_t budget, int32_t extra_target) {
+    if (!plan || budget < 1 || extra_target < 0) return OGC_ERR_INVALID_ARG;
+    plan->barrier_budget.store(budget);
+    plan->barrier_extra.store(extra_target);
+    return OGC_OK;
+}
+
+ogc_status ogc_mlp_cluster_layout(ogc_mlp_plan_t plan, int32_t* members, int32_t* ksplit, uint32_t* whole_mask, size_t* tile_stride) {
+    if (!plan || !members || !ksplit || !whole_mask || !tile_stride) return OGC_ERR_INVALID_ARG;
+    *members = plan->mode == OGC_MODE_COOP ? plan->cluster_split : 0;
+    *ksplit = plan->cluster_ksplit;
+    *whole_mask = plan->cluster_whole_mask;
+    *tile_stride = plan->cluster_tile_stride;
+    return OGC_OK;
 }
 
 void ogc_mlp_destroy(ogc_mlp_plan_t plan) { delete plan; }
@@ -796,6 +883,7 @@ const char* ogc_status_string(ogc_status s) {
     case OGC_ERR_WORKSPACE: return "workspace missing";
     case OGC_ERR_NOT_PREPACKED: return "weights not prepacked";
     case OGC_ERR_DEVICE: return "HIP runtime error";
+    case OGC_ERR_TIMEOUT: return "a barrier wait of the cooperative mode gave up: the output of that run is invalid";
     }
     return "unknown status";
 }

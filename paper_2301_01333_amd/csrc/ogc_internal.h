@@ -66,11 +66,18 @@ struct OgcChainArgs {
     int32_t fused_tiles;    // fused and cluster kernels: number of 32-row tiles
     int32_t cluster_split;  // cluster kernel: workgroups that share a row tile
     uint32_t cluster_whole_mask;  // cluster kernel: bit l set = every member computes the whole of layer l (no exchange)
+    uint32_t cluster_tile_stride; // cluster kernels: bytes between the exchange regions of two row tiles inside a workspace
+                                  // slot (the widest exchanged row block: the same for every layer, so that the regions
+                                  // of different tiles never overlap whichever layers the tiles are at)
+    int32_t barrier_budget;       // cooperative and cluster kernels: polls before a barrier wait gives up
+    int32_t barrier_extra;        // added to every barrier's target; 0 except in the test of the give-up path
     OgcLayerArgs layer[OGC_MAX_LAYERS];
 };
 
 #define OGC_SYNC_STRIDE 16    // 64-bit words between the counters of two row tiles: a 128-byte line each
 #define OGC_SYNC_WORDS 2048   // 64-bit words at the end of the packed blob (cooperative and cluster kernels)
+#define OGC_SYNC_ERR_WORD 2   // set to 1 by a workgroup whose barrier wait gave up; read and cleared by ogc_mlp_check
+#define OGC_BARRIER_BUDGET (1 << 22)
 
 enum { OGC_TILE_BIG = 0, OGC_TILE_MID = 1, OGC_TILE_SMALL = 2, OGC_TILE_DMA = 3, OGC_TILE_DMA8 = 4, OGC_NUM_TILES = 5 };
 
@@ -88,8 +95,10 @@ int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain, const OgcL
 int ogc_launch_fused(int dtype, const OgcChainArgs* c, int m_blocks, void* stream);
 int ogc_launch_coop(int dtype, const OgcChainArgs* c, int m_blocks, int grid, void* sync, void* stream);
 int ogc_launch_zero_sync(void* sync, void* stream);
+int ogc_launch_zero_words(void* words, int n, void* stream);
 int ogc_cluster_xcds(int m_blocks, int split, int spread);
-int ogc_launch_cluster(int dtype, int ksplit, const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync, void* stream);
+int ogc_launch_cluster(int dtype, int ksplit, const OgcChainArgs* c, int m_blocks, int split, int spread, int cus, void* sync,
+                       void* stream);
 size_t ogc_cluster_ksplit_lds_bytes(size_t lds_buf_bytes);
 int ogc_device_cu_count(void);
 const char* ogc_coop_kernel_name(int dtype);

@@ -11,6 +11,8 @@
 
 #include <stdio.h>
 #include <string.h>
+#include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "ogc_internal.h"
@@ -639,19 +641,38 @@ __global__ void ogc_prepack_weights_kernel(const uint8_t* __restrict__ w, uint8_
     *(v4i*)(out + (size_t)idx * 16) = (v4i){(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
 }
 
-__global__ void ogc_prepack_params_kernel(int dtype, const int8_t* __restrict__ wq, const float* __restrict__ w_scale,
-                                          const float* __restrict__ bias, float in_scale, int in_zp, int K, int N, int NPw,
-                                          float* __restrict__ scale_out, float* __restrict__ bias_out,
-                                          int32_t* __restrict__ ncomp_out) {
-    const int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= NPw) return;
+// Per-channel parameters.  A workgroup covers 64 channels; its eight waves take every eighth row of the plain [K,N]
+// weights each (a wave's 64 lanes read 64 consecutive bytes of a row) and their partial column sums are added through
+// LDS.  The sums are integers: the order does not matter.
+#define OGC_PARAMS_SLICES 8
+__global__ void __launch_bounds__(64 * OGC_PARAMS_SLICES)
+ogc_prepack_params_kernel(int dtype, const int8_t* __restrict__ wq, const float* __restrict__ w_scale,
+                          const float* __restrict__ bias, float in_scale, int in_zp, int K, int N, int NPw,
+                          float* __restrict__ scale_out, float* __restrict__ bias_out, int32_t* __restrict__ ncomp_out) {
+    __shared__ int32_t part[OGC_PARAMS_SLICES][64];
+    const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int n = blockIdx.x * 64 + col;
     const bool valid = n < N;
+    int32_t wsum = 0;
+    if (dtype == OGC_I8 && valid) {
+        const int8_t* p = wq + n;
+        int k = slice;
+        for (; k + 3 * OGC_PARAMS_SLICES < K; k += 4 * OGC_PARAMS_SLICES) {  // four rows in flight
+            const int32_t a = p[(size_t)k * N], b = p[(size_t)(k + OGC_PARAMS_SLICES) * N];
+            const int32_t c = p[(size_t)(k + 2 * OGC_PARAMS_SLICES) * N], d = p[(size_t)(k + 3 * OGC_PARAMS_SLICES) * N];
+            wsum += (a + b) + (c + d);
+        }
+        for (; k < K; k += OGC_PARAMS_SLICES) wsum += (int32_t)p[(size_t)k * N];
+    }
+    part[slice][col] = wsum;
+    __syncthreads();
+    if (slice != 0 || n >= NPw) return;
     bias_out[n] = (valid && bias) ? bias[n] : 0.0f;
     if (dtype == OGC_I8) {
-        int32_t wsum = 0;
-        if (valid)
-            for (int k = 0; k < K; ++k) wsum += (int32_t)wq[(size_t)k * N + n];
-        ncomp_out[n] = -(in_zp - 128) * wsum;
+        int32_t total = 0;
+#pragma unroll
+        for (int s2 = 0; s2 < OGC_PARAMS_SLICES; ++s2) total += part[s2][col];
+        ncomp_out[n] = -(in_zp - 128) * total;
         scale_out[n] = valid ? in_scale * w_scale[n] : 0.0f;
     }
 }
@@ -738,16 +759,37 @@ template <int DT> OGC_DEV void partial_add(v4i (*red)[4][64], int slot, int lane
 #define OGC_COOP_U 4      // k-steps a wave keeps in flight (8 measured: no better)
 #define OGC_COOP_THREADS (OGC_COOP_WAVES * 64)
 
-OGC_DEV void coop_grid_barrier(unsigned long long* ctr, unsigned long long target, int tid) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's result stores (inline assembly) have completed
-    __syncthreads();
+// The wait of a barrier on a counter in global memory, after the caller's waves have synchronised: thread 0 arrives and
+// polls until `target` arrivals or until `budget` polls have passed.  A wait that gives up sets the error word of the
+// sync area (system scope: the host reads it, ogc_mlp_check) and the function returns false in every thread of the
+// workgroup, which then abandons the rest of the chain; the workgroups still waiting for it give up the same way, so
+// every workgroup exits.  flag: four bytes of LDS that are free at this point (the verdict crosses the workgroup there).
+OGC_DEV bool barrier_wait(unsigned long long* ctr, unsigned long long target, int budget, unsigned long long* err, int* flag,
+                          int tid) {
     if (tid == 0) {
         __hip_atomic_fetch_add(ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int budget = 1 << 22;
-        while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target && --budget > 0)
+        bool reached = false;
+        for (int polls = 0; polls < budget; ++polls) {
+            if (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) {
+                reached = true;
+                break;
+            }
             __builtin_amdgcn_s_sleep(1);
+        }
+        if (!reached) __hip_atomic_store(err, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        *(volatile int*)flag = reached ? 1 : 0;
     }
     __syncthreads();
+    const bool ok = *(volatile int*)flag != 0;
+    __syncthreads();  // the caller reuses the flag's storage
+    return ok;
+}
+
+OGC_DEV bool coop_grid_barrier(unsigned long long* ctr, unsigned long long target, int budget, unsigned long long* err, int* flag,
+                               int tid) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's result stores (inline assembly) have completed
+    __syncthreads();
+    return barrier_wait(ctr, target, budget, err, flag, tid);
 }
 
 // 16 bytes of another workgroup's result, read coherently at system scope (two relaxed 64-bit atomic loads)
@@ -859,7 +901,9 @@ __global__ void __launch_bounds__(OGC_COOP_THREADS) ogc_coop_chain_kernel(const 
             }
             __syncthreads();  // red is reused by the next block
         }
-        if (!last) coop_grid_barrier(sync, (unsigned long long)(l + 1) * G, tid);
+        if (!last && !coop_grid_barrier(sync, (unsigned long long)(l + 1) * G + c.barrier_extra, c.barrier_budget,
+                                        sync + OGC_SYNC_ERR_WORD, (int*)&red[0][0][0], tid))
+            break;  // the wait gave up (recorded in the sync area): the rest of the chain is abandoned
     }
     // the last workgroup out resets the counters for the next run
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -926,9 +970,15 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_chain_kernel(co
             fused_layer<DT, 0>(a, xin, xout, m0, wave, OGC_FUSED_WAVES, lane);
             __syncthreads();
         } else if (l + 1 < c.n_layers) {
-            uint8_t* ytile = a.y + (size_t)tile * a.KC_out * 512;  // the tile in blocked layout = its LDS image
+            // the tile in blocked layout = its LDS image; a.y is the layer's exchange slot, in which every tile owns a
+            // region at a fixed stride (not the layer's own row-block size: a tile two layers ahead of its neighbour
+            // must not reach into the neighbour's region)
+            uint8_t* ytile = a.y + (size_t)tile * c.cluster_tile_stride;
             fused_layer<DT, 0>(a, xin, GlobalY{ytile}, m0, vwave, vwaves, lane);
-            coop_grid_barrier(ctr, (unsigned long long)(++barriers) * S, tid);
+            // xout is free until the copy below fills it: its first bytes carry the barrier's verdict
+            if (!coop_grid_barrier(ctr, (unsigned long long)(++barriers) * S + c.barrier_extra, c.barrier_budget,
+                                   sync + OGC_SYNC_ERR_WORD, (int*)xout, tid))
+                break;
             copy_tile_coherent(xout, ytile, a.KC_out * 32, tid);
             __syncthreads();
         } else {
@@ -994,7 +1044,7 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_ksplit_chain_ke
         const bool last = l + 1 == c.n_layers;
         const int nb = last ? ((a.N + 31) >> 5) : a.NB_out;
         const int KP2 = a.KC >> 1;  // 32-byte k-steps
-        uint8_t* ytile = last ? nullptr : a.y + (size_t)tile * a.KC_out * 512;
+        uint8_t* ytile = last ? nullptr : a.y + (size_t)tile * c.cluster_tile_stride;  // fixed stride: see the kernel above
         for (int bn = member; bn < nb; bn += S) {
             typename AccT<DT>::type acc;
 #pragma unroll
@@ -1049,14 +1099,10 @@ __global__ void __launch_bounds__(OGC_FUSED_THREADS) ogc_cluster_ksplit_chain_ke
             }
             ++barriers;
             __syncthreads();
-            if (tid == 0) {
-                __hip_atomic_fetch_add(ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const unsigned long long target = (unsigned long long)barriers * S;
-                int budget = 1 << 22;  // bounded, as in the cooperative kernel's barrier
-                while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target && --budget > 0)
-                    __builtin_amdgcn_s_sleep(1);
-            }
-            __syncthreads();
+            // bounded, as in the cooperative kernel's barrier; the reduction scratch is free here and carries the verdict
+            if (!barrier_wait(ctr, (unsigned long long)barriers * S + c.barrier_extra, c.barrier_budget, sync + OGC_SYNC_ERR_WORD,
+                              (int*)&red[0][0][0], tid))
+                break;
             copy_tile_coherent(buf, ytile, a.KC_out * 32, tid);
             __syncthreads();
         }
@@ -1114,11 +1160,11 @@ template <int DT, int TILE, int XP, int OP>
 static int launch_layer_t(const OgcLayerArgs* a, hipStream_t stream) {
     const OgcTileInfo ti = tile_info_t<TILE>();
     auto kern = ogc_layer_kernel<DT, TILE, XP, OP>;
-    static bool attr_set = false;  // raising the LDS limit is idempotent; a race only repeats it
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};  // raising the LDS limit is idempotent; two threads at once only repeat it
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ti.lds_bytes);
         if (e != hipSuccess) return (int)e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int nrows = OP ? a->N : a->NB_out * 32;
     const int tiles_n = (nrows + ti.bn - 1) / ti.bn;
@@ -1148,11 +1194,11 @@ template <int DT, int SHAPE, int XP, int OP, int EPI>
 static int launch_dma_t(const OgcLayerArgs* a, hipStream_t stream) {
     typedef StreamCfg<SHAPE> C;
     auto kern = ogc_layer_dma_kernel<DT, SHAPE, XP, OP, EPI>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
         if (e != hipSuccess) return (int)e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     // (a split-K launch always writes partials; NB_out == 0 marks the chain's last layer, whose width is N)
     const int nrows = (OP || (EPI == 2 && a->NB_out == 0)) ? a->N : a->NB_out * 32;
@@ -1215,11 +1261,15 @@ extern "C" int ogc_fused_threads(void) { return OGC_FUSED_THREADS; }
 template <int DT> static int launch_fused_t(const OgcChainArgs* c, int m_blocks, hipStream_t stream) {
     auto kern = ogc_fused_chain_kernel<DT>;
     const size_t lds = (size_t)2 * c->lds_buf_bytes;
-    static size_t attr_max = 0;
-    if (lds > attr_max) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return (int)e;
-        attr_max = lds;
+    {   // the limit only ever grows; the lock keeps raising it and remembering it together
+        static std::mutex mu;
+        static size_t attr_max = 0;
+        std::lock_guard<std::mutex> hold(mu);
+        if (lds > attr_max) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return (int)e;
+            attr_max = lds;
+        }
     }
     OgcChainArgs args = *c;
     // Up to 16 row tiles per XCD before the next XCD is used: every XCD that takes part fetches all the weights
@@ -1258,6 +1308,14 @@ extern "C" int ogc_launch_coop(int dtype, const OgcChainArgs* c, int m_blocks, i
     }
 }
 
+__global__ void ogc_zero_words_kernel(unsigned long long* w, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) w[i] = 0;
+}
+extern "C" int ogc_launch_zero_words(void* words, int n, void* stream) {
+    hipLaunchKernelGGL(ogc_zero_words_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (unsigned long long*)words, n);
+    return (int)hipGetLastError();
+}
+
 extern "C" int ogc_launch_zero_sync(void* sync, void* stream) {
     hipLaunchKernelGGL(ogc_zero_sync_kernel, dim3(1), dim3(512), 0, (hipStream_t)stream, (unsigned long long*)sync);
     return (int)hipGetLastError();
@@ -1276,18 +1334,22 @@ extern "C" int ogc_cluster_xcds(int m_blocks, int split, int spread) {
     return -1;
 }
 
-template <int DT, int KSPLIT> static int launch_cluster_t(const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync, hipStream_t stream) {
+template <int DT, int KSPLIT> static int launch_cluster_t(const OgcChainArgs* c, int m_blocks, int split, int spread, int cus, void* sync, hipStream_t stream) {
     auto kern = KSPLIT ? ogc_cluster_ksplit_chain_kernel<DT> : ogc_cluster_chain_kernel<DT>;
     const size_t lds = KSPLIT ? (size_t)c->lds_buf_bytes + OGC_KS_RED_BYTES : (size_t)2 * c->lds_buf_bytes;
-    static size_t attr_max = 0;
-    if (lds > attr_max) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return (int)e;
-        attr_max = lds;
+    {   // the limit only ever grows; the lock keeps raising it and remembering it together
+        static std::mutex mu;
+        static size_t attr_max = 0;
+        std::lock_guard<std::mutex> hold(mu);
+        if (lds > attr_max) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return (int)e;
+            attr_max = lds;
+        }
     }
     const int xcds = ogc_cluster_xcds(m_blocks, split, spread);
     // every member waits for the others of its tile: all of them need a CU at once (the plan assumed 256 CUs)
-    if (xcds < 0 || (long)m_blocks * split > ogc_device_cu_count()) return (int)hipErrorInvalidValue;
+    if (xcds < 0 || (long)m_blocks * split > cus) return (int)hipErrorInvalidValue;
     OgcChainArgs args = *c;
     args.fused_xcds = xcds;  // 0: spread
     args.fused_tiles = m_blocks;
@@ -1301,20 +1363,21 @@ extern "C" size_t ogc_cluster_ksplit_lds_bytes(size_t lds_buf_bytes) { return ld
 
 // ksplit: the kernel whose waves split K inside a member (one LDS buffer + reduction scratch) instead of the one
 // whose waves take different channel blocks (two LDS buffers)
-extern "C" int ogc_launch_cluster(int dtype, int ksplit, const OgcChainArgs* c, int m_blocks, int split, int spread, void* sync,
-                                  void* stream) {
+// cus: compute units of the device (every member of every tile needs one at the same time)
+extern "C" int ogc_launch_cluster(int dtype, int ksplit, const OgcChainArgs* c, int m_blocks, int split, int spread, int cus,
+                                  void* sync, void* stream) {
     hipStream_t s = (hipStream_t)stream;
     if (ksplit) {
         switch (dtype) {
-        case OGC_F32: return launch_cluster_t<OGC_F32, 1>(c, m_blocks, split, spread, sync, s);
-        case OGC_BF16: return launch_cluster_t<OGC_BF16, 1>(c, m_blocks, split, spread, sync, s);
-        default: return launch_cluster_t<OGC_I8, 1>(c, m_blocks, split, spread, sync, s);
+        case OGC_F32: return launch_cluster_t<OGC_F32, 1>(c, m_blocks, split, spread, cus, sync, s);
+        case OGC_BF16: return launch_cluster_t<OGC_BF16, 1>(c, m_blocks, split, spread, cus, sync, s);
+        default: return launch_cluster_t<OGC_I8, 1>(c, m_blocks, split, spread, cus, sync, s);
         }
     }
     switch (dtype) {
-    case OGC_F32: return launch_cluster_t<OGC_F32, 0>(c, m_blocks, split, spread, sync, s);
-    case OGC_BF16: return launch_cluster_t<OGC_BF16, 0>(c, m_blocks, split, spread, sync, s);
-    default: return launch_cluster_t<OGC_I8, 0>(c, m_blocks, split, spread, sync, s);
+    case OGC_F32: return launch_cluster_t<OGC_F32, 0>(c, m_blocks, split, spread, cus, sync, s);
+    case OGC_BF16: return launch_cluster_t<OGC_BF16, 0>(c, m_blocks, split, spread, cus, sync, s);
+    default: return launch_cluster_t<OGC_I8, 0>(c, m_blocks, split, spread, cus, sync, s);
     }
 }
 
@@ -1347,8 +1410,7 @@ extern "C" int ogc_launch_prepack_weights(const void* w, void* out, int K, int N
 extern "C" int ogc_launch_prepack_params(int dtype, const void* w, const float* w_scale, const float* bias, float in_scale,
                                          int in_zp, int K, int N, int NPw, float* scale_out, float* bias_out,
                                          int32_t* ncomp_out, void* stream) {
-    const int threads = 64;
-    hipLaunchKernelGGL(ogc_prepack_params_kernel, dim3((NPw + threads - 1) / threads), dim3(threads), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(ogc_prepack_params_kernel, dim3((NPw + 63) / 64), dim3(64 * OGC_PARAMS_SLICES), 0, (hipStream_t)stream,
                        dtype, (const int8_t*)w, w_scale, bias, in_scale, in_zp, K, N, NPw, scale_out, bias_out, ncomp_out);
     return (int)hipGetLastError();
 }

@@ -17,7 +17,8 @@ def _to_device(torch, arr: np.ndarray):
 class DeviceMLP:
     """A workload resident on the GPU: plan, packed weights, input and output buffers."""
 
-    def __init__(self, wl, mode: int = binding.OGC_MODE_AUTO, ld_y: Optional[int] = None, x_byte_offset: int = 0):
+    def __init__(self, wl, mode: int = binding.OGC_MODE_AUTO, ld_y: Optional[int] = None, x_byte_offset: int = 0,
+                 overrides: Optional[dict] = None):
         import torch
 
         self.torch = torch
@@ -29,7 +30,7 @@ class DeviceMLP:
         last = wl.layers[-1]
         self.out_np_dtype = np.float32 if (wl.dtype == "i8" and last.out_f32) else {"f32": np.float32, "bf16": np.uint16, "i8": np.uint8}[wl.dtype]
         self.ld_y = ld_y or last.n
-        self.mlp = binding.FusedMLP(wl.dtype, wl.m, wl.layers, self.ld_x, self.ld_y, wl.residual, mode)
+        self.mlp = binding.FusedMLP(wl.dtype, wl.m, wl.layers, self.ld_x, self.ld_y, wl.residual, mode, overrides=overrides)
         self.w = [_to_device(torch, w) for w in wl.w]
         self.bias = [None if b is None else _to_device(torch, b) for b in wl.bias]
         self.w_scale = None if wl.dtype != "i8" else [_to_device(torch, s) for s in wl.w_scale]

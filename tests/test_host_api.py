@@ -121,61 +121,133 @@ def test_mode_choice_and_sizes():
     b.ogc_mlp_destroy(p)
 
 
-def test_cluster_split_override(monkeypatch):
-    """OGC_CLUSTER_SPLIT picks the cooperative mode's kernel: 0 = blocks dealt to all workgroups, n = n workgroups
-    per row tile, where they fit one per CU; unset = the cost model's choice."""
+def test_cluster_split_override():
+    """The cluster_split override picks the cooperative mode's kernel: 0 = blocks dealt to all workgroups, n = n
+    workgroups per row tile, where they fit one per CU; unset = the cost model's choice."""
     dims = [479, 1024, 1024, 512, 256]
     ls = [layer(dims[i], dims[i + 1]) for i in range(4)]
 
     narrow = [layer(256, 512), layer(512, 256)]  # fp32 rows of 1024 values do not fit the two LDS buffers
 
+    ov = {}
+
     def name(m, dtype=b.OGC_I8):
-        p = b.ogc_mlp_plan(dtype, m, narrow if dtype == b.OGC_F32 else ls, 256 if dtype == b.OGC_F32 else 479, 256, 0, b.OGC_MODE_COOP)
+        p = b.ogc_mlp_plan_with_overrides(dtype, m, narrow if dtype == b.OGC_F32 else ls, 256 if dtype == b.OGC_F32 else 479, 256, 0,
+                                          b.OGC_MODE_COOP, overrides=ov)
         n = b.ogc_mlp_kernel_name(p, 0)
         b.ogc_mlp_destroy(p)
         return n
 
-    monkeypatch.setenv("OGC_CLUSTER_SPLIT", "0")
+    ov["cluster_split"] = 0
     assert name(256) == "ogc_coop_chain_kernel<2>"
-    monkeypatch.setenv("OGC_CLUSTER_SPLIT", "4")
+    ov["cluster_split"] = 4
     assert name(256) == "ogc_cluster_chain_kernel<2>"
     assert name(256, b.OGC_F32) == "ogc_cluster_chain_kernel<0>"
     assert name(32 * 65) == "ogc_coop_chain_kernel<2>"      # 65 tiles x 4 members do not fit 256 CUs
     # the variant whose waves split K inside a member
-    monkeypatch.setenv("OGC_CLUSTER_KSPLIT", "1")
+    ov["cluster_ksplit"] = 1
     assert name(256) == "ogc_cluster_ksplit_chain_kernel<2>"
     assert name(256, b.OGC_F32) == "ogc_cluster_ksplit_chain_kernel<0>"
     assert name(32 * 65) == "ogc_coop_chain_kernel<2>"
-    # unset: the cost model's choice; OGC_CLUSTER_KSPLIT=0 keeps the k-split variant out of it
-    monkeypatch.delenv("OGC_CLUSTER_SPLIT")
-    monkeypatch.setenv("OGC_CLUSTER_KSPLIT", "0")
+    # unset: the cost model's choice; cluster_ksplit = 0 keeps the k-split variant out of it
+    del ov["cluster_split"]
+    ov["cluster_ksplit"] = 0
     assert name(256) == "ogc_cluster_chain_kernel<2>"
     assert name(256, b.OGC_F32) == "ogc_coop_chain_kernel<0>"  # the channel-split kernel is never the model's choice for fp32
-    monkeypatch.delenv("OGC_CLUSTER_KSPLIT")
+    del ov["cluster_ksplit"]
     assert name(256).startswith("ogc_cluster_")
     assert name(256, b.OGC_F32) == "ogc_cluster_ksplit_chain_kernel<0>"
+    # a field outside its range is refused; the process environment plays no part in a plan
+    with pytest.raises(b.OgcError):
+        b.ogc_mlp_plan_with_overrides(b.OGC_I8, 256, ls, 479, 256, 0, b.OGC_MODE_COOP, overrides={"tile": 7})
 
 
-def test_cooperative_estimate_is_the_lowest_of_its_kernels(monkeypatch):
+def test_cooperative_estimate_is_the_lowest_of_its_kernels():
     """ogc_mlp_mode_estimates()[2] is the estimate of the kernel the cooperative mode would launch: never above the
-    block-dealing kernel's own estimate (what OGC_CLUSTER_SPLIT=0 leaves), equal to it where no cluster kernel fits."""
-    def coop_est(dtype, m, dims):
-        p = b.ogc_mlp_plan(dtype, m, [layer(dims[i], dims[i + 1]) for i in range(len(dims) - 1)], dims[0], dims[-1], 0, 0)
+    block-dealing kernel's own estimate (what cluster_split = 0 leaves), equal to it where no cluster kernel fits."""
+    def coop_est(dtype, m, dims, ov=None):
+        p = b.ogc_mlp_plan_with_overrides(dtype, m, [layer(dims[i], dims[i + 1]) for i in range(len(dims) - 1)], dims[0], dims[-1], 0, 0,
+                                          overrides=ov)
         e, name = b.ogc_mlp_mode_estimates(p)[2], b.ogc_mlp_kernel_name(p, 0) if b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_COOP else ""
         b.ogc_mlp_destroy(p)
         return e, name
     cases = [(b.OGC_I8, 256, [479, 1024, 1024, 512, 256]), (b.OGC_F32, 512, [479, 1024, 1024, 512, 256]),
              (b.OGC_BF16, 128, [1024, 1024, 1024]), (b.OGC_I8, 64, [64, 64, 64]), (b.OGC_F32, 32 * 300, [512, 512, 512])]
     for dtype, m, dims in cases:
-        monkeypatch.setenv("OGC_CLUSTER_SPLIT", "0")
-        base, _ = coop_est(dtype, m, dims)
-        monkeypatch.delenv("OGC_CLUSTER_SPLIT")
+        base, _ = coop_est(dtype, m, dims, {"cluster_split": 0})
         best, name = coop_est(dtype, m, dims)
         assert 0 < best <= base
         if m > 32 * 128:                      # 300 row tiles: no cluster kernel has a CU for every member
             assert best == base and "cluster" not in name
         if name.startswith("ogc_cluster"):
             assert best < base
+
+
+def test_cluster_exchange_regions_are_private_per_tile():
+    """The members of a row tile are synchronised only among themselves, so two tiles may be layers apart: for every
+    pair of exchanged layers that share a workspace slot, the regions of DISTINCT tiles must be disjoint whatever the
+    layers' widths, consecutive exchanged layers must sit in different slots, and everything must fit the workspace."""
+    def regions(dtype, m, dims, ov):
+        ls = [layer(dims[i], dims[i + 1]) for i in range(len(dims) - 1)]
+        p = b.ogc_mlp_plan_with_overrides(dtype, m, ls, dims[0], dims[-1], 0, b.OGC_MODE_COOP, overrides=ov)
+        members, ksplit, whole, stride = b.ogc_mlp_cluster_layout(p)
+        assert members == ov["cluster_split"] and ksplit == ov.get("cluster_ksplit", 0)
+        esz = {b.OGC_F32: 4, b.OGC_BF16: 2, b.OGC_I8: 1}[dtype]
+        gran = 64 if dtype == b.OGC_I8 else 32
+        tiles = (m + 31) // 32
+        out = []   # (layer, slot, [(start, end) per tile])
+        for l in range(len(ls) - 1):
+            slot, off = b.ogc_mlp_buffer_assignment(p, l)
+            if (whole >> l) & 1:
+                assert slot == -1
+                continue
+            row_block = 32 * ((dims[l + 1] + gran - 1) // gran * gran) * esz    # one tile's rows of the next layer's input
+            assert row_block <= stride
+            out.append((l, slot, [(off + t * stride, off + t * stride + row_block) for t in range(tiles)]))
+        ws = b.ogc_mlp_workspace_bytes(p)
+        b.ogc_mlp_destroy(p)
+        return out, ws, whole
+
+    cases = [(b.OGC_I8, 256, [479, 1024, 1024, 512, 256, 1], {"cluster_split": 32, "cluster_ksplit": 1}),   # config 3's launch
+             (b.OGC_I8, 256, [479, 1024, 1024, 512, 256, 1], {"cluster_split": 4}),                          # one layer computed whole
+             (b.OGC_I8, 256, [479, 1024, 1024, 512, 256, 1], {"cluster_split": 4, "cluster_whole": 0}),
+             (b.OGC_BF16, 270, [48, 64, 320, 64, 320, 16], {"cluster_split": 8, "cluster_whole": 0}),
+             (b.OGC_F32, 200, [100, 333, 72, 33], {"cluster_split": 16, "cluster_ksplit": 1})]
+    saw_whole = False
+    for dtype, m, dims, ov in cases:
+        regs, ws, whole = regions(dtype, m, dims, ov)
+        saw_whole |= whole != 0
+        assert regs, "no exchanged layer"
+        for i, (l, slot, iv) in enumerate(regs):
+            assert slot in (0, 1) and all(e <= ws for _, e in iv)
+            if i > 0:
+                assert slot != regs[i - 1][1]           # consecutive exchanges alternate (also across whole layers)
+            for l2, slot2, iv2 in regs[:i + 1]:
+                if slot2 != slot:
+                    assert all(e <= iv2[0][0] or s >= iv2[-1][1] for s, e in iv)   # the two slots do not overlap at all
+                    continue
+                for t, (s, e) in enumerate(iv):
+                    for t2, (s2, e2) in enumerate(iv2):
+                        if t != t2:
+                            assert e <= s2 or e2 <= s, (l, l2, t, t2)
+    assert saw_whole
+
+
+def test_check_without_waits_and_test_hook_arguments():
+    """ogc_mlp_check answers OGC_OK at once for plans whose kernels have no bounded waits (no device call, so it runs
+    here); the barrier test hook validates its arguments."""
+    p = b.ogc_mlp_plan(b.OGC_I8, 64, [layer(64, 64)], 64, 64, 0, b.OGC_MODE_FUSED)
+    assert b.ogc_mlp_check(p, 256, 0) == b.OGC_OK
+    with pytest.raises(b.OgcError):
+        b.ogc_mlp_check(0, 256, 0)
+    with pytest.raises(b.OgcError):
+        b.ogc_mlp_check(p, 0, 0)
+    b.ogc_mlp_test_barrier(p, 100, 1)
+    for bad in ((0, 0), (10, -1)):
+        with pytest.raises(b.OgcError):
+            b.ogc_mlp_test_barrier(p, *bad)
+    b.ogc_mlp_destroy(p)
+    assert "gave up" in b.status_string(b.OGC_ERR_TIMEOUT)
 
 
 def test_buffer_reuse_is_ping_pong_for_a_chain():
@@ -205,12 +277,10 @@ def test_buffer_reuse_is_ping_pong_for_a_chain():
     b.ogc_mlp_destroy(p)
 
 
-def test_split_k_plan_sizes_and_kernel_names(monkeypatch):
+def test_split_k_plan_sizes_and_kernel_names():
     """A layer with few 256x256 tiles and a long reduction axis is cut into k ranges (k-slicing, Section III):
     the workspace then carries the partial accumulators behind the activation slots, the layer is still one
     launch step, and kernel names carry their template arguments."""
-    monkeypatch.delenv("OGC_TILE", raising=False)
-    monkeypatch.delenv("OGC_KSPLIT", raising=False)
     m, k0, hid = 4096, 1024, 4096
     lay = [layer(k0, hid, act=b.OGC_ACT_GELU_TANH, has_bias=1), layer(hid, k0, act=b.OGC_ACT_NONE, has_bias=1)]
     p = b.ogc_mlp_plan(b.OGC_BF16, m, lay, k0, k0, 1, b.OGC_MODE_AUTO)
@@ -225,19 +295,17 @@ def test_split_k_plan_sizes_and_kernel_names(monkeypatch):
     assert 25.0 < b.ogc_mlp_estimated_us(p, 0) < 45.0 and 40.0 < b.ogc_mlp_estimated_us(p, 1) < 65.0
     b.ogc_mlp_destroy(p)
     # forced off: no partial region, the second layer takes the four-wave stream shape (128 tiles of 128x256)
-    monkeypatch.setenv("OGC_KSPLIT", "0")
-    p = b.ogc_mlp_plan(b.OGC_BF16, m, lay, k0, k0, 1, b.OGC_MODE_AUTO)
+    p = b.ogc_mlp_plan_with_overrides(b.OGC_BF16, m, lay, k0, k0, 1, b.OGC_MODE_AUTO, overrides={"ksplit_log2": 0})
     assert b.ogc_mlp_workspace_bytes(p) == hidden_slot
     assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 0, 0, 1, 0>"
     b.ogc_mlp_destroy(p)
     # a forced split that does not divide the k-steps is ignored
-    monkeypatch.setenv("OGC_TILE", "4")
-    monkeypatch.setenv("OGC_KSPLIT", "3")
-    p = b.ogc_mlp_plan(b.OGC_I8, 300, [layer(64 * 4, 64)], 256, 64, 0, b.OGC_MODE_PER_LAYER)   # 4 k-steps
+    p = b.ogc_mlp_plan_with_overrides(b.OGC_I8, 300, [layer(64 * 4, 64)], 256, 64, 0, b.OGC_MODE_PER_LAYER,
+                                      overrides={"tile": 4, "ksplit_log2": 3})   # 4 k-steps
     assert b.ogc_mlp_workspace_bytes(p) == 0
     b.ogc_mlp_destroy(p)
-    monkeypatch.setenv("OGC_KSPLIT", "2")
-    p = b.ogc_mlp_plan(b.OGC_I8, 300, [layer(64 * 4, 64)], 256, 64, 0, b.OGC_MODE_PER_LAYER)
+    p = b.ogc_mlp_plan_with_overrides(b.OGC_I8, 300, [layer(64 * 4, 64)], 256, 64, 0, b.OGC_MODE_PER_LAYER,
+                                      overrides={"tile": 4, "ksplit_log2": 2})
     assert b.ogc_mlp_workspace_bytes(p) == 4 * 512 * 256 * 4      # ranges x padded rows x padded channels x 4 bytes
     b.ogc_mlp_destroy(p)
 
@@ -319,7 +387,12 @@ def test_auto_mode_choice_follows_the_cost_models():
     pl = b.ogc_mlp_plan(b.OGC_I8, 100, lay, 64, 64, 0, b.OGC_MODE_FUSED)
     assert b.ogc_mlp_num_launches(pc) == 1 and b.ogc_mlp_kernel_name(pc, 0) in (
         "ogc_coop_chain_kernel<2>", "ogc_cluster_chain_kernel<2>", "ogc_cluster_ksplit_chain_kernel<2>")
-    assert b.ogc_mlp_workspace_bytes(pc) == 256 * 256 + 256 * 512
+    members, _, whole, stride = b.ogc_mlp_cluster_layout(pc)
+    if members:   # a cluster kernel: two slots (one if a single layer is exchanged) of a private region per row tile
+        exchanged = 2 - bin(whole & 3).count("1")
+        assert stride >= 32 * 512 and b.ogc_mlp_workspace_bytes(pc) == min(exchanged, 2) * 4 * stride
+    else:
+        assert b.ogc_mlp_workspace_bytes(pc) == 256 * 256 + 256 * 512
     assert b.ogc_mlp_packed_bytes(pc) == b.ogc_mlp_packed_bytes(pl) + 2048 * 8
     b.ogc_mlp_destroy(pc)
     b.ogc_mlp_destroy(pl)
@@ -371,16 +444,13 @@ def test_mha_kernel_names_and_null_checks():
     assert e.value.status == -4
 
 
-def test_cost_model_choices(monkeypatch):
+def test_cost_model_choices():
     """The plan's cost model (Section III: score candidate template parameters, no tuning run) on shapes whose
     fastest candidate was measured: big batches take the eight-wave stream tile, a short wide layer with a long
     reduction axis is cut along K on the four-wave tile, mid-size layers take the small register-staged tile."""
-    monkeypatch.delenv("OGC_TILE", raising=False)
-    monkeypatch.delenv("OGC_KSPLIT", raising=False)
-
-    def mid_layer(dtype, m, dims):
+    def mid_layer(dtype, m, dims, ov=None):
         lay = [layer(dims[i], dims[i + 1], has_bias=0) for i in range(3)]
-        p = b.ogc_mlp_plan(dtype, m, lay, dims[0], dims[3], 0, b.OGC_MODE_PER_LAYER)
+        p = b.ogc_mlp_plan_with_overrides(dtype, m, lay, dims[0], dims[3], 0, b.OGC_MODE_PER_LAYER, overrides=ov)
         r = b.ogc_mlp_kernel_name(p, 1), b.ogc_mlp_estimated_us(p, 1)
         b.ogc_mlp_destroy(p)
         return r
@@ -393,14 +463,9 @@ def test_cost_model_choices(monkeypatch):
     e1, e2 = mid_layer(b.OGC_I8, 16384, [1024] * 4)[1], mid_layer(b.OGC_I8, 32768, [1024] * 4)[1]
     assert 0 < e1 < e2 < 2.5 * e1
     best = mid_layer(b.OGC_I8, 256, [256, 8192, 256, 8192])[1]
-    monkeypatch.setenv("OGC_TILE", "4")
-    monkeypatch.setenv("OGC_KSPLIT", "0")
-    assert mid_layer(b.OGC_I8, 256, [256, 8192, 256, 8192])[1] > 2 * best
+    assert mid_layer(b.OGC_I8, 256, [256, 8192, 256, 8192], {"tile": 4, "ksplit_log2": 0})[1] > 2 * best
     # fp32 layers choose among the register-staged tiles: the big one once the batch is large
-    monkeypatch.delenv("OGC_TILE")
-    monkeypatch.delenv("OGC_KSPLIT")
     assert mid_layer(b.OGC_F32, 128, [512] * 4)[0] == "ogc_layer_kernel<0, 2, 0, 0>"
     assert mid_layer(b.OGC_F32, 16384, [2048] * 4)[0] == "ogc_layer_kernel<0, 0, 0, 0>"
     # a forced stream tile falls back to the mid register-staged tile where the stream kernel cannot run
-    monkeypatch.setenv("OGC_TILE", "4")
-    assert mid_layer(b.OGC_F32, 4096, [512] * 4)[0] == "ogc_layer_kernel<0, 1, 0, 0>"
+    assert mid_layer(b.OGC_F32, 4096, [512] * 4, {"tile": 4})[0] == "ogc_layer_kernel<0, 1, 0, 0>"
