@@ -184,6 +184,20 @@ ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, co
  * (see ogc_mlp_plan and ogc_mlp_check). */
 ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream);
 
+/* ogc_mlp_run for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the workspace is a fixed array inside the library's device image, 8 MiB per GPU
+ * (ogc_mlp_static_workspace_limit), held from the library's load until the process ends.  The call allocates nothing
+ * and frees nothing; x, y and packed are the caller's as in ogc_mlp_run.  The array's device address is looked up
+ * once per device, at the first call made with that device current.
+ * OGC_ERR_WORKSPACE: the plan needs more than the limit (ogc_mlp_workspace_bytes); nothing is launched.
+ * Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (different streams, or
+ * different plans) race on it; the array keeps the last call's contents, which no later call relies on (every
+ * intermediate and every split-K partial is written before it is read). */
+ogc_status ogc_mlp_run_static(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* stream);
+
+/* The size in bytes of the static workspace behind ogc_mlp_run_static. */
+size_t ogc_mlp_static_workspace_limit(void);
+
 /* Number of timed launch steps of one ogc_mlp_run: 1 for the fused-chain kernel, n_layers otherwise (a layer
  * whose reduction axis is split runs two kernels, the k ranges and the pass that adds them, and counts as one). */
 ogc_status ogc_mlp_num_launches(ogc_mlp_plan_t plan, int32_t* n /*host*/);

@@ -26,7 +26,7 @@ EXPORTS = [
     "ogc_mlp_plan", "ogc_mlp_packed_bytes", "ogc_mlp_workspace_bytes", "ogc_mlp_chosen_mode",
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
     "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes", "ogc_mlp_estimated_us", "ogc_mlp_mode_estimates",
-    "ogc_mlp_plan_with_overrides", "ogc_mlp_check", "ogc_mlp_test_barrier", "ogc_mlp_cluster_layout",
+    "ogc_mlp_run_static", "ogc_mlp_static_workspace_limit", "ogc_mlp_plan_with_overrides", "ogc_mlp_check", "ogc_mlp_test_barrier", "ogc_mlp_cluster_layout",
     "ogc_mha_validate", "ogc_mha_run", "ogc_mha_kernel_name",
 ]
 OGC_ERR_TIMEOUT = -8
@@ -99,6 +99,10 @@ def lib():
         l.ogc_mlp_prepack_weights.restype = i32
         l.ogc_mlp_run.argtypes = [vp, vp, vp, vp, vp, vp]
         l.ogc_mlp_run.restype = i32
+        l.ogc_mlp_run_static.argtypes = [vp, vp, vp, vp, vp]
+        l.ogc_mlp_run_static.restype = i32
+        l.ogc_mlp_static_workspace_limit.argtypes = []
+        l.ogc_mlp_static_workspace_limit.restype = sz
         l.ogc_mlp_num_launches.argtypes = [vp, ctypes.POINTER(i32)]
         l.ogc_mlp_num_launches.restype = i32
         l.ogc_mlp_run_profiled.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
@@ -237,6 +241,14 @@ def ogc_mlp_prepack_weights(plan: int, w_ptrs, bias_ptrs, w_scale_ptrs, packed_p
 
 def ogc_mlp_run(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, workspace_ptr: int, stream: int = 0) -> None:
     _check(lib().ogc_mlp_run(plan, x_ptr, y_ptr, packed_ptr, workspace_ptr or None, stream), "ogc_mlp_run")
+
+
+def ogc_mlp_run_static(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, stream: int = 0) -> None:
+    _check(lib().ogc_mlp_run_static(plan, x_ptr, y_ptr, packed_ptr, stream), "ogc_mlp_run_static")
+
+
+def ogc_mlp_static_workspace_limit() -> int:
+    return int(lib().ogc_mlp_static_workspace_limit())
 
 
 def ogc_mlp_num_launches(plan: int) -> int:

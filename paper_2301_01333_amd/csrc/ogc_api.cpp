@@ -813,6 +813,16 @@ ogc_status ogc_mlp_run(ogc_mlp_plan_t plan, const void* x, void* y, const void* 
     return run_impl(plan, x, y, packed, workspace, stream, nullptr);
 }
 
+ogc_status ogc_mlp_run_static(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* stream) {
+    if (!plan) return OGC_ERR_INVALID_ARG;
+    if (plan->workspace_bytes > (size_t)OGC_STATIC_SCRATCH_BYTES) return OGC_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (plan->workspace_bytes > 0 && ogc_static_scratch(&ws) != 0) return OGC_ERR_DEVICE;
+    return run_impl(plan, x, y, packed, ws, stream, nullptr);
+}
+
+size_t ogc_mlp_static_workspace_limit(void) { return (size_t)OGC_STATIC_SCRATCH_BYTES; }
+
 ogc_status ogc_mlp_num_launches(ogc_mlp_plan_t plan, int32_t* n) {
     if (!plan || !n) return OGC_ERR_INVALID_ARG;
     *n = plan->mode == OGC_MODE_PER_LAYER ? (int32_t)plan->layers.size() : 1;

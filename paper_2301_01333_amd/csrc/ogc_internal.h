@@ -74,6 +74,8 @@ struct OgcChainArgs {
     OgcLayerArgs layer[OGC_MAX_LAYERS];
 };
 
+#define OGC_STATIC_SCRATCH_BYTES (8u << 20)  // the library's own workspace for ogc_mlp_run_static, per GPU
+
 #define OGC_SYNC_STRIDE 16    // 64-bit words between the counters of two row tiles: a 128-byte line each
 #define OGC_SYNC_WORDS 2048   // 64-bit words at the end of the packed blob (cooperative and cluster kernels)
 #define OGC_SYNC_ERR_WORD 2   // set to 1 by a workgroup whose barrier wait gave up; read and cleared by ogc_mlp_check
@@ -101,6 +103,7 @@ int ogc_launch_cluster(int dtype, int ksplit, const OgcChainArgs* c, int m_block
                        void* stream);
 size_t ogc_cluster_ksplit_lds_bytes(size_t lds_buf_bytes);
 int ogc_device_cu_count(void);
+int ogc_static_scratch(void** ptr);  // device address of the static workspace on the current device (asked once per device)
 const char* ogc_coop_kernel_name(int dtype);
 const char* ogc_cluster_kernel_name(int dtype, int ksplit);
 int ogc_launch_prepack_weights(const void* w, void* out, int K, int N, int KC, int NPw, int esz, void* stream);

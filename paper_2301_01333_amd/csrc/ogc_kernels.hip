@@ -1381,6 +1381,34 @@ extern "C" int ogc_launch_cluster(int dtype, int ksplit, const OgcChainArgs* c, 
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Workspace for callers that cannot allocate (ogc_mlp_run_static): a fixed array in the library's device image, one
+// copy per GPU, held until the process ends.  In host code the array's name is only a stand-in: the device address
+// comes from hipGetSymbolAddress, asked once per device with that device current, and only that address is ever
+// handed to kernels.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[OGC_STATIC_SCRATCH_BYTES];
+
+extern "C" int ogc_static_scratch(void** ptr) {
+    enum { MAX_DEVICES = 64 };
+    static std::mutex mu;
+    static void* addr[MAX_DEVICES];  // zero-initialised: not asked yet
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= MAX_DEVICES) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p || ((uintptr_t)p & 255) != 0) return (int)hipErrorInvalidSymbol;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return 0;
+}
+
 extern "C" int ogc_device_cu_count(void) {
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
