@@ -276,10 +276,9 @@ OGC_DEV void store_plain(const v4i (&chunk)[EO], const OgcLayerArgs& a, int m, i
 //   v_cvt_pk_u8_f32 rounds to nearest even and packs the byte; zp is added to four packed bytes at once
 //   (no byte can carry: each is <= 255-zp).  q_add / q_xor are precomputed on the host: zp*0x01010101 and,
 //   for the internal s8 form, 0x80808080 (both 0 when zp = 128 and the result stays internal).
-template <int OUT_PLAIN, typename YP>
-OGC_DEV void epilogue_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, const BlockParams& p, int n0, int m0, int lane,
-                                    YP yblk) {
-    const int h = lane >> 5, mm = lane & 31;
+// The arithmetic of that epilogue alone: the lane's 16 consecutive result bytes (channels n0 + 16*(lane/32) ..) of
+// row lane%32, as one 16-byte chunk.
+OGC_DEV v4i requant_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, const BlockParams& p) {
     const float inv = a.inv_cs, hi = a.q_hi;
     uint32_t dw[4];
 #pragma unroll
@@ -296,12 +295,39 @@ OGC_DEV void epilogue_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, cons
     }
     swap32(dw[0], dw[2]);
     swap32(dw[1], dw[3]);
-    const v4i ch = {(int)dw[0], (int)dw[2], (int)dw[1], (int)dw[3]};  // 16 consecutive channels from n0+16h
+    return (v4i){(int)dw[0], (int)dw[2], (int)dw[1], (int)dw[3]};  // 16 consecutive channels from n0+16h
+}
+
+template <int OUT_PLAIN, typename YP>
+OGC_DEV void epilogue_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, const BlockParams& p, int n0, int m0, int lane,
+                                    YP yblk) {
+    const int h = lane >> 5, mm = lane & 31;
+    const v4i ch = requant_block_i8_relu(acc, a, p);
     if constexpr (OUT_PLAIN) {
         const v4i arr[1] = {ch};
         store_plain<1>(arr, a, m0 + mm, n0 + 16 * h);
     } else {
         store16(yblk + ((size_t)((n0 >> 5) * 2 + h) * 32 + mm) * 16, ch);
+    }
+}
+
+// Final store of two neighbouring 32-channel blocks of the same 32 rows (u8 results, 64 consecutive bytes per row) to
+// the caller's plain y as whole 64-byte row segments: the chunks cross the wave through 2 KiB of LDS (row r keeps
+// piece c in slot (c + r/4) mod 4: conflict-free both ways), after which four neighbouring lanes hold one row's
+// segment and a store instruction writes 16 rows x 64 bytes instead of 32 rows x two separate 16-byte pieces.
+// c0 / c1: the lane's chunk of the block at channels n0 / n0 + 32.  Needs 16-byte aligned rows and N % 64 == 0.
+typedef __attribute__((address_space(3))) uint8_t ogc_lds_u8;
+OGC_DEV void store_plain_rows64(const v4i& c0, const v4i& c1, const OgcLayerArgs& a, int n0, int m0, int lane, ogc_lds_u8* scratch) {
+    typedef __attribute__((address_space(3))) v4i lds_v4i;
+    const int r = lane & 31, h = lane >> 5, rot = r >> 2;
+    *(lds_v4i*)(scratch + r * 64 + (((h + rot) & 3) << 4)) = c0;
+    *(lds_v4i*)(scratch + r * 64 + (((2 + h + rot) & 3) << 4)) = c1;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int rr = pass * 16 + (lane >> 2), c = lane & 3;
+        const v4i v = *(const lds_v4i*)(scratch + rr * 64 + (((c + (rr >> 2)) & 3) << 4));
+        const int m = m0 + rr;
+        if (m < a.M) store16_through(a.y + (long long)m * a.ldy_bytes + n0 + c * 16, v);
     }
 }
 

@@ -32,7 +32,7 @@
 // X_PLAIN reads the caller's row-major x (16-byte aligned rows, no K padding; rows past M are clamped to
 // the last row and never stored); u8 inputs are flipped to s8 after the LDS read.
 // Loads land in order: waiting until at most 6*(newer stages) remain guarantees the oldest stage is
-// complete.  After an epilogue (whose own loads and stores share that counter) the next wait is for zero.
+// complete.  An epilogue's stores share that counter and complete in issue order with the loads.
 #ifndef OGC_LAYER_STREAM_H
 #define OGC_LAYER_STREAM_H
 
@@ -52,7 +52,10 @@ template <int SHAPE> struct StreamCfg {
         TN = 2, TM = 4, WAVES_N = SHAPE ? 4 : 2, WAVES_M = 2, WAVES = WAVES_N * WAVES_M, NT = WAVES * 64,
         NST = SHAPE ? 4 : 3, BN = WAVES_N * TN * 32, BM = WAVES_M * TM * 32,
         W_OPS = BN / 16, X_OPS = BM / 16, OPS = W_OPS + X_OPS, OPW = OPS / WAVES,
-        STAGE = (BN + BM) * 64, RING = STAGE * NST, PARAMS = 2 * BN * 4, LDS = RING + 2 * PARAMS,
+        STAGE = (BN + BM) * 64, RING = STAGE * NST, PARAMS = 2 * BN * 4,
+        // the eight-wave shape (one workgroup per CU) has room for 2 KiB per wave through which the last layer's
+        // result chunks are regrouped into whole row segments
+        ROWS64 = SHAPE ? WAVES * 2048 : 0, LDS = RING + 2 * PARAMS + ROWS64,
         COMPILER_VGPRS = 80, NUM_VGPR_ATTR = COMPILER_VGPRS / 2
     };
     static_assert(OPW == (SHAPE ? 4 : 6) && OPS % WAVES == 0, "loads per wave and stage");
@@ -64,13 +67,15 @@ template <int SHAPE> struct StreamCfg {
 #define OGC_X(F, j) "v[" #F "+8+4*" #j ":" #F "+11+4*" #j "]"
 #define OGC_ACC(b) "v[128+16*" #b ":143+16*" #b "]"
 // reads the operand set F from LDS at the addresses in the registers WA / XA
-#define OGC_READ(F, WA, XA)                                         \
+#define OGC_READ_W(F, WA)                                           \
     "ds_read_b128 " OGC_W(F, 0) ", " WA "\n\t"                       \
-    "ds_read_b128 " OGC_W(F, 1) ", " WA " offset:2048\n\t"           \
+    "ds_read_b128 " OGC_W(F, 1) ", " WA " offset:2048\n\t"
+#define OGC_READ_X(F, XA)                                           \
     "ds_read_b128 " OGC_X(F, 0) ", " XA "\n\t"                       \
     "ds_read_b128 " OGC_X(F, 1) ", " XA " offset:2048\n\t"           \
     "ds_read_b128 " OGC_X(F, 2) ", " XA " offset:4096\n\t"           \
     "ds_read_b128 " OGC_X(F, 3) ", " XA " offset:6144\n\t"
+#define OGC_READ(F, WA, XA) OGC_READ_W(F, WA) OGC_READ_X(F, XA)
 // u8 -> s8 on the four registers of activation operand j of set F; %[flip] = 0x80808080
 #define OGC_FLIP4(F, j)                                          \
     "v_xor_b32 v[" #F "+8+4*" #j "], %[flip], v[" #F "+8+4*" #j "]\n\t"   \
@@ -99,11 +104,11 @@ template <int SHAPE> struct StreamCfg {
 //   loads of a wave fetch weights (ops 0,1) and activations (the rest); OFS: LDS stride between a wave's loads
 #define OGC_STEP_HEAD                                   \
     "v_add_u32 %[t0], %[soc], %[wrd]\n\t"               \
-    "v_add_u32 %[t1], %[soc], %[xrd]\n\t"               \
+    "v_add_u32 %[t1], %[sox], %[xrdh]\n\t"              \
     "v_add_u32 %[t2], %[son], %[wrd]\n\t"               \
     "v_add_u32 %[t3], %[son], %[xrd]\n\t"
 #define OGC_STEP_FIRST(OP, MZ, FL)                                                                        \
-    OGC_READ(104, "%[t0]", "%[t1]")                                                                       \
+    OGC_READ_W(104, "%[t0]") OGC_READ_X(104, "%[t1]")                                                                     \
     FL(80, 0) MZ(OP, 80, 0, 0, 0) FL(80, 1) MZ(OP, 80, 1, 0, 1) FL(80, 2) MZ(OP, 80, 2, 0, 2) FL(80, 3)   \
         MZ(OP, 80, 3, 0, 3) MZ(OP, 80, 4, 1, 0) MZ(OP, 80, 5, 1, 1) MZ(OP, 80, 6, 1, 2) MZ(OP, 80, 7, 1, 3) \
             "s_waitcnt lgkmcnt(0)\n\t" FL(104, 0) OGC_MFMA(OP, 104, 0, 0, 0) FL(104, 1) OGC_MFMA(OP, 104, 1, 0, 1)
@@ -120,16 +125,18 @@ template <int SHAPE> struct StreamCfg {
             D(3, O3, "incx") OGC_MFMA(OP, 104, 6, 1, 2) OGC_MFMA(OP, 104, 7, 1, 3) "s_waitcnt lgkmcnt(0)"
 
 // Step modes: 0 = loads of the stage NST steps ahead are issued and VM newer loads may stay in flight at the
-// barrier; 1 = the same but everything outstanding is awaited (after an epilogue, whose stores share the
-// counter); 2 = no loads left to issue, everything awaited; 3 = last step of the stream: no barrier, no reads
+// barrier (after an epilogue too: its stores were issued after the loads this wait is for, and loads and stores
+// complete in issue order, so they only make the wait longer than needed); 2 = no loads left to issue, everything
+// awaited; 3 = last step of the stream: no barrier, no reads
 template <int DT, int OPW, int VM, int MODE, bool ZERO, bool FLIP>
-OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t soc, uint32_t son, uint64_t (&g)[6], uint64_t incw, uint64_t incx,
-                    uint32_t m0b) {
+OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint32_t soc, uint32_t son, uint64_t (&g)[6], uint64_t incw,
+                    uint64_t incx, uint32_t m0b) {
+    const uint32_t sox = soc - 1024;  // the stage itself: the second half's activation chunks are addressed from x_rd_hi
     static_assert((OPW == 6 && VM == 6) || (OPW == 4 && (VM == 8 || VM == 4)), "loads allowed in flight at the barrier");
     const uint32_t flip = 0x80808080u;
     uint32_t t0, t1, t2, t3;
 #define OGC_STEP_OUT [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3)
-#define OGC_STEP_IN [wrd] "v"(w_rd), [xrd] "v"(x_rd), [soc] "s"(soc), [son] "s"(son), [flip] "s"(flip)
+#define OGC_STEP_IN [wrd] "v"(w_rd), [xrd] "v"(x_rd), [xrdh] "v"(x_rd_hi), [soc] "s"(soc), [sox] "s"(sox), [son] "s"(son), [flip] "s"(flip)
 #define OGC_STEP_G6 [g0] "+v"(g[0]), [g1] "+v"(g[1]), [g2] "+v"(g[2]), [g3] "+v"(g[3]), [g4] "+v"(g[4]), [g5] "+v"(g[5])
 #define OGC_STEP_G4 [g0] "+v"(g[0]), [g1] "+v"(g[1]), [g2] "+v"(g[2]), [g3] "+v"(g[3])
 #define OGC_STEP_DMA_IN [incw] "s"(incw), [incx] "s"(incx), [m0b] "s"(m0b)
@@ -138,20 +145,12 @@ OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t soc, uint32_t son, ui
         asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(6)                                      \
                          OGC_STEP_REST6(OP, FL, OGC_DMA, 4096, 8192, 12288, 16384, 20480)                           \
                      : OGC_STEP_OUT, OGC_STEP_G6 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
-    else if constexpr (MODE == 1 && OPW == 6)                                                                       \
-        asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(0)                                      \
-                         OGC_STEP_REST6(OP, FL, OGC_DMA, 4096, 8192, 12288, 16384, 20480)                           \
-                     : OGC_STEP_OUT, OGC_STEP_G6 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
     else if constexpr (MODE == 0 && OPW == 4 && VM == 8)                                                            \
         asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(8)                                      \
                          OGC_STEP_REST4(OP, FL, OGC_DMA, 8192, 16384, 24576)                                        \
                      : OGC_STEP_OUT, OGC_STEP_G4 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
     else if constexpr (MODE == 0 && OPW == 4 && VM == 4)                                                            \
         asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(4)                                      \
-                         OGC_STEP_REST4(OP, FL, OGC_DMA, 8192, 16384, 24576)                                        \
-                     : OGC_STEP_OUT, OGC_STEP_G4 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
-    else if constexpr (MODE == 1 && OPW == 4)                                                                       \
-        asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(0)                                      \
                          OGC_STEP_REST4(OP, FL, OGC_DMA, 8192, 16384, 24576)                                        \
                      : OGC_STEP_OUT, OGC_STEP_G4 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
     else if constexpr (MODE == 2)                                                                                   \
@@ -192,23 +191,24 @@ OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t soc, uint32_t son, ui
 // LATE waves issue their loads among the first-half MFMAs (for the stage freed by the previous step's
 // barrier), the others after the barrier: the two waves of a SIMD then never wait for the texture-address
 // unit at the same time, and only half the workgroup's loads queue up there at once.
-#define OGC_READ_HI(F, WA, XA)                                      \
+#define OGC_READ_HI(F, WA, XH)                                      \
     "ds_read_b128 " OGC_W(F, 0) ", " WA " offset:1024\n\t"           \
     "ds_read_b128 " OGC_W(F, 1) ", " WA " offset:3072\n\t"           \
-    "ds_read_b128 " OGC_X(F, 0) ", " XA " offset:1024\n\t"           \
-    "ds_read_b128 " OGC_X(F, 1) ", " XA " offset:3072\n\t"           \
-    "ds_read_b128 " OGC_X(F, 2) ", " XA " offset:5120\n\t"           \
-    "ds_read_b128 " OGC_X(F, 3) ", " XA " offset:7168\n\t"
+    "ds_read_b128 " OGC_X(F, 0) ", " XH "\n\t"                       \
+    "ds_read_b128 " OGC_X(F, 1) ", " XH " offset:2048\n\t"           \
+    "ds_read_b128 " OGC_X(F, 2) ", " XH " offset:4096\n\t"           \
+    "ds_read_b128 " OGC_X(F, 3) ", " XH " offset:6144\n\t"
 #define OGC_RUN(OP, FL, DA, DB, SLOT, VMN, O1, O2, O3, O4, O5, D45)                                             \
     ".Lks%=:\n\t"                                                                                                \
     "s_add_u32 %[son], %[sst], %[stg]\n\t"                                                                       \
     "s_cmp_lg_u32 %[son], %[ring]\n\t"                                                                           \
     "s_cselect_b32 %[son], %[son], 0\n\t"                                                                        \
-    OGC_READ_HI(104, "%[tw]", "%[tx]")                                                                           \
+    OGC_READ_HI(104, "%[tw]", "%[txh]")                                                                          \
     "s_waitcnt lgkmcnt(6)\n\t"                                                                                   \
     FL(80, 0) OGC_MFMA(OP, 80, 0, 0, 0)                                                                          \
     "v_add_u32 %[tw], %[son], %[wrd]\n\t"                                                                        \
     "v_add_u32 %[tx], %[son], %[xrd]\n\t"                                                                        \
+    "v_add_u32 %[txh], %[son], %[xrdh]\n\t"                                                                      \
     FL(80, 1) OGC_MFMA(OP, 80, 1, 0, 1)                                                                          \
     "s_add_u32 %[kph], %[kph], 1\n\t"                                                                            \
     "s_cmp_eq_u32 %[kph], %[ktt]\n\t"                                                                            \
@@ -235,7 +235,7 @@ OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t soc, uint32_t son, ui
     "s_waitcnt lgkmcnt(0)"
 
 template <int DT, int SHAPE, bool LATE, bool FLIP>
-OGC_DEV void k_steps_run(uint32_t w_rd, uint32_t x_rd, uint64_t (&g)[6], uint32_t& sst, uint32_t& sprev, uint32_t& kph, uint32_t n,
+OGC_DEV void k_steps_run(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint64_t (&g)[6], uint32_t& sst, uint32_t& sprev, uint32_t& kph, uint32_t n,
                          uint32_t kt_total, uint32_t m0w, uint64_t incwn, uint64_t incww, uint64_t incxn, uint64_t incxw) {
     typedef StreamCfg<SHAPE> C;
     static_assert(!(LATE && SHAPE == 0), "only the eight-wave shape splits its waves into two groups");
@@ -246,11 +246,11 @@ OGC_DEV void k_steps_run(uint32_t w_rd, uint32_t x_rd, uint64_t (&g)[6], uint32_
     n = __builtin_amdgcn_readfirstlane(n);
     kt_total = __builtin_amdgcn_readfirstlane(kt_total);
     m0w = __builtin_amdgcn_readfirstlane(m0w);
-    uint32_t tw = sst + w_rd, tx = sst + x_rd, son, m0b;
+    uint32_t tw = sst + w_rd, tx = sst + x_rd, txh = sst + x_rd_hi, son, m0b;
     uint64_t incw, incx;
-#define OGC_RUN_OUT [son] "=&s"(son), [m0b] "=&s"(m0b), [incw] "=&s"(incw), [incx] "=&s"(incx), [tw] "+v"(tw), [tx] "+v"(tx), \
+#define OGC_RUN_OUT [son] "=&s"(son), [m0b] "=&s"(m0b), [incw] "=&s"(incw), [incx] "=&s"(incx), [tw] "+v"(tw), [tx] "+v"(tx), [txh] "+v"(txh), \
                     [sst] "+s"(sst), [sprev] "+s"(sprev), [kph] "+s"(kph), [n] "+s"(n)
-#define OGC_RUN_IN [wrd] "v"(w_rd), [xrd] "v"(x_rd), [ktt] "s"(kt_total), [m0w] "s"(m0w), [incwn] "s"(incwn), [incww] "s"(incww), \
+#define OGC_RUN_IN [wrd] "v"(w_rd), [xrd] "v"(x_rd), [xrdh] "v"(x_rd_hi), [ktt] "s"(kt_total), [m0w] "s"(m0w), [incwn] "s"(incwn), [incww] "s"(incww), \
                    [incxn] "s"(incxn), [incxw] "s"(incxw), [flip] "s"(flip), [stg] "n"(C::STAGE), [ring] "n"(C::RING)
 #define OGC_RUN_SHAPES(OP, FL)                                                                                              \
     if constexpr (SHAPE == 0)                                                                                               \
@@ -364,9 +364,10 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             } else {
                 const int ox = o - C::W_OPS;
                 if constexpr (X_PLAIN) {
-                    int row = m_base + (ox >> 1) * 32 + (lane & 31);
+                    const int qrow = lane >> 2;  // 16 rows per load, four lanes per row
+                    int row = m_base + ox * 16 + qrow;
                     row = row < a.M ? row : a.M - 1;
-                    src = a.x + (long long)row * a.ldx_bytes + ((ox & 1) * 2 + (lane >> 5)) * 16;
+                    src = a.x + (long long)row * a.ldx_bytes + ((((lane & 3) + (qrow >> 2)) & 3) << 4);
                 } else {
                     src = a.x + ((size_t)((m_base >> 5) + (ox >> 1)) * a.KC + (ox & 1) * 2) * 512 + lane * 16;
                 }
@@ -398,7 +399,22 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     const uint32_t lds0 = lds_addr_of(smem);
     const uint32_t m0_wave = lds0 + wave * 1024;  // + stage*STAGE + i*WAVES*1024: where this wave's load i lands
     const uint32_t w_rd = lds0 + (wn * TN) * 2048 + lane * 16;
-    const uint32_t x_rd = lds0 + C::BN * 64 + (wm * TM) * 2048 + lane * 16;
+    // Activation chunks of a stage.  From a blocked tensor: [32-row block][4 chunks of a k-step][32 rows][16 bytes], the
+    // operand order, the second half of a k-step 1 KiB after the first.  From the caller's plain rows (X_PLAIN): a load
+    // instruction fetches the 64 bytes of a k-step for 16 rows, four lanes per row, so that each group of four lanes
+    // reads one contiguous segment (32 rows x 32 bytes per instruction, as the operand order would need, costs the
+    // texture-address unit four cache lines per lane group and made the first layer that much slower).  They land
+    // [32-row block][32 rows][4 slots of 16 bytes]; row r keeps chunk c in slot (c - r/4) mod 4, which makes the 128-bit
+    // reads of 16 consecutive rows conflict-free; the second half of a k-step is the slot two further, i.e. address ^ 32.
+    uint32_t x_rd, x_rd_hi;
+    if constexpr (X_PLAIN) {
+        const int r = lane & 31;
+        x_rd = lds0 + C::BN * 64 + (wm * TM) * 2048 + r * 64 + ((((lane >> 5) - (r >> 2)) & 3) << 4);
+        x_rd_hi = x_rd ^ 32;
+    } else {
+        x_rd = lds0 + C::BN * 64 + (wm * TM) * 2048 + lane * 16;
+        x_rd_hi = x_rd + 1024;
+    }
 
     // Schedule (the ring slot of step q is q % NST):
     //   prologue: loads of the first steps in flight; wait for step 0; barrier; read F0(step 0)
@@ -414,12 +430,18 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     // selects this kernel only for int8 layers whose input zero point is 128: no compensation term.)
     typedef __attribute__((address_space(3))) uint8_t lds_u8;
     lds_u8* const params_lds = (lds_u8*)smem + C::RING;
+    // The parameters go from global memory straight into LDS as well (one dword per lane and load): no staging
+    // register, hence no compiler-inserted wait for everything outstanding in the middle of the stream.  They are
+    // issued ahead of a tile's epilogue stores and are older than every load that a later step waits for, so the
+    // ordinary in-order waits of the steps cover them.
     auto stage_params = [&](int n_tile, int buf) {
-        if (EPI != 2 && tid < C::BN) {
+        if (EPI != 2 && wave < C::BN / 64) {
             const int n = n_tile * C::BN + tid;
-            lds_u8* pb = params_lds + buf * C::PARAMS;
-            ((__attribute__((address_space(3))) float*)pb)[tid] = (DT == OGC_I8) ? a.scale[n] : 0.0f;
-            ((__attribute__((address_space(3))) float*)pb)[C::BN + tid] = a.has_bias ? a.bias[n] : 0.0f;
+            const uint64_t sp = (uint64_t)(uintptr_t)(a.scale + n), bp = (uint64_t)(uintptr_t)(a.bias + n);
+            const uint32_t m0s = __builtin_amdgcn_readfirstlane(lds0 + C::RING + buf * C::PARAMS + wave * 256);
+            asm volatile("s_mov_b32 m0, %[ms]\n\ts_nop 0\n\tglobal_load_lds_dword %[sp], off\n\t"
+                         "s_add_u32 m0, %[ms], %[bo]\n\ts_nop 0\n\tglobal_load_lds_dword %[bp], off\n\ts_nop 0"
+                         :: [sp] "v"(sp), [bp] "v"(bp), [ms] "s"(m0s), [bo] "n"(C::BN * 4) : "memory", "scc");
         }
     };
     const bool late = SHAPE == 1 && wave >= 4;
@@ -456,17 +478,16 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     asm volatile(OGC_READ(80, "%[wa]", "%[xa]") "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
     uint32_t sst = 0, sprev = (NST - 1) * C::STAGE;  // ring offsets of the current and the previous step's stage
     int kt = 0, q = 0;
-    bool drained = false;  // an epilogue ran since the last wait: its loads and stores are pending too
     while (q < total_steps) {
         const bool can_fetch = fetched < total_steps;
-        if (kt > 0 && !drained && can_fetch) {
+        if (kt > 0 && can_fetch) {
             // a run of ordinary steps: up to the end of this tile, of the cursor's tile, or of the stream
             int n = KT - kt;
             n = n < KT - pf_kt ? n : KT - pf_kt;
             n = n < total_steps - fetched ? n : total_steps - fetched;
             uint32_t kph = (uint32_t)pf_kphys;
-            if (late) k_steps_run<DT, SHAPE, SHAPE == 1, FLIP>(w_rd, x_rd, g, sst, sprev, kph, n, KT, m0_wave, 2048, incw_wrap, (uint64_t)x_step, incx_wrap);
-            else k_steps_run<DT, SHAPE, false, FLIP>(w_rd, x_rd, g, sst, sprev, kph, n, KT, m0_wave, 2048, incw_wrap, (uint64_t)x_step, incx_wrap);
+            if (late) k_steps_run<DT, SHAPE, SHAPE == 1, FLIP>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, 2048, incw_wrap, (uint64_t)x_step, incx_wrap);
+            else k_steps_run<DT, SHAPE, false, FLIP>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, 2048, incw_wrap, (uint64_t)x_step, incx_wrap);
             pf_kphys = (int)kph;
             kt += n;
             q += n;
@@ -480,28 +501,24 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                 set_increments();
                 const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + (late ? sprev : sst));
                 // a late wave has one stage fewer in flight at this point (its loads follow the barrier here)
-                if (drained) {
-                    if (zero) k_step<DT, OPW, VM, 1, true, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
-                    else k_step<DT, OPW, VM, 1, false, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
-                } else if (late) {
-                    if (zero) k_step<DT, OPW, SHAPE == 1 ? 4 : VM, 0, true, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
-                    else k_step<DT, OPW, SHAPE == 1 ? 4 : VM, 0, false, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
+                if (late) {
+                    if (zero) k_step<DT, OPW, SHAPE == 1 ? 4 : VM, 0, true, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
+                    else k_step<DT, OPW, SHAPE == 1 ? 4 : VM, 0, false, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
                 } else {
-                    if (zero) k_step<DT, OPW, VM, 0, true, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
-                    else k_step<DT, OPW, VM, 0, false, FLIP>(w_rd, x_rd, soc, son, g, incw, incx, m0b);
+                    if (zero) k_step<DT, OPW, VM, 0, true, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
+                    else k_step<DT, OPW, VM, 0, false, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
                 }
                 ++fetched;
                 cursor_advanced(1);
             } else if (q + 1 < total_steps) {
-                if (zero) k_step<DT, OPW, VM, 2, true, FLIP>(w_rd, x_rd, soc, son, g, 0, 0, 0);
-                else k_step<DT, OPW, VM, 2, false, FLIP>(w_rd, x_rd, soc, son, g, 0, 0, 0);
+                if (zero) k_step<DT, OPW, VM, 2, true, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
+                else k_step<DT, OPW, VM, 2, false, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
             } else {
-                if (zero) k_step<DT, OPW, VM, 3, true, FLIP>(w_rd, x_rd, soc, son, g, 0, 0, 0);
-                else k_step<DT, OPW, VM, 3, false, FLIP>(w_rd, x_rd, soc, son, g, 0, 0, 0);
+                if (zero) k_step<DT, OPW, VM, 3, true, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
+                else k_step<DT, OPW, VM, 3, false, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
             }
             sprev = sst;
             sst = snext;
-            drained = false;
             ++kt;
             ++q;
         }
@@ -543,26 +560,58 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                                                      GlobalY{a.y + (size_t)(m0 >> 5) * a.KC_out * 512});
                 }
             };
-            if constexpr (EPI != 2) read_params(0);
-            block(std::integral_constant<int, 0>());
-            block(std::integral_constant<int, 1>());
-            block(std::integral_constant<int, 2>());
-            block(std::integral_constant<int, 3>());
-            if constexpr (EPI != 2) read_params(1);
-            block(std::integral_constant<int, 4>());
-            block(std::integral_constant<int, 5>());
-            block(std::integral_constant<int, 6>());
-            block(std::integral_constant<int, 7>());
-            // the next tile's parameters go to the other buffer (waves still in this epilogue keep reading this
-            // one); the barrier of the next tile's first step orders the writes before its epilogue's reads, and
-            // a one-step tile has no such barrier, hence the explicit one
-            next_tile(cur_n, cur_m);
-            if (--tiles_left > 0) {
+            // The next tile's parameters go to the other buffer (waves still in this epilogue keep reading this one),
+            // ahead of this epilogue's stores: loads and stores complete in the order they were issued, so every wait
+            // of the next tile's steps that covers a later ring load covers them, and the steps' barriers order them
+            // before the next epilogue's reads.  The waits of those steps count ring loads only: the stores issued
+            // here in between make them wait for more than they need, never for less.
+            int next_n = cur_n, next_m = cur_m;
+            next_tile(next_n, next_m);
+            if (tiles_left > 1 && KT >= 4) stage_params(next_n >> LS, pbuf ^ 1);
+            bool done = false;
+            if constexpr (EPI == 1 && OUT_PLAIN && C::ROWS64 > 0) {
+                if (a.y_vec_ok && (a.N & 63) == 0) {
+                    // whole 64-byte row segments: the two channel blocks of the same rows one after the other
+                    lds_u8* const scratch = (lds_u8*)smem + C::RING + 2 * C::PARAMS + wave * 2048;
+                    auto pair = [&](auto tag) {
+                        constexpr int J = decltype(tag)::value;
+                        const int m0 = m_base + J * 32;
+                        if (m0 < a.M) {  // (n_base < N: N is a multiple of 64 and the tile starts inside it, or the wave has no work)
+                            read_params(0);
+                            const v4i c0 = requant_block_i8_relu(take_acc_block<DT, J>(), a, prm);
+                            read_params(1);
+                            const v4i c1 = requant_block_i8_relu(take_acc_block<DT, 4 + J>(), a, prm);
+                            store_plain_rows64(c0, c1, a, n_base, m0, lane, scratch);
+                        }
+                    };
+                    if (n_base < a.N) {
+                        pair(std::integral_constant<int, 0>());
+                        pair(std::integral_constant<int, 1>());
+                        pair(std::integral_constant<int, 2>());
+                        pair(std::integral_constant<int, 3>());
+                    }
+                    done = true;
+                }
+            }
+            if (!done) {
+                if constexpr (EPI != 2) read_params(0);
+                block(std::integral_constant<int, 0>());
+                block(std::integral_constant<int, 1>());
+                block(std::integral_constant<int, 2>());
+                block(std::integral_constant<int, 3>());
+                if constexpr (EPI != 2) read_params(1);
+                block(std::integral_constant<int, 4>());
+                block(std::integral_constant<int, 5>());
+                block(std::integral_constant<int, 6>());
+                block(std::integral_constant<int, 7>());
+            }
+            cur_n = next_n, cur_m = next_m;
+            if (--tiles_left > 0 && KT < 4) {
+                // too few steps for the steps' own waits to cover the parameter loads before the next epilogue
                 stage_params(cur_n >> LS, pbuf ^ 1);
-                if (KT == 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
             }
             pbuf ^= 1;
-            drained = true;
         }
     }
 }
