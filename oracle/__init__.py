@@ -16,4 +16,4 @@ from .oracle import (  # noqa: F401
     mlp,
     num_threads,
 )
-from .mha import SOFTMAX_FAST, SOFTMAX_STABLE, attention  # noqa: F401,E402
+from .mha import SOFTMAX_FAST, SOFTMAX_STABLE, attention, attention_i8  # noqa: F401,E402
