@@ -254,22 +254,29 @@ def mha_report(steps, warmup, with_cpu=True, only=None):
         if only and only[0] != row:
             continue
         big = synth.make_mha_table1(row, "f32", 128)
-        for dtype in ("f32", "bf16"):
+        big8 = synth.make_mha_table1(row, "i8", 128)   # the Int8 rows of Table I: int8 q, k, v and output
+        for dtype in ("f32", "bf16", "i8"):
             conv = (lambda t: t) if dtype == "f32" else synth.f32_to_bf16_bits
             for batch in (32, 128):
                 if only and (only[1] != dtype or int(only[2]) != batch):
                     continue
-                wl = dataclasses.replace(big, dtype=dtype, batch=batch, q=conv(big.q[:batch]), k=conv(big.k[:batch]),
-                                         v=conv(big.v[:batch]), mask=big.mask[:batch], name="%s %s batch %d" % (row, dtype, batch))
+                if dtype == "i8":
+                    wl = dataclasses.replace(big8, batch=batch, q=big8.q[:batch], k=big8.k[:batch], v=big8.v[:batch],
+                                             mask=big8.mask[:batch], name="%s %s batch %d" % (row, dtype, batch))
+                else:
+                    wl = dataclasses.replace(big, dtype=dtype, batch=batch, q=conv(big.q[:batch]), k=conv(big.k[:batch]),
+                                             v=conv(big.v[:batch]), mask=big.mask[:batch], name="%s %s batch %d" % (row, dtype, batch))
                 dev = DeviceMHA(wl)
                 sec, ev = time_steps(dev, max(steps // 3, 10), max(warmup // 3, 3))
-                fast_dev = DeviceMHA(wl, binding.OGC_SOFTMAX_FAST)   # the softmax without the max reduction (Section VII)
-                fast_sec, _ = time_steps(fast_dev, max(steps // 6, 10), 3)
-                del fast_dev
+                fast_sec = None
+                if dtype != "i8":   # the softmax without the max reduction (Section VII); the Int8 form needs the maximum
+                    fast_dev = DeviceMHA(wl, binding.OGC_SOFTMAX_FAST)
+                    fast_sec, _ = time_steps(fast_dev, max(steps // 6, 10), 3)
+                    del fast_dev
                 peak = PEAK[dtype][0]
                 r = {"workload": wl.name, "seq": wl.seq, "heads": wl.heads, "head_dim": wl.head_dim,
-                     "kernel": binding.ogc_mha_kernel_name(dev.desc, True), "us_per_run": sec * 1e6,
-                     "us_per_run_fast_softmax": fast_sec * 1e6,
+                     "kernel": binding.ogc_mha_i8_kernel_name(dev.desc) if dtype == "i8" else binding.ogc_mha_kernel_name(dev.desc, True),
+                     "us_per_run": sec * 1e6, "us_per_run_fast_softmax": None if fast_sec is None else fast_sec * 1e6,
                      "tflops": wl.ops / sec / 1e12, "frac_of_mfma_peak": wl.ops / sec / peak,
                      "gb_per_s_algorithmic": wl.algorithmic_bytes / sec / 1e9}
                 rows.append(r)
@@ -292,7 +299,7 @@ def mha_report(steps, warmup, with_cpu=True, only=None):
                                "kind": "oracle", "sample": "%d of %d batch entries of %s, float64 numpy, %d passes" % (
                                    nb, wl.batch, wl.name, reps)}
                 del dev
-        del big
+        del big, big8
     torch.cuda.synchronize()
     return {"rows": rows, "roofline": roof, "cpu_baseline": cpu}
 

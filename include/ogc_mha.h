@@ -26,7 +26,8 @@
  *
  * Arithmetic: OGC_F32 multiplies fp32 operands with fp32 accumulation throughout.  OGC_BF16 multiplies bf16
  * operands with fp32 accumulation; scores, exponentials and row sums are fp32; the softmax weights are rounded
- * to bf16 (nearest even) for the second matmul and o is rounded to bf16 once at the end.  OGC_I8 is not covered.
+ * to bf16 (nearest even) for the second matmul and o is rounded to bf16 once at the end.  OGC_I8 (Table I lists the
+ * MHA rows as Int8 too) has an entry point of its own, ogc_mha_run_i8, because it needs quantization scales.
  *
  * Errors are return codes (ogc_status of ogc_mlp.h); every check happens before the launch.
  */
@@ -53,11 +54,13 @@ typedef struct ogc_mha_desc {
     int64_t k_stride[3];
     int64_t v_stride[3];
     int64_t o_stride[3];
+    int32_t query_groups; /* 0: the library's choice; 1 or 2: 32-query groups per wavefront, forced (tests, sweeps; 2 needs
+                             OGC_BF16 and head_dim <= 64, otherwise 1 is taken) */
 } ogc_mha_desc;
 
 /* Checks a description without touching the device.
  * OGC_ERR_INVALID_ARG: NULL, bad enum, non-finite scale.  OGC_ERR_SHAPE: non-positive sizes, limits above.
- * OGC_ERR_UNSUPPORTED: OGC_I8, head_dim outside {32,64,96,128}.  OGC_ERR_ALIGNMENT: a stride that is not a
+ * OGC_ERR_UNSUPPORTED: OGC_I8 (see ogc_mha_run_i8), head_dim outside {32,64,96,128}.  OGC_ERR_ALIGNMENT: a stride that is not a
  * multiple of 16 bytes or is negative. */
 ogc_status ogc_mha_validate(const ogc_mha_desc* desc);
 
@@ -73,9 +76,33 @@ ogc_status ogc_mha_run(const ogc_mha_desc* desc, const void* q, const void* k, c
  * mask), as a profiler's kernel trace prints it (static storage), or NULL for an invalid description.  A run
  * without a mask whose sequence is a whole number of key blocks (bf16: 64, fp32: 32) and whose scale is
  * positive takes a variant that spends no per-key addend; bf16 with head_dim <= 64 and seq >= 256 takes one in
- * which a wavefront owns 64 queries instead of 32 (the last template argument; the environment variable
- * OGC_MHA_QS = 1 or 2, read by ogc_mha_run and by this function, overrides that choice for tests and sweeps). */
+ * which a wavefront owns 64 queries instead of 32 (the last template argument; desc->query_groups forces either). */
 const char* ogc_mha_kernel_name(const ogc_mha_desc* desc, int32_t has_mask);
+
+/* Quantization scales of the Int8 attention: real value = scale * integer, zero point 0 for all four tensors
+ * (a batch matmul has no constant operand into which a zero point could be folded, Section V). */
+typedef struct ogc_mha_quant {
+    float q_scale, k_scale, v_scale, o_scale; /* > 0, finite */
+} ogc_mha_quant;
+
+/* Int8 rows of Table I (Section VII; low-precision conversion of Section V).  q, k, v, o: int8, same strides and
+ * alignment rules as above (strides in elements = bytes).  Per batch entry, head and query i:
+ *     S[j] = sum_c q[i][c] k[j][c]                          int32, exact
+ *     s[j] = S[j] * (q_scale*k_scale*scale) + mask[j]       fp32
+ *     P[j] = rne(127 * exp(s[j] - max_j s[j]))              softmax numerators quantized to 7 bits unsigned
+ *     A[c] = sum_j P[j] v[j][c],  L = sum_j P[j]            int32, exact
+ *     o[c] = clamp(rne((float(A[c]) / float(L)) * (v_scale / o_scale)), -128, 127)
+ *            (int -> float, IEEE divide, multiply by the fp32 quotient v_scale / o_scale, each rounded to nearest even)
+ * Everything after P is exact integer arithmetic and three fp32 operations, reproducible bit for bit; P itself can
+ * differ by one step from another implementation's where 127 * exp(..) lies within rounding error of a tie.
+ * desc->dtype must be OGC_I8 and desc->softmax OGC_SOFTMAX_STABLE (the numerators are quantized against the row
+ * maximum; OGC_SOFTMAX_FAST returns OGC_ERR_UNSUPPORTED).  Other codes as ogc_mha_validate / ogc_mha_run, plus
+ * OGC_ERR_INVALID_ARG for a NULL quant or a scale that is not positive and finite.  One asynchronous launch. */
+ogc_status ogc_mha_i8_validate(const ogc_mha_desc* desc, const ogc_mha_quant* quant);
+ogc_status ogc_mha_run_i8(const ogc_mha_desc* desc, const ogc_mha_quant* quant, const void* q, const void* k, const void* v,
+                          const float* mask, void* o, void* stream);
+/* Kernel instantiation ogc_mha_run_i8 launches for this description, as a kernel trace prints it, or NULL. */
+const char* ogc_mha_i8_kernel_name(const ogc_mha_desc* desc);
 
 #ifdef __cplusplus
 }

@@ -27,7 +27,7 @@ EXPORTS = [
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
     "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes", "ogc_mlp_estimated_us", "ogc_mlp_mode_estimates",
     "ogc_mlp_run_static", "ogc_mlp_static_workspace_limit", "ogc_mlp_plan_with_overrides", "ogc_mlp_check", "ogc_mlp_test_barrier", "ogc_mlp_cluster_layout",
-    "ogc_mha_validate", "ogc_mha_run", "ogc_mha_kernel_name",
+    "ogc_mha_validate", "ogc_mha_run", "ogc_mha_kernel_name", "ogc_mha_i8_validate", "ogc_mha_run_i8", "ogc_mha_i8_kernel_name",
 ]
 OGC_ERR_TIMEOUT = -8
 
@@ -54,7 +54,11 @@ class ogc_mha_desc(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("seq", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("softmax", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
-                ("o_stride", ctypes.c_int64 * 3)]
+                ("o_stride", ctypes.c_int64 * 3), ("query_groups", ctypes.c_int32)]
+
+
+class ogc_mha_quant(ctypes.Structure):
+    _fields_ = [("q_scale", ctypes.c_float), ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float), ("o_scale", ctypes.c_float)]
 
 
 class OgcError(RuntimeError):
@@ -123,6 +127,12 @@ def lib():
         l.ogc_mha_run.restype = i32
         l.ogc_mha_kernel_name.argtypes = [ctypes.POINTER(ogc_mha_desc), i32]
         l.ogc_mha_kernel_name.restype = ctypes.c_char_p
+        l.ogc_mha_i8_validate.argtypes = [ctypes.POINTER(ogc_mha_desc), ctypes.POINTER(ogc_mha_quant)]
+        l.ogc_mha_i8_validate.restype = i32
+        l.ogc_mha_run_i8.argtypes = [ctypes.POINTER(ogc_mha_desc), ctypes.POINTER(ogc_mha_quant), vp, vp, vp, vp, vp, vp]
+        l.ogc_mha_run_i8.restype = i32
+        l.ogc_mha_i8_kernel_name.argtypes = [ctypes.POINTER(ogc_mha_desc)]
+        l.ogc_mha_i8_kernel_name.restype = ctypes.c_char_p
         _lib = l
     return _lib
 
@@ -288,12 +298,13 @@ def ogc_mlp_kernel_name(plan: int, layer: int) -> str:
 
 
 def mha_desc(dtype: int, batch: int, heads: int, seq: int, head_dim: int, scale: float, softmax: int = OGC_SOFTMAX_STABLE,
-             q_stride=None, k_stride=None, v_stride=None, o_stride=None) -> ogc_mha_desc:
+             q_stride=None, k_stride=None, v_stride=None, o_stride=None, query_groups: int = 0) -> ogc_mha_desc:
     """Strides default to the [batch, seq, heads*head_dim] layout."""
     plain = (seq * heads * head_dim, head_dim, heads * head_dim)
     arrs = [(ctypes.c_int64 * 3)(*[int(v) for v in (st if st is not None else plain)])
             for st in (q_stride, k_stride, v_stride, o_stride)]
-    return ogc_mha_desc(int(dtype), int(batch), int(heads), int(seq), int(head_dim), int(softmax), float(scale), *arrs)
+    return ogc_mha_desc(int(dtype), int(batch), int(heads), int(seq), int(head_dim), int(softmax), float(scale), *arrs,
+                        int(query_groups))
 
 
 def ogc_mha_validate(desc: ogc_mha_desc) -> int:
@@ -303,6 +314,21 @@ def ogc_mha_validate(desc: ogc_mha_desc) -> int:
 def ogc_mha_run(desc: ogc_mha_desc, q_ptr: int, k_ptr: int, v_ptr: int, mask_ptr: int, o_ptr: int, stream: int = 0) -> None:
     _check(lib().ogc_mha_run(ctypes.byref(desc), q_ptr or None, k_ptr or None, v_ptr or None, mask_ptr or None, o_ptr or None,
                              stream), "ogc_mha_run")
+
+
+def ogc_mha_i8_validate(desc: ogc_mha_desc, quant: ogc_mha_quant) -> int:
+    return int(lib().ogc_mha_i8_validate(ctypes.byref(desc), ctypes.byref(quant)))
+
+
+def ogc_mha_run_i8(desc: ogc_mha_desc, quant: ogc_mha_quant, q_ptr: int, k_ptr: int, v_ptr: int, mask_ptr: int, o_ptr: int,
+                   stream: int = 0) -> None:
+    _check(lib().ogc_mha_run_i8(ctypes.byref(desc), ctypes.byref(quant), q_ptr or None, k_ptr or None, v_ptr or None,
+                                mask_ptr or None, o_ptr or None, stream), "ogc_mha_run_i8")
+
+
+def ogc_mha_i8_kernel_name(desc: ogc_mha_desc) -> str:
+    r = lib().ogc_mha_i8_kernel_name(ctypes.byref(desc))
+    return r.decode() if r else ""
 
 
 def ogc_mha_kernel_name(desc: ogc_mha_desc, has_mask: bool = True) -> str:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libogc_mlp.so")
-SOURCES = ["ogc_kernels.hip", "ogc_mha.hip", "ogc_api.cpp"]
+SOURCES = ["ogc_kernels.hip", "ogc_mha.hip", "ogc_mha_i8.hip", "ogc_api.cpp"]
 
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -409,9 +409,8 @@ template <int DT> hipError_t launch_dim(int d32, int qs, int fast, int plain, co
 // 32-query groups per wavefront.  Two where the registers allow it (bf16, head_dim <= 64) and the sequence is long
 // enough to keep the four wavefronts of a workgroup busy: the bf16 kernel is then no longer bound by LDS reads.
 int query_groups(const ogc_mha_desc* d) {
-    const char* e = getenv("OGC_MHA_QS");
     const bool can = d->dtype == OGC_BF16 && d->head_dim <= 64;
-    if (e && *e) return (atoi(e) == 2 && can) ? 2 : 1;
+    if (d->query_groups != 0) return (d->query_groups == 2 && can) ? 2 : 1;
     return (can && d->seq >= 256) ? 2 : 1;
 }
 
@@ -435,6 +434,7 @@ ogc_status ogc_mha_validate(const ogc_mha_desc* d) {
     if (!d) return OGC_ERR_INVALID_ARG;
     if (d->dtype != OGC_F32 && d->dtype != OGC_BF16 && d->dtype != OGC_I8) return OGC_ERR_INVALID_ARG;
     if (d->softmax != OGC_SOFTMAX_STABLE && d->softmax != OGC_SOFTMAX_FAST) return OGC_ERR_INVALID_ARG;
+    if (d->query_groups < 0 || d->query_groups > 2) return OGC_ERR_INVALID_ARG;
     if (!isfinite(d->scale)) return OGC_ERR_INVALID_ARG;
     if (d->batch <= 0 || d->heads <= 0 || d->seq <= 0 || d->head_dim <= 0) return OGC_ERR_SHAPE;
     if (d->seq > 65536 || (int64_t)d->batch * d->heads > 65535) return OGC_ERR_SHAPE;

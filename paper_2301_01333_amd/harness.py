@@ -61,18 +61,25 @@ class DeviceMLP:
 class DeviceMHA:
     """An attention workload resident on the GPU (q, k, v, mask uploaded; o allocated and poisoned)."""
 
-    def __init__(self, wl, softmax: int = binding.OGC_SOFTMAX_STABLE, use_mask: bool = True):
+    def __init__(self, wl, softmax: int = binding.OGC_SOFTMAX_STABLE, use_mask: bool = True, query_groups: int = 0):
         import torch
 
         self.torch = torch
         self.wl = wl
-        self.np_dtype = np.float32 if wl.dtype == "f32" else np.uint16
+        self.np_dtype = {"f32": np.float32, "bf16": np.uint16, "i8": np.int8}[wl.dtype]
         self.q, self.k, self.v = (_to_device(torch, t) for t in (wl.q, wl.k, wl.v))
         self.mask = _to_device(torch, wl.mask) if (use_mask and wl.mask is not None) else None
         self.o = torch.full((wl.q.nbytes,), 0xCD, dtype=torch.uint8, device="cuda")
-        self.desc = binding.mha_desc(binding.DTYPES[wl.dtype], wl.batch, wl.heads, wl.seq, wl.head_dim, wl.scale, softmax)
+        self.desc = binding.mha_desc(binding.DTYPES[wl.dtype], wl.batch, wl.heads, wl.seq, wl.head_dim, wl.scale, softmax,
+                                     query_groups=query_groups)
+        self.quant = binding.ogc_mha_quant(*[float(x) for x in wl.quant]) if wl.dtype == "i8" else None
 
     def run(self) -> None:
+        stream = int(self.torch.cuda.current_stream().cuda_stream)
+        if self.quant is not None:
+            binding.ogc_mha_run_i8(self.desc, self.quant, self.q.data_ptr(), self.k.data_ptr(), self.v.data_ptr(),
+                                   self.mask.data_ptr() if self.mask is not None else 0, self.o.data_ptr(), stream)
+            return
         binding.ogc_mha_run(self.desc, self.q.data_ptr(), self.k.data_ptr(), self.v.data_ptr(),
                             self.mask.data_ptr() if self.mask is not None else 0, self.o.data_ptr(),
                             int(self.torch.cuda.current_stream().cuda_stream))

@@ -197,17 +197,18 @@ MHA_TABLE1 = {  # name: (seq, hidden, heads)
 @dataclass
 class MhaWorkload:
     name: str
-    dtype: str           # "f32" | "bf16"
+    dtype: str           # "f32" | "bf16" | "i8"
     batch: int
     seq: int
     heads: int
     head_dim: int
-    q: np.ndarray        # [batch, seq, heads*head_dim]; fp32, or bf16 bit patterns as uint16
+    q: np.ndarray        # [batch, seq, heads*head_dim]; fp32, bf16 bit patterns as uint16, or int8
     k: np.ndarray
     v: np.ndarray
     mask: Optional[np.ndarray]  # [batch, seq] fp32 additive, or None
     scale: float         # fp32 value of 1/sqrt(head_dim)
     seed: int = 0
+    quant: Optional[tuple] = None   # "i8": (q_scale, k_scale, v_scale, o_scale), real value = scale * integer
 
     @property
     def hidden(self) -> int:
@@ -221,25 +222,36 @@ class MhaWorkload:
     @property
     def algorithmic_bytes(self) -> int:
         """q, k, v read once, o written once, the mask once; the S x S scores count zero."""
-        e = 4 if self.dtype == "f32" else 2
+        e = {"f32": 4, "bf16": 2, "i8": 1}[self.dtype]
         return 4 * self.batch * self.seq * self.hidden * e + (self.batch * self.seq * 4 if self.mask is not None else 0)
 
 
 def make_mha(dtype: str, batch: int, seq: int, hidden: int, heads: int, seed: int, *, has_mask: bool = True,
              name: str = "custom", amplitude: float = 1.0) -> MhaWorkload:
     """Draw order: q, k, v, then the valid lengths, from one default_rng(seed) stream."""
-    assert dtype in ("f32", "bf16") and hidden % heads == 0
+    assert dtype in ("f32", "bf16", "i8") and hidden % heads == 0
     rng = np.random.default_rng(seed)
     d = hidden // heads
     ts = []
+    quant = None
+    if dtype == "i8":
+        # static symmetric scales mapping 4 standard deviations of the N(0, amplitude^2) tensors onto 127; the
+        # integers are drawn directly (round of a scaled normal, clipped)
+        # (averages over the keys are much smaller than the values: the output step is a quarter of the input step,
+        # which saturates the few outputs of very short sequences and exercises the clamp)
+        step = float(np.float32(4.0 * amplitude / 127.0))
+        quant = (step, step, step, float(np.float32(amplitude / 127.0)))
     for _ in range(3):
         t = (rng.standard_normal((batch, seq, hidden)) * amplitude).astype(np.float32)
-        ts.append(t if dtype == "f32" else f32_to_bf16_bits(t))
+        if dtype == "i8":
+            ts.append(np.clip(np.rint(t / np.float32(quant[0])), -127, 127).astype(np.int8))
+        else:
+            ts.append(t if dtype == "f32" else f32_to_bf16_bits(t))
     mask = None
     if has_mask:
         lens = rng.integers(max(seq // 2, 1), seq + 1, size=(batch,))
         mask = np.where(np.arange(seq)[None, :] < lens[:, None], np.float32(0.0), np.float32(-10000.0)).astype(np.float32)
-    return MhaWorkload(name, dtype, batch, seq, heads, d, ts[0], ts[1], ts[2], mask, float(np.float32(1.0 / math.sqrt(d))), seed)
+    return MhaWorkload(name, dtype, batch, seq, heads, d, ts[0], ts[1], ts[2], mask, float(np.float32(1.0 / math.sqrt(d))), seed, quant)
 
 
 def make_mha_table1(row: str, dtype: str, batch: int) -> MhaWorkload:

@@ -142,3 +142,89 @@ def test_run_rejects_bad_pointers():
     with pytest.raises(binding.OgcError) as e:
         binding.ogc_mha_run(desc, t.data_ptr() + 4, t.data_ptr(), t.data_ptr(), 0, t.data_ptr())
     assert e.value.status == -4
+
+
+# ---------------------------------------------------------------- Int8 rows of Table I
+def check_i8(oracle_mod, wl, use_mask=True, batches=None, exact=False):
+    """The Int8 attention against its oracle.  Everything after the quantized softmax numerators P is integer
+    arithmetic and three fp32 operations that both sides do identically, so outputs can differ only where a P differs:
+    the kernel evaluates 127 * exp(..) in fp32 with the hardware's exp2, the oracle in float64, and within about 1e-4 of
+    a tie the two round apart by one step (a few in ten thousand numerators).  The gate: no output differs by more
+    than one step, fewer than 1 % differ at all, and the dequantized output is within the bf16 tolerance of the oracle's.
+    exact: a case built so that no numerator is near a tie, where every byte must agree."""
+    from paper_2301_01333_amd.harness import DeviceMHA
+
+    print("case:", wl.name, "i8 B=%d S=%d H=%d d=%d mask=%s" % (wl.batch, wl.seq, wl.heads, wl.head_dim, use_mask and wl.mask is not None),
+          flush=True)
+    dev = DeviceMHA(wl, STABLE, use_mask)
+    dev.run()
+    got = dev.result()
+    sel = slice(None) if batches is None else batches
+    q, k, v = (heads_view(t, wl)[sel] for t in (wl.q, wl.k, wl.v))
+    mask = wl.mask[sel] if (use_mask and wl.mask is not None) else None
+    ref = oracle_mod.attention_i8(q, k, v, mask, wl.scale, *wl.quant).transpose(0, 2, 1, 3).reshape(-1, wl.seq, wl.hidden)
+    got = got[sel].astype(np.int32)
+    diff = np.abs(got - ref.astype(np.int32))
+    if exact:
+        assert diff.max() == 0, "%s: %d bytes differ" % (wl.name, int((diff > 0).sum()))
+        return
+    assert diff.max() <= 1, "%s: an output differs by %d steps" % (wl.name, int(diff.max()))
+    assert (diff > 0).mean() < 0.01, "%s: %.3f %% of the outputs differ" % (wl.name, 100.0 * (diff > 0).mean())
+    o_scale = float(np.float32(wl.quant[3]))
+    assert_close(got * o_scale, ref.astype(np.float64) * o_scale, TOL["bf16"], wl.name)
+
+
+@pytest.mark.parametrize("head_dim", [32, 64, 96, 128])
+def test_i8_head_dims_ragged_sequence(oracle_mod, head_dim):
+    check_i8(oracle_mod, synth.make_mha("i8", 2, 200, 3 * head_dim, 3, 5100 + head_dim, name="i8 ragged d%d" % head_dim))
+
+
+@pytest.mark.parametrize("seq", [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 257])
+def test_i8_sequence_lengths(oracle_mod, seq):
+    wl = synth.make_mha("i8", 3, seq, 128, 2, 5300 + seq, name="i8 S=%d" % seq)
+    check_i8(oracle_mod, wl)
+    check_i8(oracle_mod, wl, use_mask=False)
+
+
+@pytest.mark.parametrize("row", ["MHA-1", "MHA-2", "MHA-3", "MHA-4"])
+def test_i8_table1_shapes(oracle_mod, row):
+    """The four MHA rows of Table I in Int8 at batch 2 (whole output), and MHA-4 at a full batch on sampled entries."""
+    check_i8(oracle_mod, synth.make_mha_table1(row, "i8", 2))
+    if row == "MHA-4":
+        check_i8(oracle_mod, synth.make_mha_table1(row, "i8", 32), batches=[0, 13, 31])
+
+
+def test_i8_exact_where_no_numerator_is_near_a_tie(oracle_mod):
+    """Zero queries: every score equals its key's mask entry, chosen as log(k/127) for integers k, so every numerator
+    is 127 * (k/127) = k up to rounding error far from a tie, on the GPU as in the oracle; then both integer products,
+    the row sum and the fp32 normalisation must agree to the byte.  Also a single valid key (P = [127])."""
+    rng = np.random.default_rng(5600)
+    b, seq, heads, d = 2, 150, 2, 64
+    wl = synth.make_mha("i8", b, seq, heads * d, heads, 5601, name="i8 exact")
+    wl.q = np.zeros_like(wl.q)
+    ks = rng.integers(1, 128, size=(b, seq))
+    ks[:, 7] = 127                                           # the row maximum: log(127/127) = 0
+    wl.mask = np.log(ks / 127.0).astype(np.float32)
+    check_i8(oracle_mod, wl, exact=True)
+    one = synth.make_mha("i8", b, 70, heads * d, heads, 5602, name="i8 one key")
+    one.mask = np.full((b, 70), -10000.0, np.float32)
+    one.mask[:, 33] = 0.0
+    check_i8(oracle_mod, one, exact=True)
+
+
+def test_i8_entry_point_checks():
+    import torch
+
+    d = binding.mha_desc(binding.OGC_I8, 1, 1, 64, 64, 0.125)
+    good = binding.ogc_mha_quant(0.03, 0.03, 0.03, 0.03)
+    assert binding.ogc_mha_i8_validate(d, good) == 0
+    assert binding.ogc_mha_validate(d) == -2                              # the float entry point does not take int8
+    assert binding.ogc_mha_i8_validate(d, binding.ogc_mha_quant(0.03, 0.0, 0.03, 0.03)) == -1
+    assert binding.ogc_mha_i8_validate(binding.mha_desc(binding.OGC_I8, 1, 1, 64, 64, 0.125, FAST), good) == -2
+    assert binding.ogc_mha_i8_validate(binding.mha_desc(binding.OGC_BF16, 1, 1, 64, 64, 0.125), good) == -1
+    assert binding.ogc_mha_i8_validate(binding.mha_desc(binding.OGC_I8, 1, 1, 64, 48, 0.125), good) == -2
+    assert binding.ogc_mha_i8_kernel_name(d) == "ogc_mha_i8_kernel<2>"
+    buf = torch.zeros(64 * 64 + 16, dtype=torch.int8, device="cuda")
+    with pytest.raises(binding.OgcError) as e:
+        binding.ogc_mha_run_i8(d, good, buf.data_ptr() + 1, buf.data_ptr(), buf.data_ptr(), 0, buf.data_ptr())
+    assert e.value.status == -4
