@@ -126,10 +126,12 @@ ogc_status ogc_mlp_plan(const ogc_mlp_desc* desc /*host*/, ogc_mlp_plan_t* out_p
 /* Forced choices for ogc_mlp_plan_with_overrides; -1 in a field leaves that choice to the cost model.  For tests,
  * sweeps and the calibration of the cost models (every candidate of Section III's heuristic can be timed by itself). */
 typedef struct {
-    int32_t tile;            /* per-layer mode: tile configuration of every layer, 0..4 (0-2 register-staged 256x256 /
-                                128x128 / 64x32 channels x rows, 3 / 4 the four- / eight-wave stream tile); a stream tile
-                                falls back to 1 on a layer the stream kernel cannot run */
-    int32_t ksplit_log2;     /* per-layer mode: log2 of the number of k ranges of every stream-tile layer, 0..3 */
+    int32_t tile;            /* per-layer mode: tile configuration of every layer, 0..5 (0-2 register-staged 256x256 /
+                                128x128 / 64x32 channels x rows; 3 / 4 the four- / eight-wave stream tile, 128x256 /
+                                256x256; 5 the k-sliced stream tile: 128x128, two groups of four waves take alternate
+                                k-steps and add up in LDS at the end of a tile); a stream tile falls back to 1 on a layer
+                                the stream kernel cannot run (5 also where the number of 64-byte k-steps is odd) */
+    int32_t ksplit_log2;     /* per-layer mode: log2 of the number of k ranges of every layer on stream tile 3 or 4, 0..3 */
     int32_t cluster_split;   /* cooperative mode: 0 = kernel (a); n = kernel (b) with n workgroups per row tile where
                                 they fit (any dtype) */
     int32_t cluster_ksplit;  /* cooperative mode: 1 together with cluster_split = n: kernel (c) with n members;

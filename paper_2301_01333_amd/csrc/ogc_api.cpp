@@ -119,23 +119,15 @@ struct CostTable {
     TileCost t[OGC_NUM_TILES];  // indexed by tile id; OGC_TILE_BIG is not a candidate
     float r0, r1, r2, px, l0;
 };
-const CostTable kCostI8 = {{{0, 0, 0, 0, 0},
-                            {7.354f, 0.452f, 2.362f, 0.349f, 0.097f},
-                            {4.896f, 0.339f, 0.479f, 0.086f, 0.102f},
-                            {7.931f, 0.289f, 0.051f, 0.565f, 0.260f},
-                            {9.489f, 0.486f, 4.848f, 0.805f, 0.115f}},
-                           0.933f, 0.160f, 0.981f, 3.013f, 2.651f};
-const CostTable kCostBf16 = {{{0, 0, 0, 0, 0},
-                              {6.767f, 0.452f, 2.365f, 0.327f, 0.171f},
-                              {4.596f, 0.337f, 0.517f, 0.081f, 0.133f},
-                              {8.151f, 0.289f, 0.756f, 0.579f, 0.277f},
-                              {9.995f, 0.480f, 8.036f, 0.829f, 0.244f}},
-                             0.889f, 0.119f, 0.922f, 4.469f, 0.061f};
+// kCostI8, kCostBf16: written by paper_2301_01333_amd/calibration/fit_layers.py from the measured launches in
+// paper_2301_01333_amd/calibration/data/layer_times.csv (a test refits and compares)
+#include "ogc_cost_layers.inc"
 
 // fp32 runs on the register-staged tiles only (256x256, 128x128, 64x32), never split: 1044 timed launches, 11 % rms.
 const CostTable kCostF32 = {{{12.688f, 4.093f, 26.438f, 3.881f, 0.131f},
                              {7.964f, 1.128f, 2.877f, 1.215f, 0.157f},
                              {4.817f, 0.380f, 0.177f, 0.193f, 0.305f},
+                             {0, 0, 0, 0, 0},
                              {0, 0, 0, 0, 0},
                              {0, 0, 0, 0, 0}},
                             0.0f, 0.0f, 0.0f, 0.0f, 6.245f};
@@ -170,16 +162,17 @@ void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int for
     auto split_ok = [&](int ks) { return ks >= 0 && ks <= 3 && kt % (1 << ks) == 0 && (kt >> ks) >= 4; };
     int tile = -1, ks = 0;
     if (forced >= 0 && forced < OGC_NUM_TILES)
-        tile = ((forced == OGC_TILE_DMA || forced == OGC_TILE_DMA8) && !dma_ok) ? OGC_TILE_MID : forced;
-    const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8;
+        tile = ((forced == OGC_TILE_DMA || forced == OGC_TILE_DMA8 || forced == OGC_TILE_DMAK2) && !dma_ok) ? OGC_TILE_MID : forced;
+    if (tile == OGC_TILE_DMAK2 && kt % 2 != 0) tile = OGC_TILE_MID;  // its stages hold two k-steps
+    const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8;  // (the k-sliced shape is never split between workgroups)
     if (tile >= 0) {
         if (stream && forced_split > 0 && forced_split <= 3 && kt % (1 << forced_split) == 0) ks = forced_split;
     } else {
         double best = 0.0;
         // the 256x256 register-staged tile is timed for fp32 only; the stream tiles replace it for int8 / bf16
-        const int cands[5] = {OGC_TILE_SMALL, OGC_TILE_MID, dtype == OGC_F32 ? OGC_TILE_BIG : -1, dma_ok ? OGC_TILE_DMA : -1,
-                              dma_ok ? OGC_TILE_DMA8 : -1};
-        for (int c = 0; c < 5; ++c) {
+        const int cands[6] = {OGC_TILE_SMALL, OGC_TILE_MID, dtype == OGC_F32 ? OGC_TILE_BIG : -1, dma_ok ? OGC_TILE_DMA : -1,
+                              dma_ok ? OGC_TILE_DMA8 : -1, (dma_ok && kt % 2 == 0) ? OGC_TILE_DMAK2 : -1};
+        for (int c = 0; c < 6; ++c) {
             if (cands[c] < 0) continue;
             const bool st = cands[c] == OGC_TILE_DMA || cands[c] == OGC_TILE_DMA8;
             if (forced_split > 0 && !st && dma_ok) continue;  // a forced split needs a stream tile

@@ -81,7 +81,7 @@ struct OgcChainArgs {
 #define OGC_SYNC_ERR_WORD 2   // set to 1 by a workgroup whose barrier wait gave up; read and cleared by ogc_mlp_check
 #define OGC_BARRIER_BUDGET (1 << 22)
 
-enum { OGC_TILE_BIG = 0, OGC_TILE_MID = 1, OGC_TILE_SMALL = 2, OGC_TILE_DMA = 3, OGC_TILE_DMA8 = 4, OGC_NUM_TILES = 5 };
+enum { OGC_TILE_BIG = 0, OGC_TILE_MID = 1, OGC_TILE_SMALL = 2, OGC_TILE_DMA = 3, OGC_TILE_DMA8 = 4, OGC_TILE_DMAK2 = 5, OGC_NUM_TILES = 6 };
 
 struct OgcTileInfo {
     int bn, bm, threads;

@@ -717,10 +717,13 @@ template <int TILE> static OgcTileInfo tile_info_t() {
 }
 
 extern "C" OgcTileInfo ogc_tile_info(int tile) {
-    if (tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8) {
+    if (tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8 || tile == OGC_TILE_DMAK2) {
         OgcTileInfo i;
         if (tile == OGC_TILE_DMA) {
             typedef StreamCfg<0> C;
+            i.bn = C::BN, i.bm = C::BM, i.threads = C::NT, i.lds_bytes = C::LDS;
+        } else if (tile == OGC_TILE_DMAK2) {
+            typedef StreamCfg<2> C;
             i.bn = C::BN, i.bm = C::BM, i.threads = C::NT, i.lds_bytes = C::LDS;
         } else {
             typedef StreamCfg<1> C;
@@ -1232,7 +1235,7 @@ static int launch_dma_t(const OgcLayerArgs* a, hipStream_t stream) {
     const int tiles_m = (a->M + C::BM - 1) / C::BM;
     const int total = tiles_n * tiles_m;
     const int per_xcd = (total + 7) / 8;
-    const int max_slots = SHAPE ? 32 : 64;  // 32 CUs per XCD, one or two resident workgroups per CU
+    const int max_slots = SHAPE ? 32 : 64;  // 32 CUs per XCD, two resident workgroups per CU for the four-wave shape
     const int slots = per_xcd < max_slots ? per_xcd : max_slots;
     hipLaunchKernelGGL(kern, dim3(slots * 8), dim3(C::NT), C::LDS, stream, *a, tiles_n, total, per_xcd, slots);
     return (int)hipGetLastError();
@@ -1248,6 +1251,15 @@ static int launch_dma_io(int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
 // followed by the reduction pass that owns the epilogue
 template <int SHAPE>
 static int launch_dma_dtype(int dtype, int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
+    if constexpr (SHAPE == 2) {
+        if (a->ksplit_log2 > 0) return (int)hipErrorInvalidValue;  // the plan never splits this shape between workgroups
+        if (dtype == OGC_BF16) return launch_dma_io<OGC_BF16, 2, 0>(xp, op, a, s);
+        if (dtype == OGC_I8) {
+            if (a->act == OGC_ACT_RELU && !a->out_f32) return launch_dma_io<OGC_I8, 2, 1>(xp, op, a, s);
+            return launch_dma_io<OGC_I8, 2, 0>(xp, op, a, s);
+        }
+        return (int)hipErrorInvalidValue;
+    } else
     if (a->ksplit_log2 > 0) {
         int rc;
         if (dtype == OGC_BF16) rc = xp ? launch_dma_t<OGC_BF16, SHAPE, 1, 0, 2>(a, s) : launch_dma_t<OGC_BF16, SHAPE, 0, 0, 2>(a, s);
@@ -1266,11 +1278,12 @@ static int launch_dma_dtype(int dtype, int xp, int op, const OgcLayerArgs* a, hi
 
 extern "C" int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain, const OgcLayerArgs* a, void* stream) {
     hipStream_t s = (hipStream_t)stream;
-    if (tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8) {
+    if (tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8 || tile == OGC_TILE_DMAK2) {
         if (x_plain && !a->x_vec_ok) {
             tile = OGC_TILE_MID;  // caller's x is not 16-byte aligned: same channel padding, register-staged loads
         } else {
             if (tile == OGC_TILE_DMA) return launch_dma_dtype<0>(dtype, x_plain, out_plain, a, s);
+            if (tile == OGC_TILE_DMAK2) return launch_dma_dtype<2>(dtype, x_plain, out_plain, a, s);
             return launch_dma_dtype<1>(dtype, x_plain, out_plain, a, s);
         }
     }
@@ -1473,14 +1486,15 @@ extern "C" int ogc_launch_prepack_params(int dtype, const void* w, const float* 
 extern "C" const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, int out_plain, int act, int out_f32, int split) {
     static char names[3][OGC_NUM_TILES][2][2][3][48];
     if (dtype < 0 || dtype > 2 || tile < 0 || tile >= OGC_NUM_TILES) return "?";
-    const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8;
+    const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8 || tile == OGC_TILE_DMAK2;
     const int epi = (stream && split) ? 2 : (stream && dtype == OGC_I8 && act == OGC_ACT_RELU && !out_f32);
     if (epi == 2) out_plain = 0;
     char* n = names[dtype][tile][x_plain != 0][out_plain != 0][epi];
     if (!n[0]) {
         char tmp[48];
         if (stream)
-            snprintf(tmp, sizeof tmp, "ogc_layer_dma_kernel<%d, %d, %d, %d, %d>", dtype, tile == OGC_TILE_DMA8, x_plain != 0, out_plain != 0, epi);
+            snprintf(tmp, sizeof tmp, "ogc_layer_dma_kernel<%d, %d, %d, %d, %d>", dtype,
+                     tile == OGC_TILE_DMA8 ? 1 : (tile == OGC_TILE_DMAK2 ? 2 : 0), x_plain != 0, out_plain != 0, epi);
         else
             snprintf(tmp, sizeof tmp, "ogc_layer_kernel<%d, %d, %d, %d>", dtype, tile, x_plain != 0, out_plain != 0);
         memcpy(n, tmp, sizeof tmp);  // every writer stores the same bytes

@@ -47,15 +47,23 @@ OGC_DEV uint32_t lds_addr_of(const void* p) {
 //            per CU clock at MFMA peak -- the global->LDS path delivers about 53, so this is the shape for
 //            layers with enough tiles to fill the chip
 // In both, a wave owns 64 channels x 128 rows (2 x 4 MFMA blocks) and 256 VGPRs.
+//   shape 2: 8 waves as 2 x 2 x 2: two k groups of four waves, each group on every second k-step of the same
+//            128 x 128 tile (k-slicing inside the workgroup, Section III), a wave owning 64 x 64 (2 x 2 blocks).  For
+//            layers with few outputs against a long reduction axis: 128 x 128 is what a CU's share of such a layer
+//            comes to, and cutting K between workgroups instead costs a pass over fp32 partials in memory.  A stage
+//            holds two k-steps (32 KiB); at the end of a tile the second group's accumulators cross LDS to the first
 template <int SHAPE> struct StreamCfg {
     enum {
-        TN = 2, TM = 4, WAVES_N = SHAPE ? 4 : 2, WAVES_M = 2, WAVES = WAVES_N * WAVES_M, NT = WAVES * 64,
+        KG = SHAPE == 2 ? 2 : 1,  // k groups: k-steps of a stage, each taken by its own group of waves
+        TN = 2, TM = SHAPE == 2 ? 2 : 4, WAVES_N = SHAPE == 1 ? 4 : 2, WAVES_M = 2, WAVES = WAVES_N * WAVES_M * KG, NT = WAVES * 64,
         NST = SHAPE ? 4 : 3, BN = WAVES_N * TN * 32, BM = WAVES_M * TM * 32,
-        W_OPS = BN / 16, X_OPS = BM / 16, OPS = W_OPS + X_OPS, OPW = OPS / WAVES,
-        STAGE = (BN + BM) * 64, RING = STAGE * NST, PARAMS = 2 * BN * 4,
+        W_OPS = KG * BN / 16, X_OPS = KG * BM / 16, OPS = W_OPS + X_OPS, OPW = OPS / WAVES,
+        STAGE = KG * (BN + BM) * 64, RING = STAGE * NST, PARAMS = 2 * BN * 4,
         // the eight-wave shape (one workgroup per CU) has room for 2 KiB per wave through which the last layer's
         // result chunks are regrouped into whole row segments
-        ROWS64 = SHAPE ? WAVES * 2048 : 0, LDS = RING + 2 * PARAMS + ROWS64,
+        ROWS64 = SHAPE == 1 ? WAVES * 2048 : 0,
+        KRED = SHAPE == 2 ? 4 * 4096 : 0,  // one accumulator block of each wave of the second k group
+        LDS = RING + 2 * PARAMS + ROWS64 + KRED,
         COMPILER_VGPRS = 80, NUM_VGPR_ATTR = COMPILER_VGPRS / 2
     };
     static_assert(OPW == (SHAPE ? 4 : 6) && OPS % WAVES == 0, "loads per wave and stage");
@@ -124,11 +132,64 @@ template <int SHAPE> struct StreamCfg {
         D(1, O1, "incw") OGC_MFMA(OP, 104, 4, 1, 0) D(2, O2, "incx") OGC_MFMA(OP, 104, 5, 1, 1)           \
             D(3, O3, "incx") OGC_MFMA(OP, 104, 6, 1, 2) OGC_MFMA(OP, 104, 7, 1, 3) "s_waitcnt lgkmcnt(0)"
 
+// ---- the 64 x 64 wave tile of shape 2: operands W0 W1 X0 X1, blocks 0, 1 (W0 x X0, X1) and 4, 5 (W1 x X0, X1) ----
+#define OGC_READ2_X(F, XA)                                          \
+    "ds_read_b128 " OGC_X(F, 0) ", " XA "\n\t"                       \
+    "ds_read_b128 " OGC_X(F, 1) ", " XA " offset:2048\n\t"
+#define OGC_READ2(F, WA, XA) OGC_READ_W(F, WA) OGC_READ2_X(F, XA)
+#define OGC_READ2_HI(F, WA, XH)                                     \
+    "ds_read_b128 " OGC_W(F, 0) ", " WA " offset:1024\n\t"           \
+    "ds_read_b128 " OGC_W(F, 1) ", " WA " offset:3072\n\t"           \
+    OGC_READ2_X(F, XH)
+// single step: reads F1 | 4 MFMAs on F0 | wait F1 | 1 MFMA on F1 | wait for the next stage's loads, barrier |
+// reads F0 of the next step | 3 MFMAs on F1 with the direct loads between and after them | wait F0
+#define OGC_STEP2_FIRST(OP, MZ, FL)                                                                       \
+    OGC_READ_W(104, "%[t0]") OGC_READ2_X(104, "%[t1]")                                                    \
+    FL(80, 0) MZ(OP, 80, 0, 0, 0) FL(80, 1) MZ(OP, 80, 1, 0, 1) MZ(OP, 80, 4, 1, 0) MZ(OP, 80, 5, 1, 1)   \
+    "s_waitcnt lgkmcnt(0)\n\t" FL(104, 0) OGC_MFMA(OP, 104, 0, 0, 0)
+#define OGC_STEP2_SYNC(VMN) "s_waitcnt vmcnt(" #VMN ")\n\ts_barrier\n\t" OGC_READ2(80, "%[t2]", "%[t3]")
+#define OGC_STEP2_REST(OP, FL, D)                                                                         \
+    FL(104, 1) OGC_MFMA(OP, 104, 1, 0, 1) D(0, 0, "incw") D(1, 8192, "incw") OGC_MFMA(OP, 104, 4, 1, 0)   \
+    D(2, 16384, "incx") D(3, 24576, "incx") OGC_MFMA(OP, 104, 5, 1, 1) "s_waitcnt lgkmcnt(0)"
+#define OGC_RUN2(OP, FL, DA, DB, SLOT)                                                                    \
+    ".Lks%=:\n\t"                                                                                         \
+    "s_add_u32 %[son], %[sst], %[stg]\n\t"                                                                \
+    "s_cmp_lg_u32 %[son], %[ring]\n\t"                                                                    \
+    "s_cselect_b32 %[son], %[son], 0\n\t"                                                                 \
+    OGC_READ2_HI(104, "%[tw]", "%[txh]")                                                                  \
+    "s_waitcnt lgkmcnt(4)\n\t"                                                                            \
+    FL(80, 0) OGC_MFMA(OP, 80, 0, 0, 0)                                                                   \
+    "v_add_u32 %[tw], %[son], %[wrd]\n\t"                                                                 \
+    "v_add_u32 %[tx], %[son], %[xrd]\n\t"                                                                 \
+    "v_add_u32 %[txh], %[son], %[xrdh]\n\t"                                                               \
+    FL(80, 1) OGC_MFMA(OP, 80, 1, 0, 1)                                                                   \
+    "s_add_u32 %[kph], %[kph], 1\n\t"                                                                     \
+    "s_cmp_eq_u32 %[kph], %[ktt]\n\t"                                                                     \
+    "s_cselect_b64 %[incw], %[incww], %[incwn]\n\t"                                                       \
+    "s_cselect_b64 %[incx], %[incxw], %[incxn]\n\t"                                                       \
+    "s_cselect_b32 %[kph], 0, %[kph]\n\t"                                                                 \
+    "s_add_u32 %[m0b], %[m0w], %[" SLOT "]\n\t"                                                           \
+    DA(0, 0, "incw") DA(1, 8192, "incw") OGC_MFMA(OP, 80, 4, 1, 0)                                        \
+    DA(2, 16384, "incx") DA(3, 24576, "incx") OGC_MFMA(OP, 80, 5, 1, 1)                                   \
+    "s_waitcnt lgkmcnt(0)\n\t"                                                                            \
+    FL(104, 0) OGC_MFMA(OP, 104, 0, 0, 0)                                                                 \
+    "s_waitcnt vmcnt(8)\n\ts_barrier\n\t"                                                                 \
+    FL(104, 1) OGC_MFMA(OP, 104, 1, 0, 1)                                                                 \
+    OGC_READ2(80, "%[tw]", "%[tx]")                                                                       \
+    DB(0, 0, "incw") DB(1, 8192, "incw") OGC_MFMA(OP, 104, 4, 1, 0)                                       \
+    DB(2, 16384, "incx") DB(3, 24576, "incx") OGC_MFMA(OP, 104, 5, 1, 1)                                  \
+    "s_mov_b32 %[sprev], %[sst]\n\t"                                                                      \
+    "s_mov_b32 %[sst], %[son]\n\t"                                                                        \
+    "s_sub_u32 %[n], %[n], 1\n\t"                                                                         \
+    "s_cmp_lg_u32 %[n], 0\n\t"                                                                            \
+    "s_cbranch_scc1 .Lks%=\n\t"                                                                           \
+    "s_waitcnt lgkmcnt(0)"
+
 // Step modes: 0 = loads of the stage NST steps ahead are issued and VM newer loads may stay in flight at the
 // barrier (after an epilogue too: its stores were issued after the loads this wait is for, and loads and stores
 // complete in issue order, so they only make the wait longer than needed); 2 = no loads left to issue, everything
 // awaited; 3 = last step of the stream: no barrier, no reads
-template <int DT, int OPW, int VM, int MODE, bool ZERO, bool FLIP>
+template <int DT, int OPW, int VM, int MODE, bool ZERO, bool FLIP, int TMV = 4>
 OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint32_t soc, uint32_t son, uint64_t (&g)[6], uint64_t incw,
                     uint64_t incx, uint32_t m0b) {
     const uint32_t sox = soc - 1024;  // the stage itself: the second half's activation chunks are addressed from x_rd_hi
@@ -141,7 +202,19 @@ OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint32_t soc
 #define OGC_STEP_G4 [g0] "+v"(g[0]), [g1] "+v"(g[1]), [g2] "+v"(g[2]), [g3] "+v"(g[3])
 #define OGC_STEP_DMA_IN [incw] "s"(incw), [incx] "s"(incx), [m0b] "s"(m0b)
 #define OGC_STEP(OP, MZ, FL)                                                                                        \
-    if constexpr (MODE == 0 && OPW == 6)                                                                            \
+    if constexpr (TMV == 2 && MODE == 0 && VM == 8)                                                                 \
+        asm volatile(OGC_STEP_HEAD OGC_STEP2_FIRST(OP, MZ, FL) OGC_STEP2_SYNC(8) OGC_STEP2_REST(OP, FL, OGC_DMA)    \
+                     : OGC_STEP_OUT, OGC_STEP_G4 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
+    else if constexpr (TMV == 2 && MODE == 0)                                                                       \
+        asm volatile(OGC_STEP_HEAD OGC_STEP2_FIRST(OP, MZ, FL) OGC_STEP2_SYNC(4) OGC_STEP2_REST(OP, FL, OGC_DMA)    \
+                     : OGC_STEP_OUT, OGC_STEP_G4 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
+    else if constexpr (TMV == 2 && MODE == 2)                                                                       \
+        asm volatile(OGC_STEP_HEAD OGC_STEP2_FIRST(OP, MZ, FL) OGC_STEP2_SYNC(0) OGC_STEP2_REST(OP, FL, OGC_NODMA)  \
+                     : OGC_STEP_OUT : OGC_STEP_IN : "memory");                                                      \
+    else if constexpr (TMV == 2)                                                                                    \
+        asm volatile(OGC_STEP_HEAD OGC_STEP2_FIRST(OP, MZ, FL) OGC_STEP2_REST(OP, FL, OGC_NODMA)                    \
+                     : OGC_STEP_OUT : OGC_STEP_IN : "memory");                                                      \
+    else if constexpr (MODE == 0 && OPW == 6)                                                                            \
         asm volatile(OGC_STEP_HEAD OGC_STEP_FIRST(OP, MZ, FL) OGC_STEP_SYNC(6)                                      \
                          OGC_STEP_REST6(OP, FL, OGC_DMA, 4096, 8192, 12288, 16384, 20480)                           \
                      : OGC_STEP_OUT, OGC_STEP_G6 : OGC_STEP_IN, OGC_STEP_DMA_IN : "memory");                        \
@@ -238,7 +311,7 @@ template <int DT, int SHAPE, bool LATE, bool FLIP>
 OGC_DEV void k_steps_run(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint64_t (&g)[6], uint32_t& sst, uint32_t& sprev, uint32_t& kph, uint32_t n,
                          uint32_t kt_total, uint32_t m0w, uint64_t incwn, uint64_t incww, uint64_t incxn, uint64_t incxw) {
     typedef StreamCfg<SHAPE> C;
-    static_assert(!(LATE && SHAPE == 0), "only the eight-wave shape splits its waves into two groups");
+    static_assert(!(LATE && SHAPE == 0), "only the eight-wave shapes split their waves into an early and a late group");
     const uint32_t flip = 0x80808080u;
     sst = __builtin_amdgcn_readfirstlane(sst);
     sprev = __builtin_amdgcn_readfirstlane(sprev);
@@ -253,7 +326,11 @@ OGC_DEV void k_steps_run(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint64_
 #define OGC_RUN_IN [wrd] "v"(w_rd), [xrd] "v"(x_rd), [xrdh] "v"(x_rd_hi), [ktt] "s"(kt_total), [m0w] "s"(m0w), [incwn] "s"(incwn), [incww] "s"(incww), \
                    [incxn] "s"(incxn), [incxw] "s"(incxw), [flip] "s"(flip), [stg] "n"(C::STAGE), [ring] "n"(C::RING)
 #define OGC_RUN_SHAPES(OP, FL)                                                                                              \
-    if constexpr (SHAPE == 0)                                                                                               \
+    if constexpr (SHAPE == 2 && !LATE)                                                                                      \
+        asm volatile(OGC_RUN2(OP, FL, OGC_NODMA, OGC_DMA, "sst") : OGC_RUN_OUT, OGC_STEP_G4 : OGC_RUN_IN : "memory", "scc"); \
+    else if constexpr (SHAPE == 2)                                                                                          \
+        asm volatile(OGC_RUN2(OP, FL, OGC_DMA, OGC_NODMA, "sprev") : OGC_RUN_OUT, OGC_STEP_G4 : OGC_RUN_IN : "memory", "scc"); \
+    else if constexpr (SHAPE == 0)                                                                                               \
         asm volatile(OGC_RUN(OP, FL, OGC_NODMA, OGC_DMA, "sst", 6, 4096, 8192, 12288, 16384, 20480, OGC_DMA)                \
                      : OGC_RUN_OUT, OGC_STEP_G6 : OGC_RUN_IN : "memory", "scc");                                            \
     else if constexpr (!LATE)                                                                                               \
@@ -276,6 +353,13 @@ OGC_DEV void k_steps_run(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint64_
 #undef OGC_RUN_FL
 #undef OGC_RUN_SHAPES
 }
+
+// block b of the accumulators to LDS as four 16-byte pieces per lane, 1 KiB apart (ra: the lane's LDS address)
+#define OGC_LDS_PUT_ACC(b)                                                                            \
+    asm volatile("ds_write_b128 %0, v[128+16*" #b ":131+16*" #b "]\n\t"                                \
+                 "ds_write_b128 %0, v[132+16*" #b ":135+16*" #b "] offset:1024\n\t"                    \
+                 "ds_write_b128 %0, v[136+16*" #b ":139+16*" #b "] offset:2048\n\t"                    \
+                 "ds_write_b128 %0, v[140+16*" #b ":143+16*" #b "] offset:3072" ::"v"(ra) : "memory")
 
 // Hands accumulator block B (v[128+16B ..]) to the compiler where it is: the empty statement declares the
 // sixteen registers as its output, and the epilogue then reads them as source operands (no copies; the
@@ -314,9 +398,11 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     // v80..v255 are used by the assembly below only; naming the last one makes the kernel own all 256.
     asm volatile("; operand sets and accumulators live in v80..v255" ::: "v255");
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wn = wave % C::WAVES_N, wm = wave / C::WAVES_N;
+    constexpr int KG = C::KG;
+    static_assert(!(KG == 2 && EPI == 2), "the shape that slices K inside the workgroup is not split between workgroups");
+    const int wn = wave % C::WAVES_N, wm = (wave / C::WAVES_N) % C::WAVES_M, kg = wave / (C::WAVES_N * C::WAVES_M);
     const int LS = EPI == 2 ? a.ksplit_log2 : 0;  // log2 of the number of k ranges
-    const int KT = (a.KC >> 2) >> LS;             // k-steps of one tile (of one k range of it)
+    const int KT = ((a.KC >> 2) >> LS) / KG;      // steps of one tile (of one k range of it); a step is KG k-steps of 64 bytes
     const int xcd = blockIdx.x & 7;
     int t_end = (xcd + 1) * tiles_per_xcd;
     t_end = t_end < tiles_total ? t_end : tiles_total;
@@ -340,29 +426,39 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     // A stage is OPS loads of 1 KiB (two 512-byte slabs of one 32-row chunk); load i of wave w is op
     // o = i*WAVES + w, so loads 0 and 1 of every wave fetch weights and the others activations.  g[i] is the
     // global address of this wave's load i for the k-step the cursor points at; the step block advances it.
-    // The k-steps of a tile are walked in rotated order, starting at rot = n_tile*KT/tiles_n: the workgroups
-    // that share a batch tile (its n-tiles, resident together on one XCD) then touch different k-slices of the
-    // activations at any moment, so each slice is missed in L2 by one of them and hit by the others later,
-    // instead of all of them waiting on the same miss.  Accumulation order within a tile is free (integer
-    // sums are exact; float sums stay within the stated tolerance).
+    // The k-steps of a tile are walked in rotated order, starting at rot = min(n_tile, n_tile*KT/tiles_n): the
+    // workgroups that share a batch tile (its n-tiles, resident together on one XCD) then touch neighbouring
+    // k-slices of the activations at any moment, so each slice is missed in L2 by one of them and hit by the others
+    // a step later, instead of all of them waiting on the same miss.  One step apart and no more: spread over the
+    // whole reduction axis (as first built) the n-tiles of a long-K layer each pulled their own copy of every
+    // slice through the fabric, the first having long left the 4 MiB L2 when the next arrived (K = 4096, eight
+    // n-tiles: 41 against 49 us).  Accumulation order within a tile is free (integer sums are exact; float sums
+    // stay within the stated tolerance).
     static_assert(C::W_OPS == 2 * C::WAVES, "loads 0,1 of a wave are weights, the rest activations");
     uint64_t g[6] = {0, 0, 0, 0, 0, 0};
-    const long long x_step = X_PLAIN ? 64 : 2048;
+    const long long x_step = (X_PLAIN ? 64 : 2048) * KG, w_step = 2048 * KG;  // bytes a step advances along K
     int pf_m = __builtin_amdgcn_readfirstlane(first_tile / tiles_n), pf_n = first_tile - pf_m * tiles_n;
     int pf_left = my_tiles, pf_kt = 0, pf_kphys = 0;
     auto setup_src = [&]() {  // addresses of the cursor tile's first (rotated) k-step
         pf_kphys = __builtin_amdgcn_readfirstlane((int)((uint32_t)(pf_n * KT) / (uint32_t)tiles_n));
+        pf_kphys = pf_kphys < pf_n ? pf_kphys : pf_n;  // one step apart at most (see above)
         pf_kt = 0;
         const int n_base = (pf_n >> LS) * C::BN, m_base = pf_m * C::BM;
         const int k_first = (pf_n & ((1 << LS) - 1)) * KT + pf_kphys;  // physical k-step in the whole reduction axis
 #pragma unroll
         for (int i = 0; i < OPW; ++i) {
-            const int o = i * C::WAVES + wave;
+            long long src_kofs = 0;
+            // (with two k groups the ops of a stage are [W group 0][W group 1][X group 0][X group 1]: the second group's
+            // pieces are those of the next k-step)
+            const int oo = i * C::WAVES + wave;
+            const int og = KG == 2 ? ((oo % (C::W_OPS)) >= C::W_OPS / 2 ? 1 : 0) : 0;     // k group of this op (W and X have the same count)
+            const int o = KG == 2 ? (oo < C::W_OPS ? oo - og * (C::W_OPS / 2) : oo - og * (C::X_OPS / 2) - C::W_OPS / 2) : oo;
             const uint8_t* src;
             if (i < 2) {
-                src = a.w + ((size_t)((n_base >> 5) + (o >> 1)) * a.KC + (o & 1) * 2) * 512 + lane * 16 + (long long)k_first * 2048;
+                src = a.w + ((size_t)((n_base >> 5) + (o >> 1)) * a.KC + (o & 1) * 2) * 512 + lane * 16 + (long long)k_first * w_step + og * 2048;
             } else {
-                const int ox = o - C::W_OPS;
+                const int ox = o - C::W_OPS / KG;
+                if (og) src_kofs = X_PLAIN ? 64 : 2048;
                 if constexpr (X_PLAIN) {
                     const int qrow = lane >> 2;  // 16 rows per load, four lanes per row
                     int row = m_base + ox * 16 + qrow;
@@ -371,18 +467,18 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                 } else {
                     src = a.x + ((size_t)((m_base >> 5) + (ox >> 1)) * a.KC + (ox & 1) * 2) * 512 + lane * 16;
                 }
-                src += (long long)k_first * x_step;
+                src += (long long)k_first * x_step + src_kofs;
             }
             g[i] = (uint64_t)(uintptr_t)src;
         }
     };
     // The address increments that take the cursor from its current k-step to the next one of the same tile
     // (the rotated walk wraps from the last physical k-step back to the first).
-    uint64_t incw = 2048, incx = (uint64_t)x_step;
-    const uint64_t incw_wrap = (uint64_t)(-(long long)(KT - 1) * 2048), incx_wrap = (uint64_t)(-(long long)(KT - 1) * x_step);
+    uint64_t incw = (uint64_t)w_step, incx = (uint64_t)x_step;
+    const uint64_t incw_wrap = (uint64_t)(-(long long)(KT - 1) * w_step), incx_wrap = (uint64_t)(-(long long)(KT - 1) * x_step);
     auto set_increments = [&]() {  // for the transition out of the cursor's current k-step
         const bool wrap = pf_kphys + 1 == KT;
-        incw = wrap ? incw_wrap : (uint64_t)2048;
+        incw = wrap ? incw_wrap : (uint64_t)w_step;
         incx = wrap ? incx_wrap : (uint64_t)x_step;
         pf_kphys = wrap ? 0 : pf_kphys + 1;
     };
@@ -398,7 +494,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     };
     const uint32_t lds0 = lds_addr_of(smem);
     const uint32_t m0_wave = lds0 + wave * 1024;  // + stage*STAGE + i*WAVES*1024: where this wave's load i lands
-    const uint32_t w_rd = lds0 + (wn * TN) * 2048 + lane * 16;
+    const uint32_t w_rd = lds0 + kg * (C::BN * 64) + (wn * TN) * 2048 + lane * 16;
     // Activation chunks of a stage.  From a blocked tensor: [32-row block][4 chunks of a k-step][32 rows][16 bytes], the
     // operand order, the second half of a k-step 1 KiB after the first.  From the caller's plain rows (X_PLAIN): a load
     // instruction fetches the 64 bytes of a k-step for 16 rows, four lanes per row, so that each group of four lanes
@@ -409,10 +505,10 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     uint32_t x_rd, x_rd_hi;
     if constexpr (X_PLAIN) {
         const int r = lane & 31;
-        x_rd = lds0 + C::BN * 64 + (wm * TM) * 2048 + r * 64 + ((((lane >> 5) - (r >> 2)) & 3) << 4);
+        x_rd = lds0 + KG * C::BN * 64 + kg * (C::BM * 64) + (wm * TM) * 2048 + r * 64 + ((((lane >> 5) - (r >> 2)) & 3) << 4);
         x_rd_hi = x_rd ^ 32;
     } else {
-        x_rd = lds0 + C::BN * 64 + (wm * TM) * 2048 + lane * 16;
+        x_rd = lds0 + KG * C::BN * 64 + kg * (C::BM * 64) + (wm * TM) * 2048 + lane * 16;
         x_rd_hi = x_rd + 1024;
     }
 
@@ -444,7 +540,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                          :: [sp] "v"(sp), [bp] "v"(bp), [ms] "s"(m0s), [bo] "n"(C::BN * 4) : "memory", "scc");
         }
     };
-    const bool late = SHAPE == 1 && wave >= 4;
+    const bool late = SHAPE != 0 && wave >= 4;  // (shape 2: the second k group; the two groups pair up on the SIMDs)
     int cur_n = pf_n, cur_m = pf_m, tiles_left = my_tiles;
     int pbuf = 0;
     stage_params(cur_n >> LS, 0);
@@ -475,7 +571,8 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
         else if (fetched == 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(OPW) : "memory");
         else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     }
-    asm volatile(OGC_READ(80, "%[wa]", "%[xa]") "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
+    if constexpr (TM == 2) asm volatile(OGC_READ2(80, "%[wa]", "%[xa]") "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
+    else asm volatile(OGC_READ(80, "%[wa]", "%[xa]") "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
     uint32_t sst = 0, sprev = (NST - 1) * C::STAGE;  // ring offsets of the current and the previous step's stage
     int kt = 0, q = 0;
     while (q < total_steps) {
@@ -486,8 +583,8 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             n = n < KT - pf_kt ? n : KT - pf_kt;
             n = n < total_steps - fetched ? n : total_steps - fetched;
             uint32_t kph = (uint32_t)pf_kphys;
-            if (late) k_steps_run<DT, SHAPE, SHAPE == 1, FLIP>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, 2048, incw_wrap, (uint64_t)x_step, incx_wrap);
-            else k_steps_run<DT, SHAPE, false, FLIP>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, 2048, incw_wrap, (uint64_t)x_step, incx_wrap);
+            if (late) k_steps_run<DT, SHAPE, SHAPE != 0, FLIP>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, (uint64_t)w_step, incw_wrap, (uint64_t)x_step, incx_wrap);
+            else k_steps_run<DT, SHAPE, false, FLIP>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, (uint64_t)w_step, incw_wrap, (uint64_t)x_step, incx_wrap);
             pf_kphys = (int)kph;
             kt += n;
             q += n;
@@ -502,20 +599,20 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                 const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + (late ? sprev : sst));
                 // a late wave has one stage fewer in flight at this point (its loads follow the barrier here)
                 if (late) {
-                    if (zero) k_step<DT, OPW, SHAPE == 1 ? 4 : VM, 0, true, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
-                    else k_step<DT, OPW, SHAPE == 1 ? 4 : VM, 0, false, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
+                    if (zero) k_step<DT, OPW, SHAPE != 0 ? 4 : VM, 0, true, FLIP, TM>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
+                    else k_step<DT, OPW, SHAPE != 0 ? 4 : VM, 0, false, FLIP, TM>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
                 } else {
-                    if (zero) k_step<DT, OPW, VM, 0, true, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
-                    else k_step<DT, OPW, VM, 0, false, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
+                    if (zero) k_step<DT, OPW, VM, 0, true, FLIP, TM>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
+                    else k_step<DT, OPW, VM, 0, false, FLIP, TM>(w_rd, x_rd, x_rd_hi, soc, son, g, incw, incx, m0b);
                 }
                 ++fetched;
                 cursor_advanced(1);
             } else if (q + 1 < total_steps) {
-                if (zero) k_step<DT, OPW, VM, 2, true, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
-                else k_step<DT, OPW, VM, 2, false, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
+                if (zero) k_step<DT, OPW, VM, 2, true, FLIP, TM>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
+                else k_step<DT, OPW, VM, 2, false, FLIP, TM>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
             } else {
-                if (zero) k_step<DT, OPW, VM, 3, true, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
-                else k_step<DT, OPW, VM, 3, false, FLIP>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
+                if (zero) k_step<DT, OPW, VM, 3, true, FLIP, TM>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
+                else k_step<DT, OPW, VM, 3, false, FLIP, TM>(w_rd, x_rd, x_rd_hi, soc, son, g, 0, 0, 0);
             }
             sprev = sst;
             sst = snext;
@@ -592,6 +689,55 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                     }
                     done = true;
                 }
+            }
+            if constexpr (KG == 2) {
+                // The two k groups hold two halves of every sum.  Block by block, the second group's sixteen registers
+                // cross LDS (4 KiB per wave pair, next to the ring: the next tile's loads keep landing in the ring
+                // meanwhile), the first group adds them to its own and runs the epilogue: group 0 + group 1, a fixed order.
+                lds_u8* const red = (lds_u8*)smem + C::RING + 2 * C::PARAMS + (wave & 3) * 4096 + lane * 16;
+                auto round = [&](auto tag) {
+                    constexpr int B = decltype(tag)::value;
+                    if (kg == 1) {
+                        const uint32_t ra = (uint32_t)(uintptr_t)red;
+                        if constexpr (B == 0) OGC_LDS_PUT_ACC(0);
+                        if constexpr (B == 1) OGC_LDS_PUT_ACC(1);
+                        if constexpr (B == 4) OGC_LDS_PUT_ACC(4);
+                        if constexpr (B == 5) OGC_LDS_PUT_ACC(5);
+                    }
+                    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                    if (kg == 0) {
+                        typedef __attribute__((address_space(3))) v4i lds_v4i;
+                        v4i o[4];
+#pragma unroll
+                        for (int qq = 0; qq < 4; ++qq) o[qq] = *(const lds_v4i*)(red + qq * 1024);
+                        const auto mine = take_acc_block<DT, B>();
+                        typename AccT<DT>::type sum;
+#pragma unroll
+                        for (int qq = 0; qq < 4; ++qq) {
+                            const v4f of = __builtin_bit_cast(v4f, o[qq]);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                if constexpr (DT == OGC_I8) sum[4 * qq + e] = mine[4 * qq + e] + o[qq][e];
+                                else sum[4 * qq + e] = mine[4 * qq + e] + of[e];
+                            }
+                        }
+                        const int n0 = n_base + (B / 4) * 32, m0 = m_base + (B % 4) * 32;
+                        if constexpr (OUT_PLAIN) {
+                            if (n0 < a.N && m0 < a.M) epilogue_block<DT, 1, false, EPI>(sum, a, prm, n0, m0, lane, (uint8_t*)nullptr);
+                        } else {
+                            if ((n0 >> 5) < a.NB_out)
+                                epilogue_block<DT, 0, false, EPI>(sum, a, prm, n0, m0, lane, GlobalY{a.y + (size_t)(m0 >> 5) * a.KC_out * 512});
+                        }
+                    }
+                    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // the scratch is written again next round
+                };
+                if (kg == 0) read_params(0);
+                round(std::integral_constant<int, 0>());
+                round(std::integral_constant<int, 1>());
+                if (kg == 0) read_params(1);
+                round(std::integral_constant<int, 4>());
+                round(std::integral_constant<int, 5>());
+                done = true;
             }
             if (!done) {
                 if constexpr (EPI != 2) read_params(0);

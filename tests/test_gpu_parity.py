@@ -108,10 +108,10 @@ def test_cfg5_full_size_every_row(oracle_mod):
 
 
 # ---------------------------------------------------------------- reduced sizes: several tiles + ragged tails
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])
 @pytest.mark.parametrize("dtype", ["i8", "bf16", "f32"])
 def test_per_layer_ragged(oracle_mod, dtype, tile):
-    m = {0: 300, 1: 150, 2: 77, 3: 600, 4: 700}[tile]
+    m = {0: 300, 1: 150, 2: 77, 3: 600, 4: 700, 5: 333}[tile]
     dims = [100, 333, 72, 33] if dtype == "i8" else [50, 290, 40, 19]
     wl = synth.make_mlp(dtype, m, dims, [RELU, RELU, NONE if dtype != "i8" else RELU], seed=500 + tile, name="ragged")
     check(wl, "per_layer", oracle_mod, tile=tile)
@@ -129,13 +129,15 @@ def test_reduced_cfg4_and_cfg5(oracle_mod, mode):
     check(synth.make_config(5, m=96), mode, oracle_mod)
 
 
-@pytest.mark.parametrize("tile", [3, 4])
+@pytest.mark.parametrize("tile", [3, 4, 5])
 @pytest.mark.parametrize("dtype", ["i8", "bf16", "f32"])
 def test_pipelined_kernel_plain_input(oracle_mod, dtype, tile):
-    """Tiles 3 and 4 = the two shapes of the persistent global->LDS stream kernel (fp32 falls back to the
-    register-staged kernel), reading the caller's plain x directly (aligned rows, no K padding), with a ragged
+    """Tiles 3, 4 and 5 = the three shapes of the persistent global->LDS stream kernel (fp32 falls back to the
+    register-staged kernel; tile 5, whose stages hold two k-steps, falls back where a layer has an odd number of them), reading the caller's plain x directly (aligned rows, no K padding), with a ragged
     batch, short and long K, several tiles per workgroup, and a misaligned x that must fall back."""
     k = {"i8": 192, "bf16": 96, "f32": 64}[dtype]
+    if tile == 5:
+        k *= 2   # an even number of 64-byte k-steps in the first layer: the shape under test really runs it
     wl = synth.make_mlp(dtype, 700, [k, 160, 64, 40], [RELU, RELU, RELU], seed=700, name="dma")
     check(wl, "per_layer", oracle_mod, tile=tile)
     check(synth.make_mlp(dtype, 300, [64, 200], [RELU], seed=701, name="dma-1layer"), "per_layer", oracle_mod, tile=tile)

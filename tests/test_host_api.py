@@ -278,26 +278,33 @@ def test_buffer_reuse_is_ping_pong_for_a_chain():
 
 
 def test_split_k_plan_sizes_and_kernel_names():
-    """A layer with few 256x256 tiles and a long reduction axis is cut into k ranges (k-slicing, Section III):
-    the workspace then carries the partial accumulators behind the activation slots, the layer is still one
-    launch step, and kernel names carry their template arguments."""
+    """A layer with few 256x256 tiles and a long reduction axis takes k-slicing (Section III): by the model's own
+    choice the eight waves of a 128x128 tile split the k-steps between them and add up on chip; a forced split-K
+    cuts the axis into ranges computed by different workgroups, and the workspace then carries the partial
+    accumulators behind the activation slots.  Either way the layer is one launch step, and kernel names carry
+    their template arguments."""
     m, k0, hid = 4096, 1024, 4096
     lay = [layer(k0, hid, act=b.OGC_ACT_GELU_TANH, has_bias=1), layer(hid, k0, act=b.OGC_ACT_NONE, has_bias=1)]
     p = b.ogc_mlp_plan(b.OGC_BF16, m, lay, k0, k0, 1, b.OGC_MODE_AUTO)
     assert b.ogc_mlp_chosen_mode(p) == b.OGC_MODE_PER_LAYER
     assert b.ogc_mlp_num_launches(p) == 2
     hidden_slot = m * hid * 2
-    partial = 2 * m * k0 * 4          # 128 tiles of 128x256 -> two ranges of fp32 accumulators, 256 workgroups
-    assert b.ogc_mlp_workspace_bytes(p) == hidden_slot + partial
-    assert b.ogc_mlp_kernel_name(p, 0) == "ogc_layer_dma_kernel<1, 1, 1, 0, 0>"
-    assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 0, 0, 0, 2>"
-    # the figures the choice was made by: the estimate of the chosen candidate, in microseconds
-    assert 25.0 < b.ogc_mlp_estimated_us(p, 0) < 45.0 and 40.0 < b.ogc_mlp_estimated_us(p, 1) < 65.0
-    b.ogc_mlp_destroy(p)
-    # forced off: no partial region, the second layer takes the four-wave stream shape (128 tiles of 128x256)
-    p = b.ogc_mlp_plan_with_overrides(b.OGC_BF16, m, lay, k0, k0, 1, b.OGC_MODE_AUTO, overrides={"ksplit_log2": 0})
     assert b.ogc_mlp_workspace_bytes(p) == hidden_slot
-    assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 0, 0, 1, 0>"
+    assert b.ogc_mlp_kernel_name(p, 0) == "ogc_layer_dma_kernel<1, 1, 1, 0, 0>"
+    assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 2, 0, 1, 0>"
+    # the figures the choice was made by: the estimate of the chosen candidate, in microseconds
+    assert 25.0 < b.ogc_mlp_estimated_us(p, 0) < 45.0 and 30.0 < b.ogc_mlp_estimated_us(p, 1) < 50.0
+    b.ogc_mlp_destroy(p)
+    # forced: two ranges per layer on the four-wave stream shape, fp32 accumulators of both layers' ranges behind the slot
+    p = b.ogc_mlp_plan_with_overrides(b.OGC_BF16, m, lay, k0, k0, 1, b.OGC_MODE_AUTO, overrides={"tile": 3, "ksplit_log2": 1})
+    assert b.ogc_mlp_workspace_bytes(p) == hidden_slot + 2 * m * hid * 4
+    assert b.ogc_mlp_kernel_name(p, 0) == "ogc_layer_dma_kernel<1, 0, 1, 0, 2>"
+    assert b.ogc_mlp_kernel_name(p, 1) == "ogc_layer_dma_kernel<1, 0, 0, 0, 2>"
+    assert b.ogc_mlp_estimated_us(p, 1) > 45.0
+    b.ogc_mlp_destroy(p)
+    # the k-sliced shape needs an even number of k-steps: forced where it cannot run, the plan falls back
+    p = b.ogc_mlp_plan_with_overrides(b.OGC_I8, 300, [layer(64 * 3, 64)], 192, 64, 0, b.OGC_MODE_PER_LAYER, overrides={"tile": 5})
+    assert "dma" not in b.ogc_mlp_kernel_name(p, 0)
     b.ogc_mlp_destroy(p)
     # a forced split that does not divide the k-steps is ignored
     p = b.ogc_mlp_plan_with_overrides(b.OGC_I8, 300, [layer(64 * 4, 64)], 256, 64, 0, b.OGC_MODE_PER_LAYER,
