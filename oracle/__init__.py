@@ -11,6 +11,7 @@ from .oracle import (  # noqa: F401
     build,
     layer_bf16,
     layer_f32,
+    layer_f8,
     layer_i8,
     layer_i8_unfused,
     mlp,

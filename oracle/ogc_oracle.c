@@ -1,5 +1,5 @@
 /*
- * CPU oracle for the fused-MLP path (MatMul + bias + activation chains in fp32, bf16 and int8).
+ * CPU oracle for the fused-MLP path (MatMul + bias + activation chains in fp32, bf16, int8 and 8-bit float).
  *
  * THIS FILE IS TEST INFRASTRUCTURE.  It is the plain definition of what the GPU library must
  * compute, written to be checked against the paper by eye: a triple-loop GEMM, one layer at a
@@ -241,6 +241,94 @@ int oracle_layer_i8_unfused(int M, int K, int N, const uint8_t* Xq, int ldx, con
             if (r < 0.0) r = 0.0;
             if (r > 255.0) r = 255.0;
             Y[(size_t)m * ldy + n] = (uint8_t)r;
+        }
+    }
+    return 0;
+}
+
+/* ---- 8-bit floating point, the OCP "E4M3" encoding: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits;
+ * exponent field 0 holds the subnormals m/8 * 2^-6; there are no infinities; S.1111.111 is the only NaN, so the
+ * largest finite magnitude is S.1111.110 = 1.75 * 2^8 = 448.  (The paper has no 8-bit float path; this is the
+ * fp8 variant of its int8 scheme, with the encoding fixed by the matrix instructions of the target.) ---- */
+static double e4m3_to_f64(uint8_t b) {
+    int sign = b >> 7, e = (b >> 3) & 15, m = b & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m, -9);             /* m/8 * 2^-6 */
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+/* fp32 -> E4M3, round to nearest with ties to the even mantissa, saturating: every finite value (and +-inf) whose
+ * rounded magnitude would exceed 448 gives +-448; NaN gives the NaN code with the sign kept.  -0 keeps its sign. */
+static uint8_t f32_to_e4m3_rne_sat(float f) {
+    uint8_t sign = signbit(f) ? 0x80 : 0x00;
+    if (isnan(f)) return (uint8_t)(sign | 0x7f);
+    double a = fabs((double)f);
+    if (a >= 464.0) return (uint8_t)(sign | 0x7e);    /* 464 is the midpoint of 448 and the absent 480; the tie goes to 448 */
+    int ex;
+    (void)frexp(a, &ex);                              /* a = frac * 2^ex, frac in [0.5, 1) : floor(log2 a) = ex - 1 */
+    int e = (a == 0.0) ? -6 : ex - 1;
+    if (e < -6) e = -6;                               /* subnormal range: fixed step 2^-9 */
+    double step = ldexp(1.0, e - 3);                  /* spacing of representable values in [2^e, 2^(e+1)) */
+    double q = nearbyint(a / step);                   /* exact division by a power of two; ties to even */
+    double v = q * step;                              /* may be 2^(e+1): the next binade's first value */
+    /* encode v, which is representable */
+    if (v == 0.0) return sign;
+    if (v < ldexp(1.0, -6)) return (uint8_t)(sign | (uint8_t)(v / ldexp(1.0, -9)));
+    (void)frexp(v, &ex);
+    int ee = ex - 1;
+    int mant = (int)((v / ldexp(1.0, ee) - 1.0) * 8.0);
+    return (uint8_t)(sign | ((ee + 7) << 3) | mant);
+}
+
+float oracle_e4m3_to_f32(uint8_t b) { return (float)e4m3_to_f64(b); }
+uint8_t oracle_f32_to_e4m3(float f) { return f32_to_e4m3_rne_sat(f); }
+
+/*
+ * One fp8 layer: the int8 scheme of Section V carried over to E4M3 operands.  There is no zero point (the format
+ * is signed and symmetric), so the constant-weight preprocessing reduces to the scale product:
+ *   real x = a_s * x8,  real w[k,n] = b_s[n] * w8[k,n]
+ *   acc        = sum_k x8[m,k] * w8[k,n]      each product is exact (two 4-bit significands);
+ *                accum_double != 0: summed in fp64 (exact for any K the tests use) and rounded to fp32 once;
+ *                accum_double == 0: fp32 running sum, k ascending
+ *   s    (f32) = a_s * b_s[n]
+ *   y    (f32) = fmaf(acc, s, bias[n])   (no bias: y = acc*s)
+ *   y          = act(y)
+ *   out_f32 != 0:  Y[m,n] = y as fp32, stop
+ *   inv  (f32) = 1.0f / c_s ;  t = y * inv ;  Y[m,n] = E4M3(t), nearest-even, saturating at +-448
+ * readings: as for int8 (reciprocal multiply, fused dequantize+bias, fp32 bias, fp32 activation), plus saturation
+ * instead of NaN on overflow.  A NaN operand code propagates as the arithmetic propagates it.
+ */
+int oracle_layer_f8(int M, int K, int N, const uint8_t* X8, int ldx, const uint8_t* W8, const float* w_scale,
+                    const float* bias, float a_s, int act, int out_f32, float c_s, void* Yv, int ldy, int accum_double) {
+    if (M < 0 || K < 0 || N < 0 || !Yv || !w_scale || (M && K && N && (!X8 || !W8))) return -1;
+    const float inv = out_f32 ? 0.0f : 1.0f / c_s;
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) {
+            float f;
+            if (accum_double) {
+                double acc = 0.0;
+                for (int k = 0; k < K; ++k) acc += e4m3_to_f64(X8[(size_t)m * ldx + k]) * e4m3_to_f64(W8[(size_t)k * N + n]);
+                f = (float)acc;
+            } else {
+                float acc = 0.0f;
+                for (int k = 0; k < K; ++k) {
+                    float prod = (float)e4m3_to_f64(X8[(size_t)m * ldx + k]) * (float)e4m3_to_f64(W8[(size_t)k * N + n]);
+                    acc = acc + prod;
+                }
+                f = acc;
+            }
+            float s = a_s * w_scale[n];
+            float y = bias ? fmaf(f, s, bias[n]) : f * s;
+            y = act_f32(y, act);
+            if (out_f32) {
+                ((float*)Yv)[(size_t)m * ldy + n] = y;
+            } else {
+                float t = y * inv;
+                ((uint8_t*)Yv)[(size_t)m * ldy + n] = f32_to_e4m3_rne_sat(t);
+            }
         }
     }
     return 0;

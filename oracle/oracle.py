@@ -49,6 +49,13 @@ def _load():
         lib.oracle_layer_i8_unfused.argtypes = [c_int] * 3 + [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_float,
                                                               c_int, c_int, c_float, c_int, c_void_p, c_int]
         lib.oracle_layer_i8_unfused.restype = c_int
+        lib.oracle_layer_f8.argtypes = [c_int] * 3 + [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_float, c_int, c_int,
+                                                      c_float, c_void_p, c_int, c_int]
+        lib.oracle_layer_f8.restype = c_int
+        lib.oracle_e4m3_to_f32.argtypes = [ctypes.c_uint8]
+        lib.oracle_e4m3_to_f32.restype = c_float
+        lib.oracle_f32_to_e4m3.argtypes = [c_float]
+        lib.oracle_f32_to_e4m3.restype = ctypes.c_uint8
         lib.oracle_num_threads.restype = c_int
         lib.oracle_act_f64.argtypes = [ctypes.c_double, c_int]
         lib.oracle_act_f64.restype = ctypes.c_double
@@ -148,6 +155,32 @@ def layer_i8_unfused(xq, wq, w_scale, bias, a_s, a_z, act, c_s, c_z) -> np.ndarr
     return y
 
 
+def e4m3_to_f32(code: int) -> float:
+    """Value of one E4M3 code (NaN for 0x7f / 0xff)."""
+    return float(_load().oracle_e4m3_to_f32(int(code) & 0xFF))
+
+
+def f32_to_e4m3(value: float) -> int:
+    """fp32 -> E4M3 code, nearest-even, saturating at +-448."""
+    return int(_load().oracle_f32_to_e4m3(float(np.float32(value))))
+
+
+def layer_f8(x8, w8, w_scale, bias, a_s, act, c_s=1.0, out_f32=False, accum_double=True) -> np.ndarray:
+    """E4M3 activations x E4M3 per-channel-scaled weights -> E4M3 (requantized) or fp32 (out_f32)."""
+    x8, w8 = _c(x8, np.uint8), np.ascontiguousarray(_c(w8, np.uint8))
+    w_scale = np.ascontiguousarray(_c(w_scale, np.float32))
+    bias = None if bias is None else np.ascontiguousarray(_c(bias, np.float32))
+    m, k = x8.shape
+    k2, n = w8.shape
+    assert k == k2 and w_scale.shape == (n,) and (bias is None or bias.shape == (n,))
+    y = np.zeros((m, n), dtype=np.float32 if out_f32 else np.uint8)
+    rc = _load().oracle_layer_f8(m, k, n, _ptr(x8), _ld(x8), _ptr(w8), _ptr(w_scale), _ptr(bias), float(a_s), int(act),
+                                 int(bool(out_f32)), float(c_s), _ptr(y), n, int(bool(accum_double)))
+    if rc != 0:
+        raise RuntimeError("oracle fp8 layer failed: %d" % rc)
+    return y
+
+
 def mlp(wl, rows: Optional[slice] = None, accum_double: bool = False, keep: bool = False):
     """Run a whole chain described by a synthetic workload object (fields: dtype, layers, x, w,
     bias, w_scale, residual).  Returns the final output, or the list of every layer's output if
@@ -167,6 +200,10 @@ def mlp(wl, rows: Optional[slice] = None, accum_double: bool = False, keep: bool
             assert res is None
             cur = layer_i8(cur, wl.w[i], wl.w_scale[i], bias, ly.in_scale, ly.in_zp, ly.act, ly.out_scale, ly.out_zp,
                            ly.out_f32)
+        elif wl.dtype == "f8":
+            assert res is None
+            # the fp64 sum is exact, so it is the reference whichever order the hardware adds in
+            cur = layer_f8(cur, wl.w[i], wl.w_scale[i], bias, ly.in_scale, ly.act, ly.out_scale, ly.out_f32, accum_double=True)
         else:
             raise ValueError(wl.dtype)
         outs.append(cur)

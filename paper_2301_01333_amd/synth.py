@@ -50,7 +50,7 @@ class Layer:
 @dataclass
 class Workload:
     name: str
-    dtype: str              # "f32" | "bf16" | "i8"
+    dtype: str              # "f32" | "bf16" | "i8" | "f8" (E4M3 codes in uint8 arrays)
     m: int
     layers: List[Layer]
     residual: bool
@@ -71,7 +71,7 @@ class Workload:
 
     @property
     def elt(self) -> int:
-        return {"f32": 4, "bf16": 2, "i8": 1}[self.dtype]
+        return {"f32": 4, "bf16": 2, "i8": 1, "f8": 1}[self.dtype]
 
     @property
     def algorithmic_bytes(self) -> int:
@@ -81,10 +81,12 @@ class Workload:
         wbytes = sum(l.k * l.n for l in self.layers) * e
         if self.dtype == "i8":
             params = sum(l.n for l in self.layers) * 12  # scale, bias, compensation
+        elif self.dtype == "f8":
+            params = sum(l.n for l in self.layers) * 8   # scale, bias
         else:
             params = sum(l.n for l in self.layers if l.has_bias) * 4
         last = self.layers[-1]
-        out_e = 4 if (self.dtype == "i8" and last.out_f32) else e
+        out_e = 4 if (self.dtype in ("i8", "f8") and last.out_f32) else e
         return wbytes + params + self.m * self.layers[0].k * e + self.m * last.n * out_e
 
 
@@ -106,6 +108,35 @@ def int8_output_scales(dims: Sequence[int], a_s: float, a_z: int, c_z: int, ws_l
     return scales
 
 
+# The non-negative finite E4M3 values in code order (OCP 8-bit float: 4 exponent bits with bias 7, 3 mantissa bits,
+# subnormals at exponent field 0, largest finite value 448 = code 0x7E).  Used only to draw input codes.
+E4M3_VALUES = np.array([(m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+                        for e in range(16) for m in range(8)][:0x7F], dtype=np.float64)
+
+
+def e4m3_nearest_codes(a: np.ndarray) -> np.ndarray:
+    """Input drawing helper: the E4M3 code nearest to each value (values beyond +-448 take +-448; which neighbour an
+    exact midpoint takes is immaterial here, any code is a valid input)."""
+    a = np.asarray(a, dtype=np.float64)
+    mag = np.minimum(np.abs(a), 448.0)
+    hi = np.clip(np.searchsorted(E4M3_VALUES, mag), 1, len(E4M3_VALUES) - 1)
+    lo = hi - 1
+    code = np.where(mag - E4M3_VALUES[lo] <= E4M3_VALUES[hi] - mag, lo, hi).astype(np.uint8)
+    return (code | (np.signbit(a).astype(np.uint8) << 7)).astype(np.uint8)
+
+
+def f8_output_scales(dims: Sequence[int], acts: Sequence[int], x_var: float) -> List[float]:
+    """Closed-form static output scales for an E4M3 chain with weights of variance 1/K: the pre-activation of
+    layer l has variance E[x^2]; the scale maps 4 sigma onto the largest finite value 448.  After ReLU E[x^2]
+    halves; any other activation is taken to keep it."""
+    scales, e_x2 = [], x_var
+    for l in range(len(dims) - 1):
+        sigma = math.sqrt(e_x2)
+        scales.append(float(np.float32(4.0 * sigma / 448.0)))
+        e_x2 = e_x2 / 2.0 if acts[l] == ACT_RELU else e_x2
+    return scales
+
+
 def make_mlp(dtype: str, m: int, dims: Sequence[int], acts: Sequence[int], seed: int, *, has_bias: bool = True,
              residual: bool = False, name: str = "custom", x_scale: Optional[float] = None,
              w_std: Optional[Sequence[float]] = None, a_s: float = 0.05, a_z: int = 128, c_z: int = 128,
@@ -121,6 +152,10 @@ def make_mlp(dtype: str, m: int, dims: Sequence[int], acts: Sequence[int], seed:
     layers, ws, bs, wss = [], [], [], []
     if dtype == "i8":
         xfull = rng.integers(0, 256, size=(m, ldx), dtype=np.uint8)
+    elif dtype == "f8":
+        f8_in_scale = float(np.float32(4.0 / 448.0))   # N(0,1) inputs, 4 sigma on the largest code
+        xfull = e4m3_nearest_codes(rng.standard_normal((m, ldx)) / f8_in_scale)
+        f8_cs = f8_output_scales(dims, acts, 1.0)
     else:
         xf = rng.standard_normal((m, ldx)).astype(np.float32)
         if x_scale is not None:
@@ -132,6 +167,10 @@ def make_mlp(dtype: str, m: int, dims: Sequence[int], acts: Sequence[int], seed:
         k, n = dims[l], dims[l + 1]
         if dtype == "i8":
             w = rng.integers(wq_lo, 128, size=(k, n), dtype=np.int8)
+        elif dtype == "f8":
+            wf = rng.standard_normal((k, n)) / math.sqrt(k)
+            f8_ws = (np.abs(wf).max(axis=0) / 448.0).astype(np.float32)   # per output channel: its largest weight on 448
+            w = e4m3_nearest_codes(wf / f8_ws.astype(np.float64))
         else:
             std = (w_std[l] if w_std is not None else 1.0 / math.sqrt(k))
             wf = (rng.standard_normal((k, n)) * std).astype(np.float32)
@@ -142,6 +181,11 @@ def make_mlp(dtype: str, m: int, dims: Sequence[int], acts: Sequence[int], seed:
             f32_out = bool(last_f32 and l == nl - 1)
             ly = Layer(k, n, has_bias, acts[l], in_scale=(a_s if l == 0 else cs[l - 1]), in_zp=(a_z if l == 0 else c_z),
                        out_scale=(1.0 if f32_out else cs[l]), out_zp=(0 if f32_out else c_z), out_f32=f32_out)
+        elif dtype == "f8":
+            wsc = f8_ws
+            f32_out = bool(last_f32 and l == nl - 1)
+            ly = Layer(k, n, has_bias, acts[l], in_scale=(f8_in_scale if l == 0 else f8_cs[l - 1]), in_zp=0,
+                       out_scale=(1.0 if f32_out else f8_cs[l]), out_zp=0, out_f32=f32_out)
         else:
             wsc = None
             ly = Layer(k, n, has_bias, acts[l])
