@@ -46,14 +46,16 @@ typedef enum {
     OGC_ERR_TIMEOUT = -8        /* ogc_mlp_check / ogc_mlp_run_profiled: a barrier wait of the cooperative mode gave up */
 } ogc_status;
 
-typedef enum { OGC_F32 = 0, OGC_BF16 = 1, OGC_I8 = 2 } ogc_dtype; /* OGC_I8: u8 activations x s8 weights */
+typedef enum { OGC_F32 = 0, OGC_BF16 = 1, OGC_I8 = 2, OGC_F8 = 3 } ogc_dtype;
+/* OGC_I8: u8 activations x s8 weights.  OGC_F8: 8-bit floats in the OCP E4M3 encoding (1 sign, 4 exponent bits with bias 7,
+ * 3 mantissa bits, no infinities, S.1111.111 = NaN, largest finite value 448), activations and weights alike. */
 typedef enum { OGC_ACT_NONE = 0, OGC_ACT_RELU = 1, OGC_ACT_GELU_TANH = 2, OGC_ACT_SIGMOID = 3 } ogc_act;
 typedef enum { OGC_OUT_SAME = 0, OGC_OUT_F32 = 1 } ogc_out_kind;
 typedef enum { OGC_MODE_AUTO = 0, OGC_MODE_PER_LAYER = 1, OGC_MODE_FUSED = 2, OGC_MODE_COOP = 3 } ogc_mode;
 /* Layout of x / y at the boundary.  OGC_LAYOUT_BLOCKED is the library's operand layout (the blocked layout of
  * Section III, as propagated between the layers of a chain, Section V): with it one chain's y is the next
  * chain's x without the round trip through the plain layout.  A blocked tensor of m rows and c columns holds
- * round_up(m,256) rows of c padded to a multiple of 64 (u8) or 32 (bf16, fp32) elements, as
+ * round_up(m,256) rows of c padded to a multiple of 64 (u8, E4M3) or 32 (bf16, fp32) elements, as
  * [rows/32][row bytes/16][32 rows][16 bytes]; u8 values are stored with 128 subtracted.  Its size is ogc_mlp_blocked_bytes(); only a chain of this library should write it. */
 typedef enum { OGC_LAYOUT_PLAIN = 0, OGC_LAYOUT_BLOCKED = 1 } ogc_layout;
 
@@ -66,16 +68,27 @@ typedef enum { OGC_LAYOUT_PLAIN = 0, OGC_LAYOUT_BLOCKED = 1 } ogc_layout;
  *       y    = act(y)
  *       out == OGC_OUT_F32: store y as fp32 (last layer only);
  *       else q = clamp(rne(y * (1.0f/out_scale)) + out_zp, 0, 255) stored as u8.
- * For OGC_I8 the caller sets in_scale/in_zp of layer l+1 equal to out_scale/out_zp of layer l. */
+ *   OGC_F8 (the same scheme with E4M3 operands; the format is signed, so there is no zero point and no compensation;
+ *   not in the paper, whose low-precision type is int8):
+ *       acc  = sum_k x8*w8                     (exact products, added by the matrix unit: fp32 result, but the
+ *                                               products of one instruction are aligned to the largest and about
+ *                                               13 bits below it are kept)
+ *       y    = fma(acc, in_scale*w_scale[n], bias[n]) ; y = act(y)
+ *       out == OGC_OUT_F32: store y as fp32 (last layer only);
+ *       else the E4M3 code nearest to y * (1.0f/out_scale), ties to the even mantissa, saturating at +-448
+ *       (never NaN from overflow; a NaN value stays NaN).
+ *   acc therefore agrees with the exact sum to about 2^-12 of the largest product, not to fp32 rounding: a
+ *   requantized code differs from an exact-sum reference where that much moves the value across a rounding boundary.
+ * For OGC_I8 and OGC_F8 the caller sets in_scale (and in_zp) of layer l+1 equal to out_scale (out_zp) of layer l. */
 typedef struct {
     int32_t k, n;          /* > 0; k of layer l+1 must equal n of layer l; OGC_I8: k <= 65536 */
     int32_t has_bias;      /* 0 or 1; bias is fp32[n] for every dtype */
     int32_t act;           /* ogc_act */
-    float in_scale;        /* OGC_I8: a_s > 0, finite.  Ignored otherwise */
-    int32_t in_zp;         /* OGC_I8: a_z in [0,255] */
-    float out_scale;       /* OGC_I8 with OGC_OUT_SAME: c_s > 0, finite */
-    int32_t out_zp;        /* OGC_I8 with OGC_OUT_SAME: c_z in [0,255] */
-    int32_t out;           /* ogc_out_kind; OGC_OUT_F32 only for OGC_I8 and only on the last layer */
+    float in_scale;        /* OGC_I8, OGC_F8: a_s > 0, finite.  Ignored otherwise */
+    int32_t in_zp;         /* OGC_I8: a_z in [0,255]; OGC_F8: must be 0 */
+    float out_scale;       /* OGC_I8, OGC_F8 with OGC_OUT_SAME: c_s > 0, finite */
+    int32_t out_zp;        /* OGC_I8 with OGC_OUT_SAME: c_z in [0,255]; OGC_F8: must be 0 */
+    int32_t out;           /* ogc_out_kind; OGC_OUT_F32 only for OGC_I8 / OGC_F8 and only on the last layer */
 } ogc_layer_desc;
 
 typedef struct {
@@ -172,13 +185,13 @@ ogc_status ogc_mlp_buffer_assignment(ogc_mlp_plan_t plan, int32_t layer, int32_t
  *   w       host array of n_layers dev pointers: fp32 / bf16 / s8 weights, plain [k,n] row-major, contiguous
  *   bias    host array of n_layers dev pointers to fp32[n] (entry may be NULL where has_bias == 0);
  *           the array itself may be NULL if no layer has a bias
- *   w_scale OGC_I8: host array of n_layers dev pointers to fp32[n] (> 0); otherwise NULL
+ *   w_scale OGC_I8, OGC_F8: host array of n_layers dev pointers to fp32[n] (> 0); otherwise NULL
  *   packed  dev, ogc_mlp_packed_bytes() bytes, 256-byte aligned; fully overwritten */
 ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, const float* const* bias,
                                    const float* const* w_scale, void* packed, void* stream);
 
 /* Runs the chain: x[m, k0] (row stride ld_x) -> y[m, n_last] (row stride ld_y), both dev, plain row-major,
- * element type of the plan's dtype (u8 for OGC_I8; fp32 y if the last layer has OGC_OUT_F32).
+ * element type of the plan's dtype (u8 for OGC_I8, E4M3 bytes for OGC_F8; fp32 y if the last layer has OGC_OUT_F32).
  * (A blocked x or y, see ogc_layout, is a buffer of ogc_mlp_blocked_bytes() bytes instead.)
  * x and y must not overlap.  packed is the blob written by ogc_mlp_prepack_weights for this plan;
  * workspace is dev, 256-byte aligned, ogc_mlp_workspace_bytes() bytes (may be NULL when that is 0) and
@@ -199,6 +212,14 @@ ogc_status ogc_mlp_run_static(ogc_mlp_plan_t plan, const void* x, void* y, const
 
 /* The size in bytes of the static workspace behind ogc_mlp_run_static. */
 size_t ogc_mlp_static_workspace_limit(void);
+
+/* The quantize and dequantize nodes of the low-precision graph (Section V) for OGC_F8 tensors at the boundary of a
+ * chain: out[i] = E4M3(x[i] * (1.0f/scale)), nearest with ties to the even mantissa, saturating at +-448, NaN kept
+ * (exactly a layer's requantized output); and out[i] = value(x[i]) * scale.  x, out: device, n elements, contiguous;
+ * fp32 pointers 4-byte aligned (OGC_ERR_ALIGNMENT); scale > 0 and finite for quantize, finite for dequantize
+ * (OGC_ERR_INVALID_ARG).  n == 0 is a no-op.  Asynchronous on `stream`. */
+ogc_status ogc_quantize_e4m3(const float* x /*device*/, uint8_t* out /*device*/, size_t n, float scale, void* stream);
+ogc_status ogc_dequantize_e4m3(const uint8_t* x /*device*/, float* out /*device*/, size_t n, float scale, void* stream);
 
 /* Number of timed launch steps of one ogc_mlp_run: 1 for the fused-chain kernel, n_layers otherwise (a layer
  * whose reduction axis is split runs two kernels, the k ranges and the pass that adds them, and counts as one). */

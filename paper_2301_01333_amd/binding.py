@@ -10,14 +10,14 @@ import ctypes
 import os
 from typing import List, Optional, Sequence
 
-OGC_F32, OGC_BF16, OGC_I8 = 0, 1, 2
+OGC_F32, OGC_BF16, OGC_I8, OGC_F8 = 0, 1, 2, 3
 OGC_ACT_NONE, OGC_ACT_RELU, OGC_ACT_GELU_TANH, OGC_ACT_SIGMOID = 0, 1, 2, 3
 OGC_OUT_SAME, OGC_OUT_F32 = 0, 1
 OGC_MODE_AUTO, OGC_MODE_PER_LAYER, OGC_MODE_FUSED, OGC_MODE_COOP = 0, 1, 2, 3
 OGC_LAYOUT_PLAIN, OGC_LAYOUT_BLOCKED = 0, 1
 OGC_SOFTMAX_STABLE, OGC_SOFTMAX_FAST = 0, 1
 OGC_OK = 0
-DTYPES = {"f32": OGC_F32, "bf16": OGC_BF16, "i8": OGC_I8}
+DTYPES = {"f32": OGC_F32, "bf16": OGC_BF16, "i8": OGC_I8, "f8": OGC_F8}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libogc_mlp.so")
@@ -27,6 +27,7 @@ EXPORTS = [
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
     "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes", "ogc_mlp_estimated_us", "ogc_mlp_mode_estimates",
     "ogc_mlp_run_static", "ogc_mlp_static_workspace_limit", "ogc_mlp_plan_with_overrides", "ogc_mlp_check", "ogc_mlp_test_barrier", "ogc_mlp_cluster_layout",
+    "ogc_quantize_e4m3", "ogc_dequantize_e4m3",
     "ogc_mha_validate", "ogc_mha_run", "ogc_mha_kernel_name", "ogc_mha_i8_validate", "ogc_mha_run_i8", "ogc_mha_i8_kernel_name",
 ]
 OGC_ERR_TIMEOUT = -8
@@ -121,6 +122,10 @@ def lib():
         l.ogc_mlp_estimated_us.restype = i32
         l.ogc_mlp_mode_estimates.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
         l.ogc_mlp_mode_estimates.restype = i32
+        l.ogc_quantize_e4m3.argtypes = [vp, vp, sz, ctypes.c_float, vp]
+        l.ogc_quantize_e4m3.restype = i32
+        l.ogc_dequantize_e4m3.argtypes = [vp, vp, sz, ctypes.c_float, vp]
+        l.ogc_dequantize_e4m3.restype = i32
         l.ogc_mha_validate.argtypes = [ctypes.POINTER(ogc_mha_desc)]
         l.ogc_mha_validate.restype = i32
         l.ogc_mha_run.argtypes = [ctypes.POINTER(ogc_mha_desc), vp, vp, vp, vp, vp, vp]
@@ -255,6 +260,14 @@ def ogc_mlp_run(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, workspace_pt
 
 def ogc_mlp_run_static(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, stream: int = 0) -> None:
     _check(lib().ogc_mlp_run_static(plan, x_ptr, y_ptr, packed_ptr, stream), "ogc_mlp_run_static")
+
+
+def ogc_quantize_e4m3(x: int, out: int, n: int, scale: float, stream: int = 0) -> None:
+    _check(lib().ogc_quantize_e4m3(x, out, n, scale, stream), "ogc_quantize_e4m3")
+
+
+def ogc_dequantize_e4m3(x: int, out: int, n: int, scale: float, stream: int = 0) -> None:
+    _check(lib().ogc_dequantize_e4m3(x, out, n, scale, stream), "ogc_dequantize_e4m3")
 
 
 def ogc_mlp_static_workspace_limit() -> int:

@@ -134,7 +134,7 @@ const CostTable kCostF32 = {{{12.688f, 4.093f, 26.438f, 3.881f, 0.131f},
 
 // m rows x n channels, kt = 64-byte steps of the (padded) reduction axis.
 double estimate_layer_us(int dtype, int m, int n, int kt, int tile, int ks) {
-    const CostTable& ct = dtype == OGC_I8 ? kCostI8 : (dtype == OGC_BF16 ? kCostBf16 : kCostF32);
+    const CostTable& ct = (dtype == OGC_I8 || dtype == OGC_F8) ? kCostI8 : (dtype == OGC_BF16 ? kCostBf16 : kCostF32);
     const TileCost& tc = ct.t[tile];
     const OgcTileInfo ti = ogc_tile_info(tile);
     const double cus = 256.0;
@@ -195,6 +195,9 @@ void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int for
 // dtypes; 2-10 % rms).  A chain run layer by layer costs the sum of its layers' estimates less the event overhead
 // each of those carries from the way it was timed.
 constexpr double kProfiledLaunchExtraUs = 2.0;
+// The E4M3 path has no constants of its own: it moves the same bytes as int8 through the same kernels, and the chains
+// these models decide between are bound by weight streaming and launch latency, so it borrows the int8 constants.
+inline int model_dtype(int dtype) { return dtype == OGC_F8 ? OGC_I8 : dtype; }
 struct FusedCost { float f0, per_mb, per_layer, fill, per_block; };
 struct CoopCost { float c0, barrier, block, step, fill; };
 const FusedCost kFused[3] = {{4.706f, 30.663f, 1.174f, 0.225f, 0.0f}, {6.163f, 9.580f, 0.0f, 0.429f, 0.363f},
@@ -204,7 +207,7 @@ const CoopCost kCoop[3] = {{3.243f, 2.691f, 0.809f, 0.0321f, 0.821f}, {1.153f, 2
 
 // One workgroup per 32 rows streams every weight: flat in the batch up to 8192 rows (256 CUs), then in rounds.
 double estimate_fused_us(const ogc_mlp_plan_s* p) {
-    const FusedCost& c = kFused[p->desc.dtype];
+    const FusedCost& c = kFused[model_dtype(p->desc.dtype)];
     const double m = p->desc.m, rounds = std::max(1.0, m / 8192.0);
     double sum = 0.0;
     for (const LayerPlan& lp : p->layers) {
@@ -218,7 +221,7 @@ double estimate_fused_us(const ogc_mlp_plan_s* p) {
 
 // Every CU takes 32x32 blocks of the current layer, a device-wide barrier between layers.
 double estimate_coop_us(const ogc_mlp_plan_s* p) {
-    const CoopCost& c = kCoop[p->desc.dtype];
+    const CoopCost& c = kCoop[model_dtype(p->desc.dtype)];
     const double mb = (p->desc.m + 31) / 32;
     double most = 0.0;
     for (const LayerPlan& lp : p->layers) most = std::max(most, mb * ((lp.d.n + 31) / 32));
@@ -243,7 +246,7 @@ const ClusterCost kCluster[3] = {{0.0f, 15.37f, 0.4852f, 2.127f, 1.000f, 11.72f,
 
 // One layer of the cluster kernel: the busiest member's weight stream, and the exchange if the layer is split.
 double cluster_layer_us(const ogc_mlp_plan_s* p, int l, int split, bool whole) {
-    const ClusterCost& c = kCluster[p->desc.dtype];
+    const ClusterCost& c = kCluster[model_dtype(p->desc.dtype)];
     const int L = (int)p->layers.size(), waves = 8 * (whole ? 1 : split);
     const LayerPlan& lp = p->layers[l];
     const bool last = l == L - 1;
@@ -270,7 +273,7 @@ uint32_t cluster_whole_layers(const ogc_mlp_plan_s* p, int split) {
 }
 
 double estimate_cluster_us(const ogc_mlp_plan_s* p, int split) {
-    const ClusterCost& c = kCluster[p->desc.dtype];
+    const ClusterCost& c = kCluster[model_dtype(p->desc.dtype)];
     const int L = (int)p->layers.size();
     const double tiles = (p->desc.m + 31) / 32;
     const uint32_t whole = cluster_whole_layers(p, split);
@@ -294,7 +297,7 @@ const KsplitCost kKsplit[3] = {{4.405f, 1.028f, 0.3281f, 1.861f, 17.28f, 0.0529f
                                {4.530f, 1.151f, 0.1613f, 1.583f, 12.22f, 0.0737f, 0.0132f},
                                {3.661f, 1.266f, 0.1496f, 1.823f, 13.51f, 0.0859f, 0.0067f}};
 double estimate_cluster_ksplit_us(const ogc_mlp_plan_s* p, int split) {
-    const KsplitCost& c = kKsplit[p->desc.dtype];
+    const KsplitCost& c = kKsplit[model_dtype(p->desc.dtype)];
     const int L = (int)p->layers.size();
     const double tiles = (p->desc.m + 31) / 32;
     double t = c.c0, all_mb = 0.0;
@@ -343,7 +346,8 @@ void assign_cluster_buffers(ogc_mlp_plan_s* p) {
 
 ogc_status validate(const ogc_mlp_desc* d) {
     if (!d || !d->layers) return OGC_ERR_INVALID_ARG;
-    if (d->dtype != OGC_F32 && d->dtype != OGC_BF16 && d->dtype != OGC_I8) return OGC_ERR_INVALID_ARG;
+    if (d->dtype != OGC_F32 && d->dtype != OGC_BF16 && d->dtype != OGC_I8 && d->dtype != OGC_F8) return OGC_ERR_INVALID_ARG;
+    const bool quant = d->dtype == OGC_I8 || d->dtype == OGC_F8;
     if (d->mode != OGC_MODE_AUTO && d->mode != OGC_MODE_PER_LAYER && d->mode != OGC_MODE_FUSED && d->mode != OGC_MODE_COOP)
         return OGC_ERR_INVALID_ARG;
     if (d->n_layers < 1 || d->n_layers > OGC_MAX_LAYERS) return OGC_ERR_SHAPE;
@@ -363,7 +367,7 @@ ogc_status validate(const ogc_mlp_desc* d) {
         if (y.has_bias != 0 && y.has_bias != 1) return OGC_ERR_INVALID_ARG;
         if (y.act < OGC_ACT_NONE || y.act > OGC_ACT_SIGMOID) return OGC_ERR_INVALID_ARG;
         if (y.out != OGC_OUT_SAME && y.out != OGC_OUT_F32) return OGC_ERR_INVALID_ARG;
-        if (y.out == OGC_OUT_F32 && (d->dtype != OGC_I8 || l != d->n_layers - 1)) return OGC_ERR_INVALID_ARG;
+        if (y.out == OGC_OUT_F32 && (!quant || l != d->n_layers - 1)) return OGC_ERR_INVALID_ARG;
         if (y.out == OGC_OUT_F32 && d->y_layout == OGC_LAYOUT_BLOCKED) return OGC_ERR_INVALID_ARG;
         if (d->dtype == OGC_I8) {
             if (y.k > 65536) return OGC_ERR_SHAPE;
@@ -374,12 +378,16 @@ ogc_status validate(const ogc_mlp_desc* d) {
                 if (y.out_zp < 0 || y.out_zp > 255) return OGC_ERR_INVALID_ARG;
             }
         }
+        if (d->dtype == OGC_F8) {  // a signed format: scales only, the zero-point fields must be left at 0
+            if (!(y.in_scale > 0.0f) || !std::isfinite(y.in_scale) || y.in_zp != 0) return OGC_ERR_INVALID_ARG;
+            if (y.out == OGC_OUT_SAME && (!(y.out_scale > 0.0f) || !std::isfinite(y.out_scale) || y.out_zp != 0)) return OGC_ERR_INVALID_ARG;
+        }
     }
     const int k0 = d->layers[0].k, nl = d->layers[d->n_layers - 1].n;
     if (d->x_layout == OGC_LAYOUT_PLAIN && d->ld_x < k0) return OGC_ERR_SHAPE;
     if (d->y_layout == OGC_LAYOUT_PLAIN && d->ld_y < nl) return OGC_ERR_SHAPE;
     if (d->residual) {
-        if (d->dtype == OGC_I8) return OGC_ERR_INVALID_ARG;
+        if (quant) return OGC_ERR_INVALID_ARG;
         if (nl != k0) return OGC_ERR_SHAPE;
     }
     return OGC_OK;
@@ -445,7 +453,8 @@ ogc_status ogc_mlp_plan_with_overrides(const ogc_mlp_desc* desc, const ogc_plan_
     const int L = desc->n_layers;
     const int esz = desc->dtype == OGC_F32 ? 4 : (desc->dtype == OGC_BF16 ? 2 : 1);
     p->esz = esz;
-    const int kgran = desc->dtype == OGC_I8 ? 64 : 32;  // padded K granularity in elements (>= 64 bytes)
+    const bool quant = desc->dtype == OGC_I8 || desc->dtype == OGC_F8;
+    const int kgran = quant ? 64 : 32;  // padded K granularity in elements (>= 64 bytes)
     p->layers.resize(L);
     int max_kc = 0;
     for (int l = 0; l < L; ++l) {
@@ -454,7 +463,7 @@ ogc_status ogc_mlp_plan_with_overrides(const ogc_mlp_desc* desc, const ogc_plan_
         lp.kp = (int)round_up((size_t)lp.d.k, kgran);
         lp.kc = lp.kp * esz / 16;
         if (lp.kc > max_kc) max_kc = lp.kc;
-        lp.inv_cs = (desc->dtype == OGC_I8 && lp.d.out == OGC_OUT_SAME) ? 1.0f / lp.d.out_scale : 0.0f;
+        lp.inv_cs = (quant && lp.d.out == OGC_OUT_SAME) ? 1.0f / lp.d.out_scale : 0.0f;
     }
     for (int l = 0; l < L; ++l) {
         LayerPlan& lp = p->layers[l];
@@ -490,7 +499,7 @@ ogc_status ogc_mlp_plan_with_overrides(const ogc_mlp_desc* desc, const ogc_plan_
         LayerPlan& lp = p->layers[l];
         const int rows = lp.nb_out * 32 > lp.d.n ? lp.nb_out * 32 : lp.d.n;
         // the stream kernel keeps its accumulators in fixed registers: no out-of-line calls (sigmoid) in it
-        const bool dma_ok = desc->dtype != OGC_F32 && lp.d.act != OGC_ACT_SIGMOID &&
+        const bool dma_ok = desc->dtype != OGC_F32 && desc->dtype != OGC_F8 && lp.d.act != OGC_ACT_SIGMOID &&
                             !(desc->dtype == OGC_I8 && lp.d.in_zp != 128) &&
                             (l > 0 || desc->x_layout == OGC_LAYOUT_BLOCKED ||
                              (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));
@@ -500,7 +509,7 @@ ogc_status ogc_mlp_plan_with_overrides(const ogc_mlp_desc* desc, const ogc_plan_
         per_us += lp.est_us - kProfiledLaunchExtraUs;
     }
     p->mode_us[0] = per_timed ? per_us : -1.0;
-    p->mode_us[1] = (fused_fits && (desc->dtype == OGC_I8 || wbytes <= (size_t)2600000)) ? estimate_fused_us(p) : -1.0;
+    p->mode_us[1] = (fused_fits && (quant || wbytes <= (size_t)2600000)) ? estimate_fused_us(p) : -1.0;
     p->mode_us[2] = (!blocked_io && L > 1) ? estimate_coop_us(p) : -1.0;
     // The cooperative mode has two kernels: blocks dealt to all workgroups (above), or a few workgroups per row tile
     // (the cluster kernel).  The split with the lowest estimate competes; the cluster_split override forces one (0: never).
@@ -667,7 +676,7 @@ ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, co
     if (!plan || !w || !packed) return OGC_ERR_INVALID_ARG;
     if (((uintptr_t)packed & 255) != 0) return OGC_ERR_ALIGNMENT;
     const int L = (int)plan->layers.size();
-    const bool i8 = plan->desc.dtype == OGC_I8;
+    const bool i8 = plan->desc.dtype == OGC_I8 || plan->desc.dtype == OGC_F8;  // the quantized scheme: per-channel weight scales
     if (i8 && !w_scale) return OGC_ERR_INVALID_ARG;
     for (int l = 0; l < L; ++l) {
         if (!w[l]) return OGC_ERR_INVALID_ARG;
@@ -815,6 +824,18 @@ ogc_status ogc_mlp_run_static(ogc_mlp_plan_t plan, const void* x, void* y, const
 }
 
 size_t ogc_mlp_static_workspace_limit(void) { return (size_t)OGC_STATIC_SCRATCH_BYTES; }
+
+ogc_status ogc_quantize_e4m3(const float* x, uint8_t* out, size_t n, float scale, void* stream) {
+    if ((n && (!x || !out)) || !(scale > 0.0f) || !std::isfinite(scale)) return OGC_ERR_INVALID_ARG;
+    if (((uintptr_t)x & 3) != 0) return OGC_ERR_ALIGNMENT;
+    return ogc_launch_quantize_e4m3(x, out, n, 1.0f / scale, stream) == 0 ? OGC_OK : OGC_ERR_DEVICE;
+}
+
+ogc_status ogc_dequantize_e4m3(const uint8_t* x, float* out, size_t n, float scale, void* stream) {
+    if ((n && (!x || !out)) || !std::isfinite(scale)) return OGC_ERR_INVALID_ARG;
+    if (((uintptr_t)out & 3) != 0) return OGC_ERR_ALIGNMENT;
+    return ogc_launch_dequantize_e4m3(x, out, n, scale, stream) == 0 ? OGC_OK : OGC_ERR_DEVICE;
+}
 
 ogc_status ogc_mlp_num_launches(ogc_mlp_plan_t plan, int32_t* n) {
     if (!plan || !n) return OGC_ERR_INVALID_ARG;

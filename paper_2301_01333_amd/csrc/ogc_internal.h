@@ -109,6 +109,8 @@ const char* ogc_cluster_kernel_name(int dtype, int ksplit);
 int ogc_launch_prepack_weights(const void* w, void* out, int K, int N, int KC, int NPw, int esz, void* stream);
 int ogc_launch_prepack_params(int dtype, const void* w, const float* w_scale, const float* bias, float in_scale, int in_zp,
                               int K, int N, int NPw, float* scale_out, float* bias_out, int32_t* ncomp_out, void* stream);
+int ogc_launch_quantize_e4m3(const float* x, uint8_t* out, size_t n, float inv_scale, void* stream);
+int ogc_launch_dequantize_e4m3(const uint8_t* x, float* out, size_t n, float scale, void* stream);
 const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, int out_plain, int act, int out_f32, int split);
 const char* ogc_fused_kernel_name(int dtype);
 size_t ogc_fused_lds_limit(void);

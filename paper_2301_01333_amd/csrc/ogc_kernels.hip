@@ -22,6 +22,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef long v2l __attribute__((ext_vector_type(2)));
 
 #define OGC_DEV static __device__ __forceinline__
 
@@ -29,6 +30,17 @@ template <int DT> struct AccT { typedef v16f type; };
 template <> struct AccT<OGC_I8> { typedef v16i type; };
 
 template <int DT> struct Elt { enum { size = DT == OGC_F32 ? 4 : (DT == OGC_BF16 ? 2 : 1) }; };
+// dtypes that follow the quantized scheme of Section V: one-byte operands, a combined per-channel scale, a
+// requantized or fp32 result
+template <int DT> struct Quant { enum { yes = DT == OGC_I8 || DT == OGC_F8 }; };
+
+// Four fp32 -> four packed E4M3 bytes (v_cvt_pk_fp8_f32: nearest even), saturating at +-448; a NaN stays a NaN.
+OGC_DEV float e4m3_clamp(float t) { return t != t ? t : __builtin_amdgcn_fmed3f(t, -448.0f, 448.0f); }
+OGC_DEV uint32_t f32x4_to_e4m3x4(float a, float b, float c, float d) {
+    int r = __builtin_amdgcn_cvt_pk_fp8_f32(e4m3_clamp(a), e4m3_clamp(b), 0, false);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(e4m3_clamp(c), e4m3_clamp(d), r, true);
+    return (uint32_t)r;
+}
 
 // One 32(n) x 32(m) x 32-byte-of-K MFMA step (GEMM main loop; the role of the batch-reduce GEMM
 // microkernel of Section III).  w and x are the lane's 16 bytes of the two operands.
@@ -37,6 +49,12 @@ template <int DT> OGC_DEV void mma32(typename AccT<DT>::type& c, const v4i& w, c
         c = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, c, 0, 0, 0);
     } else if constexpr (DT == OGC_BF16) {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, w), __builtin_bit_cast(v8bf, x), c, 0, 0, 0);
+    } else if constexpr (DT == OGC_F8) {
+        // two 8-byte halves of the lane's 16 bytes: which k a byte stands for is the same in both operands, and that
+        // is all a dot product needs
+        const v2l wl = __builtin_bit_cast(v2l, w), xl = __builtin_bit_cast(v2l, x);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(wl.x, xl.x, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(wl.y, xl.y, c, 0, 0, 0);
     } else {
         const v4f wf = __builtin_bit_cast(v4f, w), xf = __builtin_bit_cast(v4f, x);
         c = __builtin_amdgcn_mfma_f32_32x32x2f32(wf.x, xf.x, c, 0, 0, 0);
@@ -111,8 +129,8 @@ OGC_DEV void load_block_params(BlockParams& p, const OgcLayerArgs& a, int n0, in
         p.b[g] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
         p.c[g] = (v4i){0, 0, 0, 0};
         if (a.has_bias) p.b[g] = *(const v4f*)(a.bias + n);
+        if constexpr (Quant<DT>::yes) p.s[g] = *(const v4f*)(a.scale + n);
         if constexpr (DT == OGC_I8) {
-            p.s[g] = *(const v4f*)(a.scale + n);
             if (a.has_comp) p.c[g] = *(const v4i*)(a.ncomp + n);
         }
     }
@@ -128,12 +146,22 @@ OGC_DEV void epilogue_values(const typename AccT<DT>::type& acc, const OgcLayerA
                 const float f = (float)(acc[4 * g + e] + p.c[g][e]);
                 out[4 * g + e] = __builtin_fmaf(f, p.s[g][e], p.b[g][e]);
             }
+        } else if constexpr (DT == OGC_F8) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[4 * g + e] = __builtin_fmaf(acc[4 * g + e], p.s[g][e], p.b[g][e]);
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) out[4 * g + e] = acc[4 * g + e] + p.b[g][e];
         }
     }
     act_apply16<CALLS>(out, a.act);
+    if constexpr (DT == OGC_F8) {
+        if (!a.out_f32) {  // the value the E4M3 conversion in pack_block rounds
+            const float inv = a.inv_cs;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) out[i] = out[i] * inv;
+        }
+    }
     if constexpr (DT == OGC_I8) {
         if (!a.out_f32) {
             const float inv = a.inv_cs, zp = a.zp_out;
@@ -168,12 +196,15 @@ OGC_DEV void store16(GlobalY g, const v4i& v) { store16_through(g.p, v); }
 // each lane holds 16 CONSECUTIVE channels (n0 + 16*(lane/32) ...), and returns them as NDW 16-byte chunks.
 //   EO = bytes per stored element (1: u8/s8, 2: bf16, 4: fp32); NDW == EO.
 //   bias_s8: store u8 values with 128 subtracted (internal activation form).
-template <int EO>
+//   F8: EO == 1 and the bytes are E4M3 codes of the values (rounded here) instead of integers already rounded.
+template <int EO, bool F8 = false>
 OGC_DEV void pack_block(const float (&out)[16], bool bias_s8, v4i (&chunk)[EO]) {
     uint32_t dw[4][EO];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        if constexpr (EO == 1) {
+        if constexpr (EO == 1 && F8) {
+            dw[g][0] = f32x4_to_e4m3x4(out[4 * g], out[4 * g + 1], out[4 * g + 2], out[4 * g + 3]);
+        } else if constexpr (EO == 1) {
             uint32_t p = (uint32_t)out[4 * g] | ((uint32_t)out[4 * g + 1] << 8) | ((uint32_t)out[4 * g + 2] << 16) |
                          ((uint32_t)out[4 * g + 3] << 24);
             dw[g][0] = bias_s8 ? (p ^ 0x80808080u) : p;
@@ -347,21 +378,21 @@ OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerAr
     epilogue_values<DT, CALLS>(acc, a, p, out);
     constexpr int E = Elt<DT>::size;
     if constexpr (OUT_PLAIN) {
-        if constexpr (DT != OGC_I8) {
+        if constexpr (!Quant<DT>::yes) {
             if (a.res) add_residual<DT>(out, a, m0 + mm, n0, h);
         }
-        if (DT == OGC_I8 && a.out_f32) {
+        if (Quant<DT>::yes && a.out_f32) {
             v4i ch[4];
             pack_block<4>(out, false, ch);
             store_plain<4>(ch, a, m0 + mm, n0 + 16 * h);
         } else {
             v4i ch[E];
-            pack_block<E>(out, false, ch);
+            pack_block<E, DT == OGC_F8>(out, false, ch);
             store_plain<E>(ch, a, m0 + mm, n0 + 16 * h);
         }
     } else {
         v4i ch[E];
-        pack_block<E>(out, DT == OGC_I8, ch);
+        pack_block<E, DT == OGC_F8>(out, DT == OGC_I8, ch);
         const int c0 = ((n0 >> 5) * 2 + h) * E;
 #pragma unroll
         for (int c = 0; c < E; ++c) store16(yblk + ((size_t)(c0 + c) * 32 + mm) * 16, ch[c]);
@@ -699,8 +730,41 @@ ogc_prepack_params_kernel(int dtype, const int8_t* __restrict__ wq, const float*
 #pragma unroll
         for (int s2 = 0; s2 < OGC_PARAMS_SLICES; ++s2) total += part[s2][col];
         ncomp_out[n] = -(in_zp - 128) * total;
-        scale_out[n] = valid ? in_scale * w_scale[n] : 0.0f;
     }
+    if (dtype == OGC_I8 || dtype == OGC_F8) scale_out[n] = valid ? in_scale * w_scale[n] : 0.0f;
+}
+
+// Quantize / dequantize nodes of the low-precision graph (Section V) for E4M3 tensors at the boundary: elementwise,
+// four elements per thread, the same reciprocal multiply, rounding and saturation as a layer's requantized output.
+__global__ void ogc_quantize_e4m3_kernel(const float* __restrict__ x, uint8_t* __restrict__ out, size_t n, float inv_scale) {
+    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= n) return;
+    float v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = i + j < n ? x[i + j] * inv_scale : 0.0f;
+    const uint32_t q = f32x4_to_e4m3x4(v[0], v[1], v[2], v[3]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (i + j < n) out[i + j] = (uint8_t)(q >> (8 * j));
+}
+__global__ void ogc_dequantize_e4m3_kernel(const uint8_t* __restrict__ x, float* __restrict__ out, size_t n, float scale) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    out[i] = __builtin_amdgcn_cvt_f32_fp8((int)x[i], 0) * scale;
+}
+extern "C" int ogc_launch_quantize_e4m3(const float* x, uint8_t* out, size_t n, float inv_scale, void* stream) {
+    const size_t threads = (n + 3) / 4, blocks = (threads + 255) / 256;
+    if (blocks == 0) return 0;
+    if (blocks > 0x7fffffffu) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(ogc_quantize_e4m3_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, x, out, n, inv_scale);
+    return (int)hipGetLastError();
+}
+extern "C" int ogc_launch_dequantize_e4m3(const uint8_t* x, float* out, size_t n, float scale, void* stream) {
+    const size_t blocks = (n + 255) / 256;
+    if (blocks == 0) return 0;
+    if (blocks > 0x7fffffffu) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(ogc_dequantize_e4m3_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, x, out, n, scale);
+    return (int)hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1290,6 +1354,7 @@ extern "C" int ogc_launch_layer(int dtype, int tile, int x_plain, int out_plain,
     switch (dtype) {
     case OGC_F32: return launch_layer_tile<OGC_F32>(tile, x_plain, out_plain, a, s);
     case OGC_BF16: return launch_layer_tile<OGC_BF16>(tile, x_plain, out_plain, a, s);
+    case OGC_F8: return launch_layer_tile<OGC_F8>(tile, x_plain, out_plain, a, s);
     default: return launch_layer_tile<OGC_I8>(tile, x_plain, out_plain, a, s);
     }
 }
@@ -1328,6 +1393,7 @@ extern "C" int ogc_launch_fused(int dtype, const OgcChainArgs* c, int m_blocks, 
     switch (dtype) {
     case OGC_F32: return launch_fused_t<OGC_F32>(c, m_blocks, s);
     case OGC_BF16: return launch_fused_t<OGC_BF16>(c, m_blocks, s);
+    case OGC_F8: return launch_fused_t<OGC_F8>(c, m_blocks, s);
     default: return launch_fused_t<OGC_I8>(c, m_blocks, s);
     }
 }
@@ -1343,6 +1409,7 @@ extern "C" int ogc_launch_coop(int dtype, const OgcChainArgs* c, int m_blocks, i
     switch (dtype) {
     case OGC_F32: return launch_coop_t<OGC_F32>(c, m_blocks, grid, sync, s);
     case OGC_BF16: return launch_coop_t<OGC_BF16>(c, m_blocks, grid, sync, s);
+    case OGC_F8: return launch_coop_t<OGC_F8>(c, m_blocks, grid, sync, s);
     default: return launch_coop_t<OGC_I8>(c, m_blocks, grid, sync, s);
     }
 }
@@ -1410,12 +1477,14 @@ extern "C" int ogc_launch_cluster(int dtype, int ksplit, const OgcChainArgs* c, 
         switch (dtype) {
         case OGC_F32: return launch_cluster_t<OGC_F32, 1>(c, m_blocks, split, spread, cus, sync, s);
         case OGC_BF16: return launch_cluster_t<OGC_BF16, 1>(c, m_blocks, split, spread, cus, sync, s);
+        case OGC_F8: return launch_cluster_t<OGC_F8, 1>(c, m_blocks, split, spread, cus, sync, s);
         default: return launch_cluster_t<OGC_I8, 1>(c, m_blocks, split, spread, cus, sync, s);
         }
     }
     switch (dtype) {
     case OGC_F32: return launch_cluster_t<OGC_F32, 0>(c, m_blocks, split, spread, cus, sync, s);
     case OGC_BF16: return launch_cluster_t<OGC_BF16, 0>(c, m_blocks, split, spread, cus, sync, s);
+    case OGC_F8: return launch_cluster_t<OGC_F8, 0>(c, m_blocks, split, spread, cus, sync, s);
     default: return launch_cluster_t<OGC_I8, 0>(c, m_blocks, split, spread, cus, sync, s);
     }
 }
@@ -1455,14 +1524,17 @@ extern "C" int ogc_device_cu_count(void) {
     return n;
 }
 
+static const char* chain_kernel_name(const char* const (&names)[4], int dtype) { return (dtype >= 0 && dtype < 4) ? names[dtype] : "?"; }
 extern "C" const char* ogc_coop_kernel_name(int dtype) {
-    return dtype == OGC_F32 ? "ogc_coop_chain_kernel<0>" : dtype == OGC_BF16 ? "ogc_coop_chain_kernel<1>" : "ogc_coop_chain_kernel<2>";
+    static const char* const names[4] = {"ogc_coop_chain_kernel<0>", "ogc_coop_chain_kernel<1>", "ogc_coop_chain_kernel<2>", "ogc_coop_chain_kernel<3>"};
+    return chain_kernel_name(names, dtype);
 }
 extern "C" const char* ogc_cluster_kernel_name(int dtype, int ksplit) {
-    if (ksplit)
-        return dtype == OGC_F32 ? "ogc_cluster_ksplit_chain_kernel<0>"
-                                : dtype == OGC_BF16 ? "ogc_cluster_ksplit_chain_kernel<1>" : "ogc_cluster_ksplit_chain_kernel<2>";
-    return dtype == OGC_F32 ? "ogc_cluster_chain_kernel<0>" : dtype == OGC_BF16 ? "ogc_cluster_chain_kernel<1>" : "ogc_cluster_chain_kernel<2>";
+    static const char* const ks[4] = {"ogc_cluster_ksplit_chain_kernel<0>", "ogc_cluster_ksplit_chain_kernel<1>",
+                                      "ogc_cluster_ksplit_chain_kernel<2>", "ogc_cluster_ksplit_chain_kernel<3>"};
+    static const char* const plain[4] = {"ogc_cluster_chain_kernel<0>", "ogc_cluster_chain_kernel<1>", "ogc_cluster_chain_kernel<2>",
+                                         "ogc_cluster_chain_kernel<3>"};
+    return ksplit ? chain_kernel_name(ks, dtype) : chain_kernel_name(plain, dtype);
 }
 
 extern "C" int ogc_launch_prepack_weights(const void* w, void* out, int K, int N, int KC, int NPw, int esz, void* stream) {
@@ -1484,8 +1556,8 @@ extern "C" int ogc_launch_prepack_params(int dtype, const void* w, const float* 
 
 // Kernel names with their template arguments, spelled the way a kernel trace prints them.
 extern "C" const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, int out_plain, int act, int out_f32, int split) {
-    static char names[3][OGC_NUM_TILES][2][2][3][48];
-    if (dtype < 0 || dtype > 2 || tile < 0 || tile >= OGC_NUM_TILES) return "?";
+    static char names[4][OGC_NUM_TILES][2][2][3][48];
+    if (dtype < 0 || dtype > 3 || tile < 0 || tile >= OGC_NUM_TILES) return "?";
     const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8 || tile == OGC_TILE_DMAK2;
     const int epi = (stream && split) ? 2 : (stream && dtype == OGC_I8 && act == OGC_ACT_RELU && !out_f32);
     if (epi == 2) out_plain = 0;
@@ -1502,5 +1574,6 @@ extern "C" const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, i
     return n;
 }
 extern "C" const char* ogc_fused_kernel_name(int dtype) {
-    return dtype == OGC_F32 ? "ogc_fused_chain_kernel<0>" : dtype == OGC_BF16 ? "ogc_fused_chain_kernel<1>" : "ogc_fused_chain_kernel<2>";
+    static const char* const names[4] = {"ogc_fused_chain_kernel<0>", "ogc_fused_chain_kernel<1>", "ogc_fused_chain_kernel<2>", "ogc_fused_chain_kernel<3>"};
+    return chain_kernel_name(names, dtype);
 }

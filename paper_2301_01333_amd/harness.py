@@ -28,12 +28,13 @@ class DeviceMLP:
             xb = np.ascontiguousarray(wl.x)
         self.ld_x = xb.shape[1]
         last = wl.layers[-1]
-        self.out_np_dtype = np.float32 if (wl.dtype == "i8" and last.out_f32) else {"f32": np.float32, "bf16": np.uint16, "i8": np.uint8}[wl.dtype]
+        self.out_np_dtype = (np.float32 if (wl.dtype in ("i8", "f8") and last.out_f32)
+                             else {"f32": np.float32, "bf16": np.uint16, "i8": np.uint8, "f8": np.uint8}[wl.dtype])
         self.ld_y = ld_y or last.n
         self.mlp = binding.FusedMLP(wl.dtype, wl.m, wl.layers, self.ld_x, self.ld_y, wl.residual, mode, overrides=overrides)
         self.w = [_to_device(torch, w) for w in wl.w]
         self.bias = [None if b is None else _to_device(torch, b) for b in wl.bias]
-        self.w_scale = None if wl.dtype != "i8" else [_to_device(torch, s) for s in wl.w_scale]
+        self.w_scale = None if wl.dtype not in ("i8", "f8") else [_to_device(torch, s) for s in wl.w_scale]
         self.mlp.prepack(self.w, self.bias, self.w_scale)
         xbytes = np.ascontiguousarray(xb).view(np.uint8).reshape(-1)
         if x_byte_offset:
