@@ -26,8 +26,10 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSV = os.path.join(HERE, "data", "layer_times.csv")
 INC = os.path.join(os.path.dirname(HERE), "csrc", "ogc_cost_layers.inc")
-GEO = {1: (128, 128), 2: (32, 64), 3: (256, 128), 4: (256, 256), 5: (128, 128)}   # tile id -> (rows, channels)
-TILES = (1, 2, 3, 4, 5)
+GEO = {0: (256, 256), 1: (128, 128), 2: (32, 64), 3: (256, 128), 4: (256, 256), 5: (128, 128)}   # tile id -> (rows, channels)
+TILES = (1, 2, 3, 4, 5)          # candidates of int8 and bf16 layers
+TILES_F32 = (0, 1, 2)            # fp32 runs on the register-staged tiles only, never split
+NUM_TILES = 6
 NEAR_BEST_WEIGHT = 2.0
 
 
@@ -35,16 +37,16 @@ def read_rows(path: str = CSV):
     out = []
     with open(path) as f:
         for r in csv.DictReader(f):
-            esz = 1 if r["dtype"] == "i8" else 2
+            esz = {"i8": 1, "bf16": 2, "f32": 4}[r["dtype"]]
             out.append(dict(dtype=r["dtype"], m=int(r["m"]), k=int(r["k"]), n=int(r["n"]), tile=int(r["tile"]), ks=int(r["ks"]),
                             us=float(r["us"]), kt=(int(r["k"]) * esz + 63) // 64))
     return out
 
 
-def model(p, r) -> float:
-    i = TILES.index(r["tile"])
+def model(p, r, tiles_of=TILES) -> float:
+    i = tiles_of.index(r["tile"])
     c, d, a, b, g = p[5 * i:5 * i + 5]
-    r0, r1, r2, px, l0 = p[5 * len(TILES):5 * len(TILES) + 5]
+    r0, r1, r2, px, l0 = p[5 * len(tiles_of):5 * len(tiles_of) + 5]
     bm, bn = GEO[r["tile"]]
     tiles = math.ceil(r["m"] / bm) * math.ceil(r["n"] / bn)
     w, k = tiles << r["ks"], r["kt"] >> r["ks"]
@@ -61,7 +63,8 @@ def fit(rows, dtype: str):
     """Returns (parameter vector, rms log error, geometric-mean loss of the model's pick against the fastest measured)."""
     from scipy.optimize import least_squares
 
-    rs = [r for r in rows if r["dtype"] == dtype]
+    tiles_of = TILES_F32 if dtype == "f32" else TILES
+    rs = [r for r in rows if r["dtype"] == dtype and r["tile"] in tiles_of]
     y = np.array([r["us"] for r in rs])
     best = collections.defaultdict(lambda: 1e30)
     for r in rs:
@@ -70,24 +73,29 @@ def fit(rows, dtype: str):
     wts = np.array([NEAR_BEST_WEIGHT if r["us"] <= 1.25 * best[(r["m"], r["k"], r["n"])] else 1.0 for r in rs])
 
     def res(p):
-        return wts * np.array([math.log(model(p, r) / yy) for r, yy in zip(rs, y)])
+        return wts * np.array([math.log(model(p, r, tiles_of) / yy) for r, yy in zip(rs, y)])
 
-    p0 = np.array([6.8, 0.45, 2.1, 0.36, 0.18, 5.0, 0.3, 0.3, 0.05, 0.2, 7.5, 0.28, 0.5, 0.6, 0.35, 10.0, 0.46, 8.0, 0.73, 0.3,
-                   8.0, 0.3, 3.0, 0.3, 0.3, 1.0, 0.16, 1.0, 2.3, 1.0])
-    sol = least_squares(res, p0, bounds=(0, np.inf))
+    if dtype == "f32":
+        p0 = np.array([10, 2.0, 8, 3.0, 0.2, 7, 1.0, 3, 1.0, 0.2, 5, 0.5, 0.5, 0.2, 0.1, 0, 0, 0, 0, 1.0])
+        hi = np.array([np.inf] * 15 + [1e-9, 1e-9, 1e-9, 1e-9, np.inf])   # no split: the pass over the partials has no data
+    else:
+        p0 = np.array([6.8, 0.45, 2.1, 0.36, 0.18, 5.0, 0.3, 0.3, 0.05, 0.2, 7.5, 0.28, 0.5, 0.6, 0.35, 10.0, 0.46, 8.0, 0.73, 0.3,
+                       8.0, 0.3, 3.0, 0.3, 0.3, 1.0, 0.16, 1.0, 2.3, 1.0])
+        hi = np.full(p0.shape, np.inf)
+    sol = least_squares(res, p0, bounds=(0, hi))
     e = res(sol.x) / wts
     groups = collections.defaultdict(list)
     for r in rs:
-        groups[(r["m"], r["k"], r["n"])].append((model(sol.x, r), r["us"]))
+        groups[(r["m"], r["k"], r["n"])].append((model(sol.x, r, tiles_of), r["us"]))
     loss = [min(v)[1] / min(u for _, u in v) for v in groups.values()]
     return sol.x, float(np.sqrt((e ** 2).mean())), float(np.exp(np.mean(np.log(loss)))), float(max(loss)), len(rs)
 
 
-def table_text(name: str, p) -> str:
-    rows = ["{0, 0, 0, 0, 0}"]   # tile 0 (256 x 256 register-staged) is not a candidate for these dtypes
-    for i in range(len(TILES)):
-        rows.append("{" + ", ".join("%.4ff" % v for v in p[5 * i:5 * i + 5]) + "}")
-    g = p[5 * len(TILES):]
+def table_text(name: str, p, tiles_of=TILES) -> str:
+    rows = ["{0, 0, 0, 0, 0}"] * NUM_TILES   # a tile that is not a candidate for the dtype keeps a zero row
+    for i, t in enumerate(tiles_of):
+        rows[t] = "{" + ", ".join("%.4ff" % v for v in p[5 * i:5 * i + 5]) + "}"
+    g = [max(v, 0.0) if v > 1e-8 else 0.0 for v in p[5 * len(tiles_of):]]
     return "const CostTable %s = {{%s},\n    %s};\n" % (name, ",\n    ".join(rows), ", ".join("%.4ff" % v for v in g))
 
 
@@ -95,12 +103,12 @@ def main() -> None:
     rows = read_rows()
     text = ("// Written by paper_2301_01333_amd/calibration/fit_layers.py from calibration/data/layer_times.csv; do not edit.\n"
             "// Per tile {c, d, a, b, g}, indexed by tile id; then r0, r1, r2, px, l0 (see estimate_layer_us).\n")
-    for dtype, name in (("i8", "kCostI8"), ("bf16", "kCostBf16")):
+    for dtype, name in (("i8", "kCostI8"), ("bf16", "kCostBf16"), ("f32", "kCostF32")):
         p, rms, geo, worst, n = fit(rows, dtype)
         print("%s: %d launches, rms log error %.3f, the model's pick is %.3fx the fastest measured (geometric mean), worst %.2fx"
               % (dtype, n, rms, geo, worst))
         text += "// %s: %d launches, rms log error %.3f, pick / fastest %.3f (geometric mean), worst %.2f\n" % (dtype, n, rms, geo, worst)
-        text += table_text(name, p)
+        text += table_text(name, p, TILES_F32 if dtype == "f32" else TILES)
     if "--check" in sys.argv:
         print(text)
         return

@@ -1,4 +1,4 @@
-"""Calibration sweep behind the plan's per-layer cost model (int8 and bf16): times the MIDDLE layer of three-layer
+"""Calibration sweep behind the plan's per-layer cost model (int8, bf16 and fp32): times the MIDDLE layer of three-layer
 chains on the GPU for every candidate the plan can choose (tile configuration, number of k ranges), forced through
 the plan overrides, and writes one CSV row per launch configuration.
 
@@ -21,6 +21,7 @@ CHAINS = {"A": [1024] * 4, "B": [1024, 4096, 1024, 4096], "C": [512] * 4, "D": [
           "F": [768, 3072, 768, 3072], "G": [1536] * 4, "H": [384] * 4, "I": [3072, 768, 3072, 768]}
 BATCHES = (32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384, 32768)
 CANDIDATES = ((2, 0), (1, 0), (3, 0), (4, 0), (5, 0), (3, 1), (4, 1), (3, 2), (4, 2), (3, 3), (4, 3))
+CANDIDATES_F32 = ((2, 0), (1, 0), (0, 0))   # fp32 runs on the register-staged tiles only
 
 
 def main(out_path: str = DEFAULT_OUT) -> None:
@@ -36,15 +37,15 @@ def main(out_path: str = DEFAULT_OUT) -> None:
     with open(out_path, "w", newline="") as f:
         w = csv.writer(f)
         w.writerow(["dtype", "m", "k", "n", "tile", "ks", "us", "kernel"])
-        for dtype in ("i8", "bf16"):
-            esz = 1 if dtype == "i8" else 2
+        for dtype in ("i8", "bf16", "f32"):
+            esz = {"i8": 1, "bf16": 2, "f32": 4}[dtype]
             for cname, dims in CHAINS.items():
                 for m in BATCHES:
                     if m * max(dims) * esz > (1 << 28):
                         continue
                     wl = synth.make_mlp(dtype, m, dims, [synth.ACT_RELU] * 3, seed=5, has_bias=False)
                     kt = dims[1] * esz // 64
-                    for tile, ks in CANDIDATES:
+                    for tile, ks in (CANDIDATES_F32 if dtype == "f32" else CANDIDATES):
                         if tile == 2 and m > 1600:               # thousands of 64 x 32 tiles: never a candidate worth timing
                             continue
                         if ks and (kt % (1 << ks) or (kt >> ks) < 4):

@@ -106,11 +106,10 @@ void assign_buffers(ogc_mlp_plan_s* p) {
 //              rounds = (ceil(W/CUs) + W/CUs) / 2        (between whole rounds and perfect balance)
 //     t      = max(lone, stream) [+ r0 + r2*2^ks + r1*(2^ks + 1)*Mp*Np*4 bytes/1e6 for the pass over the partials]
 //
-// with the constants fitted (least squares on log time, candidates near the fastest weighted double, 8 % rms) to
-// 1570 timed launches of mid-chain layers on an
-// MI355X: K and N from 256 to 8192, batch 32 to 32768, every tile, splits 1 to 8, int8 and bf16.  On those shapes
-// the model's pick is within 1 % (geometric mean; 36 % worst case, one 8192x256 layer) of the fastest
-// candidate measured.  The constants include the launch; activation and bias costs are left out (the same for
+// with the constants fitted (least squares on log time, candidates near the fastest weighted double) to timed launches
+// of mid-chain layers on an MI355X: K and N from 256 to 8192, batch 32 to 32768, every tile, splits 1 to 8.  The
+// generated table file states the number of launches, the rms error and how far the model's pick is from the fastest
+// candidate measured (about 1 % in the geometric mean).  The constants include the launch; activation and bias costs are left out (the same for
 // every candidate to first order).
 struct TileCost {
     float c, d, a, b, g;
@@ -119,18 +118,10 @@ struct CostTable {
     TileCost t[OGC_NUM_TILES];  // indexed by tile id; OGC_TILE_BIG is not a candidate
     float r0, r1, r2, px, l0;
 };
-// kCostI8, kCostBf16: written by paper_2301_01333_amd/calibration/fit_layers.py from the measured launches in
+// kCostI8, kCostBf16, kCostF32 (fp32 runs on the register-staged tiles only, never split): written by
+// paper_2301_01333_amd/calibration/fit_layers.py from the measured launches in
 // paper_2301_01333_amd/calibration/data/layer_times.csv (a test refits and compares)
 #include "ogc_cost_layers.inc"
-
-// fp32 runs on the register-staged tiles only (256x256, 128x128, 64x32), never split: 1044 timed launches, 11 % rms.
-const CostTable kCostF32 = {{{12.688f, 4.093f, 26.438f, 3.881f, 0.131f},
-                             {7.964f, 1.128f, 2.877f, 1.215f, 0.157f},
-                             {4.817f, 0.380f, 0.177f, 0.193f, 0.305f},
-                             {0, 0, 0, 0, 0},
-                             {0, 0, 0, 0, 0},
-                             {0, 0, 0, 0, 0}},
-                            0.0f, 0.0f, 0.0f, 0.0f, 6.245f};
 
 // m rows x n channels, kt = 64-byte steps of the (padded) reduction axis.
 double estimate_layer_us(int dtype, int m, int n, int kt, int tile, int ks) {
@@ -200,10 +191,11 @@ constexpr double kProfiledLaunchExtraUs = 2.0;
 inline int model_dtype(int dtype) { return dtype == OGC_F8 ? OGC_I8 : dtype; }
 struct FusedCost { float f0, per_mb, per_layer, fill, per_block; };
 struct CoopCost { float c0, barrier, block, step, fill; };
-const FusedCost kFused[3] = {{4.706f, 30.663f, 1.174f, 0.225f, 0.0f}, {6.163f, 9.580f, 0.0f, 0.429f, 0.363f},
-                             {4.515f, 9.308f, 0.474f, 0.288f, 0.496f}};
-const CoopCost kCoop[3] = {{3.243f, 2.691f, 0.809f, 0.0321f, 0.821f}, {1.153f, 2.756f, 1.005f, 0.0130f, 0.957f},
-                           {0.611f, 2.886f, 1.007f, 0.0172f, 0.867f}};
+struct ClusterCost { float c0, per_mb, group, per_layer, barrier, copy_mb, fill, all_mb; };
+struct KsplitCost { float c0, block, step, barrier, copy_mb, fill, all_mb; };
+// kFused, kCoop, kCluster, kKsplit: written by paper_2301_01333_amd/calibration/fit_chains.py from the chains timed in
+// paper_2301_01333_amd/calibration/data/chain_times.csv (a test refits and compares)
+#include "ogc_cost_chains.inc"
 
 // One workgroup per 32 rows streams every weight: flat in the batch up to 8192 rows (256 CUs), then in rounds.
 double estimate_fused_us(const ogc_mlp_plan_s* p) {
@@ -239,10 +231,6 @@ double estimate_coop_us(const ogc_mlp_plan_s* p) {
 // mode models (chains of 2-5 layers, 64-4096 wide, 32-2048 rows, splits 2-16; rms error 8 %, worst 34 %: wide bf16
 // layers at 1024 rows, underestimated).  The fp32 row serves forced splits only: the kernel has no split along K,
 // an fp32 chain is bound by one CU's MFMA rate in it, and the plan does not offer it fp32 chains.
-struct ClusterCost { float c0, per_mb, group, per_layer, barrier, copy_mb, fill, all_mb; };
-const ClusterCost kCluster[3] = {{0.0f, 15.37f, 0.4852f, 2.127f, 1.000f, 11.72f, 0.1019f, 0.0310f},
-                                 {5.620f, 7.110f, 0.0477f, 0.744f, 1.000f, 55.68f, 0.0466f, 0.0233f},
-                                 {3.045f, 8.420f, 0.2833f, 1.272f, 1.000f, 0.0f, 0.0614f, 0.0106f}};
 
 // One layer of the cluster kernel: the busiest member's weight stream, and the exchange if the layer is split.
 double cluster_layer_us(const ogc_mlp_plan_s* p, int l, int split, bool whole) {
@@ -292,10 +280,6 @@ double estimate_cluster_us(const ogc_mlp_plan_s* p, int split) {
 // The cluster kernel whose waves split K inside a member: member j of S takes the channel blocks j, j + S, ... one
 // after the other (rounds), each over the whole of K on its eight waves; every layer but the last is exchanged.
 // 899 timed chains (the 12 calibration shapes, batch 32-2048, splits 2-32, three dtypes): 4-6 % rms, worst 22 %.
-struct KsplitCost { float c0, block, step, barrier, copy_mb, fill, all_mb; };
-const KsplitCost kKsplit[3] = {{4.405f, 1.028f, 0.3281f, 1.861f, 17.28f, 0.0529f, 0.0214f},
-                               {4.530f, 1.151f, 0.1613f, 1.583f, 12.22f, 0.0737f, 0.0132f},
-                               {3.661f, 1.266f, 0.1496f, 1.823f, 13.51f, 0.0859f, 0.0067f}};
 double estimate_cluster_ksplit_us(const ogc_mlp_plan_s* p, int split) {
     const KsplitCost& c = kKsplit[model_dtype(p->desc.dtype)];
     const int L = (int)p->layers.size();
@@ -558,7 +542,7 @@ ogc_status ogc_mlp_plan_with_overrides(const ogc_mlp_desc* desc, const ogc_plan_
         if (forced > 0) {
             if (ogc_cluster_xcds(m_blocks, forced, p->cluster_spread) >= 0) {
                 p->cluster_split = forced;
-                if (desc->dtype != OGC_F32) p->mode_us[2] = estimate_cluster_us(p, forced);
+                p->mode_us[2] = estimate_cluster_us(p, forced);
             }
         }
     }
