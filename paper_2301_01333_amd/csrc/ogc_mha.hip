@@ -126,7 +126,9 @@ template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_boun
 
     // ---- prefetch registers for one block of keys / values / mask
     v4i kreg[KU], vreg[VU][DT == OGC_BF16 ? 2 : 1];
-    float mreg = 0.0f;
+    float mreg = 0.0f;   // the mask value as loaded; scaled when it is written to LDS (scaling here would wait for the load,
+                         // and with it for every key / value load issued just before)
+    bool mpad = false;   // the key lies beyond the sequence
     auto prefetch = [&](int key0) {
         const bool full = key0 + KB <= S;  // uniform: every key of the block exists, no row needs a zero fill
 #pragma unroll
@@ -151,7 +153,9 @@ template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_boun
         }
         if (tid < KB) {
             const int key = key0 + tid;
-            mreg = key < S ? (a.mask ? a.mask[(long long)b * S + key] * LOG2E : 0.0f) : -INFINITY;
+            mpad = key >= S;
+            mreg = 0.0f;
+            if (!mpad && a.mask) mreg = a.mask[(long long)b * S + key];
         }
     };
     auto fill_lds = [&]() {
@@ -184,7 +188,7 @@ template <int DT, int D32, int FAST, int PLAIN, int QS> __global__ __launch_boun
                 for (int j = 0; j < 4; ++j) *(int*)(vt_lds + (4 * c + j) * VSTR + kl * 4) = vreg[i][0][j];
             }
         }
-        if (tid < KB) m_lds[tid] = mreg;
+        if (tid < KB) m_lds[tid] = mpad ? -INFINITY : mreg * LOG2E;
     };
 
     const int nkb = (S + KB - 1) / KB;

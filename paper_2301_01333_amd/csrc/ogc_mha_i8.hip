@@ -99,7 +99,9 @@ template <int D32> __global__ __launch_bounds__(256, 2) void ogc_mha_i8_kernel(M
     }
 
     v4i kreg[KU], vreg[KU];
-    float mreg = 0.0f;
+    float mreg = 0.0f;   // the mask value as loaded; scaled when it is written to LDS (scaling here would wait for the load,
+                         // and with it for every key / value load issued just before)
+    bool mpad = false;   // the key lies beyond the sequence
     auto prefetch = [&](int key0, bool with_v) {
 #pragma unroll
         for (int i = 0; i < KU; ++i) {
@@ -110,7 +112,9 @@ template <int D32> __global__ __launch_bounds__(256, 2) void ogc_mha_i8_kernel(M
         }
         if (tid < KB) {
             const int key = key0 + tid;
-            mreg = key < S ? (a.mask ? a.mask[(long long)b * S + key] * 1.44269504088896340736f : 0.0f) : -INFINITY;
+            mpad = key >= S;
+            mreg = 0.0f;
+            if (!mpad && a.mask) mreg = a.mask[(long long)b * S + key];
         }
     };
     auto fill_lds = [&](bool with_v) {
@@ -130,7 +134,7 @@ template <int D32> __global__ __launch_bounds__(256, 2) void ogc_mha_i8_kernel(M
                 }
             }
         }
-        if (tid < KB) m_lds[tid] = mreg;
+        if (tid < KB) m_lds[tid] = mpad ? -INFINITY : mreg * 1.44269504088896340736f;
     };
     // scores of the current block in the base-2 domain, scalar and mask applied: t[sb][4g+e] <-> key 32 sb + 8g + 4h + e
     auto scores = [&](float (&t)[SB][16]) {
