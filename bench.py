@@ -21,7 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK = {"i8": (5.0e15, "TOP/s"), "bf16": (2.5e15, "TFLOP/s"), "f32": (157.3e12, "TFLOP/s")}
+PEAK = {"i8": (5.0e15, "TOP/s"), "bf16": (2.5e15, "TFLOP/s"), "f32": (157.3e12, "TFLOP/s"), "f8": (5.0e15, "TFLOP/s")}
 HBM_PEAK = 8.0e12
 METRIC = "fused-MLP TFLOPS/TOPS + fraction of MFMA or HBM roofline, per config"
 MODE_NAMES = {1: "per_layer", 2: "fused", 3: "coop"}
@@ -208,6 +208,29 @@ def blocked_io_report(idx, steps, warmup):
     chain.close()
     return {"workload": wl.name + ", x and y in the blocked hand-off layout", "ms_per_step": sec * 1e3,
             "ms_per_step_hip_events": ev_sec * 1e3, "tops_or_tflops": wl.ops / sec / 1e12, "frac_of_peak": wl.ops / sec / peak}
+
+
+def fp8_report(steps, warmup):
+    """The 8-bit-float (E4M3) variant of the quantized chain on the shapes of configurations 3 and 5 (seeded synthetic
+    E4M3 tensors): time per chain with the plan's own choice of kernels, against the dense fp8 matrix peak."""
+    from paper_2301_01333_amd import binding, synth
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    rows = []
+    cases = [synth.make_mlp("f8", 256, [479, 1024, 1024, 512, 256, 1], [synth.ACT_RELU] * 4 + [synth.ACT_SIGMOID], seed=3001,
+                            last_f32=True, name="config 3's shape in E4M3: M=256 479-1024-1024-512-256-1, fp32 sigmoid out"),
+             synth.make_mlp("f8", 32768, [1024] * 5, [synth.ACT_RELU] * 4, seed=3002, has_bias=False,
+                            name="config 5's shape in E4M3: M=32768 4x(1024-1024) ReLU + requantize")]
+    for wl in cases:
+        dev = DeviceMLP(wl)
+        sec, ev = time_steps(dev, min(steps, 100), min(warmup, 10))
+        nl = binding.ogc_mlp_num_launches(dev.mlp.plan)
+        rows.append({"workload": wl.name, "mode": MODE_NAMES[dev.mlp.mode],
+                     "kernels": sorted({binding.ogc_mlp_kernel_name(dev.mlp.plan, j) for j in range(nl)}),
+                     "ms_per_step": sec * 1e3, "ms_per_step_hip_events": ev * 1e3, "tflops": wl.ops / sec / 1e12,
+                     "frac_of_fp8_mfma_peak": wl.ops / sec / PEAK["f8"][0]})
+        dev.close()
+    return rows
 
 
 def table1_sweep(steps, warmup):
@@ -434,6 +457,7 @@ def main():
         "per_config": per,
         "blocked_io": blocked,
         "mha": None if (args.only_headline or args.no_mha) else mha_report(args.steps, args.warmup, not args.no_cpu),
+        "fp8_variant": None if args.only_headline else fp8_report(args.steps, args.warmup),
         # the MLP rows of the paper's Table I over its batch range, each with the plan's own choice of kernel
         "table1_mlp_sweep": None if args.only_headline else table1_sweep(min(args.steps, 200), min(args.warmup, 20)),
     }
