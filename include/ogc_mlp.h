@@ -143,8 +143,10 @@ typedef struct {
                                 128x128 / 64x32 channels x rows; 3 / 4 the four- / eight-wave stream tile, 128x256 /
                                 256x256; 5 the k-sliced stream tile: 128x128, two groups of four waves take alternate
                                 k-steps and add up in LDS at the end of a tile); a stream tile falls back to 1 on a layer
-                                the stream kernel cannot run (5 also where the number of 64-byte k-steps is odd) */
-    int32_t ksplit_log2;     /* per-layer mode: log2 of the number of k ranges of every layer on stream tile 3 or 4, 0..3 */
+                                the stream kernel cannot run (5 also where the number of 64-byte k-steps is odd;
+                                OGC_F8 has stream tile 4 only, 3 and 5 fall back) */
+    int32_t ksplit_log2;     /* per-layer mode: log2 of the number of k ranges of every layer on stream tile 3 or 4, 0..3
+                                (ignored for OGC_F8) */
     int32_t cluster_split;   /* cooperative mode: 0 = kernel (a); n = kernel (b) with n workgroups per row tile where
                                 they fit (any dtype) */
     int32_t cluster_ksplit;  /* cooperative mode: 1 together with cluster_split = n: kernel (c) with n members;

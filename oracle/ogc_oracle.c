@@ -304,18 +304,20 @@ int oracle_layer_f8(int M, int K, int N, const uint8_t* X8, int ldx, const uint8
                     const float* bias, float a_s, int act, int out_f32, float c_s, void* Yv, int ldy, int accum_double) {
     if (M < 0 || K < 0 || N < 0 || !Yv || !w_scale || (M && K && N && (!X8 || !W8))) return -1;
     const float inv = out_f32 ? 0.0f : 1.0f / c_s;
+    double val[256]; /* the value of every code, decoded once (every E4M3 value is exact in fp32 and fp64) */
+    for (int c = 0; c < 256; ++c) val[c] = e4m3_to_f64((uint8_t)c);
 #pragma omp parallel for schedule(static)
     for (int m = 0; m < M; ++m) {
         for (int n = 0; n < N; ++n) {
             float f;
             if (accum_double) {
                 double acc = 0.0;
-                for (int k = 0; k < K; ++k) acc += e4m3_to_f64(X8[(size_t)m * ldx + k]) * e4m3_to_f64(W8[(size_t)k * N + n]);
+                for (int k = 0; k < K; ++k) acc += val[X8[(size_t)m * ldx + k]] * val[W8[(size_t)k * N + n]];
                 f = (float)acc;
             } else {
                 float acc = 0.0f;
                 for (int k = 0; k < K; ++k) {
-                    float prod = (float)e4m3_to_f64(X8[(size_t)m * ldx + k]) * (float)e4m3_to_f64(W8[(size_t)k * N + n]);
+                    float prod = (float)val[X8[(size_t)m * ldx + k]] * (float)val[W8[(size_t)k * N + n]];
                     acc = acc + prod;
                 }
                 f = acc;

@@ -152,20 +152,22 @@ void choose_tile_and_split(int dtype, int m, int n, int kt, bool dma_ok, int for
     };
     auto split_ok = [&](int ks) { return ks >= 0 && ks <= 3 && kt % (1 << ks) == 0 && (kt >> ks) >= 4; };
     int tile = -1, ks = 0;
+    const bool f8 = dtype == OGC_F8;  // E4M3: of the stream shapes only the eight-wave one, never split along K
     if (forced >= 0 && forced < OGC_NUM_TILES)
         tile = ((forced == OGC_TILE_DMA || forced == OGC_TILE_DMA8 || forced == OGC_TILE_DMAK2) && !dma_ok) ? OGC_TILE_MID : forced;
+    if (f8 && (tile == OGC_TILE_DMA || tile == OGC_TILE_DMAK2)) tile = OGC_TILE_MID;
     if (tile == OGC_TILE_DMAK2 && kt % 2 != 0) tile = OGC_TILE_MID;  // its stages hold two k-steps
     const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8;  // (the k-sliced shape is never split between workgroups)
     if (tile >= 0) {
-        if (stream && forced_split > 0 && forced_split <= 3 && kt % (1 << forced_split) == 0) ks = forced_split;
+        if (stream && !f8 && forced_split > 0 && forced_split <= 3 && kt % (1 << forced_split) == 0) ks = forced_split;
     } else {
         double best = 0.0;
         // the 256x256 register-staged tile is timed for fp32 only; the stream tiles replace it for int8 / bf16
-        const int cands[6] = {OGC_TILE_SMALL, OGC_TILE_MID, dtype == OGC_F32 ? OGC_TILE_BIG : -1, dma_ok ? OGC_TILE_DMA : -1,
-                              dma_ok ? OGC_TILE_DMA8 : -1, (dma_ok && kt % 2 == 0) ? OGC_TILE_DMAK2 : -1};
+        const int cands[6] = {OGC_TILE_SMALL, OGC_TILE_MID, dtype == OGC_F32 ? OGC_TILE_BIG : -1, (dma_ok && !f8) ? OGC_TILE_DMA : -1,
+                              dma_ok ? OGC_TILE_DMA8 : -1, (dma_ok && !f8 && kt % 2 == 0) ? OGC_TILE_DMAK2 : -1};
         for (int c = 0; c < 6; ++c) {
             if (cands[c] < 0) continue;
-            const bool st = cands[c] == OGC_TILE_DMA || cands[c] == OGC_TILE_DMA8;
+            const bool st = (cands[c] == OGC_TILE_DMA || cands[c] == OGC_TILE_DMA8) && !f8;
             if (forced_split > 0 && !st && dma_ok) continue;  // a forced split needs a stream tile
             for (int s = 0; s <= (st ? 3 : 0); ++s) {
                 if (forced_split >= 0 && st && s != forced_split) continue;
@@ -483,7 +485,7 @@ ogc_status ogc_mlp_plan_with_overrides(const ogc_mlp_desc* desc, const ogc_plan_
         LayerPlan& lp = p->layers[l];
         const int rows = lp.nb_out * 32 > lp.d.n ? lp.nb_out * 32 : lp.d.n;
         // the stream kernel keeps its accumulators in fixed registers: no out-of-line calls (sigmoid) in it
-        const bool dma_ok = desc->dtype != OGC_F32 && desc->dtype != OGC_F8 && lp.d.act != OGC_ACT_SIGMOID &&
+        const bool dma_ok = desc->dtype != OGC_F32 && lp.d.act != OGC_ACT_SIGMOID &&
                             !(desc->dtype == OGC_I8 && lp.d.in_zp != 128) &&
                             (l > 0 || desc->x_layout == OGC_LAYOUT_BLOCKED ||
                              (((long long)desc->ld_x * esz) % 16 == 0 && lp.kp == lp.d.k));

@@ -1337,6 +1337,9 @@ static int launch_dma_dtype(int dtype, int xp, int op, const OgcLayerArgs* a, hi
         if (a->act == OGC_ACT_RELU && !a->out_f32) return launch_dma_io<OGC_I8, SHAPE, 1>(xp, op, a, s);
         return launch_dma_io<OGC_I8, SHAPE, 0>(xp, op, a, s);
     }
+    if constexpr (SHAPE == 1) {
+        if (dtype == OGC_F8) return launch_dma_io<OGC_F8, 1, 0>(xp, op, a, s);  // E4M3: the eight-wave shape only
+    }
     return (int)hipErrorInvalidValue;  // the plan never selects this kernel for fp32
 }
 

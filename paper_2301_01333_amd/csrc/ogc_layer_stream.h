@@ -247,7 +247,7 @@ OGC_DEV void k_step(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint32_t soc
     if constexpr (DT == OGC_I8) {
         OGC_STEP_ZF("v_mfma_i32_32x32x32_i8")
     } else {
-        static_assert(DT == OGC_BF16, "the stream kernel covers int8 and bf16");
+        static_assert(DT == OGC_BF16, "this step covers int8 and bf16 (E4M3 has k_step8)");
         OGC_STEP_ZF("v_mfma_f32_32x32x16_bf16")
     }
 #undef OGC_STEP_ZF
@@ -354,6 +354,122 @@ OGC_DEV void k_steps_run(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint64_
 #undef OGC_RUN_SHAPES
 }
 
+// ---- 8-bit floats (E4M3), eight-wave shape only ------------------------------------------------------------
+// The full-rate fp8 matrix instruction contracts 64 bytes of K at once and takes each operand as EIGHT consecutive
+// registers: the lane's 16 bytes of the first half k-step followed by its 16 bytes of the second half.  Register map
+// of the operands (accumulators as above): W0 = v[80:87], W1 = v[88:95], X0..X3 = v[96:103] .. v[120:127]; a k-step is
+// eight instructions, W0 x X0..X3 then W1 x X0..X3, 64 clocks each.  There is one operand set, so the reads of the next
+// step go out as this step's instructions retire their operands (an instruction reads its A / B registers when it
+// issues; LDS data comes back a hundred clocks later): the barrier sits after the fourth instruction, then
+//   W1xX0 | read W0' | W1xX1 | read X0' | W1xX2 | read X1' | W1xX3 | read X2', X3', W1'
+// and the next step's instructions wait for exactly the reads they need (LDS reads return in order): 8, 6, 4, 2
+// outstanding before W0'xX0'..X3', none before W1'xX0'.
+#define OGC8_W(i) "v[80+8*" #i ":87+8*" #i "]"
+#define OGC8_X(j) "v[96+8*" #j ":103+8*" #j "]"
+#define OGC8_MFMA(b, i, j) "v_mfma_f32_32x32x64_f8f6f4 " OGC_ACC(b) ", " OGC8_W(i) ", " OGC8_X(j) ", " OGC_ACC(b) "\n\t"
+#define OGC8_MFMA_Z(b, i, j) "v_mfma_f32_32x32x64_f8f6f4 " OGC_ACC(b) ", " OGC8_W(i) ", " OGC8_X(j) ", 0\n\t"
+// both halves of weight operand i (WA: LDS address of the stage's weights for this wave) / activation operand j
+// (XA / XH: addresses of the first / second half)
+#define OGC8_READ_W(i, WA)                                                                          \
+    "ds_read_b128 v[80+8*" #i ":83+8*" #i "], " WA " offset:2048*" #i "\n\t"                         \
+    "ds_read_b128 v[84+8*" #i ":87+8*" #i "], " WA " offset:1024+2048*" #i "\n\t"
+#define OGC8_READ_X(j, XA, XH)                                                                      \
+    "ds_read_b128 v[96+8*" #j ":99+8*" #j "], " XA " offset:2048*" #j "\n\t"                         \
+    "ds_read_b128 v[100+8*" #j ":103+8*" #j "], " XH " offset:2048*" #j "\n\t"
+#define OGC8_FIRST(MZ)                                                                              \
+    "s_waitcnt lgkmcnt(8)\n\t" MZ(0, 0, 0) "s_waitcnt lgkmcnt(6)\n\t" MZ(1, 0, 1)                   \
+    "s_waitcnt lgkmcnt(4)\n\t" MZ(2, 0, 2) "s_waitcnt lgkmcnt(2)\n\t" MZ(3, 0, 3)
+// second half with the reads of the next step (TW / TX / TXH: its addresses) and the direct loads D between
+#define OGC8_SECOND(MZ, D, TW, TX, TXH)                                                             \
+    "s_waitcnt lgkmcnt(0)\n\t" MZ(4, 1, 0) OGC8_READ_W(0, TW) D(0, 0, "incw")                        \
+    MZ(5, 1, 1) OGC8_READ_X(0, TX, TXH) D(1, 8192, "incw")                                          \
+    MZ(6, 1, 2) OGC8_READ_X(1, TX, TXH) D(2, 16384, "incx")                                         \
+    MZ(7, 1, 3) OGC8_READ_X(2, TX, TXH) D(3, 24576, "incx") OGC8_READ_X(3, TX, TXH) OGC8_READ_W(1, TW)
+#define OGC8_SECOND_NOREAD(MZ) "s_waitcnt lgkmcnt(0)\n\t" MZ(4, 1, 0) MZ(5, 1, 1) MZ(6, 1, 2) MZ(7, 1, 3)
+
+// One k-step.  MODE / VM / ZERO as for k_step; son: ring offset of the next step's stage.
+template <int VM, int MODE, bool ZERO>
+OGC_DEV void k_step8(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint32_t son, uint64_t (&g)[6], uint64_t incw, uint64_t incx,
+                     uint32_t m0b) {
+    static_assert(VM == 8 || VM == 4, "loads allowed in flight at the barrier");
+    uint32_t tw, tx, txh;
+#define OGC8_HEAD "v_add_u32 %[tw], %[son], %[wrd]\n\tv_add_u32 %[tx], %[son], %[xrd]\n\tv_add_u32 %[txh], %[son], %[xrdh]\n\t"
+#define OGC8_OUT [tw] "=&v"(tw), [tx] "=&v"(tx), [txh] "=&v"(txh)
+#define OGC8_IN [wrd] "v"(w_rd), [xrd] "v"(x_rd), [xrdh] "v"(x_rd_hi), [son] "s"(son)
+#define OGC8_STEP(MZ)                                                                                                   \
+    if constexpr (MODE == 0 && VM == 8)                                                                                 \
+        asm volatile(OGC8_HEAD OGC8_FIRST(MZ) "s_waitcnt vmcnt(8)\n\ts_barrier\n\t"                                    \
+                         OGC8_SECOND(MZ, OGC_DMA, "%[tw]", "%[tx]", "%[txh]") "s_waitcnt lgkmcnt(0)"                    \
+                     : OGC8_OUT, OGC_STEP_G4 : OGC8_IN, OGC_STEP_DMA_IN : "memory");                                    \
+    else if constexpr (MODE == 0)                                                                                       \
+        asm volatile(OGC8_HEAD OGC8_FIRST(MZ) "s_waitcnt vmcnt(4)\n\ts_barrier\n\t"                                    \
+                         OGC8_SECOND(MZ, OGC_DMA, "%[tw]", "%[tx]", "%[txh]") "s_waitcnt lgkmcnt(0)"                    \
+                     : OGC8_OUT, OGC_STEP_G4 : OGC8_IN, OGC_STEP_DMA_IN : "memory");                                    \
+    else if constexpr (MODE == 2)                                                                                       \
+        asm volatile(OGC8_HEAD OGC8_FIRST(MZ) "s_waitcnt vmcnt(0)\n\ts_barrier\n\t"                                    \
+                         OGC8_SECOND(MZ, OGC_NODMA, "%[tw]", "%[tx]", "%[txh]") "s_waitcnt lgkmcnt(0)"                  \
+                     : OGC8_OUT : OGC8_IN : "memory");                                                                  \
+    else                                                                                                                \
+        asm volatile(OGC8_FIRST(MZ) OGC8_SECOND_NOREAD(MZ) ::: "memory");
+    if constexpr (ZERO) {
+        OGC8_STEP(OGC8_MFMA_Z)
+    } else {
+        OGC8_STEP(OGC8_MFMA)
+    }
+#undef OGC8_STEP
+}
+
+// A run of n ordinary k-steps with the loop control inside (see k_steps_run): LATE waves issue their direct loads
+// among the first four instructions, into the stage freed by the previous step's barrier, the others after the barrier.
+#define OGC8_RUN(DA, DB, SLOT, VMN)                                                                      \
+    ".Lks8%=:\n\t"                                                                                       \
+    "s_add_u32 %[son], %[sst], %[stg]\n\t"                                                               \
+    "s_cmp_lg_u32 %[son], %[ring]\n\t"                                                                   \
+    "s_cselect_b32 %[son], %[son], 0\n\t"                                                                \
+    "s_waitcnt lgkmcnt(8)\n\t" OGC8_MFMA(0, 0, 0)                                                        \
+    "v_add_u32 %[tw], %[son], %[wrd]\n\t"                                                                \
+    "v_add_u32 %[tx], %[son], %[xrd]\n\t"                                                                \
+    "v_add_u32 %[txh], %[son], %[xrdh]\n\t"                                                              \
+    "s_add_u32 %[kph], %[kph], 1\n\t"                                                                    \
+    "s_cmp_eq_u32 %[kph], %[ktt]\n\t"                                                                    \
+    "s_cselect_b64 %[incw], %[incww], %[incwn]\n\t"                                                      \
+    "s_cselect_b64 %[incx], %[incxw], %[incxn]\n\t"                                                      \
+    "s_cselect_b32 %[kph], 0, %[kph]\n\t"                                                                \
+    "s_add_u32 %[m0b], %[m0w], %[" SLOT "]\n\t"                                                          \
+    "s_waitcnt lgkmcnt(6)\n\t" OGC8_MFMA(1, 0, 1) DA(0, 0, "incw") DA(1, 8192, "incw")                   \
+    "s_waitcnt lgkmcnt(4)\n\t" OGC8_MFMA(2, 0, 2) DA(2, 16384, "incx")                                   \
+    "s_waitcnt lgkmcnt(2)\n\t" OGC8_MFMA(3, 0, 3) DA(3, 24576, "incx")                                   \
+    "s_waitcnt vmcnt(" #VMN ")\n\ts_barrier\n\t"                                                        \
+    OGC8_SECOND(OGC8_MFMA, DB, "%[tw]", "%[tx]", "%[txh]")                                               \
+    "s_mov_b32 %[sprev], %[sst]\n\t"                                                                     \
+    "s_mov_b32 %[sst], %[son]\n\t"                                                                       \
+    "s_sub_u32 %[n], %[n], 1\n\t"                                                                        \
+    "s_cmp_lg_u32 %[n], 0\n\t"                                                                           \
+    "s_cbranch_scc1 .Lks8%=\n\t"                                                                         \
+    "s_waitcnt lgkmcnt(0)"
+
+template <bool LATE>
+OGC_DEV void k_steps_run8(uint32_t w_rd, uint32_t x_rd, uint32_t x_rd_hi, uint64_t (&g)[6], uint32_t& sst, uint32_t& sprev, uint32_t& kph,
+                          uint32_t n, uint32_t kt_total, uint32_t m0w, uint64_t incwn, uint64_t incww, uint64_t incxn, uint64_t incxw) {
+    typedef StreamCfg<1> C;
+    sst = __builtin_amdgcn_readfirstlane(sst);
+    sprev = __builtin_amdgcn_readfirstlane(sprev);
+    kph = __builtin_amdgcn_readfirstlane(kph);
+    n = __builtin_amdgcn_readfirstlane(n);
+    kt_total = __builtin_amdgcn_readfirstlane(kt_total);
+    m0w = __builtin_amdgcn_readfirstlane(m0w);
+    uint32_t tw = 0, tx = 0, txh = 0, son, m0b;
+    uint64_t incw, incx;
+#define OGC8_RUN_OUT [son] "=&s"(son), [m0b] "=&s"(m0b), [incw] "=&s"(incw), [incx] "=&s"(incx), [tw] "+v"(tw), [tx] "+v"(tx), [txh] "+v"(txh), \
+                     [sst] "+s"(sst), [sprev] "+s"(sprev), [kph] "+s"(kph), [n] "+s"(n)
+#define OGC8_RUN_IN [wrd] "v"(w_rd), [xrd] "v"(x_rd), [xrdh] "v"(x_rd_hi), [ktt] "s"(kt_total), [m0w] "s"(m0w), [incwn] "s"(incwn), [incww] "s"(incww), \
+                    [incxn] "s"(incxn), [incxw] "s"(incxw), [stg] "n"(C::STAGE), [ring] "n"(C::RING)
+    if constexpr (!LATE)
+        asm volatile(OGC8_RUN(OGC_NODMA, OGC_DMA, "sst", 8) : OGC8_RUN_OUT, OGC_STEP_G4 : OGC8_RUN_IN : "memory", "scc");
+    else
+        asm volatile(OGC8_RUN(OGC_DMA, OGC_NODMA, "sprev", 8) : OGC8_RUN_OUT, OGC_STEP_G4 : OGC8_RUN_IN : "memory", "scc");
+}
+
 // block b of the accumulators to LDS as four 16-byte pieces per lane, 1 KiB apart (ra: the lane's LDS address)
 #define OGC_LDS_PUT_ACC(b)                                                                            \
     asm volatile("ds_write_b128 %0, v[128+16*" #b ":131+16*" #b "]\n\t"                                \
@@ -394,6 +510,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     constexpr int OPW = C::OPW, NST = C::NST, VM = (NST - 2) * OPW;
     constexpr int TN = C::TN, TM = C::TM;
     constexpr bool FLIP = X_PLAIN && DT == OGC_I8;
+    static_assert(DT != OGC_F8 || (SHAPE == 1 && EPI == 0), "E4M3 runs the eight-wave shape with the general epilogue");
     extern __shared__ __align__(1024) uint8_t smem[];
     // v80..v255 are used by the assembly below only; naming the last one makes the kernel own all 256.
     asm volatile("; operand sets and accumulators live in v80..v255" ::: "v255");
@@ -571,7 +688,11 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
         else if (fetched == 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(OPW) : "memory");
         else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     }
-    if constexpr (TM == 2) asm volatile(OGC_READ2(80, "%[wa]", "%[xa]") "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
+    if constexpr (DT == OGC_F8)
+        asm volatile(OGC8_READ_W(0, "%[wa]") OGC8_READ_X(0, "%[xa]", "%[xh]") OGC8_READ_X(1, "%[xa]", "%[xh]") OGC8_READ_X(2, "%[xa]", "%[xh]")
+                         OGC8_READ_X(3, "%[xa]", "%[xh]") OGC8_READ_W(1, "%[wa]") "s_waitcnt lgkmcnt(0)"
+                     ::[wa] "v"(w_rd), [xa] "v"(x_rd), [xh] "v"(x_rd_hi) : "memory");
+    else if constexpr (TM == 2) asm volatile(OGC_READ2(80, "%[wa]", "%[xa]") "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
     else asm volatile(OGC_READ(80, "%[wa]", "%[xa]") "s_waitcnt lgkmcnt(0)" ::[wa] "v"(w_rd), [xa] "v"(x_rd) : "memory");
     uint32_t sst = 0, sprev = (NST - 1) * C::STAGE;  // ring offsets of the current and the previous step's stage
     int kt = 0, q = 0;
@@ -583,7 +704,10 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             n = n < KT - pf_kt ? n : KT - pf_kt;
             n = n < total_steps - fetched ? n : total_steps - fetched;
             uint32_t kph = (uint32_t)pf_kphys;
-            if (late) k_steps_run<DT, SHAPE, SHAPE != 0, FLIP>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, (uint64_t)w_step, incw_wrap, (uint64_t)x_step, incx_wrap);
+            if constexpr (DT == OGC_F8) {
+                if (late) k_steps_run8<true>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, (uint64_t)w_step, incw_wrap, (uint64_t)x_step, incx_wrap);
+                else k_steps_run8<false>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, (uint64_t)w_step, incw_wrap, (uint64_t)x_step, incx_wrap);
+            } else if (late) k_steps_run<DT, SHAPE, SHAPE != 0, FLIP>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, (uint64_t)w_step, incw_wrap, (uint64_t)x_step, incx_wrap);
             else k_steps_run<DT, SHAPE, false, FLIP>(w_rd, x_rd, x_rd_hi, g, sst, sprev, kph, n, KT, m0_wave, (uint64_t)w_step, incw_wrap, (uint64_t)x_step, incx_wrap);
             pf_kphys = (int)kph;
             kt += n;
@@ -594,6 +718,27 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             const uint32_t snext = sst + C::STAGE == C::RING ? 0 : sst + C::STAGE;
             const uint32_t soc = sst + 1024, son = snext;
             const bool zero = kt == 0;
+            if constexpr (DT == OGC_F8) {
+                if (can_fetch) {
+                    set_increments();
+                    const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + (late ? sprev : sst));
+                    if (late) {
+                        if (zero) k_step8<4, 0, true>(w_rd, x_rd, x_rd_hi, son, g, incw, incx, m0b);
+                        else k_step8<4, 0, false>(w_rd, x_rd, x_rd_hi, son, g, incw, incx, m0b);
+                    } else {
+                        if (zero) k_step8<8, 0, true>(w_rd, x_rd, x_rd_hi, son, g, incw, incx, m0b);
+                        else k_step8<8, 0, false>(w_rd, x_rd, x_rd_hi, son, g, incw, incx, m0b);
+                    }
+                    ++fetched;
+                    cursor_advanced(1);
+                } else if (q + 1 < total_steps) {
+                    if (zero) k_step8<8, 2, true>(w_rd, x_rd, x_rd_hi, son, g, 0, 0, 0);
+                    else k_step8<8, 2, false>(w_rd, x_rd, x_rd_hi, son, g, 0, 0, 0);
+                } else {
+                    if (zero) k_step8<8, 3, true>(w_rd, x_rd, x_rd_hi, son, g, 0, 0, 0);
+                    else k_step8<8, 3, false>(w_rd, x_rd, x_rd_hi, son, g, 0, 0, 0);
+                }
+            } else
             if (can_fetch) {
                 set_increments();
                 const uint32_t m0b = __builtin_amdgcn_readfirstlane(m0_wave + (late ? sprev : sst));

@@ -146,7 +146,8 @@ def test_quantize_and_dequantize_match_the_oracle_encoding(oracle_mod):
 # ---------------------------------------------------------------- one layer, every kernel
 @pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])
 def test_one_layer_every_tile(oracle_mod, tile):
-    """Tiles 3-5 (the stream shapes) are not built for E4M3: the plan falls back to the register-staged 128x128 tile."""
+    """Of the stream shapes only the eight-wave one (tile 4) is built for E4M3: forced tiles 3 and 5, and tile 4 on a first
+    layer whose rows need K padding, fall back to the register-staged 128x128 tile."""
     m = {0: 300, 1: 150, 2: 77, 3: 260, 4: 100, 5: 64}[tile]
     for dims, act, f32 in (([100, 333], RELU, False), ([256, 72], NONE, False), ([479, 33], GELU, False), ([64, 5], SIGM, True)):
         wl = synth.make_mlp("f8", m, dims, [act], seed=1500 + tile, last_f32=f32, name="one-layer")
@@ -182,6 +183,30 @@ def test_saturation_subnormals_and_signed_zero(oracle_mod):
     wl.w[0][:] = 0
     got, _ = run_gpu(wl, "per_layer")
     assert (got == 0).all() and (oracle_mod.mlp(wl) == 0).all()
+
+
+def test_stream_kernel(oracle_mod):
+    """The persistent stream kernel on the full-rate fp8 matrix instruction (K = 64 per instruction): plain and blocked
+    input, plain and blocked output, several tiles per workgroup, short (4 steps) and long reduction axes, ragged
+    channel counts, every layer also alone against the oracle's intermediate."""
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    wl = synth.make_mlp("f8", 700, [256, 512, 320, 64], [RELU, GELU, NONE], seed=2200, name="stream")
+    d = DeviceMLP(wl, binding.OGC_MODE_PER_LAYER, overrides={"tile": 4})
+    names = [binding.ogc_mlp_kernel_name(d.mlp.plan, l) for l in range(3)]
+    d.close()
+    assert names == ["ogc_layer_dma_kernel<3, 1, 1, 0, 0>", "ogc_layer_dma_kernel<3, 1, 0, 0, 0>", "ogc_layer_dma_kernel<3, 1, 0, 1, 0>"], names
+    check_chain(oracle_mod, wl, "per_layer", tile=4)
+    check_chain(oracle_mod, synth.make_mlp("f8", 16500, [512, 1024, 512], [RELU, RELU], seed=2201, name="stream-260-tiles"), "per_layer", tile=4)
+    check_chain(oracle_mod, synth.make_mlp("f8", 300, [4096, 256, 2048], [RELU, NONE], seed=2202, has_bias=False, name="stream-long-k"),
+                "per_layer", tile=4)
+    check_chain(oracle_mod, synth.make_mlp("f8", 1, [64 * 4, 1], [NONE], seed=2203, name="stream-1x1"), "per_layer", tile=4)
+    # the plan's own choice for a large layer is this kernel
+    big = synth.make_mlp("f8", 8192, [1024, 1024, 1024], [RELU, RELU], seed=2204, has_bias=False, name="stream-auto")
+    d = DeviceMLP(big, binding.OGC_MODE_AUTO)
+    assert binding.ogc_mlp_kernel_name(d.mlp.plan, 1).startswith("ogc_layer_dma_kernel<3, 1,")
+    d.close()
+    check_chain(oracle_mod, big, "auto", layers_alone=False)
 
 
 # ---------------------------------------------------------------- chains
