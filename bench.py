@@ -352,7 +352,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
+    # (the chip's clock takes about 250 steps of the headline workload, 35 ms, to come up from idle: 162 us for the first
+    # 50 steps after a pause, 148, 137, 136, 134 for the next blocks of 50, 131-133 from then on)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--config", type=int, default=5, help="headline configuration (1..5)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--only-headline", action="store_true", help="skip the per_config table")
