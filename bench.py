@@ -37,6 +37,13 @@ def time_steps(dev, steps, warmup):
     the launch stream around the same region.  Returns (wall seconds per step, event seconds per step)."""
     import torch
 
+    # The chip's clock comes up from idle over tens of milliseconds of load (DESIGN.md, section 9): whatever `warmup` is,
+    # the untimed part lasts at least 50 ms, so that the timed steps run at the clock a loop of such steps settles at.
+    t_end = time.perf_counter() + 0.05
+    while time.perf_counter() < t_end:
+        for _ in range(20):
+            dev.run()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         dev.run()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
