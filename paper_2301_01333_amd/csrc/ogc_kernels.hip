@@ -342,6 +342,47 @@ OGC_DEV void epilogue_block_i8_relu(const v16i& acc, const OgcLayerArgs& a, cons
     }
 }
 
+// The E4M3 counterpart: ReLU and a requantized E4M3 result in three and a half operations per element.  Equivalent,
+// code for code, to the general sequence relu -> *inv -> clamp[-448, 448] (NaN kept) -> convert: a negative y lands on
+// zero either way, a NaN does not survive the ReLU in either (the maximum of a NaN and 0 is 0, and so is the median of a
+// NaN, 0 and 448), and the conversion instruction rounds to nearest even.
+OGC_DEV v4i requant_block_f8_relu(const v16f& acc, const OgcLayerArgs& a, const BlockParams& p) {
+    const float inv = a.inv_cs;
+    uint32_t dw[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        float t[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float y = __builtin_fmaf(acc[4 * g + e], p.s[g][e], p.b[g][e]);
+            t[e] = __builtin_amdgcn_fmed3f(y * inv, 0.0f, 448.0f);
+        }
+        int r = __builtin_amdgcn_cvt_pk_fp8_f32(t[0], t[1], 0, false);
+        dw[g] = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(t[2], t[3], r, true);
+    }
+    swap32(dw[0], dw[2]);
+    swap32(dw[1], dw[3]);
+    return (v4i){(int)dw[0], (int)dw[2], (int)dw[1], (int)dw[3]};  // 16 consecutive channels from n0+16h
+}
+
+// The ReLU-requantize arithmetic of a block for the dtype at hand (int8: u8 results, E4M3: E4M3 codes).
+template <int DT> OGC_DEV v4i requant_block_relu(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, const BlockParams& p) {
+    if constexpr (DT == OGC_F8) return requant_block_f8_relu(acc, a, p);
+    else return requant_block_i8_relu(acc, a, p);
+}
+
+template <int OUT_PLAIN, typename YP>
+OGC_DEV void epilogue_block_f8_relu(const v16f& acc, const OgcLayerArgs& a, const BlockParams& p, int n0, int m0, int lane, YP yblk) {
+    const int h = lane >> 5, mm = lane & 31;
+    const v4i ch = requant_block_f8_relu(acc, a, p);
+    if constexpr (OUT_PLAIN) {
+        const v4i arr[1] = {ch};
+        store_plain<1>(arr, a, m0 + mm, n0 + 16 * h);
+    } else {
+        store16(yblk + ((size_t)((n0 >> 5) * 2 + h) * 32 + mm) * 16, ch);
+    }
+}
+
 // Final store of two neighbouring 32-channel blocks of the same 32 rows (u8 results, 64 consecutive bytes per row) to
 // the caller's plain y as whole 64-byte row segments: the chunks cross the wave through 2 KiB of LDS (row r keeps
 // piece c in slot (c + r/4) mod 4: conflict-free both ways), after which four neighbouring lanes hold one row's
@@ -372,6 +413,10 @@ OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerAr
             epilogue_block_i8_relu<OUT_PLAIN>(acc, a, p, n0, m0, lane, yblk);
             return;
         }
+    }
+    if constexpr (DT == OGC_F8 && PATH == 1) {  // the caller knows: ReLU, E4M3 result
+        epilogue_block_f8_relu<OUT_PLAIN>(acc, a, p, n0, m0, lane, yblk);
+        return;
     }
     const int h = lane >> 5, mm = lane & 31;
     float out[16];
@@ -1338,7 +1383,10 @@ static int launch_dma_dtype(int dtype, int xp, int op, const OgcLayerArgs* a, hi
         return launch_dma_io<OGC_I8, SHAPE, 0>(xp, op, a, s);
     }
     if constexpr (SHAPE == 1) {
-        if (dtype == OGC_F8) return launch_dma_io<OGC_F8, 1, 0>(xp, op, a, s);  // E4M3: the eight-wave shape only
+        if (dtype == OGC_F8) {  // E4M3: the eight-wave shape only
+            if (a->act == OGC_ACT_RELU && !a->out_f32) return launch_dma_io<OGC_F8, 1, 1>(xp, op, a, s);
+            return launch_dma_io<OGC_F8, 1, 0>(xp, op, a, s);
+        }
     }
     return (int)hipErrorInvalidValue;  // the plan never selects this kernel for fp32
 }
@@ -1562,7 +1610,7 @@ extern "C" const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, i
     static char names[4][OGC_NUM_TILES][2][2][3][48];
     if (dtype < 0 || dtype > 3 || tile < 0 || tile >= OGC_NUM_TILES) return "?";
     const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8 || tile == OGC_TILE_DMAK2;
-    const int epi = (stream && split) ? 2 : (stream && dtype == OGC_I8 && act == OGC_ACT_RELU && !out_f32);
+    const int epi = (stream && split) ? 2 : (stream && (dtype == OGC_I8 || dtype == OGC_F8) && act == OGC_ACT_RELU && !out_f32);
     if (epi == 2) out_plain = 0;
     char* n = names[dtype][tile][x_plain != 0][out_plain != 0][epi];
     if (!n[0]) {

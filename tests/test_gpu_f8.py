@@ -195,12 +195,15 @@ def test_stream_kernel(oracle_mod):
     d = DeviceMLP(wl, binding.OGC_MODE_PER_LAYER, overrides={"tile": 4})
     names = [binding.ogc_mlp_kernel_name(d.mlp.plan, l) for l in range(3)]
     d.close()
-    assert names == ["ogc_layer_dma_kernel<3, 1, 1, 0, 0>", "ogc_layer_dma_kernel<3, 1, 0, 0, 0>", "ogc_layer_dma_kernel<3, 1, 0, 1, 0>"], names
+    # (the last template argument: 1 = the ReLU-requantize epilogue, 0 = the general one)
+    assert names == ["ogc_layer_dma_kernel<3, 1, 1, 0, 1>", "ogc_layer_dma_kernel<3, 1, 0, 0, 0>", "ogc_layer_dma_kernel<3, 1, 0, 1, 0>"], names
     check_chain(oracle_mod, wl, "per_layer", tile=4)
     check_chain(oracle_mod, synth.make_mlp("f8", 16500, [512, 1024, 512], [RELU, RELU], seed=2201, name="stream-260-tiles"), "per_layer", tile=4)
     check_chain(oracle_mod, synth.make_mlp("f8", 300, [4096, 256, 2048], [RELU, NONE], seed=2202, has_bias=False, name="stream-long-k"),
                 "per_layer", tile=4)
     check_chain(oracle_mod, synth.make_mlp("f8", 1, [64 * 4, 1], [NONE], seed=2203, name="stream-1x1"), "per_layer", tile=4)
+    # ReLU-requantize epilogue into plain rows that are not whole 64-byte segments, and into a ragged last channel block
+    check_chain(oracle_mod, synth.make_mlp("f8", 333, [256, 328, 200], [RELU, RELU], seed=2205, name="stream-relu-ragged"), "per_layer", tile=4)
     # the plan's own choice for a large layer is this kernel
     big = synth.make_mlp("f8", 8192, [1024, 1024, 1024], [RELU, RELU], seed=2204, has_bias=False, name="stream-auto")
     d = DeviceMLP(big, binding.OGC_MODE_AUTO)
