@@ -103,8 +103,21 @@ def check_stream_kernel_registers(verbose: bool = True) -> None:
         checked += 1
     if checked == 0:
         raise RuntimeError("no stream kernels found in the assembly")
+    # Kernels with one fixed epilogue (last template argument 1, 3, 4: ReLU / no activation / GELU with a requantized
+    # result, and 2: split-K partials) must not touch scratch memory: a reload of a spilled register in the code between
+    # the assembly blocks makes the compiler wait for every outstanding vector-memory operation, the ring's direct loads
+    # included (a third more time per launch when it happened).
+    spilling = 0
+    for m in re.finditer(r"\.name:\s+(_Z20ogc_layer_dma_kernel\w+)\s*\n\s+\.private_segment_fixed_size:\s+(\d+)", text):
+        name, scratch = m.group(1), int(m.group(2))
+        fixed = re.search(r"Li([1-4])EEv", name)
+        if scratch > 0:
+            spilling += 1
+            if fixed:
+                raise RuntimeError("%s uses %d bytes of scratch memory per lane (register spills)" % (name, scratch))
     if verbose:
-        print("stream kernels checked: %d (compiler writes nothing at or above v80, no calls)" % checked, flush=True)
+        print("stream kernels checked: %d (compiler writes nothing at or above v80, no calls; %d kernels of the general "
+              "epilogue use scratch memory)" % (checked, spilling), flush=True)
 
 
 if __name__ == "__main__":

@@ -403,12 +403,65 @@ OGC_DEV void store_plain_rows64(const v4i& c0, const v4i& c1, const OgcLayerArgs
     }
 }
 
+// One value through activation ACT (a compile-time constant here: the caller branches once per block, not per value).
+template <int ACT> OGC_DEV float act_apply1(float y) {
+    if constexpr (ACT == OGC_ACT_RELU) return __builtin_fmaxf(y, 0.0f);
+    if constexpr (ACT == OGC_ACT_GELU_TANH) {  // as in act_apply16
+        const float arg = y * __builtin_fmaf(-0.10294324f, y * y, -2.3022082f);
+        return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(arg));
+    }
+    return y;
+}
+
+// A quantized block with activation ACT (none, ReLU or GELU) and a requantized result (u8 or E4M3 codes), four values at
+// a time: each quad is scaled, activated, rounded and packed into its dword on its own.  Same results as
+// epilogue_values + pack_block:
+//   int8: clamp(rne(t) + zp, 0, 255) = rne(med3(t, -zp, 255 - zp)) + zp, both bounds being integers; the sum of two
+//         integers is exact and `v_cvt_pk_u8_f32` then packs it unchanged; `internal` results are stored as s8 (x ^ 0x80);
+//   E4M3: the clamp to +-448 that keeps NaN, then the packed conversion (nearest, ties to even).
+template <int DT, int ACT>
+OGC_DEV v4i requant_block_act(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, const BlockParams& p, bool internal) {
+    static_assert(Quant<DT>::yes, "requantized results are those of the int8 and E4M3 schemes");
+    const float inv = a.inv_cs, zp = a.zp_out, lo = -zp, hi = a.q_hi;
+    uint32_t dw[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        float t[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float f;
+            if constexpr (DT == OGC_I8) f = (float)(acc[4 * g + e] + p.c[g][e]);
+            else f = acc[4 * g + e];
+            t[e] = act_apply1<ACT>(__builtin_fmaf(f, p.s[g][e], p.b[g][e])) * inv;
+        }
+        if constexpr (DT == OGC_I8) {
+            uint32_t q = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                q = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_rintf(__builtin_amdgcn_fmed3f(t[e], lo, hi)) + zp, e, q);
+            dw[g] = internal ? (q ^ 0x80808080u) : q;
+        } else {
+            dw[g] = f32x4_to_e4m3x4(t[0], t[1], t[2], t[3]);
+        }
+    }
+    swap32(dw[0], dw[2]);
+    swap32(dw[1], dw[3]);
+    return (v4i){(int)dw[0], (int)dw[2], (int)dw[1], (int)dw[3]};  // 16 consecutive channels from n0+16h
+}
+// The requantizing arithmetic of a block whose epilogue the caller has fixed at compile time (the stream kernel's EPI:
+// 1 ReLU, 3 no activation, 4 GELU), for a result in the caller's plain rows.
+template <int DT, int EPI> OGC_DEV v4i requant_block_epi(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, const BlockParams& p) {
+    if constexpr (EPI == 1) return requant_block_relu<DT>(acc, a, p);
+    else return requant_block_act<DT, EPI == 3 ? OGC_ACT_NONE : OGC_ACT_GELU_TANH>(acc, a, p, false);
+}
+
 // PATH: -1 = pick the int8 ReLU-requantize fast path at run time, 1 = the caller knows it applies (only that
-// code is generated), 0 = the caller knows it does not.
+// code is generated), 0 = the caller knows it does not; 3 / 4 = the caller knows: a quantized layer without activation /
+// with GELU and a requantized result (only that code is generated).
 template <int DT, int OUT_PLAIN, bool CALLS = true, int PATH = -1, typename YP>
 OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerArgs& a, const BlockParams& p, int n0, int m0,
                             int lane, YP yblk) {
-    if constexpr (DT == OGC_I8 && PATH != 0) {
+    if constexpr (DT == OGC_I8 && (PATH == -1 || PATH == 1)) {
         if (PATH == 1 || (a.act == OGC_ACT_RELU && !a.out_f32)) {
             epilogue_block_i8_relu<OUT_PLAIN>(acc, a, p, n0, m0, lane, yblk);
             return;
@@ -419,6 +472,16 @@ OGC_DEV void epilogue_block(const typename AccT<DT>::type& acc, const OgcLayerAr
         return;
     }
     const int h = lane >> 5, mm = lane & 31;
+    if constexpr (Quant<DT>::yes && (PATH == 3 || PATH == 4)) {  // the caller knows: no activation / GELU, requantized result
+        const v4i ch = requant_block_act<DT, PATH == 3 ? OGC_ACT_NONE : OGC_ACT_GELU_TANH>(acc, a, p, DT == OGC_I8 && !OUT_PLAIN);
+        if constexpr (OUT_PLAIN) {
+            const v4i arr[1] = {ch};
+            store_plain<1>(arr, a, m0 + mm, n0 + 16 * h);
+        } else {
+            store16(yblk + ((size_t)((n0 >> 5) * 2 + h) * 32 + mm) * 16, ch);
+        }
+        return;
+    }
     float out[16];
     epilogue_values<DT, CALLS>(acc, a, p, out);
     constexpr int E = Elt<DT>::size;
@@ -1356,17 +1419,35 @@ static int launch_dma_io(int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
     return op ? launch_dma_t<DT, SHAPE, 0, 1, EPI>(a, s) : launch_dma_t<DT, SHAPE, 0, 0, EPI>(a, s);
 }
 
-// EPI = 1: int8 layer with ReLU and a requantized result (the five-op epilogue only); 2: split-K partials,
-// followed by the reduction pass that owns the epilogue
+// EPI = 1: quantized layer with ReLU and a requantized result (that epilogue only); 2: split-K partials, followed by the
+// reduction pass that owns the epilogue; 3 / 4 (not the k-sliced shape, whose reduction across the k groups needs the
+// registers): quantized layer without activation / with GELU and a requantized result; 0: everything else, activation and result type looked up at run time.  One epilogue per kernel
+// is not a matter of a few branches: with all of them in one kernel the compiler runs out of the 80 registers it is left
+// with and spills, and a reload from scratch memory in the code between the assembly blocks makes it wait for EVERY
+// outstanding vector-memory operation, the ring's direct loads included (measured: 45 instead of 34 us per launch).
+static int stream_epi(const OgcLayerArgs* a, bool k_sliced) {
+    if (a->out_f32) return 0;
+    if (a->act == OGC_ACT_RELU) return 1;
+    if (!k_sliced && a->act == OGC_ACT_NONE) return 3;
+    if (!k_sliced && a->act == OGC_ACT_GELU_TANH) return 4;
+    return 0;
+}
+template <int DT, int SHAPE>
+static int launch_dma_quant(int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
+    const int epi = stream_epi(a, SHAPE == 2);
+    if (epi == 1) return launch_dma_io<DT, SHAPE, 1>(xp, op, a, s);
+    if constexpr (SHAPE != 2) {
+        if (epi == 3) return launch_dma_io<DT, SHAPE, 3>(xp, op, a, s);
+        if (epi == 4) return launch_dma_io<DT, SHAPE, 4>(xp, op, a, s);
+    }
+    return launch_dma_io<DT, SHAPE, 0>(xp, op, a, s);
+}
 template <int SHAPE>
 static int launch_dma_dtype(int dtype, int xp, int op, const OgcLayerArgs* a, hipStream_t s) {
     if constexpr (SHAPE == 2) {
         if (a->ksplit_log2 > 0) return (int)hipErrorInvalidValue;  // the plan never splits this shape between workgroups
         if (dtype == OGC_BF16) return launch_dma_io<OGC_BF16, 2, 0>(xp, op, a, s);
-        if (dtype == OGC_I8) {
-            if (a->act == OGC_ACT_RELU && !a->out_f32) return launch_dma_io<OGC_I8, 2, 1>(xp, op, a, s);
-            return launch_dma_io<OGC_I8, 2, 0>(xp, op, a, s);
-        }
+        if (dtype == OGC_I8) return launch_dma_quant<OGC_I8, 2>(xp, op, a, s);
         return (int)hipErrorInvalidValue;
     } else
     if (a->ksplit_log2 > 0) {
@@ -1378,15 +1459,9 @@ static int launch_dma_dtype(int dtype, int xp, int op, const OgcLayerArgs* a, hi
         return dtype == OGC_BF16 ? launch_splitk_reduce<OGC_BF16>(op, a, s) : launch_splitk_reduce<OGC_I8>(op, a, s);
     }
     if (dtype == OGC_BF16) return launch_dma_io<OGC_BF16, SHAPE, 0>(xp, op, a, s);
-    if (dtype == OGC_I8) {
-        if (a->act == OGC_ACT_RELU && !a->out_f32) return launch_dma_io<OGC_I8, SHAPE, 1>(xp, op, a, s);
-        return launch_dma_io<OGC_I8, SHAPE, 0>(xp, op, a, s);
-    }
+    if (dtype == OGC_I8) return launch_dma_quant<OGC_I8, SHAPE>(xp, op, a, s);
     if constexpr (SHAPE == 1) {
-        if (dtype == OGC_F8) {  // E4M3: the eight-wave shape only
-            if (a->act == OGC_ACT_RELU && !a->out_f32) return launch_dma_io<OGC_F8, 1, 1>(xp, op, a, s);
-            return launch_dma_io<OGC_F8, 1, 0>(xp, op, a, s);
-        }
+        if (dtype == OGC_F8) return launch_dma_quant<OGC_F8, 1>(xp, op, a, s);  // E4M3: the eight-wave shape only
     }
     return (int)hipErrorInvalidValue;  // the plan never selects this kernel for fp32
 }
@@ -1607,10 +1682,18 @@ extern "C" int ogc_launch_prepack_params(int dtype, const void* w, const float* 
 
 // Kernel names with their template arguments, spelled the way a kernel trace prints them.
 extern "C" const char* ogc_layer_kernel_name(int dtype, int tile, int x_plain, int out_plain, int act, int out_f32, int split) {
-    static char names[4][OGC_NUM_TILES][2][2][3][48];
+    static char names[4][OGC_NUM_TILES][2][2][5][48];
     if (dtype < 0 || dtype > 3 || tile < 0 || tile >= OGC_NUM_TILES) return "?";
     const bool stream = tile == OGC_TILE_DMA || tile == OGC_TILE_DMA8 || tile == OGC_TILE_DMAK2;
-    const int epi = (stream && split) ? 2 : (stream && (dtype == OGC_I8 || dtype == OGC_F8) && act == OGC_ACT_RELU && !out_f32);
+    int epi = 0;
+    if (stream && split) {
+        epi = 2;
+    } else if (stream && (dtype == OGC_I8 || dtype == OGC_F8)) {
+        OgcLayerArgs probe;
+        memset(&probe, 0, sizeof probe);
+        probe.act = act, probe.out_f32 = out_f32;
+        epi = stream_epi(&probe, tile == OGC_TILE_DMAK2);
+    }
     if (epi == 2) out_plain = 0;
     char* n = names[dtype][tile][x_plain != 0][out_plain != 0][epi];
     if (!n[0]) {

@@ -500,7 +500,7 @@ template <int DT, int B> OGC_DEV typename AccT<DT>::type take_acc_block() {
 // it; XCD x owns the contiguous tile range [x*tiles_per_xcd, (x+1)*tiles_per_xcd) and its slots walk that
 // range with stride `slots`, so the workgroups of one XCD always work on neighbouring tiles (the n-tiles of
 // one batch tile share its activations through that XCD's L2).
-// EPI: 1 = ReLU + requantize epilogue only (int8 or E4M3), 0 = every other combination, 2 = split-K: `tiles_n` counts
+// EPI: 1 / 3 / 4 = requantizing epilogue with ReLU / no activation / GELU only (int8 or E4M3), 0 = every other combination, 2 = split-K: `tiles_n` counts
 // (channel tile, k range) pairs, a workgroup accumulates one k range of its tile and stores the raw accumulators
 template <int DT, int SHAPE, int X_PLAIN, int OUT_PLAIN, int EPI>
 __global__ void __launch_bounds__(StreamCfg<SHAPE>::NT, 2) __attribute__((amdgpu_num_vgpr(40)))
@@ -511,6 +511,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     constexpr int TN = C::TN, TM = C::TM;
     constexpr bool FLIP = X_PLAIN && DT == OGC_I8;
     static_assert(DT != OGC_F8 || (SHAPE == 1 && EPI != 2), "E4M3 runs the eight-wave shape and is not split along K");
+    static_assert(EPI <= 2 || (DT != OGC_BF16 && SHAPE != 2), "the single-activation requantizing epilogues: quantized dtypes, not the k-sliced shape");
     extern __shared__ __align__(1024) uint8_t smem[];
     // v80..v255 are used by the assembly below only; naming the last one makes the kernel own all 256.
     asm volatile("; operand sets and accumulators live in v80..v255" ::: "v255");
@@ -811,7 +812,7 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             next_tile(next_n, next_m);
             if (tiles_left > 1 && KT >= 4) stage_params(next_n >> LS, pbuf ^ 1);
             bool done = false;
-            if constexpr (EPI == 1 && OUT_PLAIN && C::ROWS64 > 0) {
+            if constexpr ((EPI == 1 || EPI == 3 || EPI == 4) && OUT_PLAIN && C::ROWS64 > 0) {
                 if (a.y_vec_ok && (a.N & 63) == 0) {
                     // whole 64-byte row segments: the two channel blocks of the same rows one after the other
                     lds_u8* const scratch = (lds_u8*)smem + C::RING + 2 * C::PARAMS + wave * 2048;
@@ -820,9 +821,9 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
                         const int m0 = m_base + J * 32;
                         if (m0 < a.M) {  // (n_base < N: N is a multiple of 64 and the tile starts inside it, or the wave has no work)
                             read_params(0);
-                            const v4i c0 = requant_block_relu<DT>(take_acc_block<DT, J>(), a, prm);
+                            const v4i c0 = requant_block_epi<DT, EPI>(take_acc_block<DT, J>(), a, prm);
                             read_params(1);
-                            const v4i c1 = requant_block_relu<DT>(take_acc_block<DT, 4 + J>(), a, prm);
+                            const v4i c1 = requant_block_epi<DT, EPI>(take_acc_block<DT, 4 + J>(), a, prm);
                             store_plain_rows64(c0, c1, a, n_base, m0, lane, scratch);
                         }
                     };

@@ -195,8 +195,8 @@ def test_stream_kernel(oracle_mod):
     d = DeviceMLP(wl, binding.OGC_MODE_PER_LAYER, overrides={"tile": 4})
     names = [binding.ogc_mlp_kernel_name(d.mlp.plan, l) for l in range(3)]
     d.close()
-    # (the last template argument: 1 = the ReLU-requantize epilogue, 0 = the general one)
-    assert names == ["ogc_layer_dma_kernel<3, 1, 1, 0, 1>", "ogc_layer_dma_kernel<3, 1, 0, 0, 0>", "ogc_layer_dma_kernel<3, 1, 0, 1, 0>"], names
+    # (the last template argument: the requantizing epilogue with ReLU (1), GELU (4), no activation (3))
+    assert names == ["ogc_layer_dma_kernel<3, 1, 1, 0, 1>", "ogc_layer_dma_kernel<3, 1, 0, 0, 4>", "ogc_layer_dma_kernel<3, 1, 0, 1, 3>"], names
     check_chain(oracle_mod, wl, "per_layer", tile=4)
     check_chain(oracle_mod, synth.make_mlp("f8", 16500, [512, 1024, 512], [RELU, RELU], seed=2201, name="stream-260-tiles"), "per_layer", tile=4)
     check_chain(oracle_mod, synth.make_mlp("f8", 300, [4096, 256, 2048], [RELU, NONE], seed=2202, has_bias=False, name="stream-long-k"),

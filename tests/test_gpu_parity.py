@@ -153,6 +153,39 @@ def test_pipelined_kernel_plain_input(oracle_mod, dtype, tile):
 
 
 @pytest.mark.parametrize("tile", [3, 4])
+def test_stream_kernel_requantizing_epilogues(oracle_mod, tile):
+    """Int8 layers without activation and with GELU on the stream kernel, each with an epilogue of its own (last template
+    argument 3 / 4; 1 is ReLU's): blocked and plain results, whole 64-byte row segments and ragged ones, several tiles
+    per workgroup.  Without activation the result is the oracle's bit for bit.  With GELU the requantized byte is decided
+    by a transcendental function that the kernel evaluates with the hardware's exp2 and reciprocal (about an ulp of fp32
+    each) and the oracle with libm: a byte may differ by one where y / c_s lies within that error of a rounding boundary,
+    which a few values in a million do."""
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    wl = synth.make_mlp("i8", 700, [256, 512, 320, 128], [NONE, RELU, NONE], seed=760, name="stream-none")
+    d = DeviceMLP(wl, binding.OGC_MODE_PER_LAYER, overrides={"tile": tile})
+    names = [binding.ogc_mlp_kernel_name(d.mlp.plan, l) for l in range(3)]
+    d.close()
+    shape = tile - 3
+    assert names == ["ogc_layer_dma_kernel<2, %d, 1, 0, 3>" % shape, "ogc_layer_dma_kernel<2, %d, 0, 0, 1>" % shape,
+                     "ogc_layer_dma_kernel<2, %d, 0, 1, 3>" % shape], names
+    check(wl, "per_layer", oracle_mod, tile=tile)
+    check(synth.make_mlp("i8", 9000, [192, 520, 300], [NONE, NONE], seed=761, name="stream-none-many-tiles"), "per_layer", oracle_mod, tile=tile)
+    check(synth.make_mlp("i8", 333, [256, 328, 200], [NONE, NONE], seed=762, name="stream-none-ragged"), "per_layer", oracle_mod, tile=tile, ld_y=208)
+    for dims, seed in (([256, 512, 320, 128], 763), ([192, 520, 300], 764)):
+        wl = synth.make_mlp("i8", 2100, dims, [GELU] * (len(dims) - 1), seed=seed, name="stream-gelu")
+        d = DeviceMLP(wl, binding.OGC_MODE_PER_LAYER, overrides={"tile": tile})
+        assert binding.ogc_mlp_kernel_name(d.mlp.plan, 0) == "ogc_layer_dma_kernel<2, %d, 1, 0, 4>" % shape
+        d.close()
+        got, _ = run_gpu(wl, "per_layer", tile)
+        ref = oracle_mod.mlp(wl)
+        diff = np.abs(got[:, :ref.shape[1]].astype(np.int32) - ref.astype(np.int32))
+        # (a moved byte of one layer moves the next layer's sums: the chain as a whole is held to one step and a small share)
+        assert diff.max() <= 1 and (diff > 0).mean() < 2e-3, (int(diff.max()), float((diff > 0).mean()))
+        print("stream-gelu", dims, "bytes that differ by one: %.2e" % (diff > 0).mean(), flush=True)
+
+
+@pytest.mark.parametrize("tile", [3, 4])
 @pytest.mark.parametrize("dtype", ["i8", "bf16"])
 def test_split_k(oracle_mod, dtype, tile):
     """The reduction axis cut into 2, 4 and 8 ranges (partial accumulators + the reduction pass that owns the
