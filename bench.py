@@ -58,6 +58,40 @@ def time_steps(dev, steps, warmup):
     return wall, e0.elapsed_time(e1) * 1e-3 / steps
 
 
+def clock_report(dev, launch_idxs, work, peak):
+    """The clock the chip actually gives the dominant kernel: diagnostic runs in which every workgroup stores the 100 MHz
+    wall clock and the shader cycle counter at its start and end (ogc_mlp_run_clocked), repeated back to back after the
+    timed region so that the chip is in the same state.  `peak` assumes 2.4 GHz; `mfma_cycles` is the work at the
+    matrix pipes' full rate (2048 int8 or 1024 bf16 operations per clock and SIMD), so `matrix_pipe_utilisation` = mfma_cycles /
+    cycles_per_launch is the kernel's efficiency in cycles, whatever the clock, and peak_at_clock what 100 % of it
+    would give at that clock."""
+    import numpy as np
+
+    for _ in range(100):
+        dev.run()
+    mhz, cycles, alive = [], [], []
+    for _ in range(20):
+        c = dev.run_clocked()
+        for j in launch_idxs:
+            w = c[j][c[j][:, 2] != 0]
+            if not len(w):
+                continue
+            dt_us = (w[:, 2] - w[:, 0]) / 100.0
+            dc = (w[:, 3] - w[:, 1]).astype(np.float64)
+            mhz.append(float((dc / dt_us).mean()))
+            cycles.append(float(dc.mean()))
+            alive.append(float(dt_us.mean()))
+    if not mhz:
+        return None
+    # operations per clock of one SIMD's matrix pipe (the published peaks are these x 1024 SIMDs x 2.4 GHz, rounded)
+    ops_per_clock_per_simd = {5.0e15: 2048.0, 2.5e15: 1024.0, 157.3e12: 64.0}[peak]
+    mfma_cycles = work / 1024.0 / ops_per_clock_per_simd
+    m, cyc = sum(mhz) / len(mhz), sum(cycles) / len(cycles)
+    return {"shader_mhz": round(m, 1), "cycles_per_launch": round(cyc), "workgroup_alive_us": round(sum(alive) / len(alive), 2),
+            "mfma_cycles": round(mfma_cycles), "matrix_pipe_utilisation": round(mfma_cycles / cyc, 4),
+            "peak_at_clock": round(peak * m / 2400.0 / 1e12, 1)}
+
+
 def time_graph_replay(dev, runs_per_graph=50, replays=6):
     """The same runs recorded once into a HIP graph (stream capture of `runs_per_graph` calls) and replayed: what a
     caller whose loop is bound by the launch path of the host gets.  Returns seconds per run."""
@@ -433,6 +467,8 @@ def main():
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = read_traffic() if args.config == 5 else None
     roof.update(dom)
+    if head["mode"] == "per_layer" and head["bound"] == "mfma":
+        roof["clock"] = clock_report(dev, idxs, work, peak)
     dev.close()
     if args.copy_calibration:
         copy_calibration(torch)

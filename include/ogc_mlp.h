@@ -223,6 +223,19 @@ size_t ogc_mlp_static_workspace_limit(void);
 ogc_status ogc_quantize_e4m3(const float* x /*device*/, uint8_t* out /*device*/, size_t n, float scale, void* stream);
 ogc_status ogc_dequantize_e4m3(const uint8_t* x /*device*/, float* out /*device*/, size_t n, float scale, void* stream);
 
+/* Diagnostic run: ogc_mlp_run, with every workgroup of the stream kernel (per-layer mode, tiles 3-5) recording when it
+ * ran on two clocks: the 100 MHz wall clock and the shader cycle counter, whose rate is the clock the chip actually gives
+ * the kernel (the published peaks assume 2.4 GHz; under matrix-instruction load the power limit sets less).  clocks:
+ * device, 8-byte aligned, ogc_mlp_num_launches() x ogc_mlp_clock_words_per_launch() 64-bit words; launch l, workgroup g
+ * writes words [l * words_per_launch + 4 g .. + 3] = wall clock at start, cycle counter at start, wall clock at end,
+ * cycle counter at end (of the workgroup's first wavefront).  Launches of other kernels and workgroups that do not exist
+ * leave their words as they are: clear the buffer first.  The section on measurement (Section VII times whole operations;
+ * this says at what clock) is what it serves; `bench.py` reports it.
+ * OGC_ERR_INVALID_ARG: NULL clocks; OGC_ERR_ALIGNMENT: clocks not 8-byte aligned; otherwise as ogc_mlp_run. */
+ogc_status ogc_mlp_run_clocked(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream,
+                               int64_t* clocks /*device*/);
+size_t ogc_mlp_clock_words_per_launch(void);
+
 /* Number of timed launch steps of one ogc_mlp_run: 1 for the fused-chain kernel, n_layers otherwise (a layer
  * whose reduction axis is split runs two kernels, the k ranges and the pass that adds them, and counts as one). */
 ogc_status ogc_mlp_num_launches(ogc_mlp_plan_t plan, int32_t* n /*host*/);

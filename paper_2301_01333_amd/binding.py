@@ -27,6 +27,7 @@ EXPORTS = [
     "ogc_mlp_buffer_assignment", "ogc_mlp_prepack_weights", "ogc_mlp_run", "ogc_mlp_destroy",
     "ogc_status_string", "ogc_mlp_kernel_name", "ogc_mlp_num_launches", "ogc_mlp_run_profiled", "ogc_mlp_blocked_bytes", "ogc_mlp_estimated_us", "ogc_mlp_mode_estimates",
     "ogc_mlp_run_static", "ogc_mlp_static_workspace_limit", "ogc_mlp_plan_with_overrides", "ogc_mlp_check", "ogc_mlp_test_barrier", "ogc_mlp_cluster_layout",
+    "ogc_mlp_run_clocked", "ogc_mlp_clock_words_per_launch",
     "ogc_quantize_e4m3", "ogc_dequantize_e4m3",
     "ogc_mha_validate", "ogc_mha_run", "ogc_mha_kernel_name", "ogc_mha_i8_validate", "ogc_mha_run_i8", "ogc_mha_i8_kernel_name",
 ]
@@ -110,6 +111,10 @@ def lib():
         l.ogc_mlp_static_workspace_limit.restype = sz
         l.ogc_mlp_num_launches.argtypes = [vp, ctypes.POINTER(i32)]
         l.ogc_mlp_num_launches.restype = i32
+        l.ogc_mlp_run_clocked.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        l.ogc_mlp_run_clocked.restype = i32
+        l.ogc_mlp_clock_words_per_launch.argtypes = []
+        l.ogc_mlp_clock_words_per_launch.restype = ctypes.c_size_t
         l.ogc_mlp_run_profiled.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
         l.ogc_mlp_run_profiled.restype = i32
         l.ogc_mlp_destroy.argtypes = [vp]
@@ -280,6 +285,14 @@ def ogc_mlp_num_launches(plan: int) -> int:
     return v.value
 
 
+def ogc_mlp_run_clocked(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, workspace_ptr: int, clocks_ptr: int, stream: int = 0) -> None:
+    _check(lib().ogc_mlp_run_clocked(plan, x_ptr, y_ptr, packed_ptr, workspace_ptr or None, stream, clocks_ptr), "ogc_mlp_run_clocked")
+
+
+def ogc_mlp_clock_words_per_launch() -> int:
+    return int(lib().ogc_mlp_clock_words_per_launch())
+
+
 def ogc_mlp_run_profiled(plan: int, x_ptr: int, y_ptr: int, packed_ptr: int, workspace_ptr: int, stream: int = 0):
     """Returns the list of per-launch durations in milliseconds."""
     n = ogc_mlp_num_launches(plan)
@@ -415,6 +428,10 @@ class FusedMLP:
     def check(self) -> int:
         """OGC_OK, or OGC_ERR_TIMEOUT if a barrier wait of the cooperative mode gave up since the last check."""
         return ogc_mlp_check(self.plan, self.packed.data_ptr(), self._stream())
+
+    def run_clocked(self, x, y, clocks) -> None:
+        ogc_mlp_run_clocked(self.plan, x.data_ptr(), y.data_ptr(), self.packed.data_ptr(),
+                            self.workspace.data_ptr() if self.workspace_bytes else 0, clocks.data_ptr(), self._stream())
 
     def run_profiled(self, x, y):
         return ogc_mlp_run_profiled(self.plan, x.data_ptr(), y.data_ptr(), self.packed.data_ptr(),

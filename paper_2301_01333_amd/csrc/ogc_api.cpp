@@ -687,7 +687,7 @@ ogc_status ogc_mlp_prepack_weights(ogc_mlp_plan_t plan, const void* const* w, co
 // Shared body of ogc_mlp_run / ogc_mlp_run_profiled.  With ev != NULL, event ev[i] is recorded on the stream
 // before launch i and ev[n] after the last one.
 static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream,
-                           hipEvent_t* ev) {
+                           hipEvent_t* ev, long long* clocks = nullptr) {
     if (!plan || !x || !y || !packed) return OGC_ERR_INVALID_ARG;
     if (!plan->prepacked.load()) return OGC_ERR_NOT_PREPACKED;
     if (((uintptr_t)packed & 255) != 0) return OGC_ERR_ALIGNMENT;
@@ -788,6 +788,8 @@ static ogc_status run_impl(ogc_mlp_plan_t plan, const void* x, void* y, const vo
             a.pmb = plan->mp / 32;
             a.pnb = plan->layers[l].npw / 32;
         }
+        const int t = plan->layers[l].tile;
+        if (clocks && (t == OGC_TILE_DMA || t == OGC_TILE_DMA8 || t == OGC_TILE_DMAK2)) a.clocks = clocks + (size_t)l * OGC_CLOCK_WORDS_PER_LAUNCH;
         if (ev && hipEventRecord(ev[l], (hipStream_t)stream) != hipSuccess) return OGC_ERR_DEVICE;
         const int rc = ogc_launch_layer(plan->desc.dtype, plan->layers[l].tile, l == 0 && !x_blocked, l == L - 1 && !y_blocked, &a,
                                         stream);
@@ -810,6 +812,14 @@ ogc_status ogc_mlp_run_static(ogc_mlp_plan_t plan, const void* x, void* y, const
 }
 
 size_t ogc_mlp_static_workspace_limit(void) { return (size_t)OGC_STATIC_SCRATCH_BYTES; }
+
+ogc_status ogc_mlp_run_clocked(ogc_mlp_plan_t plan, const void* x, void* y, const void* packed, void* workspace, void* stream,
+                               int64_t* clocks) {
+    if (!clocks || ((uintptr_t)clocks & 7) != 0) return clocks ? OGC_ERR_ALIGNMENT : OGC_ERR_INVALID_ARG;
+    return run_impl(plan, x, y, packed, workspace, stream, nullptr, (long long*)clocks);
+}
+
+size_t ogc_mlp_clock_words_per_launch(void) { return (size_t)OGC_CLOCK_WORDS_PER_LAUNCH; }
 
 ogc_status ogc_quantize_e4m3(const float* x, uint8_t* out, size_t n, float scale, void* stream) {
     if ((n && (!x || !out)) || !(scale > 0.0f) || !std::isfinite(scale)) return OGC_ERR_INVALID_ARG;

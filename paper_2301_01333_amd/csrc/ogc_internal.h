@@ -56,6 +56,9 @@ struct OgcLayerArgs {
     int32_t ksplit_log2;
     uint8_t* partial;
     int32_t pmb, pnb;      // 32-row / 32-channel blocks per range in `partial`
+    // Stream kernel, diagnostic runs only (NULL otherwise): every workgroup's first thread stores the 100 MHz wall clock and
+    // the shader cycle counter at its start and at its end, four 64-bit words per workgroup (ogc_mlp_run_clocked)
+    long long* clocks;
 };
 
 struct OgcChainArgs {
@@ -74,6 +77,7 @@ struct OgcChainArgs {
     OgcLayerArgs layer[OGC_MAX_LAYERS];
 };
 
+#define OGC_CLOCK_WORDS_PER_LAUNCH 2048  // ogc_mlp_run_clocked: 64-bit words per launch (at most 512 workgroups x 4)
 #define OGC_STATIC_SCRATCH_BYTES (8u << 20)  // the library's own workspace for ogc_mlp_run_static, per GPU
 
 #define OGC_SYNC_STRIDE 16    // 64-bit words between the counters of two row tiles: a 128-byte line each

@@ -526,6 +526,10 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
     t_end = t_end < tiles_total ? t_end : tiles_total;
     const int first_tile = xcd * tiles_per_xcd + (blockIdx.x >> 3);
     if (first_tile >= t_end) return;
+    if (a.clocks && tid == 0) {  // diagnostic runs: when this workgroup started, on both clocks
+        a.clocks[blockIdx.x * 4] = wall_clock64();
+        a.clocks[blockIdx.x * 4 + 1] = clock64();
+    }
     // (integer divisions run on the vector ALU: readfirstlane tells the compiler the results are wave-uniform)
     const int my_tiles = __builtin_amdgcn_readfirstlane((t_end - first_tile + slots - 1) / slots);
     const int total_steps = my_tiles * KT;
@@ -905,6 +909,10 @@ ogc_layer_dma_kernel(const OgcLayerArgs a, int tiles_n, int tiles_total, int til
             }
             pbuf ^= 1;
         }
+    }
+    if (a.clocks && tid == 0) {  // ... and when its first wave had issued its last instruction
+        a.clocks[blockIdx.x * 4 + 2] = wall_clock64();
+        a.clocks[blockIdx.x * 4 + 3] = clock64();
     }
 }
 

@@ -50,6 +50,16 @@ class DeviceMLP:
     def run_profiled(self):
         return self.mlp.run_profiled(self.x, self.y)
 
+    def run_clocked(self):
+        """One run with the stream kernel's workgroups recording their clocks; returns an int64 array
+        [launch][workgroup][wall start, cycles start, wall end, cycles end] (zeros where nothing was recorded)."""
+        words = binding.ogc_mlp_clock_words_per_launch()
+        n = binding.ogc_mlp_num_launches(self.mlp.plan)
+        buf = self.torch.zeros((n * words,), dtype=self.torch.int64, device="cuda")
+        self.mlp.run_clocked(self.x, self.y, buf)
+        self.torch.cuda.synchronize()
+        return buf.cpu().numpy().reshape(n, words // 4, 4)
+
     def result(self) -> np.ndarray:
         self.torch.cuda.synchronize()
         full = self.y.cpu().numpy().view(self.out_np_dtype).reshape(self.wl.m, self.ld_y)

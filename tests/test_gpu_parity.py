@@ -152,6 +152,37 @@ def test_pipelined_kernel_plain_input(oracle_mod, dtype, tile):
           ld_y=72)
 
 
+def test_clocked_run(oracle_mod):
+    """The diagnostic run that has every workgroup of the stream kernel record the wall clock and the shader cycle
+    counter: same result as an ordinary run, one record per workgroup of each stream-kernel launch, none for the other
+    kernels, clocks that advance, and a cycle counter rate in the range of this part's shader clock."""
+    from paper_2301_01333_amd.harness import DeviceMLP
+
+    wl = synth.make_config(5, m=4096)
+    d = DeviceMLP(wl, binding.OGC_MODE_PER_LAYER, overrides={"tile": 4})
+    d.run()
+    want = d.result().copy()
+    c = d.run_clocked()
+    got = d.result().copy()
+    assert np.array_equal(got, want) and np.array_equal(got[:, :wl.layers[-1].n], oracle_mod.mlp(wl))
+    assert c.shape[0] == 4
+    for l in range(4):
+        assert binding.ogc_mlp_kernel_name(d.mlp.plan, l).startswith("ogc_layer_dma_kernel")
+        rec = c[l][c[l][:, 2] != 0]
+        assert len(rec) == 64, len(rec)   # 16 x 4 tiles of 256 x 256: one workgroup each
+        assert (rec[:, 2] > rec[:, 0]).all() and (rec[:, 3] > rec[:, 1]).all()
+        mhz = (rec[:, 3] - rec[:, 1]) / ((rec[:, 2] - rec[:, 0]) / 100.0)
+        assert 300.0 < mhz.mean() < 3000.0, mhz.mean()
+    d.close()
+    # a chain that runs no stream kernel records nothing
+    d = DeviceMLP(synth.make_config(5, m=96), binding.OGC_MODE_PER_LAYER, overrides={"tile": 1})
+    c = d.run_clocked()
+    assert (c == 0).all()
+    d.close()
+    with pytest.raises(binding.OgcError):
+        binding.ogc_mlp_run_clocked(0, 0, 0, 0, 0, 0)
+
+
 @pytest.mark.parametrize("tile", [3, 4])
 def test_stream_kernel_requantizing_epilogues(oracle_mod, tile):
     """Int8 layers without activation and with GELU on the stream kernel, each with an epilogue of its own (last template
