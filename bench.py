@@ -58,7 +58,7 @@ def time_steps(dev, steps, warmup):
     return wall, e0.elapsed_time(e1) * 1e-3 / steps
 
 
-def clock_report(dev, launch_idxs, work, peak):
+def clock_report(dev, launch_idxs, work, peak, reps=20):
     """The clock the chip actually gives the dominant kernel: diagnostic runs in which every workgroup stores the 100 MHz
     wall clock and the shader cycle counter at its start and end (ogc_mlp_run_clocked), repeated back to back after the
     timed region so that the chip is in the same state.  `peak` assumes 2.4 GHz; `mfma_cycles` is the work at the
@@ -70,7 +70,7 @@ def clock_report(dev, launch_idxs, work, peak):
     for _ in range(100):
         dev.run()
     mhz, cycles, alive = [], [], []
-    for _ in range(20):
+    for _ in range(reps):
         c = dev.run_clocked()
         for j in launch_idxs:
             w = c[j][c[j][:, 2] != 0]
@@ -166,6 +166,9 @@ def config_report(idx, steps, warmup, with_floor=None):
         "frac_of_bound": (ops / sec / peak) if bound == "mfma" else (abytes / sec / HBM_PEAK),
         "ops": ops, "algorithmic_bytes": abytes,
     }
+    if bound == "mfma" and rep["mode"] == "per_layer":
+        # the clock each launch really ran at, and its efficiency in cycles (see clock_report)
+        rep["clock_per_launch"] = [clock_report(dev, [j], 2.0 * wl.m * wl.layers[j].k * wl.layers[j].n, peak, reps=8) for j in range(nl)]
     if with_floor is not None:
         rep["launch_floor_ms"] = with_floor * 1e3
         rep["frac_of_latency_aware_bound"] = (with_floor + abytes / HBM_PEAK) / sec
